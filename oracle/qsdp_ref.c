@@ -1,0 +1,408 @@
+/*
+ * qsdp_ref.c -- CPU oracle for the QSDP codec and quantized SGD step.
+ *
+ * TEST INFRASTRUCTURE ONLY (see qsdp_ref.h). Plain C, one element at a time,
+ * no blocking, no SIMD intrinsics, no code shared with the GPU library.
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
+ *
+ * Notation (per bucket): m elements v_0..v_{m-1}; b bits; L = 2^b - 1;
+ * lo = min v, hi = max v; scale = (hi-lo)/L is the grid spacing the paper calls
+ * delta, inv = L/(hi-lo); code in [0, L].
+ */
+#include "qsdp_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define MAX_BUCKET 8192
+
+static int g_threads = 1;
+
+int qsdp_ref_set_threads(int threads) {
+    if (threads >= 1) g_threads = threads;
+    return g_threads;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Random numbers. The paper only asks for "a single random scalar r" (Def. 1) */
+/* and independent coin flips (coin-flip definition); the generator is ours:   */
+/* Philox4x32-10, counter-based, so that any shard of a vector can be          */
+/* quantized alone and give the bytes the whole vector would give.             */
+/* ------------------------------------------------------------------------- */
+
+void qsdp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Gradient stream (stream id 0): one Philox block serves the 8 elements with
+ * the same e/8; element e takes 16 bits: word (e%8)/2, low half first.
+ * u = h * 2^-16 is exact in binary32 and lies in [0,1). */
+float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e) {
+    uint64_t block = e / 8u;
+    uint32_t ctr[4] = {(uint32_t)block, (uint32_t)(block >> 32), 0u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    qsdp_ref_philox4x32_10(ctr, key, out);
+    unsigned j = (unsigned)(e % 8u);
+    uint32_t w = out[j / 2u];
+    uint32_t h = (j % 2u) ? (w >> 16) : (w & 0xFFFFu);
+    return (float)h * 0x1p-16f;
+}
+
+/* Weight stream (stream id 1): one draw per call, whatever the shard.
+ * xi = (top 24 bits of word 0) * 2^-24 - 1/2, exact, in [-1/2, 1/2). */
+float qsdp_ref_weight_shift(uint64_t seed) {
+    uint32_t ctr[4] = {0u, 0u, 1u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    qsdp_ref_philox4x32_10(ctr, key, out);
+    return (float)(out[0] >> 8) * 0x1p-24f - 0.5f;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Sizes and argument checks                                                   */
+/* ------------------------------------------------------------------------- */
+
+static int args_ok(uint64_t n, int bits, int bucket) {
+    return n >= 1 && bits >= 1 && bits <= 8 && bucket >= 32 && bucket <= MAX_BUCKET &&
+           bucket % 32 == 0;
+}
+
+static uint64_t num_buckets(uint64_t n, int bucket) {
+    return (n + (uint64_t)bucket - 1u) / (uint64_t)bucket;
+}
+
+size_t qsdp_ref_codes_bytes(uint64_t n, int bits, int bucket) {
+    if (!args_ok(n, bits, bucket)) return 0;
+    return (size_t)(num_buckets(n, bucket) * (uint64_t)bucket * (uint64_t)bits / 8u);
+}
+
+size_t qsdp_ref_meta_bytes(uint64_t n, int bucket) {
+    if (!args_ok(n, 8, bucket)) return 0;
+    return (size_t)(num_buckets(n, bucket) * 2u * sizeof(float));
+}
+
+/* ------------------------------------------------------------------------- */
+/* One bucket                                                                  */
+/* ------------------------------------------------------------------------- */
+
+/* Min-max statistics of a bucket (Section 5.1: each bucket is scaled by its
+ * own min and max). Signed zeros are canonicalised to +0 so that the stored
+ * meta-data has one bit pattern. A bucket whose range is zero, not finite, or
+ * so small that L/range overflows is treated as constant: scale = inv = 0. */
+static void bucket_stats(const float* v, int m, float Lf, float* lo_out, float* hi_out,
+                         float* scale_out, float* inv_out) {
+    float lo = v[0], hi = v[0];
+    for (int i = 1; i < m; ++i) {
+        if (v[i] < lo) lo = v[i];
+        if (v[i] > hi) hi = v[i];
+    }
+    lo = lo + 0.0f;
+    hi = hi + 0.0f;
+    float range = hi - lo;
+    float scale = 0.0f, inv = 0.0f;
+    if (range > 0.0f && isfinite(range)) {
+        float inv_try = Lf / range;
+        if (isfinite(inv_try)) {
+            scale = range / Lf;
+            inv = inv_try;
+        }
+    }
+    *lo_out = lo; *hi_out = hi; *scale_out = scale; *inv_out = inv;
+}
+
+/* Coin-flip quantizer in bucket coordinates t = (g - lo)/scale in [0, L]:
+ * floor(t) with probability 1 - frac(t), floor(t)+1 with probability frac(t),
+ * decided by u < frac(t) for u uniform in [0,1). */
+static void grad_bucket(const float* g, const float* u, int m, int bits, uint8_t* code,
+                        float* base_out, float* scale_out) {
+    float Lf = (float)((1 << bits) - 1);
+    float lo, hi, scale, inv;
+    bucket_stats(g, m, Lf, &lo, &hi, &scale, &inv);
+    for (int i = 0; i < m; ++i) {
+        float t = (g[i] - lo) * inv;
+        t = fminf(fmaxf(t, 0.0f), Lf);
+        float f = floorf(t);
+        float frac = t - f;
+        int c = (int)f + (u[i] < frac ? 1 : 0);
+        code[i] = (uint8_t)c;
+    }
+    *base_out = lo;
+    *scale_out = scale;
+}
+
+/* Random-shift quantizer (Def. 1), per-bucket grid: with delta := scale and the
+ * shift r := lo + xi*scale, the nearest point of delta*Z + r to x is
+ * r + scale*round((x - lo)/scale - xi). The clamp to [0, L] only acts on the
+ * binary32 rounding of t - xi near L + 1/2 and on the tie at xi = -1/2. */
+static void weight_bucket_minmax(const float* x, int m, int bits, float xi, uint8_t* code,
+                                 float* base_out, float* scale_out) {
+    float Lf = (float)((1 << bits) - 1);
+    float lo, hi, scale, inv;
+    bucket_stats(x, m, Lf, &lo, &hi, &scale, &inv);
+    for (int i = 0; i < m; ++i) {
+        float t = (x[i] - lo) * inv;
+        float k = rintf(t - xi);
+        k = fminf(fmaxf(k, 0.0f), Lf);
+        code[i] = (uint8_t)(int)k;
+    }
+    *base_out = fmaf(xi, scale, lo);
+    *scale_out = scale;
+}
+
+/* Random-shift quantizer (Def. 1), explicit grid delta*(Z + xi): lattice
+ * coordinate k = round(x/delta - xi). A bucket stores k relative to the
+ * coordinate k0 of its smallest element, in b bits; a coordinate further than
+ * L from k0 is clamped and counted. */
+static void weight_bucket_lattice(const float* x, int m, int bits, float delta, float xi,
+                                  uint8_t* code, float* base_out, float* scale_out,
+                                  uint64_t* sat) {
+    float Lf = (float)((1 << bits) - 1);
+    float lo = x[0];
+    for (int i = 1; i < m; ++i)
+        if (x[i] < lo) lo = x[i];
+    lo = lo + 0.0f;
+    float k0 = rintf(lo / delta - xi);
+    for (int i = 0; i < m; ++i) {
+        float k = rintf(x[i] / delta - xi);
+        float c = k - k0;
+        if (c > Lf) {
+            c = Lf;
+            *sat += 1u;
+        }
+        code[i] = (uint8_t)(int)c;
+    }
+    *base_out = (k0 + xi) * delta;
+    *scale_out = delta;
+}
+
+static void weight_bucket(const float* x, int m, int bits, float delta, float xi,
+                          uint8_t* code, float* base, float* scale, uint64_t* sat) {
+    if (delta > 0.0f)
+        weight_bucket_lattice(x, m, bits, delta, xi, code, base, scale, sat);
+    else
+        weight_bucket_minmax(x, m, bits, xi, code, base, scale);
+}
+
+/* Decoding: lattice point -> value, one fused multiply-add. */
+static void dequant_bucket(const uint8_t* code, int m, float base, float scale, float* out) {
+    for (int i = 0; i < m; ++i) out[i] = fmaf((float)code[i], scale, base);
+}
+
+/* Wire format of one bucket: the codes of its `bucket` slots (slots past the
+ * end of a short last bucket hold 0) form a little-endian bit stream, element
+ * i in bits [i*b, (i+1)*b); bit p of the stream is bit p%32 of word p/32. */
+static void pack_bucket(const uint8_t* code, int m, int bits, int bucket, uint32_t* words) {
+    int nwords = bucket * bits / 32;
+    for (int w = 0; w < nwords; ++w) words[w] = 0u;
+    for (int i = 0; i < m; ++i) {
+        for (int q = 0; q < bits; ++q) {
+            if ((code[i] >> q) & 1u) {
+                int p = i * bits + q;
+                words[p / 32] |= (uint32_t)1u << (p % 32);
+            }
+        }
+    }
+}
+
+static void unpack_bucket(const uint32_t* words, int m, int bits, uint8_t* code) {
+    for (int i = 0; i < m; ++i) {
+        unsigned c = 0;
+        for (int q = 0; q < bits; ++q) {
+            int p = i * bits + q;
+            c |= ((words[p / 32] >> (p % 32)) & 1u) << q;
+        }
+        code[i] = (uint8_t)c;
+    }
+}
+
+/* binary32 -> bfloat16, round to nearest even (finite inputs). */
+uint16_t qsdp_ref_f32_to_bf16(float v) {
+    uint32_t bitsv;
+    memcpy(&bitsv, &v, sizeof bitsv);
+    bitsv += 0x7FFFu + ((bitsv >> 16) & 1u);
+    return (uint16_t)(bitsv >> 16);
+}
+
+static int bucket_len(uint64_t n, int bucket, uint64_t j) {
+    uint64_t start = j * (uint64_t)bucket;
+    uint64_t rest = n - start;
+    return rest < (uint64_t)bucket ? (int)rest : bucket;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Cores with the randomness passed in                                         */
+/* ------------------------------------------------------------------------- */
+
+int qsdp_ref_quantize_grad_u(const float* g, uint64_t n, int bits, int bucket, const float* u,
+                             uint8_t* codes, float* meta) {
+    if (!g || !u || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        grad_bucket(g + s, u + s, m, bits, codes + s, &meta[2 * j], &meta[2 * j + 1]);
+    }
+    return QSDP_REF_OK;
+}
+
+int qsdp_ref_quantize_weight_xi(const float* x, uint64_t n, int bits, int bucket, float delta,
+                                float xi, uint8_t* codes, float* meta, uint64_t* n_saturated) {
+    if (!x || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (!(delta >= 0.0f) || !isfinite(delta)) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    uint64_t sat = 0;
+#pragma omp parallel for schedule(static) num_threads(g_threads) reduction(+ : sat)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        uint64_t local = 0;
+        weight_bucket(x + s, m, bits, delta, xi, codes + s, &meta[2 * j], &meta[2 * j + 1],
+                      &local);
+        sat += local;
+    }
+    if (n_saturated) *n_saturated += sat;
+    return QSDP_REF_OK;
+}
+
+void qsdp_ref_pack(const uint8_t* codes, uint64_t n, int bits, int bucket, uint32_t* words) {
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+    for (int64_t j = 0; j < nb; ++j)
+        pack_bucket(codes + (uint64_t)j * (uint64_t)bucket, bucket_len(n, bucket, (uint64_t)j),
+                    bits, bucket, words + (uint64_t)j * (uint64_t)wpb);
+}
+
+void qsdp_ref_unpack(const uint32_t* words, uint64_t n, int bits, int bucket, uint8_t* codes) {
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+    for (int64_t j = 0; j < nb; ++j)
+        unpack_bucket(words + (uint64_t)j * (uint64_t)wpb, bucket_len(n, bucket, (uint64_t)j),
+                      bits, codes + (uint64_t)j * (uint64_t)bucket);
+}
+
+/* ------------------------------------------------------------------------- */
+/* The four operations                                                         */
+/* ------------------------------------------------------------------------- */
+
+int qsdp_ref_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                           uint64_t index_offset, uint32_t* codes, float* meta) {
+    if (!g || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float u[MAX_BUCKET];
+        uint8_t code[MAX_BUCKET];
+        for (int i = 0; i < m; ++i) u[i] = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
+        grad_bucket(g + s, u, m, bits, code, &meta[2 * j], &meta[2 * j + 1]);
+        pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
+    }
+    return QSDP_REF_OK;
+}
+
+int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float delta,
+                             uint64_t seed, uint32_t* codes, float* meta,
+                             uint64_t* n_saturated) {
+    if (!x || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (!(delta >= 0.0f) || !isfinite(delta)) return QSDP_REF_EINVAL;
+    float xi = qsdp_ref_weight_shift(seed);
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+    uint64_t sat = 0;
+#pragma omp parallel for schedule(static) num_threads(g_threads) reduction(+ : sat)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        uint8_t code[MAX_BUCKET];
+        uint64_t local = 0;
+        weight_bucket(x + s, m, bits, delta, xi, code, &meta[2 * j], &meta[2 * j + 1], &local);
+        pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
+        sat += local;
+    }
+    if (n_saturated) *n_saturated += sat;
+    return QSDP_REF_OK;
+}
+
+int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                        int bucket, int out_dtype, void* out) {
+    if (!codes || !meta || !out || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (out_dtype != QSDP_REF_F32 && out_dtype != QSDP_REF_BF16) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        uint8_t code[MAX_BUCKET];
+        float val[MAX_BUCKET];
+        unpack_bucket(codes + (uint64_t)j * (uint64_t)wpb, m, bits, code);
+        dequant_bucket(code, m, meta[2 * j], meta[2 * j + 1], val);
+        if (out_dtype == QSDP_REF_F32) {
+            for (int i = 0; i < m; ++i) ((float*)out)[s + (uint64_t)i] = val[i];
+        } else {
+            for (int i = 0; i < m; ++i) ((uint16_t*)out)[s + (uint64_t)i] = qsdp_ref_f32_to_bf16(val[i]);
+        }
+    }
+    return QSDP_REF_OK;
+}
+
+/* x <- Q^w(x - lr * Q^g(g)): per bucket, quantize the gradient, decode it,
+ * take the step, quantize the result, decode it (the iterate lives on the
+ * quantization grid). The same seed drives both random streams. */
+int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits,
+                        int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                        uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
+    if (!x || !g || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket))
+        return QSDP_REF_EINVAL;
+    if (!(delta >= 0.0f) || !isfinite(delta) || !isfinite(lr)) return QSDP_REF_EINVAL;
+    if ((wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
+    if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    float xi = qsdp_ref_weight_shift(seed);
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * wbits / 32;
+    uint64_t sat = 0;
+#pragma omp parallel for schedule(static) num_threads(g_threads) reduction(+ : sat)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float u[MAX_BUCKET], ghat[MAX_BUCKET], y[MAX_BUCKET];
+        uint8_t gcode[MAX_BUCKET], wcode[MAX_BUCKET];
+        float gbase, gscale, wbase, wscale;
+        uint64_t local = 0;
+        for (int i = 0; i < m; ++i) u[i] = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
+        grad_bucket(g + s, u, m, gbits, gcode, &gbase, &gscale);
+        dequant_bucket(gcode, m, gbase, gscale, ghat);
+        for (int i = 0; i < m; ++i) y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);
+        weight_bucket(y, m, wbits, delta, xi, wcode, &wbase, &wscale, &local);
+        dequant_bucket(wcode, m, wbase, wscale, x + s);
+        if (wcodes) {
+            pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);
+            wmeta[2 * j] = wbase;
+            wmeta[2 * j + 1] = wscale;
+        }
+        sat += local;
+    }
+    if (n_saturated) *n_saturated += sat;
+    return QSDP_REF_OK;
+}

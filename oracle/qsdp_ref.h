@@ -1,0 +1,89 @@
+/*
+ * qsdp_ref.h -- CPU oracle for the QSDP quantization codec and quantized SGD step.
+ *
+ * TEST INFRASTRUCTURE ONLY. This is a plain, slow, obviously-correct host
+ * implementation used to check the GPU library and to report a CPU baseline.
+ * Nothing in the product path may include, link or call it. It shares no code
+ * with the HIP kernels.
+ *
+ * Everything is IEEE-754 binary32, round-to-nearest-even, no contraction: an
+ * expression written a*b+c is two roundings, fmaf(a,b,c) is one.
+ *
+ * What each routine follows (paper = "Quantized Distributed Training of Large
+ * Models with Convergence Guarantees", arXiv 2302.02390):
+ *   - gradient quantizer Q^g : "quantization by flipping a coin" (appendix
+ *     definition of Q^g_delta), applied in per-bucket min-max coordinates
+ *     (Section 5.1, bucketing paragraph).
+ *   - weight quantizer  Q^w : Definition 1 "quantization by random shift",
+ *     either on a per-bucket min-max grid or on the explicit grid delta*(Z+xi).
+ *   - step              : x_{t+1} = Q^w(x_t - eta * Q^g(g_t)) (Section 3.3,
+ *     last display; Section 4.1 iteration).
+ * The paper fixes neither a random number generator nor a wire format; those
+ * are this project's choices and are documented where they are implemented.
+ *
+ * Parity pins: every routine here is pinned by tests that do not call it to
+ * produce their own expectation (closed forms of Lemma 3 and of the coin-flip
+ * lemma, exhaustive enumeration of the randomness, a textbook affine quantizer,
+ * a third-party Philox implementation, brute-force bit extraction). No routine
+ * is "parity unpinned".
+ */
+#ifndef QSDP_REF_H
+#define QSDP_REF_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { QSDP_REF_OK = 0, QSDP_REF_EINVAL = -1 };
+enum { QSDP_REF_F32 = 0, QSDP_REF_BF16 = 1 };
+
+/* Number of worker threads for the bucket loop (buckets are independent, so the
+ * output does not depend on it). Default 1. Returns the value now in force. */
+int qsdp_ref_set_threads(int threads);
+
+/* Philox4x32-10 block function (Salmon, Moraes, Dror, Shaw, SC'11). */
+void qsdp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* The uniform u in [0,1) that decides the rounding of the gradient element whose
+ * GLOBAL index is e, and the shift xi in [-1/2,1/2) of a weight quantization. */
+float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e);
+float qsdp_ref_weight_shift(uint64_t seed);
+
+/* Sizes of the packed representation. */
+size_t qsdp_ref_codes_bytes(uint64_t n, int bits, int bucket);
+size_t qsdp_ref_meta_bytes(uint64_t n, int bucket);
+
+/* --- cores with the randomness passed in (one code per byte, not packed) --- */
+int qsdp_ref_quantize_grad_u(const float* g, uint64_t n, int bits, int bucket,
+                             const float* u /* n uniforms in [0,1) */,
+                             uint8_t* codes /* n */, float* meta /* 2*nb */);
+int qsdp_ref_quantize_weight_xi(const float* x, uint64_t n, int bits, int bucket,
+                                float delta, float xi,
+                                uint8_t* codes /* n */, float* meta /* 2*nb */,
+                                uint64_t* n_saturated /* nullable, incremented */);
+void qsdp_ref_pack(const uint8_t* codes, uint64_t n, int bits, int bucket, uint32_t* words);
+void qsdp_ref_unpack(const uint32_t* words, uint64_t n, int bits, int bucket, uint8_t* codes);
+uint16_t qsdp_ref_f32_to_bf16(float v);
+
+/* --- the four operations, same meaning as the library's entry points, on host
+ * pointers, synchronous --- */
+int qsdp_ref_quantize_grad(const float* g, uint64_t n, int bits, int bucket,
+                           uint64_t seed, uint64_t index_offset,
+                           uint32_t* codes, float* meta);
+int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
+                             float delta, uint64_t seed,
+                             uint32_t* codes, float* meta, uint64_t* n_saturated);
+int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                        int bucket, int out_dtype, void* out);
+int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr,
+                        int wbits, int gbits, int bucket, float delta,
+                        uint64_t seed, uint64_t index_offset,
+                        uint32_t* wcodes /* nullable */, float* wmeta /* nullable */,
+                        uint64_t* n_saturated /* nullable */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

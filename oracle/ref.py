@@ -1,0 +1,195 @@
+"""ctypes/numpy front end of the CPU oracle (``libqsdp_ref.so``).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's CPU-baseline leg; never by the product package. Every function takes
+and returns numpy arrays on the host and holds no arithmetic of its own: the
+arithmetic is in ``qsdp_ref.c``.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        u64, i32, f32, vp = C.c_uint64, C.c_int, C.c_float, C.c_void_p
+        L.qsdp_ref_set_threads.argtypes = [i32]
+        L.qsdp_ref_set_threads.restype = i32
+        L.qsdp_ref_philox4x32_10.argtypes = [vp, vp, vp]
+        L.qsdp_ref_philox4x32_10.restype = None
+        L.qsdp_ref_grad_uniform.argtypes = [u64, u64]
+        L.qsdp_ref_grad_uniform.restype = f32
+        L.qsdp_ref_weight_shift.argtypes = [u64]
+        L.qsdp_ref_weight_shift.restype = f32
+        L.qsdp_ref_codes_bytes.argtypes = [u64, i32, i32]
+        L.qsdp_ref_codes_bytes.restype = C.c_size_t
+        L.qsdp_ref_meta_bytes.argtypes = [u64, i32]
+        L.qsdp_ref_meta_bytes.restype = C.c_size_t
+        L.qsdp_ref_quantize_grad_u.argtypes = [vp, u64, i32, i32, vp, vp, vp]
+        L.qsdp_ref_quantize_weight_xi.argtypes = [vp, u64, i32, i32, f32, f32, vp, vp, vp]
+        L.qsdp_ref_pack.argtypes = [vp, u64, i32, i32, vp]
+        L.qsdp_ref_pack.restype = None
+        L.qsdp_ref_unpack.argtypes = [vp, u64, i32, i32, vp]
+        L.qsdp_ref_unpack.restype = None
+        L.qsdp_ref_f32_to_bf16.argtypes = [f32]
+        L.qsdp_ref_f32_to_bf16.restype = C.c_uint16
+        L.qsdp_ref_quantize_grad.argtypes = [vp, u64, i32, i32, u64, u64, vp, vp]
+        L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
+        L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
+        L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
+                                          vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a.reshape(-1)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"{what}: oracle returned {rc}")
+
+
+def set_threads(t):
+    return lib().qsdp_ref_set_threads(int(t))
+
+
+def philox4x32_10(ctr, key):
+    ctr = np.asarray(ctr, dtype=np.uint32).copy()
+    key = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().qsdp_ref_philox4x32_10(_p(ctr), _p(key), _p(out))
+    return out
+
+
+def grad_uniform(seed, e):
+    return float(lib().qsdp_ref_grad_uniform(int(seed), int(e)))
+
+
+def weight_shift(seed):
+    return float(lib().qsdp_ref_weight_shift(int(seed)))
+
+
+def codes_bytes(n, bits, bucket):
+    return int(lib().qsdp_ref_codes_bytes(int(n), int(bits), int(bucket)))
+
+
+def meta_bytes(n, bucket):
+    return int(lib().qsdp_ref_meta_bytes(int(n), int(bucket)))
+
+
+def _nb(n, bucket):
+    return (n + bucket - 1) // bucket
+
+
+def quantize_grad_u(g, bits, bucket, u):
+    """Coin-flip quantizer with explicit uniforms. Returns (codes u8[n], meta f32[nb,2])."""
+    g = _f32(g)
+    u = _f32(u)
+    n = g.size
+    codes = np.zeros(n, dtype=np.uint8)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    _check(lib().qsdp_ref_quantize_grad_u(_p(g), n, bits, bucket, _p(u), _p(codes), _p(meta)),
+           "quantize_grad_u")
+    return codes, meta
+
+
+def quantize_weight_xi(x, bits, bucket, delta, xi):
+    """Random-shift quantizer with explicit shift. Returns (codes u8[n], meta, n_saturated)."""
+    x = _f32(x)
+    n = x.size
+    codes = np.zeros(n, dtype=np.uint8)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_quantize_weight_xi(_p(x), n, bits, bucket, float(delta), float(xi),
+                                             _p(codes), _p(meta), _p(sat)),
+           "quantize_weight_xi")
+    return codes, meta, int(sat[0])
+
+
+def pack(codes, bits, bucket):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1)
+    n = codes.size
+    words = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
+    lib().qsdp_ref_pack(_p(codes), n, bits, bucket, _p(words))
+    return words
+
+
+def unpack(words, n, bits, bucket):
+    words = np.ascontiguousarray(words, dtype=np.uint32).reshape(-1)
+    assert words.size * 4 == codes_bytes(n, bits, bucket)
+    codes = np.zeros(n, dtype=np.uint8)
+    lib().qsdp_ref_unpack(_p(words), n, bits, bucket, _p(codes))
+    return codes
+
+
+def f32_to_bf16(v):
+    return int(lib().qsdp_ref_f32_to_bf16(float(v)))
+
+
+def quantize_grad(g, bits, bucket, seed, index_offset=0):
+    """Returns (packed codes u32[...], meta f32[nb,2])."""
+    g = _f32(g)
+    n = g.size
+    codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    _check(lib().qsdp_ref_quantize_grad(_p(g), n, bits, bucket, int(seed), int(index_offset),
+                                        _p(codes), _p(meta)), "quantize_grad")
+    return codes, meta
+
+
+def quantize_weight(x, bits, bucket, delta, seed):
+    """Returns (packed codes, meta, n_saturated)."""
+    x = _f32(x)
+    n = x.size
+    codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_quantize_weight(_p(x), n, bits, bucket, float(delta), int(seed),
+                                          _p(codes), _p(meta), _p(sat)), "quantize_weight")
+    return codes, meta, int(sat[0])
+
+
+def dequantize(codes, meta, n, bits, bucket, out_dtype=F32):
+    """Returns f32[n], or the bf16 bit patterns as u16[n]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint32).reshape(-1)
+    meta = np.ascontiguousarray(meta, dtype=np.float32).reshape(-1)
+    assert codes.size * 4 == codes_bytes(n, bits, bucket)
+    assert meta.size == 2 * _nb(n, bucket)
+    out = np.zeros(n, dtype=np.float32 if out_dtype == F32 else np.uint16)
+    _check(lib().qsdp_ref_dequantize(_p(codes), _p(meta), n, bits, bucket, out_dtype, _p(out)),
+           "dequantize")
+    return out
+
+
+def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit_codes=False):
+    """Returns (x_new f32[n], wcodes or None, wmeta or None, n_saturated). x is not modified."""
+    x = _f32(x).copy()
+    g = _f32(g)
+    n = x.size
+    assert g.size == n
+    wcodes = wmeta = None
+    if emit_codes:
+        wcodes = np.zeros(codes_bytes(n, wbits, bucket) // 4, dtype=np.uint32)
+        wmeta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_fused_step(_p(x), _p(g), n, float(lr), wbits, gbits, bucket,
+                                     float(delta), int(seed), int(index_offset),
+                                     _p(wcodes), _p(wmeta), _p(sat)), "fused_step")
+    return x, wcodes, wmeta, int(sat[0])
