@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the QSDP fused quantized SGD step on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): a GPT-1.3B-shaped flat fp32
+parameter vector (1,315,723,264 elements: 24 layers, d = 2048, vocabulary 50257), weights
+~ 0.02*N(0,1), gradients ~ 1e-3*Student-t(3); 8-bit weights, 4-bit gradients, bucket 1024,
+lr 1e-3; step k uses seed k and updates x in place, g stays fixed.
+
+A step is one call of qsdp_fused_step over the whole vector: x <- Q^w(x - lr*Q^g(g)), i.e.
+bucket statistics, stochastic gradient rounding, decode, axpy, random-shift weight rounding
+and decode, in one pass over HBM. Algorithmic traffic: 12 bytes per parameter (read x, read
+g, write x). Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line. `--gpus` above 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0
+BYTES_PER_PARAM = 12.0
+
+# HBM bytes per fused-step launch on the 1.3B workload from rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by the same counters on a plain copy kernel); see
+# profiles/fused_step_gpt1p3b.md. None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="gpt-1.3b", choices=["gpt-1.3b", "gpt-350m", "gpt-125m", "1m"])
+    ap.add_argument("--wbits", type=int, default=8)
+    ap.add_argument("--gbits", type=int, default=None)
+    ap.add_argument("--bucket", type=int, default=1024)
+    ap.add_argument("--delta", type=float, default=0.0)
+    ap.add_argument("--emit-codes", action="store_true", help="also write packed Q^w codes + meta")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip timing the other entry points")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    return ap.parse_args()
+
+
+def time_call(fn, iters, torch):
+    """Average duration in ms of fn() over iters calls, from events on the current stream."""
+    start = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    stop = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        start[i].record()
+        fn(i)
+        stop[i].record()
+    torch.cuda.synchronize()
+    ts = [a.elapsed_time(b) for a, b in zip(start, stop)]
+    return sum(ts) / len(ts), sorted(ts)[len(ts) // 2]
+
+
+def main():
+    a = parse()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the codec has no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    from paper_2302_02390_amd import binding as qb
+    from paper_2302_02390_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qb.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if a.workload == "1m":
+        n, cfg_id, heavy = 1 << 20, 0, False
+    else:
+        shape = {"gpt-1.3b": wl.GPT_1P3B, "gpt-350m": wl.GPT_350M, "gpt-125m": wl.GPT_125M}[a.workload]
+        n, cfg_id, heavy = wl.model_numel(shape), {"gpt-125m": 1, "gpt-350m": 2, "gpt-1.3b": 3}[a.workload], True
+    gbits = a.gbits if a.gbits is not None else (4 if a.workload in ("gpt-1.3b", "gpt-350m") else 8)
+    wbits, bucket, delta, lr = a.wbits, a.bucket, a.delta, 1e-3
+
+    x = wl.weights(n, 1234 + 2 * cfg_id, dev)
+    g = wl.grads_student_t3(n, 1235 + 2 * cfg_id, dev) if heavy else wl.grads_normal(n, 1235 + 2 * cfg_id, dev)
+    x0_head = x[: min(n, a.cpu_sample)].clone()
+    wcodes = wmeta = None
+    if a.emit_codes:
+        wcodes, wmeta = qb.alloc_packed(n, wbits, bucket, dev)
+        wmeta = wmeta.reshape(-1)
+    torch.cuda.synchronize()
+
+    def step(k):
+        qb.qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, k, 0, wcodes, wmeta, None)
+
+    for k in range(a.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(a.steps):
+        step(a.warmup + k)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / max(a.steps, 1)
+
+    # per-launch kernel duration from events on the launch stream (for the roofline entry)
+    ev_iters = max(5, min(a.steps, 50))
+    ev_mean, ev_median = time_call(lambda i: step(1000 + i), ev_iters, torch)
+
+    bytes_per_param = BYTES_PER_PARAM + ((wbits / 8.0 + 8.0 / bucket) if a.emit_codes else 0.0)
+    alg_bytes = bytes_per_param * n
+    value_gbs = alg_bytes / (wall_ms * 1e-3) / 1e9
+    achieved = alg_bytes / (ev_mean * 1e-3) / 1e9
+
+    out = {
+        "metric": "fused quantize+step GB/s (fraction of HBM peak) and params/s, 1.3B fp32 shard",
+        "value": round(value_gbs, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "params_per_s": round(n / (wall_ms * 1e-3), 1),
+        "hbm_peak_frac": round(value_gbs / HBM_PEAK_GBS, 4),
+        "config": {
+            "workload": f"{a.workload}-shaped flat fp32 vector, n={n}, W{wbits} G{gbits}, bucket {bucket}, "
+                        f"delta {delta}, lr {lr}, seed = step index, in-place fused step"
+                        + (", packed codes emitted" if a.emit_codes else ""),
+            "n": n, "wbits": wbits, "gbits": gbits, "bucket": bucket, "delta": delta,
+            "spec_version": qb.spec_version(),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES if (a.workload == "gpt-1.3b" and not a.emit_codes) else None,
+            "kernel": "wave_kernel<FUSED> (qsdp_fused_step)",
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "kernel_ms_mean": round(ev_mean, 4),
+            "kernel_ms_median": round(ev_median, 4),
+        },
+    }
+
+    if not a.no_extras:
+        out["other_entry_points"] = extras(torch, qb, x, g, n, wbits, gbits, bucket, dev)
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(x0_head, g[: x0_head.numel()], lr, wbits, gbits, bucket, delta,
+                                           bytes_per_param)
+    print(json.dumps(out))
+    return 0
+
+
+def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
+    """Algorithmic GB/s of the other entry points on the same tensors (not part of `value`)."""
+    res = {}
+    meta_b = 8.0 / bucket
+    gc, gm = qb.alloc_packed(n, gbits, bucket, dev)
+    wc, wm = qb.alloc_packed(n, wbits, bucket, dev)
+    gm, wm = gm.reshape(-1), wm.reshape(-1)
+
+    def run(name, fn, bytes_per_param):
+        for i in range(3):
+            fn(i)
+        mean, median = time_call(fn, 10, torch)
+        res[name] = {"ms": round(mean, 4), "GB/s": round(bytes_per_param * n / (mean * 1e-3) / 1e9, 1),
+                     "bytes_per_param": round(bytes_per_param, 4)}
+
+    run(f"quantize_grad_b{gbits}", lambda i: qb.qsdp_quantize_grad(g, gbits, bucket, i, 0, gc, gm),
+        4 + gbits / 8.0 + meta_b)
+    run(f"quantize_weight_b{wbits}", lambda i: qb.qsdp_quantize_weight(x, wbits, bucket, 0.0, i, wc, wm),
+        4 + wbits / 8.0 + meta_b)
+    out32 = torch.empty(n, dtype=torch.float32, device=dev)
+    run(f"dequantize_b{wbits}_f32", lambda i: qb.qsdp_dequantize(wc, wm, n, wbits, bucket, out32),
+        4 + wbits / 8.0 + meta_b)
+    del out32
+    out16 = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    run(f"dequantize_b{wbits}_bf16", lambda i: qb.qsdp_dequantize(wc, wm, n, wbits, bucket, out16),
+        2 + wbits / 8.0 + meta_b)
+    run(f"dequantize_b{gbits}_bf16", lambda i: qb.qsdp_dequantize(gc, gm, n, gbits, bucket, out16),
+        2 + gbits / 8.0 + meta_b)
+    return res
+
+
+def cpu_baseline(x_head, g_head, lr, wbits, gbits, bucket, delta, bytes_per_param):
+    """The CPU oracle, as it stands, on the first elements of the same tensors (step seed 0)."""
+    from oracle import ref
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    ref.set_threads(threads)
+    xs = x_head.cpu().numpy()
+    gs = g_head.cpu().numpy()
+    m = xs.size
+    t0 = time.perf_counter()
+    ref.fused_step(xs, gs, lr, wbits, gbits, bucket, delta, 0)
+    dt = time.perf_counter() - t0
+    ref.set_threads(1)
+    return {"value": round(bytes_per_param * m / dt / 1e9, 3), "unit": "GB/s", "cores": threads,
+            "kind": "oracle", "params_per_s": round(m / dt, 1), "seconds": round(dt, 3),
+            "sample": f"first {m} elements of the same x and g, one fused step (seed 0), "
+                      f"bucket-parallel oracle on {threads} threads"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

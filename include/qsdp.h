@@ -1,0 +1,137 @@
+/*
+ * qsdp.h -- C ABI of the MI355X (gfx950) QSDP quantization codec and fused quantized
+ * SGD step.
+ *
+ * The operations are those of "Quantized Distributed Training of Large Models with
+ * Convergence Guarantees" (arXiv 2302.02390):
+ *   Q^g  unbiased stochastic ("coin-flip") quantizer of gradients (Section 3.2; appendix
+ *        definition "quantization by flipping a coin"), applied per bucket in min-max
+ *        coordinates (Section 5.1, bucketing);
+ *   Q^w  quantization of weights by random shift (Section 4.1, Definition 1), on a
+ *        per-bucket min-max grid or on the explicit grid delta*(Z + xi);
+ *   step x_{t+1} = Q^w(x_t - eta * Q^g(g_t)) (Section 3.3, last display).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All tensor pointers are DEVICE pointers (HIP global memory of the current device),
+ *    16-byte aligned, allocated and owned by the caller. The library allocates no device
+ *    memory, keeps no pointer after returning and has no mutable global state.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream). Work is
+ *    enqueued on it and the call returns without synchronising.
+ *  - Return value: QSDP_OK, or a negative error. On error nothing has been launched.
+ *  - n >= 1 elements; bits in [1,8]; bucket a multiple of 32 in [32, 8192]. The vector is
+ *    cut into buckets of `bucket` consecutive elements; the last one may be short.
+ *  - Inputs must be finite. Non-finite inputs give unspecified codes but no fault.
+ *
+ * Random numbers (the paper leaves the generator open): Philox4x32-10, key =
+ * (seed low 32 bits, seed high 32 bits), counter = (c low, c high, stream, 0).
+ *   stream 0, gradient rounding: the element with GLOBAL index e = index_offset + i uses
+ *     block c = e/8 and the 16-bit half (e%8) of its four words (word (e%8)/2, low half
+ *     first): u = h * 2^-16 in [0,1). index_offset must be a multiple of 8. Quantizing a
+ *     bucket-aligned shard with its global offset gives the bytes the whole vector gives.
+ *   stream 1, weight shift: c = 0, xi = (word0 >> 8) * 2^-24 - 1/2 in [-1/2, 1/2); one
+ *     draw per call whatever the shard ("a single random scalar" for the whole vector).
+ *
+ * Packed representation (the paper leaves the layout open)
+ * ---------------------------------------------------------
+ *  codes: bucket j owns the 32-bit words [j*bucket*bits/32, (j+1)*bucket*bits/32). Within
+ *         a bucket, element i occupies bits [i*bits, (i+1)*bits) of a little-endian bit
+ *         stream (stream bit p = bit p%32 of word p/32). Slots past the end of a short
+ *         last bucket are written as 0.
+ *  meta:  float[2*nb]: {base_j, scale_j}; the decoded value of code c is
+ *         fma(c, scale_j, base_j). For Q^w the shift is folded into base_j.
+ *
+ * Arithmetic is IEEE binary32, round to nearest even, in a fixed operation order, so that
+ * the output is a pure function of the arguments (bit-reproducible, no atomics on data).
+ */
+#ifndef QSDP_H
+#define QSDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    QSDP_OK = 0,
+    QSDP_EINVAL = -1,  /* bad n / bits / bucket / delta / lr / dtype / index_offset / NULL */
+    QSDP_EALIGN = -2,  /* a pointer is not 16-byte aligned */
+    QSDP_ELAUNCH = -3  /* the HIP runtime refused the launch */
+};
+
+typedef enum { QSDP_F32 = 0, QSDP_BF16 = 1 } qsdp_dtype;
+
+/* Version of the arithmetic/wire specification implemented (2: 16-bit uniforms, 8 per
+ * Philox block). */
+uint32_t qsdp_spec_version(void);
+
+/* Bytes of the packed codes / of the meta-data for n elements: nb*bucket*bits/8 and
+ * nb*2*sizeof(float), nb = ceil(n/bucket). 0 if the arguments are invalid. Host only. */
+size_t qsdp_codes_bytes(uint64_t n, int bits, int bucket);
+size_t qsdp_meta_bytes(uint64_t n, int bucket);
+
+/* Human-readable text for a status code (static storage). */
+const char* qsdp_status_string(int status);
+
+/*
+ * Q^g: bucketed unbiased stochastic quantization (coin-flip definition; Section 5.1).
+ * Per bucket: lo = min, hi = max, scale = (hi-lo)/L, L = 2^bits-1; t = (g-lo)*(L/(hi-lo));
+ * code = floor(t) + [u < frac(t)]; meta = {lo, scale}. A constant bucket gets scale 0 and
+ * codes 0.
+ *   g      in   device float[n]
+ *   codes  out  device uint32[qsdp_codes_bytes/4]
+ *   meta   out  device float[2*nb]
+ */
+int qsdp_quantize_grad(const float* g, uint64_t n, int bits, int bucket,
+                       uint64_t seed, uint64_t index_offset,
+                       uint32_t* codes, float* meta, void* stream);
+
+/*
+ * Q^w: quantization by random shift (Definition 1).
+ *   delta == 0: per-bucket grid lo + scale*(Z + xi), scale = (hi-lo)/L;
+ *               code = clamp(round((x-lo)/scale - xi), 0, L); meta = {lo + xi*scale, scale}.
+ *   delta  > 0: the grid delta*(Z + xi) of Definition 1; lattice coordinate
+ *               k = round(x/delta - xi); a bucket stores k - k0 (k0 = coordinate of its
+ *               minimum) in `bits` bits; meta = {(k0+xi)*delta, delta}. Coordinates more
+ *               than L above k0 are clamped to L and counted in *n_saturated.
+ *   n_saturated  in/out, nullable, device uint64: incremented (atomically) by the number of
+ *               clamped elements; the caller zeroes it.
+ */
+int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
+                         float delta, uint64_t seed,
+                         uint32_t* codes, float* meta,
+                         uint64_t* n_saturated, void* stream);
+
+/*
+ * Decoding ("takes the lattice point and undoes the shift", Section 4.1; what a worker does
+ * with a gathered quantized layer, Algorithm 2): out[i] = fma(code_i, scale_j, base_j),
+ * stored as float (QSDP_F32) or rounded to nearest-even bfloat16 (QSDP_BF16). Serves both
+ * quantizers. Elements past n are not written.
+ *   out  out  device float[n] or uint16[n]
+ */
+int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                    int bucket, qsdp_dtype out_dtype, void* out, void* stream);
+
+/*
+ * Fused quantized SGD step, in place: x <- Q^w(x - lr * Q^g(g)) (Section 3.3 / 4.1), one
+ * pass over HBM (read x, read g, write x). Per bucket: Q^g of g with `gbits`, decoded in
+ * registers; y = fma(-lr, ghat, x); Q^w of y with `wbits` (delta as in
+ * qsdp_quantize_weight), decoded into x. The same seed drives both random streams.
+ *   x        in/out device float[n]
+ *   g        in     device float[n]
+ *   wcodes   out, nullable: packed Q^w codes of the new x (what the next weight gather
+ *            would transmit); wmeta must be given iff wcodes is.
+ *   n_saturated as in qsdp_quantize_weight.
+ */
+int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
+                    int wbits, int gbits, int bucket, float delta,
+                    uint64_t seed, uint64_t index_offset,
+                    uint32_t* wcodes, float* wmeta,
+                    uint64_t* n_saturated, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSDP_H */

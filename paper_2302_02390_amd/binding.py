@@ -1,0 +1,148 @@
+"""Thin Python binding of the C ABI in ``include/qsdp.h`` (``libqsdp.so``).
+
+Argument marshalling only: torch tensors supply device memory and the current stream; every
+step of the computation runs in the HIP kernels. The functions have the names and argument
+order of the C entry points. There is no fallback: if the library is not built, importing
+the symbols raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqsdp.so")
+
+QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
+QSDP_F32, QSDP_BF16 = 0, 1
+
+EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
+           "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step")
+
+_lib = None
+
+
+class QsdpError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def lib():
+    """Load libqsdp.so (built by ``python -m paper_2302_02390_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2302_02390_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        u64, i32, f32, vp = C.c_uint64, C.c_int, C.c_float, C.c_void_p
+        L.qsdp_spec_version.argtypes = []
+        L.qsdp_spec_version.restype = C.c_uint32
+        L.qsdp_codes_bytes.argtypes = [u64, i32, i32]
+        L.qsdp_codes_bytes.restype = C.c_size_t
+        L.qsdp_meta_bytes.argtypes = [u64, i32]
+        L.qsdp_meta_bytes.restype = C.c_size_t
+        L.qsdp_status_string.argtypes = [i32]
+        L.qsdp_status_string.restype = C.c_char_p
+        L.qsdp_quantize_grad.argtypes = [vp, u64, i32, i32, u64, u64, vp, vp, vp]
+        L.qsdp_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp, vp]
+        L.qsdp_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
+        L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
+        for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().qsdp_status_string(int(status)).decode()
+
+
+def spec_version():
+    return int(lib().qsdp_spec_version())
+
+
+def codes_bytes(n, bits, bucket):
+    return int(lib().qsdp_codes_bytes(int(n), int(bits), int(bucket)))
+
+
+def meta_bytes(n, bucket):
+    return int(lib().qsdp_meta_bytes(int(n), int(bucket)))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(t):
+    return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _check(status, what):
+    if status != QSDP_OK:
+        raise QsdpError(status, what)
+
+
+def _is(t, dtype):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"expected a contiguous {dtype} tensor on the GPU")
+
+
+def alloc_packed(n, bits, bucket, device):
+    """Empty (codes uint32-as-int32[...], meta float32[nb, 2]) buffers of the right size."""
+    cb, mb = codes_bytes(n, bits, bucket), meta_bytes(n, bucket)
+    if cb == 0 or mb == 0:
+        raise QsdpError(QSDP_EINVAL, "alloc_packed")
+    codes = torch.empty(cb // 4, dtype=torch.int32, device=device)
+    meta = torch.empty((mb // 8, 2), dtype=torch.float32, device=device)
+    return codes, meta
+
+
+def qsdp_quantize_grad(g, bits, bucket, seed, index_offset, codes, meta):
+    _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_quantize_grad(_ptr(g), g.numel(), bits, bucket, seed, index_offset,
+                                        _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad")
+
+
+def qsdp_quantize_weight(x, bits, bucket, delta, seed, codes, meta, n_saturated=None):
+    _is(x, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_quantize_weight(_ptr(x), x.numel(), bits, bucket, delta, seed, _ptr(codes),
+                                          _ptr(meta), _ptr(n_saturated), _stream(x)),
+               "qsdp_quantize_weight")
+
+
+def qsdp_dequantize(codes, meta, n, bits, bucket, out):
+    _is(codes, torch.int32); _is(meta, torch.float32)
+    if out.dtype == torch.float32:
+        dt = QSDP_F32
+    elif out.dtype == torch.bfloat16:
+        dt = QSDP_BF16
+    else:
+        raise TypeError("out must be float32 or bfloat16")
+    _is(out, out.dtype)
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize(_ptr(codes), _ptr(meta), n, bits, bucket, dt, _ptr(out),
+                                     _stream(out)), "qsdp_dequantize")
+
+
+def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, wcodes=None,
+                    wmeta=None, n_saturated=None):
+    _is(x, torch.float32); _is(g, torch.float32)
+    if g.numel() != x.numel():
+        raise ValueError("x and g differ in size")
+    if wcodes is not None:
+        _is(wcodes, torch.int32)
+    if wmeta is not None:
+        _is(wmeta, torch.float32)
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
+                                     index_offset, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
+                                     _stream(x)), "qsdp_fused_step")

@@ -1,0 +1,60 @@
+"""Build ``libqsdp.so`` (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+
+``python -m paper_2302_02390_amd.build`` compiles every translation unit (in parallel) and
+links ``paper_2302_02390_amd/libqsdp.so``. Flags: strict binary32 (no contraction, no
+fast-math), packed-fp32 instruction selection switched off.
+"""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libqsdp.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+         "-fno-fast-math", "-Wall", "-Wno-unused-result",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+# bucket size -> (lanes per bucket, 8-element chunks per lane)
+WAVE_SHAPES = {128: (8, 2), 256: (16, 2), 512: (32, 2), 1024: (64, 2), 2048: (64, 4), 4096: (64, 8)}
+
+
+def _units():
+    units = [("qsdp_api.o", "qsdp_api.hip", [])]
+    for b, (g, p) in WAVE_SHAPES.items():
+        units.append((f"qsdp_wave_{b}.o", "qsdp_wave_inst.hip",
+                      [f"-DQSDP_G={g}", f"-DQSDP_P={p}", f"-DQSDP_B={b}"]))
+    return units
+
+
+def _compile(unit):
+    obj, src, defs = unit
+    out = os.path.join(OBJ, obj)
+    cmd = [HIPCC] + FLAGS + defs + ["-c", os.path.join(CSRC, src), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
+    return out
+
+
+def build(jobs=None, verbose=False):
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(_compile, _units()))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True)
+    sys.exit(0)

@@ -1,0 +1,218 @@
+// C ABI of the QSDP codec library: argument validation, launch planning, and the kernels
+// that are not specialised per bucket shape (block kernel, decoder).
+#include "../../include/qsdp.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "qsdp_launch.hpp"
+
+namespace qsdp {
+
+hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s) {
+    switch (mode) {
+        case MODE_GRAD: hipLaunchKernelGGL(block_kernel<MODE_GRAD>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_WEIGHT: hipLaunchKernelGGL(block_kernel<MODE_WEIGHT>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+namespace {
+template <int BITS>
+hipError_t dequant_go(bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
+    if (bf16) hipLaunchKernelGGL((dequant_kernel<BITS, true>), dim3(grid), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((dequant_kernel<BITS, false>), dim3(grid), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
+    switch (bits) {
+        case 1: return dequant_go<1>(bf16, p, grid, s);
+        case 2: return dequant_go<2>(bf16, p, grid, s);
+        case 3: return dequant_go<3>(bf16, p, grid, s);
+        case 4: return dequant_go<4>(bf16, p, grid, s);
+        case 5: return dequant_go<5>(bf16, p, grid, s);
+        case 6: return dequant_go<6>(bf16, p, grid, s);
+        case 7: return dequant_go<7>(bf16, p, grid, s);
+        case 8: return dequant_go<8>(bf16, p, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+
+constexpr unsigned kMaxGrid = 1u << 20;
+
+bool shape_ok(uint64_t n, int bits, int bucket) {
+    return n >= 1 && bits >= 1 && bits <= 8 && bucket >= 32 && bucket <= kMaxBucket && bucket % 32 == 0;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// 1/delta is exact iff delta is a normal power of two whose reciprocal is normal too.
+bool reciprocal_exact(float delta) {
+    uint32_t b;
+    std::memcpy(&b, &delta, sizeof b);
+    const uint32_t expo = (b >> 23) & 0xFFu;
+    return (b & 0x7FFFFFu) == 0 && expo >= 2 && expo <= 252;
+}
+
+typedef hipError_t (*WaveLauncher)(int, int, const Params&, unsigned, hipStream_t);
+
+WaveLauncher wave_launcher(int bucket, int* buckets_per_wave) {
+    switch (bucket) {
+        case 128: *buckets_per_wave = 8; return launch_wave_128;
+        case 256: *buckets_per_wave = 4; return launch_wave_256;
+        case 512: *buckets_per_wave = 2; return launch_wave_512;
+        case 1024: *buckets_per_wave = 1; return launch_wave_1024;
+        case 2048: *buckets_per_wave = 1; return launch_wave_2048;
+        case 4096: *buckets_per_wave = 1; return launch_wave_4096;
+        default: return nullptr;
+    }
+}
+
+// Full buckets go to the wave kernel of the bucket's shape when there is one for
+// (bucket, stored code width); everything else, and a short last bucket, to the block kernel.
+int run(int mode, Params p, int stored_bits, hipStream_t s) {
+    const uint64_t B = (uint64_t)p.bucket;
+    const uint64_t nb = ceil_div(p.n, B);
+    const uint64_t nb_full = p.n / B;
+    int bpw = 1;
+    WaveLauncher wl = wave_launcher(p.bucket, &bpw);
+    uint64_t done = 0;
+    if (wl != nullptr && wave_bits_supported(stored_bits) && nb_full > 0) {
+        p.first_bucket = 0;
+        p.num_buckets = nb_full;
+        const uint64_t groups = ceil_div(nb_full, (uint64_t)bpw);
+        const uint64_t blocks = ceil_div(groups, 4);
+        const unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+        if (wl(mode, stored_bits, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
+        done = nb_full;
+    }
+    if (done < nb) {
+        p.first_bucket = done;
+        p.num_buckets = nb - done;
+        const unsigned grid = (unsigned)(p.num_buckets < kMaxGrid ? p.num_buckets : kMaxGrid);
+        if (launch_block(mode, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
+    }
+    return QSDP_OK;
+}
+
+void set_common(Params& p, uint64_t n, int bucket, uint64_t seed, uint64_t index_offset, float delta) {
+    p.n = n;
+    p.bucket = bucket;
+    p.block0 = index_offset >> 3;
+    p.key0 = (uint32_t)seed;
+    p.key1 = (uint32_t)(seed >> 32);
+    p.delta = delta;
+    p.delta_pow2 = (delta > 0.0f && reciprocal_exact(delta)) ? 1 : 0;
+    p.inv_delta = p.delta_pow2 ? 1.0f / delta : 0.0f;
+}
+
+}  // namespace
+}  // namespace qsdp
+
+using namespace qsdp;
+
+extern "C" {
+
+uint32_t qsdp_spec_version(void) { return 2u; }
+
+size_t qsdp_codes_bytes(uint64_t n, int bits, int bucket) {
+    if (!shape_ok(n, bits, bucket)) return 0;
+    return (size_t)(ceil_div(n, (uint64_t)bucket) * (uint64_t)bucket * (uint64_t)bits / 8u);
+}
+
+size_t qsdp_meta_bytes(uint64_t n, int bucket) {
+    if (!shape_ok(n, 8, bucket)) return 0;
+    return (size_t)(ceil_div(n, (uint64_t)bucket) * 2u * sizeof(float));
+}
+
+const char* qsdp_status_string(int status) {
+    switch (status) {
+        case QSDP_OK: return "ok";
+        case QSDP_EINVAL: return "invalid argument";
+        case QSDP_EALIGN: return "pointer not 16-byte aligned";
+        case QSDP_ELAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int qsdp_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                       uint64_t index_offset, uint32_t* codes, float* meta, void* stream) {
+    if (!g || !codes || !meta || !shape_ok(n, bits, bucket) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(g) || !aligned16(codes) || !aligned16(meta)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, index_offset, 0.0f);
+    p.g = g;
+    p.codes = codes;
+    p.meta = meta;
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_GRAD, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float delta,
+                         uint64_t seed, uint32_t* codes, float* meta, uint64_t* n_saturated,
+                         void* stream) {
+    if (!x || !codes || !meta || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(meta)) return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, 0, delta);
+    p.xin = x;
+    p.codes = codes;
+    p.meta = meta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_WEIGHT, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
+                    qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!codes || !meta || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
+    DequantParams p = {};
+    p.codes = codes;
+    p.meta = meta;
+    p.out = out;
+    p.n = n;
+    p.nchunks = ceil_div(n, 8);
+    p.bucket = bucket;
+    const uint64_t blocks = ceil_div(p.nchunks, 256);
+    const unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+    if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                    float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes, float* wmeta,
+                    uint64_t* n_saturated, void* stream) {
+    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket)) return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
+    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta)) return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, index_offset, delta);
+    p.x = x;
+    p.g = g;
+    p.codes = wcodes;
+    p.meta = wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = gbits;
+    p.wbits = wbits;
+    p.lr = lr;
+    return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

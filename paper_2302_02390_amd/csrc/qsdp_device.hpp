@@ -1,0 +1,225 @@
+// Device-side building blocks of the QSDP codec for gfx950 (wave64).
+//
+// Arithmetic contract (binary32, round to nearest even, no contraction; this file is
+// compiled with -ffp-contract=off, fused multiply-adds are written as fmaf):
+//   bucket grid   lo = min + 0.0f, hi = max + 0.0f, range = hi - lo,
+//                 scale = range / L, inv = L / range (0, 0 for a degenerate bucket)
+//   Q^g           t = clamp((g - lo) * inv, 0, L); code = floor(t) + [u < t - floor(t)]
+//   Q^w (min-max) k = clamp(rint((x - lo) * inv - xi), 0, L); base = fma(xi, scale, lo)
+//   Q^w (lattice) k = rint(x / delta - xi); code = min(k - k0, L); base = (k0 + xi) * delta
+//   decode        fma(code, scale, base)
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qsdp {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11). The key is wave-uniform, so its schedule lives in
+// scalar registers; each round costs two 32x32->64 multiplies and three xors per lane.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The eight rounding uniforms of gradient block `block` (elements 8*block .. 8*block+7),
+// as the 16-bit integers h (u = h * 2^-16), converted to float (exact).
+__device__ __forceinline__ void grad_uniforms_x65536(uint64_t block, uint32_t k0, uint32_t k1,
+                                                     float (&h)[8]) {
+    uint32_t w[4];
+    philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        h[2 * j] = (float)(w[j] & 0xFFFFu);
+        h[2 * j + 1] = (float)(w[j] >> 16);
+    }
+}
+
+// The weight shift xi in [-1/2, 1/2): stream 1, counter 0.
+__device__ __forceinline__ float weight_shift(uint32_t k0, uint32_t k1) {
+    uint32_t w[4];
+    philox4x32_10(0u, 0u, 1u, 0u, k0, k1, w);
+    return (float)(w[0] >> 8) * 0x1p-24f - 0.5f;
+}
+
+// ---------------------------------------------------------------------------------------
+// Cross-lane min/max over aligned groups of G lanes (G a power of two, 2..64), all lanes of
+// the group end with the result. DPP inside a 16-lane row, gfx950 row/half swaps across rows.
+// ---------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ void swap16(float v, float& a, float& b) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ void swap32(float v, float& a, float& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
+template <int G>
+__device__ __forceinline__ float group_min(float v) {
+    if (G >= 2) v = fminf(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    if (G >= 4) v = fminf(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    if (G >= 8) v = fminf(v, dpp_move<0x141>(v));  // row_half_mirror
+    if (G >= 16) v = fminf(v, dpp_move<0x140>(v)); // row_mirror
+    if (G >= 32) { float a, b; swap16(v, a, b); v = fminf(a, b); }
+    if (G >= 64) { float a, b; swap32(v, a, b); v = fminf(a, b); }
+    return v;
+}
+
+template <int G>
+__device__ __forceinline__ float group_max(float v) {
+    if (G >= 2) v = fmaxf(v, dpp_move<0xB1>(v));
+    if (G >= 4) v = fmaxf(v, dpp_move<0x4E>(v));
+    if (G >= 8) v = fmaxf(v, dpp_move<0x141>(v));
+    if (G >= 16) v = fmaxf(v, dpp_move<0x140>(v));
+    if (G >= 32) { float a, b; swap16(v, a, b); v = fmaxf(a, b); }
+    if (G >= 64) { float a, b; swap32(v, a, b); v = fmaxf(a, b); }
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// Per-bucket grids
+// ---------------------------------------------------------------------------------------
+struct MinMaxGrid {
+    float lo, scale, inv;
+};
+
+__device__ __forceinline__ MinMaxGrid make_minmax_grid(float lo, float hi, float Lf) {
+    lo = lo + 0.0f;  // -0 -> +0: one bit pattern for the stored base
+    hi = hi + 0.0f;
+    const float range = hi - lo;
+    const float inv = Lf / range;
+    const float scale = range / Lf;
+    const bool ok = (range > 0.0f) && (range < __builtin_inff()) && (inv < __builtin_inff());
+    MinMaxGrid g;
+    g.lo = lo;
+    g.scale = ok ? scale : 0.0f;
+    g.inv = ok ? inv : 0.0f;
+    return g;
+}
+
+// x / delta, as a multiplication when 1/delta is exact (delta a power of two): the product
+// and the quotient are then roundings of the same real number.
+struct Divider {
+    float delta, inv_delta;
+    bool pow2;
+};
+
+__device__ __forceinline__ float div_delta(float v, const Divider& d) {
+    return d.pow2 ? v * d.inv_delta : v / d.delta;
+}
+
+// Coin-flip code of one gradient element, as a float in [0, L].
+__device__ __forceinline__ float grad_code(float g, const MinMaxGrid& grid, float Lf, float h) {
+    float t = (g - grid.lo) * grid.inv;
+    t = fminf(fmaxf(t, 0.0f), Lf);
+    const float f = floorf(t);
+    const float frac = t - f;
+    const float u = h * 0x1p-16f;
+    return f + ((u < frac) ? 1.0f : 0.0f);
+}
+
+__device__ __forceinline__ float weight_code_minmax(float x, const MinMaxGrid& grid, float Lf,
+                                                    float xi) {
+    const float t = (x - grid.lo) * grid.inv;
+    const float k = rintf(t - xi);
+    return fminf(fmaxf(k, 0.0f), Lf);
+}
+
+__device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, float xi, float k0,
+                                                     float Lf, uint32_t& saturated) {
+    const float k = rintf(div_delta(x, d) - xi);
+    float c = k - k0;
+    if (c > Lf) {
+        c = Lf;
+        saturated += 1u;
+    }
+    return c;
+}
+
+// ---------------------------------------------------------------------------------------
+// Packing of 8 consecutive codes (one lane's chunk) into BITS bytes
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ uint64_t pack8(const float (&c)[8]) {
+    uint64_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc |= (uint64_t)(uint32_t)c[i] << (i * BITS);
+    return acc;
+}
+
+// Store the BITS bytes of a packed chunk at byte address p (p is a multiple of BITS bytes
+// from a 16-byte aligned base, so the widest naturally aligned pieces are used).
+template <int BITS>
+__device__ __forceinline__ void store_chunk(uint8_t* p, uint64_t v) {
+    if (BITS == 8) {
+        u2 w = {(uint32_t)v, (uint32_t)(v >> 32)};
+        *reinterpret_cast<u2*>(p) = w;
+    } else if (BITS == 4) {
+        *reinterpret_cast<uint32_t*>(p) = (uint32_t)v;
+    } else if (BITS == 2) {
+        *reinterpret_cast<uint16_t*>(p) = (uint16_t)v;
+    } else if (BITS == 6) {
+        uint16_t* q = reinterpret_cast<uint16_t*>(p);
+        q[0] = (uint16_t)v; q[1] = (uint16_t)(v >> 16); q[2] = (uint16_t)(v >> 32);
+    } else {
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) p[i] = (uint8_t)(v >> (8 * i));
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ uint64_t load_chunk(const uint8_t* p) {
+    if (BITS == 8) {
+        u2 w = *reinterpret_cast<const u2*>(p);
+        return (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    } else if (BITS == 4) {
+        return *reinterpret_cast<const uint32_t*>(p);
+    } else if (BITS == 2) {
+        return *reinterpret_cast<const uint16_t*>(p);
+    } else if (BITS == 6) {
+        const uint16_t* q = reinterpret_cast<const uint16_t*>(p);
+        return (uint64_t)q[0] | ((uint64_t)q[1] << 16) | ((uint64_t)q[2] << 32);
+    } else {
+        uint64_t v = 0;
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) v |= (uint64_t)p[i] << (8 * i);
+        return v;
+    }
+}
+
+// binary32 -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+    uint32_t b = __float_as_uint(v);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return b >> 16;
+}
+
+}  // namespace qsdp

@@ -1,0 +1,31 @@
+// Host-side launch interface between the C ABI (qsdp_api.hip) and the kernel translation
+// units. Wave kernels are instantiated per bucket shape in qsdp_wave_inst.hip, compiled
+// once per (G, P) pair.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "qsdp_kernels.hpp"
+
+namespace qsdp {
+
+// Code widths the wave kernels are instantiated for (0 = fused step without code output).
+inline bool wave_bits_supported(int bits) {
+    return bits == 0 || bits == 2 || bits == 3 || bits == 4 || bits == 6 || bits == 8;
+}
+
+// One launcher per instantiated bucket size. `bits` is the width of the codes stored.
+#define QSDP_DECLARE_WAVE(B) \
+    hipError_t launch_wave_##B(int mode, int bits, const Params& p, unsigned grid, hipStream_t s);
+QSDP_DECLARE_WAVE(128)
+QSDP_DECLARE_WAVE(256)
+QSDP_DECLARE_WAVE(512)
+QSDP_DECLARE_WAVE(1024)
+QSDP_DECLARE_WAVE(2048)
+QSDP_DECLARE_WAVE(4096)
+#undef QSDP_DECLARE_WAVE
+
+hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s);
+hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, unsigned grid, hipStream_t s);
+
+}  // namespace qsdp

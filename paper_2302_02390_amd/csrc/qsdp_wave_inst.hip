@@ -1,0 +1,48 @@
+// Instantiations of the wave kernels for one bucket shape; compiled with
+// -DQSDP_G=<lanes per bucket> -DQSDP_P=<8-element chunks per lane> -DQSDP_B=<8*G*P>.
+#include "qsdp_launch.hpp"
+
+#if !defined(QSDP_G) || !defined(QSDP_P) || !defined(QSDP_B)
+#error "define QSDP_G, QSDP_P and QSDP_B"
+#endif
+static_assert(QSDP_B == 8 * QSDP_G * QSDP_P, "bucket = 8 * G * P");
+
+#define QSDP_CAT2(a, b) a##b
+#define QSDP_CAT(a, b) QSDP_CAT2(a, b)
+
+namespace qsdp {
+namespace {
+
+template <int MODE, int BITS>
+hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_P, BITS>), dim3(grid), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
+    switch (bits) {
+        case 2: return go<MODE, 2>(p, grid, s);
+        case 3: return go<MODE, 3>(p, grid, s);
+        case 4: return go<MODE, 4>(p, grid, s);
+        case 6: return go<MODE, 6>(p, grid, s);
+        case 8: return go<MODE, 8>(p, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, unsigned grid,
+                                          hipStream_t s) {
+    switch (mode) {
+        case MODE_GRAD: return by_bits<MODE_GRAD>(bits, p, grid, s);
+        case MODE_WEIGHT: return by_bits<MODE_WEIGHT>(bits, p, grid, s);
+        case MODE_FUSED:
+            if (bits == 0) return go<MODE_FUSED, 0>(p, grid, s);
+            return by_bits<MODE_FUSED>(bits, p, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace qsdp

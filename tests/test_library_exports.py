@@ -1,0 +1,58 @@
+"""Host-only checks of the C ABI library: it loads without a GPU, exports every symbol the
+header declares, and its size helpers and argument checks behave (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import ref
+from paper_2302_02390_amd import binding as qb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qsdp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qsdp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert set(names) == set(qb.EXPORTS)
+    lib = ctypes.CDLL(qb.LIB_PATH)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_size_helpers_match_the_wire_format_and_the_oracle():
+    for n, bits, bucket in [(1, 8, 1024), (1024, 8, 1024), (1025, 4, 1024), (10**6, 3, 128),
+                            (1315723264, 4, 1024), (125226240, 8, 1024), (77, 1, 32)]:
+        nb = -(-n // bucket)
+        assert qb.codes_bytes(n, bits, bucket) == nb * bucket * bits // 8 == ref.codes_bytes(n, bits, bucket)
+        assert qb.meta_bytes(n, bucket) == nb * 8 == ref.meta_bytes(n, bucket)
+    assert qb.codes_bytes(0, 8, 1024) == 0 and qb.codes_bytes(10, 9, 1024) == 0
+    assert qb.codes_bytes(10, 8, 100) == 0 and qb.meta_bytes(10, 8200) == 0
+    assert qb.spec_version() == 2
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = qb.lib()
+    ok = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4100)
+    assert L.qsdp_quantize_grad(None, 10, 8, 1024, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad(ok, 0, 8, 1024, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad(ok, 10, 0, 1024, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad(ok, 10, 8, 100, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad(ok, 10, 8, 1024, 0, 12, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad(odd, 10, 8, 1024, 0, 0, ok, ok, None) == qb.QSDP_EALIGN
+    assert L.qsdp_quantize_weight(ok, 10, 8, 1024, -1.0, 0, ok, ok, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_weight(ok, 10, 8, 1024, float("nan"), 0, ok, ok, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_weight(ok, 10, 8, 1024, 0.0, 0, odd, ok, None, None) == qb.QSDP_EALIGN
+    assert L.qsdp_dequantize(ok, ok, 10, 8, 1024, 2, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_dequantize(ok, ok, 10, 8, 1024, 1, odd, None) == qb.QSDP_EALIGN
+    assert L.qsdp_fused_step(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ok, None, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_fused_step(ok, ok, 10, float("inf"), 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_fused_step(ok, odd, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EALIGN
+    assert qb.status_string(qb.QSDP_EALIGN).startswith("pointer")
