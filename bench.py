@@ -41,7 +41,10 @@ def parse():
     ap.add_argument("--emit-codes", action="store_true", help="also write packed Q^w codes + meta")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip timing the other entry points")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--cpu-sample", type=int, default=1 << 29)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain device copy of the weight vector a few times (a kernel of "
+                         "known traffic, to scale rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -148,6 +151,14 @@ def main():
             "kernel_ms_median": round(ev_median, 4),
         },
     }
+
+    if a.calibration_copy:
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = {"read": 4 * n, "write": 4 * n}
+        del y
 
     if not a.no_extras:
         out["other_entry_points"] = extras(torch, qb, x, g, n, wbits, gbits, bucket, dev)

@@ -17,17 +17,17 @@ LIB = os.path.join(HERE, "libqsdp.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-fast-math", "-Wall", "-Wno-unused-result",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("QSDP_EXTRA_FLAGS", "").split()
 
-# bucket size -> (lanes per bucket, 8-element chunks per lane)
-WAVE_SHAPES = {128: (8, 2), 256: (16, 2), 512: (32, 2), 1024: (64, 2), 2048: (64, 4), 4096: (64, 8)}
+# bucket size -> (lanes per bucket G, rows R): bucket = 4 * G * R
+WAVE_SHAPES = {128: (8, 4), 256: (16, 4), 512: (32, 4), 1024: (64, 4), 2048: (64, 8), 4096: (64, 16)}
 
 
 def _units():
     units = [("qsdp_api.o", "qsdp_api.hip", [])]
-    for b, (g, p) in WAVE_SHAPES.items():
+    for b, (g, r) in WAVE_SHAPES.items():
         units.append((f"qsdp_wave_{b}.o", "qsdp_wave_inst.hip",
-                      [f"-DQSDP_G={g}", f"-DQSDP_P={p}", f"-DQSDP_B={b}"]))
+                      [f"-DQSDP_G={g}", f"-DQSDP_R={r}", f"-DQSDP_B={b}"]))
     return units
 
 

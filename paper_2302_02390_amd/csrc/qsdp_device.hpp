@@ -40,17 +40,28 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// The eight rounding uniforms of gradient block `block` (elements 8*block .. 8*block+7),
-// as the 16-bit integers h (u = h * 2^-16), converted to float (exact).
-__device__ __forceinline__ void grad_uniforms_x65536(uint64_t block, uint32_t k0, uint32_t k1,
-                                                     float (&h)[8]) {
+// Rounding uniforms of a row pair, as the 16-bit integers h (u = h * 2^-16) converted to float
+// (exact). Lane l holds elements (r*G + l)*4 .. +3 of rows r = 2c and 2c+1. A Philox block (8
+// elements) spans the lane pair (l even, l+1) of one row: the even lane computes the block of
+// row 2c, the odd lane that of row 2c+1, and the pair swaps the halves the other needs.
+// h[0..3] serve row 2c, h[4..7] row 2c+1. bucket_block = index of the bucket's first block.
+template <int G>
+__device__ __forceinline__ void grad_uniforms_rows(uint64_t bucket_block, int c, int l, uint32_t k0,
+                                                   uint32_t k1, float (&h)[8]) {
+    const int odd = l & 1;
+    const uint64_t block = bucket_block + (uint64_t)(((2 * c + odd) * G + (l - odd)) >> 1);
     uint32_t w[4];
     philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        h[2 * j] = (float)(w[j] & 0xFFFFu);
-        h[2 * j + 1] = (float)(w[j] >> 16);
-    }
+    const uint32_t send0 = odd ? w[0] : w[2];
+    const uint32_t send1 = odd ? w[1] : w[3];
+    const uint32_t recv0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send0, 0xB1, 0xF, 0xF, false);
+    const uint32_t recv1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send1, 0xB1, 0xF, 0xF, false);
+    const uint32_t a0 = odd ? recv0 : w[0], a1 = odd ? recv1 : w[1];  // row 2c
+    const uint32_t b0 = odd ? w[2] : recv0, b1 = odd ? w[3] : recv1;  // row 2c+1
+    h[0] = (float)(a0 & 0xFFFFu); h[1] = (float)(a0 >> 16);
+    h[2] = (float)(a1 & 0xFFFFu); h[3] = (float)(a1 >> 16);
+    h[4] = (float)(b0 & 0xFFFFu); h[5] = (float)(b0 >> 16);
+    h[6] = (float)(b1 & 0xFFFFu); h[7] = (float)(b1 >> 16);
 }
 
 // The weight shift xi in [-1/2, 1/2): stream 1, counter 0.
@@ -165,13 +176,13 @@ __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Packing of 8 consecutive codes (one lane's chunk) into BITS bytes
+// Packing: 4 consecutive codes of a lane, 8 consecutive codes (a chunk) = BITS bytes
 // ---------------------------------------------------------------------------------------
 template <int BITS>
-__device__ __forceinline__ uint64_t pack8(const float (&c)[8]) {
-    uint64_t acc = 0;
+__device__ __forceinline__ uint32_t pack4(const float (&c)[4]) {
+    uint32_t acc = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc |= (uint64_t)(uint32_t)c[i] << (i * BITS);
+    for (int i = 0; i < 4; ++i) acc |= (uint32_t)c[i] << (i * BITS);
     return acc;
 }
 

@@ -2,11 +2,14 @@
 //
 // Two families share the element arithmetic of qsdp_device.hpp:
 //   * wave kernels: a bucket is owned by an aligned group of G lanes of one wave and never
-//     leaves registers: one pass over HBM, no LDS, no barrier. Lane l of the group holds P
-//     chunks of 8 consecutive elements: chunk c covers elements (c*G + l)*8 .. +7 of the
-//     bucket (two 16-byte loads), which is exactly one Philox block and BITS bytes of codes.
-//     Bucket size B = 8*G*P. A wave handles 64/G buckets at a time, waves stride over the
-//     full buckets of the vector.
+//     leaves registers: one pass over HBM, no LDS, no barrier. The bucket is cut into R rows
+//     of 4*G elements; lane l of the group holds elements (r*G + l)*4 .. +3 of every row r, so
+//     each load/store instruction of a wave touches whole contiguous 16*G-byte segments.
+//     Bucket size B = 4*G*R, R even. A Philox block (8 elements) and a packed code chunk
+//     (8 codes = BITS bytes) span the lane pair (l even, l+1) of one row: for each row pair
+//     (2c, 2c+1) the even lane owns the block/chunk of row 2c and the odd lane that of row
+//     2c+1, and the pair swaps halves with one DPP quad permute. A wave handles 64/G buckets
+//     at a time; waves stride over the full buckets of the vector.
 //   * block kernel: one 256-thread workgroup per bucket, staged in LDS; any bucket size, any
 //     bits, short last bucket. Used for the shapes the wave kernels do not cover.
 #pragma once
@@ -41,59 +44,70 @@ struct Params {
 // ---------------------------------------------------------------------------------------
 // Wave kernels
 // ---------------------------------------------------------------------------------------
-template <int G, int P>
-struct Tile {
-    static constexpr int kBucket = 8 * G * P;
-    static constexpr int kBucketsPerWave = 64 / G;
-    float v[P][8];
-};
-
-template <int G, int P>
-__device__ __forceinline__ void load_tile(const float* base, int l, float (&v)[P][8]) {
+template <int G, int R>
+__device__ __forceinline__ void load_rows(const float* base, int l, float (&v)[R][4]) {
+    const f4* p = reinterpret_cast<const f4*>(base) + l;
 #pragma unroll
-    for (int c = 0; c < P; ++c) {
-        const f4* p = reinterpret_cast<const f4*>(base + (size_t)(c * G + l) * 8);
-        const f4 a = __builtin_nontemporal_load(p);
-        const f4 b = __builtin_nontemporal_load(p + 1);
-        v[c][0] = a[0]; v[c][1] = a[1]; v[c][2] = a[2]; v[c][3] = a[3];
-        v[c][4] = b[0]; v[c][5] = b[1]; v[c][6] = b[2]; v[c][7] = b[3];
+    for (int r = 0; r < R; ++r) {
+        const f4 a = __builtin_nontemporal_load(p + r * G);
+        v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
     }
 }
 
-template <int G, int P>
-__device__ __forceinline__ void store_tile(float* base, int l, const float (&v)[P][8]) {
+template <int G, int R>
+__device__ __forceinline__ void store_rows(float* base, int l, const float (&v)[R][4]) {
+    f4* p = reinterpret_cast<f4*>(base) + l;
 #pragma unroll
-    for (int c = 0; c < P; ++c) {
-        f4* p = reinterpret_cast<f4*>(base + (size_t)(c * G + l) * 8);
-        const f4 a = {v[c][0], v[c][1], v[c][2], v[c][3]};
-        const f4 b = {v[c][4], v[c][5], v[c][6], v[c][7]};
-        __builtin_nontemporal_store(a, p);
-        __builtin_nontemporal_store(b, p + 1);
+    for (int r = 0; r < R; ++r) {
+        const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
+        __builtin_nontemporal_store(a, p + r * G);
     }
 }
 
-template <int G, int P>
-__device__ __forceinline__ void tile_minmax(const float (&v)[P][8], float& lo, float& hi) {
+template <int G, int R>
+__device__ __forceinline__ void rows_minmax(const float (&v)[R][4], float& lo, float& hi) {
     lo = v[0][0];
     hi = v[0][0];
 #pragma unroll
-    for (int c = 0; c < P; ++c)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            lo = fminf(lo, v[c][i]);
-            hi = fmaxf(hi, v[c][i]);
+        for (int i = 0; i < 4; ++i) {
+            lo = fminf(lo, v[r][i]);
+            hi = fmaxf(hi, v[r][i]);
         }
     lo = group_min<G>(lo);
     hi = group_max<G>(hi);
 }
 
+// Pack and store the codes of all rows. c[r][i] are the codes (as floats) of this lane's
+// elements; `cb` points at the bucket's first code byte.
+template <int G, int R, int BITS>
+__device__ __forceinline__ void store_codes(uint8_t* cb, int l, const float (&c)[R][4]) {
+    const int odd = l & 1;
+#pragma unroll
+    for (int cp = 0; cp < R / 2; ++cp) {
+        const uint32_t q0 = pack4<BITS>(c[2 * cp]);      // this lane's 4 codes of row 2cp
+        const uint32_t q1 = pack4<BITS>(c[2 * cp + 1]);  // ... of row 2cp+1
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(odd ? q0 : q1), 0xB1, 0xF,
+                                                                    0xF, false);
+        // even lane: chunk of row 2cp = own q0 (low half) | partner's q0; odd lane: chunk of
+        // row 2cp+1 = partner's q1 (low half) | own q1
+        const uint64_t chunk = odd ? ((uint64_t)recv | ((uint64_t)q1 << (4 * BITS)))
+                                   : ((uint64_t)q0 | ((uint64_t)recv << (4 * BITS)));
+        const int chunk_index = ((2 * cp + odd) * G + (l - odd)) >> 1;
+        store_chunk<BITS>(cb + (size_t)chunk_index * BITS, chunk);
+    }
+}
+
 // MODE_GRAD / MODE_WEIGHT / MODE_FUSED over full buckets. BITS is the width of the codes
 // that are stored (0: FUSED without code output). delta > 0 selects the explicit grid (a
 // wave-uniform branch).
-template <int MODE, int G, int P, int BITS>
+template <int MODE, int G, int R, int BITS>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
-    constexpr int B = 8 * G * P;
+    static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
+    constexpr int B = 4 * G * R;
     constexpr int BPW = 64 / G;
+    constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
     const int lane = threadIdx.x & 63;
     const int sub = lane / G;
     const int l = lane % G;
@@ -117,37 +131,35 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         const uint64_t bucket = p.first_bucket + (active ? rel : 0);
         const uint64_t e0 = bucket * (uint64_t)B;    // first element of the bucket
 
-        float w[P][8];  // the values that get weight-quantized (x, or y = x - lr*ghat)
+        float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
 
         if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
-            float gv[P][8];
-            load_tile<G, P>(p.g + e0, l, gv);
-            if (MODE == MODE_FUSED) load_tile<G, P>(p.x + e0, l, w);
+            float gv[R][4];
+            load_rows<G, R>(p.g + e0, l, gv);
+            if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, w);
             float lo, hi;
-            tile_minmax<G, P>(gv, lo, hi);
+            rows_minmax<G, R>(gv, lo, hi);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg);
 #pragma unroll
-            for (int c = 0; c < P; ++c) {
+            for (int cp = 0; cp < R / 2; ++cp) {
                 float h[8];
-                grad_uniforms_x65536(p.block0 + (e0 >> 3) + (uint64_t)(c * G + l), p.key0, p.key1, h);
+                grad_uniforms_rows<G>(p.block0 + (e0 >> 3), cp, l, p.key0, p.key1, h);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float code = grad_code(gv[c][i], grid, Lg, h[i]);
+                    const int r = 2 * cp + (i >> 2);
+                    const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
                     if (MODE == MODE_GRAD) {
-                        gv[c][i] = code;
+                        gv[r][i & 3] = code;
                     } else {
                         const float ghat = fmaf(code, grid.scale, grid.lo);
-                        w[c][i] = fmaf(-p.lr, ghat, w[c][i]);
+                        w[r][i & 3] = fmaf(-p.lr, ghat, w[r][i & 3]);
                     }
                 }
             }
             if (MODE == MODE_GRAD) {
                 if (active) {
-                    uint8_t* cb = reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * BITS;
-#pragma unroll
-                    for (int c = 0; c < P; ++c)
-                        store_chunk<BITS>(cb + (size_t)(c * G + l) * BITS, pack8<BITS>(gv[c]));
+                    store_codes<G, R, SB>(reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * SB, l, gv);
                     if (l == 0) {
                         p.meta[2 * bucket] = grid.lo;
                         p.meta[2 * bucket + 1] = grid.scale;
@@ -156,45 +168,41 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                 continue;
             }
         } else {
-            load_tile<G, P>(p.xin + e0, l, w);
+            load_rows<G, R>(p.xin + e0, l, w);
         }
 
         // weight quantization of w
         if (lattice) {
             float lo = w[0][0];
 #pragma unroll
-            for (int c = 0; c < P; ++c)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) lo = fminf(lo, w[c][i]);
+                for (int i = 0; i < 4; ++i) lo = fminf(lo, w[r][i]);
             lo = group_min<G>(lo) + 0.0f;
             const float k0 = rintf(div_delta(lo, div) - xi);
             base = (k0 + xi) * p.delta;
             scale = p.delta;
             uint32_t sat_here = 0;
 #pragma unroll
-            for (int c = 0; c < P; ++c)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) w[c][i] = weight_code_lattice(w[c][i], div, xi, k0, Lw, sat_here);
+                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_here);
             if (active) saturated += sat_here;
         } else {
             float lo, hi;
-            tile_minmax<G, P>(w, lo, hi);
+            rows_minmax<G, R>(w, lo, hi);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw);
             base = fmaf(xi, grid.scale, grid.lo);
             scale = grid.scale;
 #pragma unroll
-            for (int c = 0; c < P; ++c)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) w[c][i] = weight_code_minmax(w[c][i], grid, Lw, xi);
+                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
         }
 
         if (active) {
             if (BITS != 0) {
-                uint8_t* cb = reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * BITS;
-#pragma unroll
-                for (int c = 0; c < P; ++c)
-                    store_chunk<(BITS ? BITS : 8)>(cb + (size_t)(c * G + l) * BITS,
-                                                   pack8<(BITS ? BITS : 8)>(w[c]));
+                store_codes<G, R, SB>(reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * SB, l, w);
                 if (l == 0) {
                     p.meta[2 * bucket] = base;
                     p.meta[2 * bucket + 1] = scale;
@@ -202,10 +210,10 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             }
             if (MODE == MODE_FUSED) {
 #pragma unroll
-                for (int c = 0; c < P; ++c)
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) w[c][i] = fmaf(w[c][i], scale, base);
-                store_tile<G, P>(p.x + e0, l, w);
+                    for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], scale, base);
+                store_rows<G, R>(p.x + e0, l, w);
             }
         }
     }

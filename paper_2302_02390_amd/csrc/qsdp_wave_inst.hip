@@ -1,11 +1,11 @@
 // Instantiations of the wave kernels for one bucket shape; compiled with
-// -DQSDP_G=<lanes per bucket> -DQSDP_P=<8-element chunks per lane> -DQSDP_B=<8*G*P>.
+// -DQSDP_G=<lanes per bucket> -DQSDP_R=<rows of 4*G elements> -DQSDP_B=<4*G*R>.
 #include "qsdp_launch.hpp"
 
-#if !defined(QSDP_G) || !defined(QSDP_P) || !defined(QSDP_B)
-#error "define QSDP_G, QSDP_P and QSDP_B"
+#if !defined(QSDP_G) || !defined(QSDP_R) || !defined(QSDP_B)
+#error "define QSDP_G, QSDP_R and QSDP_B"
 #endif
-static_assert(QSDP_B == 8 * QSDP_G * QSDP_P, "bucket = 8 * G * P");
+static_assert(QSDP_B == 4 * QSDP_G * QSDP_R, "bucket = 4 * G * R");
 
 #define QSDP_CAT2(a, b) a##b
 #define QSDP_CAT(a, b) QSDP_CAT2(a, b)
@@ -15,7 +15,7 @@ namespace {
 
 template <int MODE, int BITS>
 hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_P, BITS>), dim3(grid), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS>), dim3(grid), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
