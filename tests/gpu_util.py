@@ -93,3 +93,25 @@ def synth(n, seed, heavy=True):
     x = (rng.normal(size=n) * 0.02).astype(np.float32)
     g = ((rng.standard_t(3, size=n) if heavy else rng.normal(size=n)) * 1e-3).astype(np.float32)
     return x, g
+
+
+# ---------------------------------------------------------------------------------------
+# Full-size checks: the oracle recomputes a sample of buckets one by one. A bucket of a
+# long vector is a shard starting at a bucket boundary, so the oracle is called on the
+# bucket's slice with index_offset = its global offset (shard invariance is pinned in the
+# oracle's own tests).
+# ---------------------------------------------------------------------------------------
+def sample_bucket_ids(nb_full, k, seed):
+    """k distinct full-bucket indices including the first and the last."""
+    rng = np.random.default_rng(seed)
+    k = min(k, nb_full)
+    ids = set(rng.choice(nb_full, size=k, replace=False).tolist()) | {0, nb_full - 1}
+    return np.array(sorted(ids), dtype=np.int64)
+
+
+def gather_rows(t, ids, row_len):
+    """Rows `ids` of the [*, row_len] view of the first full rows of flat tensor t, on the host."""
+    nfull = t.numel() // row_len
+    view = t[: nfull * row_len].view(nfull, row_len)
+    idx = torch.from_numpy(ids).to(t.device)
+    return view.index_select(0, idx).cpu().numpy()

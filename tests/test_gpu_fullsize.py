@@ -1,0 +1,239 @@
+"""GPU parity at the benchmark's sizes and launch configuration: the GPT-shaped vectors of
+the five configurations, with the oracle recomputing a sample of buckets one by one (first,
+last, the short tail and a few hundred random ones)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2302_02390_amd import binding as qb
+from paper_2302_02390_amd import workloads as wl
+from gpu_util import DEV, bits_equal, gather_rows, sample_bucket_ids
+
+pytestmark = pytest.mark.gpu
+
+
+def u32(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def check_quantized_buckets(kind, src, codes, meta, bits, B, delta, seed, ids, n):
+    """Codes and meta of the sampled full buckets, and of the tail bucket, against the oracle."""
+    wpb = B * bits // 32
+    rows = gather_rows(src, ids, B)
+    crow = u32(gather_rows(codes, ids, wpb))
+    mrow = u32(gather_rows(meta.reshape(-1), ids, 2))
+    for r, j in enumerate(ids):
+        if kind == "grad":
+            wc, wm = ref.quantize_grad(rows[r], bits, B, seed, index_offset=int(j) * B)
+        else:
+            wc, wm, _ = ref.quantize_weight(rows[r], bits, B, delta, seed)
+        assert np.array_equal(crow[r], wc), (kind, bits, B, int(j))
+        assert np.array_equal(mrow[r], u32(wm).reshape(-1)), (kind, bits, B, int(j))
+    nb_full = n // B
+    if n % B:
+        tail = src[nb_full * B:].cpu().numpy()
+        if kind == "grad":
+            wc, wm = ref.quantize_grad(tail, bits, B, seed, index_offset=nb_full * B)
+        else:
+            wc, wm, _ = ref.quantize_weight(tail, bits, B, delta, seed)
+        assert np.array_equal(u32(codes[nb_full * wpb:].cpu().numpy()), wc)
+        assert np.array_equal(u32(meta.reshape(-1)[2 * nb_full:].cpu().numpy()), u32(wm).reshape(-1))
+
+
+def check_fused_buckets(x_before_rows, g_rows, x_after_rows, ids, B, lr, wbits, gbits, delta, seed):
+    for r, j in enumerate(ids):
+        want, _, _, _ = ref.fused_step(x_before_rows[r], g_rows[r], lr, wbits, gbits, B, delta, seed,
+                                       index_offset=int(j) * B)
+        got = x_after_rows[r]
+        assert np.all(np.abs(got.astype(np.float64) - want) <= 1e-6 * np.maximum(np.abs(want), 1e-30)), int(j)
+        assert bits_equal(got, want), int(j)
+
+
+@pytest.fixture(scope="module")
+def gpt1p3b():
+    n = wl.model_numel(wl.GPT_1P3B)
+    x = wl.weights(n, 1240, DEV)
+    g = wl.grads_student_t3(n, 1241, DEV)
+    torch.cuda.synchronize()
+    yield n, x, g
+    del x, g
+    torch.cuda.empty_cache()
+
+
+def test_config2_gpt125m_quantize_dequantize_bf16_fused():
+    """125M vector (short tail bucket of 256 elements), W8 G8, bucket 1024."""
+    n, B = wl.model_numel(wl.GPT_125M), 1024
+    assert n % B == 256
+    x = wl.weights(n, 1236, DEV)
+    g = wl.grads_student_t3(n, 1237, DEV)
+    ids = sample_bucket_ids(n // B, 400, 2)
+    gc, gm = qb.alloc_packed(n, 8, B, DEV)
+    qb.qsdp_quantize_grad(g, 8, B, 0, 0, gc, gm.reshape(-1))
+    check_quantized_buckets("grad", g, gc, gm, 8, B, 0.0, 0, ids, n)
+    wc, wm = qb.alloc_packed(n, 8, B, DEV)
+    qb.qsdp_quantize_weight(x, 8, B, 0.0, 0, wc, wm.reshape(-1))
+    check_quantized_buckets("weight", x, wc, wm, 8, B, 0.0, 0, ids, n)
+    # decode to bf16: the whole vector, compared with the oracle decode of the verified codes
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    qb.qsdp_dequantize(wc, wm.reshape(-1), n, 8, B, out)
+    ref.set_threads(8)
+    want = ref.dequantize(u32(wc.cpu().numpy()), wm.cpu().numpy(), n, 8, B, ref.BF16)
+    ref.set_threads(1)
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # fused step, including the tail bucket
+    xb = gather_rows(x, ids, B)
+    gb = gather_rows(g, ids, B)
+    tail_x = x[(n // B) * B:].cpu().numpy()
+    tail_g = g[(n // B) * B:].cpu().numpy()
+    qb.qsdp_fused_step(x, g, 1e-3, 8, 8, B, 0.0, 0)
+    check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, 8, 8, 0.0, 0)
+    want_tail, _, _, _ = ref.fused_step(tail_x, tail_g, 1e-3, 8, 8, B, 0.0, 0, index_offset=(n // B) * B)
+    assert bits_equal(x[(n // B) * B:].cpu().numpy(), want_tail)
+
+
+def test_config3_gpt350m_per_layer_tensors():
+    """350M as separate per-layer tensors (bucketing restarts per tensor), W8 G4, bucket 1024:
+    one-bucket vectors (LayerNorm, biases) in full, matrices on sampled buckets."""
+    shape, B = wl.GPT_350M, 1024
+    tensors = wl.model_tensors(shape)
+    n = sum(s for _, s in tensors)
+    x = wl.weights(n, 1238, DEV)
+    g = wl.grads_student_t3(n, 1239, DEV)
+    off = 0
+    checked = 0
+    for t, (name, size) in enumerate(tensors):
+        xs, gs = x[off:off + size], g[off:off + size]
+        off += size
+        # keep the run short: every tensor of the first and last block, wte/wpe/ln_f, and
+        # every 5th tensor in between go through the library and the check
+        layer = name.split(".")[0]
+        if not (layer in ("wte", "wpe", "ln_f_w", "ln_f_b", "h0", "h23") or t % 5 == 0):
+            continue
+        seed = t
+        gc, gm = qb.alloc_packed(size, 4, B, DEV)
+        qb.qsdp_quantize_grad(gs, 4, B, seed, 0, gc, gm.reshape(-1))
+        wc, wm = qb.alloc_packed(size, 8, B, DEV)
+        qb.qsdp_quantize_weight(xs, 8, B, 0.0, seed, wc, wm.reshape(-1))
+        k = 8 if size > 64 * B else size // B
+        ids = sample_bucket_ids(size // B, k, t)
+        check_quantized_buckets("grad", gs, gc, gm, 4, B, 0.0, seed, ids, size)
+        check_quantized_buckets("weight", xs, wc, wm, 8, B, 0.0, seed, ids, size)
+        xb, gb = gather_rows(xs, ids, B), gather_rows(gs, ids, B)
+        qb.qsdp_fused_step(xs, gs, 1e-3, 8, 4, B, 0.0, seed)
+        check_fused_buckets(xb, gb, gather_rows(xs, ids, B), ids, B, 1e-3, 8, 4, 0.0, seed)
+        checked += 1
+    assert off == n and checked > 60
+
+
+def test_config4_gpt1p3b_ten_fused_steps(gpt1p3b):
+    """The headline workload: 10 fused steps, seed = step index, x carried, W8 G4, bucket 1024."""
+    n, x0, g = gpt1p3b
+    B = 1024
+    assert n % B == 0
+    x = x0.clone()
+    ids = sample_bucket_ids(n // B, 300, 4)
+    gb = gather_rows(g, ids, B)
+    for step in range(10):
+        xb = gather_rows(x, ids, B)
+        qb.qsdp_fused_step(x, g, 1e-3, 8, 4, B, 0.0, step)
+        check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, 8, 4, 0.0, step)
+    # every iterate sits on its bucket's 8-bit grid: at most 256 distinct values per bucket
+    rows = gather_rows(x, ids[:50], B)
+    assert max(len(np.unique(r)) for r in rows) <= 256
+
+
+@pytest.mark.parametrize("B", [128, 512, 1024, 4096])
+def test_config5_bit_and_bucket_sweep_on_a_16m_slice(gpt1p3b, B):
+    n_all, x0, g_all = gpt1p3b
+    n = 1 << 24
+    g = g_all[:n]
+    ids = sample_bucket_ids(n // B, 48, B)
+    gb = gather_rows(g, ids, B)
+    xb = gather_rows(x0[:n], ids, B)
+    for gbits in (2, 3, 4, 6, 8):
+        gc, gm = qb.alloc_packed(n, gbits, B, DEV)
+        qb.qsdp_quantize_grad(g, gbits, B, 5, 0, gc, gm.reshape(-1))
+        check_quantized_buckets("grad", g, gc, gm, gbits, B, 0.0, 5, ids, n)
+        for wbits in (4, 6, 8):
+            x = x0[:n].clone()
+            wc, wm = qb.alloc_packed(n, wbits, B, DEV)
+            qb.qsdp_fused_step(x, g, 1e-3, wbits, gbits, B, 0.0, 5, 0, wc, wm.reshape(-1))
+            check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, wbits, gbits, 0.0, 5)
+            # the emitted codes decode to the new x
+            out = torch.empty(n, dtype=torch.float32, device=DEV)
+            qb.qsdp_dequantize(wc, wm.reshape(-1), n, wbits, B, out)
+            assert torch.equal(out, x)
+    for wbits in (4, 6, 8):
+        wc, wm = qb.alloc_packed(n, wbits, B, DEV)
+        qb.qsdp_quantize_weight(x0[:n], wbits, B, 0.0, 5, wc, wm.reshape(-1))
+        check_quantized_buckets("weight", x0[:n], wc, wm, wbits, B, 0.0, 5, ids, n)
+
+
+@pytest.mark.parametrize("delta,wbits", [(2.0**-6, 4), (2.0**-8, 6), (2.0**-10, 8), (2.0**-10, 4)])
+def test_config5_lattice_quantizer_full_vector(gpt1p3b, delta, wbits):
+    """Explicit-delta random-shift quantizer on the whole 1.3B vector; saturation counts are
+    compared on the sampled buckets and, for the fitting pairings, must be zero or tiny overall."""
+    n, x0, g = gpt1p3b
+    B = 1024
+    ids = sample_bucket_ids(n // B, 200, 6)
+    wc, wm = qb.alloc_packed(n, wbits, B, DEV)
+    sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+    qb.qsdp_quantize_weight(x0, wbits, B, delta, 3, wc, wm.reshape(-1), sat)
+    check_quantized_buckets("weight", x0, wc, wm, wbits, B, delta, 3, ids, n)
+    rows = gather_rows(x0, ids, B)
+    want_sat = sum(ref.quantize_weight(r, wbits, B, delta, 3)[2] for r in rows)
+    # whole-vector count: property check against the sampled rate (loose), exact on a sub-vector
+    m = 4096 * B
+    sat_small = torch.zeros(1, dtype=torch.int64, device=DEV)
+    wc2, wm2 = qb.alloc_packed(m, wbits, B, DEV)
+    qb.qsdp_quantize_weight(x0[:m], wbits, B, delta, 3, wc2, wm2.reshape(-1), sat_small)
+    ref.set_threads(8)
+    _, _, want_small = ref.quantize_weight(x0[:m].cpu().numpy(), wbits, B, delta, 3)
+    ref.set_threads(1)
+    assert int(sat_small) == want_small
+    total = int(sat)
+    if want_sat == 0 and want_small == 0:
+        assert total <= n // 10**6
+    else:
+        rate = want_small / m
+        assert 0.5 * rate * n <= total <= 2.0 * rate * n
+    # fused step on the grid
+    x = x0.clone()
+    xb, gb = gather_rows(x, ids, B), gather_rows(g, ids, B)
+    qb.qsdp_fused_step(x, g, 1e-3, wbits, 4, B, delta, 3)
+    check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, wbits, 4, delta, 3)
+
+
+@pytest.mark.parametrize("wbits,gbits,B", [(4, 2, 128), (8, 8, 4096), (6, 3, 512)])
+def test_config5_diagonal_full_vector(gpt1p3b, wbits, gbits, B):
+    n, x0, g = gpt1p3b
+    ids = sample_bucket_ids(n // B, 200, 7)
+    x = x0.clone()
+    xb, gb = gather_rows(x, ids, B), gather_rows(g, ids, B)
+    qb.qsdp_fused_step(x, g, 1e-3, wbits, gbits, B, 0.0, 8)
+    check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, wbits, gbits, 0.0, 8)
+
+
+def test_config5_layerwise_dequantize_to_bf16(gpt1p3b):
+    """What a forward-pass weight gather needs: decode each d=2048 block (50,358,272 elements)
+    to bf16. All 24 blocks are decoded; three are compared in full with the oracle."""
+    n, x0, _ = gpt1p3b
+    B = 1024
+    d = wl.GPT_1P3B.d
+    blk = wl.block_numel(d)
+    start = (wl.VOCAB + wl.N_CTX) * d
+    out = torch.empty(blk, dtype=torch.bfloat16, device=DEV)
+    for layer in range(wl.GPT_1P3B.layers):
+        xs = x0[start + layer * blk: start + (layer + 1) * blk]
+        wc, wm = qb.alloc_packed(blk, 8, B, DEV)
+        qb.qsdp_quantize_weight(xs, 8, B, 0.0, layer, wc, wm.reshape(-1))
+        qb.qsdp_dequantize(wc, wm.reshape(-1), blk, 8, B, out)
+        if layer in (0, 11, 23):
+            ref.set_threads(8)
+            want = ref.dequantize(u32(wc.cpu().numpy()), wm.cpu().numpy(), blk, 8, B, ref.BF16)
+            ref.set_threads(1)
+            assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), want)
+            ids = sample_bucket_ids(blk // B, 32, layer)
+            check_quantized_buckets("weight", xs, wc, wm, 8, B, 0.0, layer, ids, blk)
