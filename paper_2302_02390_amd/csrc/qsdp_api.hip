@@ -3,6 +3,7 @@
 #include "../../include/qsdp.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 #include "qsdp_launch.hpp"
@@ -90,7 +91,11 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
         p.num_buckets = nb_full;
         const uint64_t groups = ceil_div(nb_full, (uint64_t)bpw);
         const uint64_t blocks = ceil_div(groups, 4);
-        const unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+        unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+        if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
+            const unsigned cap = (unsigned)std::atoi(e);
+            if (cap >= 1 && grid > cap) grid = cap;
+        }
         if (wl(mode, stored_bits, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
         done = nb_full;
     }

@@ -51,7 +51,11 @@ __device__ __forceinline__ void grad_uniforms_rows(uint64_t bucket_block, int c,
     const int odd = l & 1;
     const uint64_t block = bucket_block + (uint64_t)(((2 * c + odd) * G + (l - odd)) >> 1);
     uint32_t w[4];
+#ifdef QSDP_EXP_NOPHILOX
+    w[0] = (uint32_t)block; w[1] = k0; w[2] = k1; w[3] = (uint32_t)(block >> 7);
+#else
     philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
+#endif
     const uint32_t send0 = odd ? w[0] : w[2];
     const uint32_t send1 = odd ? w[1] : w[3];
     const uint32_t recv0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send0, 0xB1, 0xF, 0xF, false);

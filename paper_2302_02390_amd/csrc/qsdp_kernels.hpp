@@ -49,7 +49,11 @@ __device__ __forceinline__ void load_rows(const float* base, int l, float (&v)[R
     const f4* p = reinterpret_cast<const f4*>(base) + l;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
+#ifdef QSDP_EXP_LD_PLAIN
+        const f4 a = p[r * G];
+#else
         const f4 a = __builtin_nontemporal_load(p + r * G);
+#endif
         v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
     }
 }
@@ -60,7 +64,11 @@ __device__ __forceinline__ void store_rows(float* base, int l, const float (&v)[
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
+#ifdef QSDP_EXP_ST_PLAIN
+        p[r * G] = a;
+#else
         __builtin_nontemporal_store(a, p + r * G);
+#endif
     }
 }
 
@@ -133,6 +141,19 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
+#ifdef QSDP_EXP_AXPY
+        if (MODE == MODE_FUSED) {
+            float gv[R][4];
+            load_rows<G, R>(p.g + e0, l, gv);
+            load_rows<G, R>(p.x + e0, l, w);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[r][i] = fmaf(-p.lr, gv[r][i], w[r][i]);
+            if (active) store_rows<G, R>(p.x + e0, l, w);
+            continue;
+        }
+#endif
 
         if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
             float gv[R][4];

@@ -1,5 +1,7 @@
 // Instantiations of the wave kernels for one bucket shape; compiled with
 // -DQSDP_G=<lanes per bucket> -DQSDP_R=<rows of 4*G elements> -DQSDP_B=<4*G*R>.
+#include <cstdlib>
+
 #include "qsdp_launch.hpp"
 
 #if !defined(QSDP_G) || !defined(QSDP_R) || !defined(QSDP_B)
@@ -15,7 +17,12 @@ namespace {
 
 template <int MODE, int BITS>
 hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS>), dim3(grid), dim3(256), 0, s, p);
+    unsigned block = 256;
+    if (const char* e = std::getenv("QSDP_DEBUG_BLOCK")) {
+        block = (unsigned)std::atoi(e);
+        grid = grid * (256 / block);
+    }
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS>), dim3(grid), dim3(block), 0, s, p);
     return hipGetLastError();
 }
 
