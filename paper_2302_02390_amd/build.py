@@ -16,7 +16,7 @@ LIB = os.path.join(HERE, "libqsdp.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
-         "-fno-fast-math", "-Wall", "-Wno-unused-result",
+         "-fno-fast-math", "-fno-honor-nans", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("QSDP_EXTRA_FLAGS", "").split()
 
 # bucket size -> (lanes per bucket G, rows R): bucket = 4 * G * R

@@ -23,8 +23,11 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
 namespace {
 template <int BITS>
 hipError_t dequant_go(bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
-    if (bf16) hipLaunchKernelGGL((dequant_kernel<BITS, true>), dim3(grid), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((dequant_kernel<BITS, false>), dim3(grid), dim3(256), 0, s, p);
+    const bool pow2 = p.bucket32_shift >= 0;
+    if (bf16 && pow2) hipLaunchKernelGGL((dequant_kernel<BITS, true, true>), dim3(grid), dim3(256), 0, s, p);
+    else if (bf16) hipLaunchKernelGGL((dequant_kernel<BITS, true, false>), dim3(grid), dim3(256), 0, s, p);
+    else if (pow2) hipLaunchKernelGGL((dequant_kernel<BITS, false, true>), dim3(grid), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((dequant_kernel<BITS, false, false>), dim3(grid), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 }  // namespace
@@ -184,15 +187,21 @@ int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bi
                     qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
     if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (n >= (1ull << 37)) return QSDP_EINVAL;  // the decoder indexes buckets with 32-bit arithmetic
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
     DequantParams p = {};
     p.codes = codes;
     p.meta = meta;
     p.out = out;
     p.n = n;
-    p.nchunks = ceil_div(n, 8);
-    p.bucket = bucket;
-    const uint64_t blocks = ceil_div(p.nchunks, 256);
+    p.nwords = qsdp_codes_bytes(n, bits, bucket) / 4;
+    const uint64_t tile = (uint64_t)kDequantRows * 64u * (out_dtype == QSDP_BF16 ? 8u : 4u);
+    p.ntiles = ceil_div(n, tile);
+    p.bucket32 = (uint32_t)bucket / 32u;
+    p.bucket32_shift = -1;
+    for (int sh = 0; sh < 9; ++sh)
+        if (p.bucket32 == (1u << sh)) p.bucket32_shift = sh;
+    const uint64_t blocks = ceil_div(p.ntiles, 4);
     const unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
     if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;

@@ -81,8 +81,9 @@ __device__ __forceinline__ float weight_shift(uint32_t k0, uint32_t k1) {
 // ---------------------------------------------------------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
-    return __int_as_float(
-        __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
+    // every lane has a valid source for the controls used here, so the previous value of the
+    // destination is irrelevant and the move can fold into the min/max that consumes it
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
 __device__ __forceinline__ void swap16(float v, float& a, float& b) {
@@ -151,21 +152,35 @@ __device__ __forceinline__ float div_delta(float v, const Divider& d) {
     return d.pow2 ? v * d.inv_delta : v / d.delta;
 }
 
-// Coin-flip code of one gradient element, as a float in [0, L].
+// Coin-flip code of one gradient element: floor(t) + [u < frac(t)], t clamped to [0, L]
+// (t >= 0 always; the upper clamp catches (hi - lo) * inv rounding above L). v_med3 is the
+// clamp and v_fract is t - floor(t), exactly, for finite t >= 0. h = u * 2^16.
+__device__ __forceinline__ float grad_position(float g, const MinMaxGrid& grid, float Lf) {
+    const float t = (g - grid.lo) * grid.inv;
+    return __builtin_amdgcn_fmed3f(t, 0.0f, Lf);
+}
+
+// ... as a float (for decoding in registers)
 __device__ __forceinline__ float grad_code(float g, const MinMaxGrid& grid, float Lf, float h) {
-    float t = (g - grid.lo) * grid.inv;
-    t = fminf(fmaxf(t, 0.0f), Lf);
-    const float f = floorf(t);
-    const float frac = t - f;
+    const float t = grad_position(g, grid, Lf);
+    const float frac = __builtin_amdgcn_fractf(t);
     const float u = h * 0x1p-16f;
-    return f + ((u < frac) ? 1.0f : 0.0f);
+    return floorf(t) + ((u < frac) ? 1.0f : 0.0f);
+}
+
+// ... as an integer (for packing): truncation is floor for t >= 0
+__device__ __forceinline__ uint32_t grad_code_int(float g, const MinMaxGrid& grid, float Lf, float h) {
+    const float t = grad_position(g, grid, Lf);
+    const float frac = __builtin_amdgcn_fractf(t);
+    const float u = h * 0x1p-16f;
+    return (uint32_t)t + ((u < frac) ? 1u : 0u);
 }
 
 __device__ __forceinline__ float weight_code_minmax(float x, const MinMaxGrid& grid, float Lf,
                                                     float xi) {
     const float t = (x - grid.lo) * grid.inv;
     const float k = rintf(t - xi);
-    return fminf(fmaxf(k, 0.0f), Lf);
+    return __builtin_amdgcn_fmed3f(k, 0.0f, Lf);
 }
 
 __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, float xi, float k0,
@@ -183,6 +198,14 @@ __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, 
 // Packing: 4 consecutive codes of a lane, 8 consecutive codes (a chunk) = BITS bytes
 // ---------------------------------------------------------------------------------------
 template <int BITS>
+__device__ __forceinline__ uint32_t pack4(const uint32_t (&c)[4]) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc |= c[i] << (i * BITS);
+    return acc;
+}
+
+template <int BITS>
 __device__ __forceinline__ uint32_t pack4(const float (&c)[4]) {
     uint32_t acc = 0;
 #pragma unroll
@@ -190,8 +213,8 @@ __device__ __forceinline__ uint32_t pack4(const float (&c)[4]) {
     return acc;
 }
 
-// Store the BITS bytes of a packed chunk at byte address p (p is a multiple of BITS bytes
-// from a 16-byte aligned base, so the widest naturally aligned pieces are used).
+// Store the BITS bytes of a packed chunk at byte address p in LDS (p is a multiple of BITS
+// bytes from a 16-byte aligned base, so the widest naturally aligned pieces are used).
 template <int BITS>
 __device__ __forceinline__ void store_chunk(uint8_t* p, uint64_t v) {
     if (BITS == 8) {
@@ -207,26 +230,6 @@ __device__ __forceinline__ void store_chunk(uint8_t* p, uint64_t v) {
     } else {
 #pragma unroll
         for (int i = 0; i < BITS; ++i) p[i] = (uint8_t)(v >> (8 * i));
-    }
-}
-
-template <int BITS>
-__device__ __forceinline__ uint64_t load_chunk(const uint8_t* p) {
-    if (BITS == 8) {
-        u2 w = *reinterpret_cast<const u2*>(p);
-        return (uint64_t)w[0] | ((uint64_t)w[1] << 32);
-    } else if (BITS == 4) {
-        return *reinterpret_cast<const uint32_t*>(p);
-    } else if (BITS == 2) {
-        return *reinterpret_cast<const uint16_t*>(p);
-    } else if (BITS == 6) {
-        const uint16_t* q = reinterpret_cast<const uint16_t*>(p);
-        return (uint64_t)q[0] | ((uint64_t)q[1] << 16) | ((uint64_t)q[2] << 32);
-    } else {
-        uint64_t v = 0;
-#pragma unroll
-        for (int i = 0; i < BITS; ++i) v |= (uint64_t)p[i] << (8 * i);
-        return v;
     }
 }
 

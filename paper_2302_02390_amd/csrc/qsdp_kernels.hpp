@@ -87,10 +87,18 @@ __device__ __forceinline__ void rows_minmax(const float (&v)[R][4], float& lo, f
     hi = group_max<G>(hi);
 }
 
-// Pack and store the codes of all rows. c[r][i] are the codes (as floats) of this lane's
-// elements; `cb` points at the bucket's first code byte.
-template <int G, int R, int BITS>
-__device__ __forceinline__ void store_codes(uint8_t* cb, int l, const float (&c)[R][4]) {
+// Pack the codes of all rows and stage them in LDS in wire order, then write the wave's code
+// tile (its 64/G buckets are consecutive, so the tile is 32*R*BITS contiguous bytes) with
+// 16-byte stores, one contiguous run per instruction. c[r][i] are the codes (as floats) of this
+// lane's elements; `stage` is this wave's LDS tile; `tile_out` the tile's place in the code
+// buffer; buckets at or past `active_buckets` of the wave's 64/G are not written.
+template <int G, int R, int BITS, typename CodeT>
+__device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int lane, int active_buckets,
+                                            const CodeT (&c)[R][4]) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;  // 16-byte pieces in the tile
+    const int l = lane % G;
+    const int sub = lane / G;
     const int odd = l & 1;
 #pragma unroll
     for (int cp = 0; cp < R / 2; ++cp) {
@@ -103,8 +111,21 @@ __device__ __forceinline__ void store_codes(uint8_t* cb, int l, const float (&c)
         const uint64_t chunk = odd ? ((uint64_t)recv | ((uint64_t)q1 << (4 * BITS)))
                                    : ((uint64_t)q0 | ((uint64_t)recv << (4 * BITS)));
         const int chunk_index = ((2 * cp + odd) * G + (l - odd)) >> 1;
-        store_chunk<BITS>(cb + (size_t)chunk_index * BITS, chunk);
+        store_chunk<BITS>(stage + sub * kBucketBytes + chunk_index * BITS, chunk);
     }
+    // LDS traffic of one wave is processed in order; keep the compiler from reordering it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const u4* staged = reinterpret_cast<const u4*>(stage);
+#pragma unroll
+    for (int k0 = 0; k0 < kPieces; k0 += 64) {
+        const int k = k0 + lane;
+        if (k < kPieces && (k * 16) / kBucketBytes < active_buckets)
+            __builtin_nontemporal_store(staged[k], tile_out + k);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 // MODE_GRAD / MODE_WEIGHT / MODE_FUSED over full buckets. BITS is the width of the codes
@@ -125,6 +146,11 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
     const uint64_t ngroups = (p.num_buckets + BPW - 1) / BPW;
 
+    // LDS staging tile of the packed codes: 32*R*BITS bytes per wave, up to 4 waves per block
+    constexpr int kTileBytes = 32 * R * SB;
+    __shared__ u4 stage_all[BITS ? 4 * kTileBytes / 16 : 1];
+    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (BITS ? wave_in_block * kTileBytes : 0);
+
     const float Lg = (float)((1 << p.gbits) - 1);
     const float Lw = (float)((1 << p.wbits) - 1);
     const Divider div = {p.delta, p.inv_delta, p.delta_pow2 != 0};
@@ -136,6 +162,11 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     for (uint64_t q = wave0; q < ngroups; q += nwaves) {
         const uint64_t rel = q * BPW + sub;          // bucket within this launch
         const bool active = rel < p.num_buckets;
+        // the wave's code tile: buckets first_bucket + q*BPW .. +BPW-1
+        const uint64_t left = p.num_buckets - q * BPW;
+        const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
+        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) +
+                                             ((p.first_bucket + q * BPW) * (uint64_t)B >> 3) * SB);
         const uint64_t bucket = p.first_bucket + (active ? rel : 0);
         const uint64_t e0 = bucket * (uint64_t)B;    // first element of the bucket
 
@@ -157,6 +188,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 
         if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
             float gv[R][4];
+            uint32_t gcode[R][4];  // MODE_GRAD only
             load_rows<G, R>(p.g + e0, l, gv);
             if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, w);
             float lo, hi;
@@ -169,22 +201,20 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int r = 2 * cp + (i >> 2);
-                    const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
-                    if (MODE == MODE_GRAD) {
-                        gv[r][i & 3] = code;
+                    if constexpr (MODE == MODE_GRAD) {
+                        gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
                     } else {
+                        const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
                         const float ghat = fmaf(code, grid.scale, grid.lo);
                         w[r][i & 3] = fmaf(-p.lr, ghat, w[r][i & 3]);
                     }
                 }
             }
-            if (MODE == MODE_GRAD) {
-                if (active) {
-                    store_codes<G, R, SB>(reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * SB, l, gv);
-                    if (l == 0) {
-                        p.meta[2 * bucket] = grid.lo;
-                        p.meta[2 * bucket + 1] = grid.scale;
-                    }
+            if constexpr (MODE == MODE_GRAD) {
+                store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
+                if (active && l == 0) {
+                    p.meta[2 * bucket] = grid.lo;
+                    p.meta[2 * bucket + 1] = grid.scale;
                 }
                 continue;
             }
@@ -221,14 +251,14 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                 for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
         }
 
-        if (active) {
-            if (BITS != 0) {
-                store_codes<G, R, SB>(reinterpret_cast<uint8_t*>(p.codes) + (e0 >> 3) * SB, l, w);
-                if (l == 0) {
-                    p.meta[2 * bucket] = base;
-                    p.meta[2 * bucket + 1] = scale;
-                }
+        if (BITS != 0) {
+            store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
+            if (active && l == 0) {
+                p.meta[2 * bucket] = base;
+                p.meta[2 * bucket + 1] = scale;
             }
+        }
+        if (active) {
             if (MODE == MODE_FUSED) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
@@ -384,52 +414,127 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Decoding: elementwise, a lane per chunk of 8 elements (BITS bytes in, 16 or 32 bytes out).
+// Decoding: elementwise. A lane decodes E consecutive elements per row (E = 4 for fp32, 8 for
+// bf16 output: one 16-byte store), a wave row is 64*E consecutive elements (one contiguous KiB
+// of output), a wave handles U rows. Buckets are padded to full size in the code stream, so
+// the codes of element e start at bit e*BITS of the whole buffer.
 // ---------------------------------------------------------------------------------------
 struct DequantParams {
     const uint32_t* codes;
     const float* meta;
     void* out;
     uint64_t n;
-    uint64_t nchunks;  // ceil(n / 8)
-    int bucket;
+    uint64_t nwords;  // 32-bit words in the code buffer
+    uint64_t ntiles;  // wave tiles of U*64*E elements
+    uint32_t bucket32;      // bucket / 32
+    int bucket32_shift;     // log2(bucket / 32) if that is a power of two, else -1 (division)
 };
 
-template <int BITS, bool BF16>
-__global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    const uint8_t* cb = reinterpret_cast<const uint8_t*>(p.codes);
-    const uint32_t chunks_per_bucket = (uint32_t)p.bucket >> 3;
-    for (uint64_t ch = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; ch < p.nchunks; ch += stride) {
-        const uint64_t v = load_chunk<BITS>(cb + ch * BITS);
-        const uint64_t bucket = ch / chunks_per_bucket;
-        const float base = p.meta[2 * bucket];
-        const float scale = p.meta[2 * bucket + 1];
-        float o[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t c = (uint32_t)(v >> (i * BITS)) & ((1u << BITS) - 1u);
-            o[i] = fmaf((float)c, scale, base);
+#ifndef QSDP_DEQ_ROWS
+#define QSDP_DEQ_ROWS 2
+#endif
+constexpr int kDequantRows = QSDP_DEQ_ROWS;
+
+// The E*BITS bits (at most 64) that start at bit `bit` of the code buffer.
+template <int NBITS>
+__device__ __forceinline__ uint64_t load_bits(const uint32_t* codes, uint64_t bit, uint64_t last_word) {
+    const uint64_t word = bit >> 5;
+    const uint32_t sh = (uint32_t)bit & 31u;
+    if (NBITS == 64) {  // 8-byte aligned
+        const u2 w = __builtin_nontemporal_load(reinterpret_cast<const u2*>(codes + word));
+        return (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    } else if (NBITS == 32) {
+        return __builtin_nontemporal_load(codes + word);
+    } else if (32 % NBITS == 0) {  // 16, 8 or 4 bits inside one word
+        return (uint64_t)(codes[word] >> sh);
+    } else {  // straddles words; the start bit is a multiple of gcd(NBITS, 32)
+        constexpr int kStep = (NBITS % 16 == 0) ? 16 : (NBITS % 8 == 0) ? 8 : 4;
+        const uint64_t w1i = word + 1 <= last_word ? word + 1 : last_word;
+        const uint64_t lo64 = (uint64_t)codes[word] | ((uint64_t)codes[w1i] << 32);
+        uint64_t v = lo64 >> sh;
+        if (32 - kStep + NBITS > 64) {  // a third word is needed (56 bits from bit 24)
+            const uint64_t w2i = word + 2 <= last_word ? word + 2 : last_word;
+            const uint64_t w2 = codes[w2i];
+            if (sh != 0) v |= w2 << (64 - sh);
         }
-        const uint64_t e = ch * 8;
-        if (e + 8 <= p.n) {
-            if (BF16) {
-                u4 w;
+        return v;
+    }
+}
+
+template <bool POW2>
+__device__ __forceinline__ uint64_t bucket_of(uint64_t e, const DequantParams& p) {
+    // e / bucket with 32-bit arithmetic (the host checks n < 2^37)
+    const uint32_t e32 = (uint32_t)(e >> 5);
+    return POW2 ? (e32 >> p.bucket32_shift) : (e32 / p.bucket32);
+}
+
+template <int BITS, bool BF16>
+__device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e, uint64_t bits, float base,
+                                             float scale, bool whole) {
+    constexpr int E = BF16 ? 8 : 4;
+    float o[E];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[i] = bf16_bits(o[2 * i]) | (bf16_bits(o[2 * i + 1]) << 16);
-                __builtin_nontemporal_store(w, reinterpret_cast<u4*>(static_cast<uint16_t*>(p.out) + e));
-            } else {
-                f4* q = reinterpret_cast<f4*>(static_cast<float*>(p.out) + e);
-                const f4 a = {o[0], o[1], o[2], o[3]};
-                const f4 b = {o[4], o[5], o[6], o[7]};
-                __builtin_nontemporal_store(a, q);
-                __builtin_nontemporal_store(b, q + 1);
-            }
+    for (int i = 0; i < E; ++i) {
+        const uint32_t c = (uint32_t)(bits >> (i * BITS)) & ((1u << BITS) - 1u);
+        o[i] = fmaf((float)c, scale, base);
+    }
+    if (whole) {
+        if (BF16) {
+            u4 w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = bf16_bits(o[2 * i]) | (bf16_bits(o[2 * i + 1]) << 16);
+            __builtin_nontemporal_store(w, reinterpret_cast<u4*>(static_cast<uint16_t*>(p.out) + e));
         } else {
-            for (int i = 0; i < 8; ++i) {
-                if (e + i < p.n) {
-                    if (BF16) static_cast<uint16_t*>(p.out)[e + i] = (uint16_t)bf16_bits(o[i]);
-                    else static_cast<float*>(p.out)[e + i] = o[i];
+            const f4 a = {o[0], o[1], o[2], o[3]};
+            __builtin_nontemporal_store(a, reinterpret_cast<f4*>(static_cast<float*>(p.out) + e));
+        }
+    } else {
+        for (int i = 0; i < E; ++i) {
+            if (e + i < p.n) {
+                if (BF16) static_cast<uint16_t*>(p.out)[e + i] = (uint16_t)bf16_bits(o[i]);
+                else static_cast<float*>(p.out)[e + i] = o[i];
+            }
+        }
+    }
+}
+
+template <int BITS, bool BF16, bool POW2>
+__global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
+    constexpr int E = BF16 ? 8 : 4;
+    constexpr int U = kDequantRows;
+    constexpr uint64_t T = (uint64_t)U * 64 * E;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t waves_per_block = blockDim.x >> 6;
+    const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
+    const uint64_t last_word = p.nwords - 1;
+    for (uint64_t tile = (uint64_t)blockIdx.x * waves_per_block + wave_in_block; tile < p.ntiles;
+         tile += nwaves) {
+        const uint64_t e0 = tile * T + (uint64_t)(lane * E);
+        if ((tile + 1) * T <= p.n) {
+            // whole tile in range (wave-uniform): all loads first, no per-lane control flow
+            uint64_t bits[U];
+            float base[U], scale[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t e = e0 + (uint64_t)(u * 64 * E);
+                bits[u] = load_bits<E * BITS>(p.codes, e * BITS, last_word);
+                const uint64_t bucket = bucket_of<POW2>(e, p);
+                base[u] = p.meta[2 * bucket];
+                scale[u] = p.meta[2 * bucket + 1];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                decode_store<BITS, BF16>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true);
+        } else {
+            // last, partial tile
+            for (int u = 0; u < U; ++u) {
+                const uint64_t e = e0 + (uint64_t)(u * 64 * E);
+                if (e < p.n) {
+                    const uint64_t bits = load_bits<E * BITS>(p.codes, e * BITS, last_word);
+                    const uint64_t bucket = bucket_of<POW2>(e, p);
+                    decode_store<BITS, BF16>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
+                                             e + E <= p.n);
                 }
             }
         }
