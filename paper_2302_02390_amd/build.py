@@ -19,15 +19,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-fno-fast-math", "-fno-honor-nans", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("QSDP_EXTRA_FLAGS", "").split()
 
-# bucket size -> (lanes per bucket G, rows R): bucket = 4 * G * R
-WAVE_SHAPES = {128: (8, 4), 256: (16, 4), 512: (32, 4), 1024: (64, 4), 2048: (64, 8), 4096: (64, 16)}
+# bucket size -> (lanes per bucket G, rows per wave R, waves per bucket W): bucket = 4 * G * R * W
+WAVE_SHAPES = {128: (8, 4, 1), 256: (16, 4, 1), 512: (32, 4, 1), 1024: (64, 4, 1), 2048: (64, 4, 2),
+               4096: (64, 4, 4)}
 
 
 def _units():
     units = [("qsdp_api.o", "qsdp_api.hip", [])]
-    for b, (g, r) in WAVE_SHAPES.items():
+    for b, (g, r, w) in WAVE_SHAPES.items():
         units.append((f"qsdp_wave_{b}.o", "qsdp_wave_inst.hip",
-                      [f"-DQSDP_G={g}", f"-DQSDP_R={r}", f"-DQSDP_B={b}"]))
+                      [f"-DQSDP_G={g}", f"-DQSDP_R={r}", f"-DQSDP_W={w}", f"-DQSDP_B={b}"]))
     return units
 
 

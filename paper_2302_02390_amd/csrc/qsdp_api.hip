@@ -74,8 +74,8 @@ WaveLauncher wave_launcher(int bucket, int* buckets_per_wave) {
         case 256: *buckets_per_wave = 4; return launch_wave_256;
         case 512: *buckets_per_wave = 2; return launch_wave_512;
         case 1024: *buckets_per_wave = 1; return launch_wave_1024;
-        case 2048: *buckets_per_wave = 1; return launch_wave_2048;
-        case 4096: *buckets_per_wave = 1; return launch_wave_4096;
+        case 2048: *buckets_per_wave = 0; return launch_wave_2048;  // 0: a workgroup per bucket
+        case 4096: *buckets_per_wave = 0; return launch_wave_4096;
         default: return nullptr;
     }
 }
@@ -92,8 +92,8 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
     if (wl != nullptr && wave_bits_supported(stored_bits) && nb_full > 0) {
         p.first_bucket = 0;
         p.num_buckets = nb_full;
-        const uint64_t groups = ceil_div(nb_full, (uint64_t)bpw);
-        const uint64_t blocks = ceil_div(groups, 4);
+        // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
+        const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb_full, (uint64_t)bpw), 4) : nb_full;
         unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
         if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
             const unsigned cap = (unsigned)std::atoi(e);

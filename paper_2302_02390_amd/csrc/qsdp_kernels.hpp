@@ -9,7 +9,9 @@
 //     (8 codes = BITS bytes) span the lane pair (l even, l+1) of one row: for each row pair
 //     (2c, 2c+1) the even lane owns the block/chunk of row 2c and the odd lane that of row
 //     2c+1, and the pair swaps halves with one DPP quad permute. A wave handles 64/G buckets
-//     at a time; waves stride over the full buckets of the vector.
+//     at a time; waves stride over the full buckets of the vector. Buckets larger than one
+//     wave's tile are shared by the W waves of a workgroup (B = 4*G*R*W, G = 64): each wave
+//     owns a contiguous 1/W of the bucket and the waves combine their min/max through LDS.
 //   * block kernel: one 256-thread workgroup per bucket, staged in LDS; any bucket size, any
 //     bits, short last bucket. Used for the shapes the wave kernels do not cover.
 #pragma once
@@ -128,13 +130,34 @@ __device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int la
     __builtin_amdgcn_wave_barrier();
 }
 
+// Combine per-wave (lo, hi) across the W waves of a workgroup that share a bucket. `slot` is a
+// [2][W] LDS array that no other reduction uses; callers alternate two slots between loop
+// iterations so that a fast wave's next write cannot overtake a slow wave's read.
+template <int W>
+__device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float* slot, uint32_t wave) {
+    if (W > 1) {
+        if ((threadIdx.x & 63) == 0) {
+            slot[wave] = lo;
+            slot[W + wave] = hi;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            lo = fminf(lo, slot[i]);
+            hi = fmaxf(hi, slot[W + i]);
+        }
+    }
+}
+
 // MODE_GRAD / MODE_WEIGHT / MODE_FUSED over full buckets. BITS is the width of the codes
-// that are stored (0: FUSED without code output). delta > 0 selects the explicit grid (a
-// wave-uniform branch).
-template <int MODE, int G, int R, int BITS>
+// that are stored (0: FUSED without code output). W = waves per bucket (W > 1: the workgroup
+// has exactly W waves and owns one bucket per iteration). delta > 0 selects the explicit grid
+// (a wave-uniform branch).
+template <int MODE, int G, int R, int BITS, int W>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
-    constexpr int B = 4 * G * R;
+    static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
+    constexpr int B = 4 * G * R * W;
     constexpr int BPW = 64 / G;
     constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
     const int lane = threadIdx.x & 63;
@@ -142,14 +165,17 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     const int l = lane % G;
     const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t waves_per_block = blockDim.x >> 6;
-    const uint64_t wave0 = (uint64_t)blockIdx.x * waves_per_block + wave_in_block;
-    const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
-    const uint64_t ngroups = (p.num_buckets + BPW - 1) / BPW;
+    // W == 1: a wave strides over groups of BPW buckets; W > 1: a workgroup strides over buckets
+    const uint64_t unit0 = W == 1 ? (uint64_t)blockIdx.x * waves_per_block + wave_in_block : blockIdx.x;
+    const uint64_t unit_stride = W == 1 ? (uint64_t)gridDim.x * waves_per_block : gridDim.x;
+    const uint64_t nunits = (p.num_buckets + BPW - 1) / BPW;
 
     // LDS staging tile of the packed codes: 32*R*BITS bytes per wave, up to 4 waves per block
     constexpr int kTileBytes = 32 * R * SB;
     __shared__ u4 stage_all[BITS ? 4 * kTileBytes / 16 : 1];
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (BITS ? wave_in_block * kTileBytes : 0);
+    __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
+    uint32_t parity = 0;
 
     const float Lg = (float)((1 << p.gbits) - 1);
     const float Lw = (float)((1 << p.wbits) - 1);
@@ -159,32 +185,23 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     if (MODE != MODE_GRAD) xi = weight_shift(p.key0, p.key1);
     uint32_t saturated = 0;
 
-    for (uint64_t q = wave0; q < ngroups; q += nwaves) {
+    for (uint64_t q = unit0; q < nunits; q += unit_stride, parity ^= 1u) {
         const uint64_t rel = q * BPW + sub;          // bucket within this launch
         const bool active = rel < p.num_buckets;
-        // the wave's code tile: buckets first_bucket + q*BPW .. +BPW-1
         const uint64_t left = p.num_buckets - q * BPW;
         const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
-        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) +
-                                             ((p.first_bucket + q * BPW) * (uint64_t)B >> 3) * SB);
         const uint64_t bucket = p.first_bucket + (active ? rel : 0);
-        const uint64_t e0 = bucket * (uint64_t)B;    // first element of the bucket
+        // first element this wave handles: the bucket's, or this wave's 1/W of it
+        const uint64_t e0 = bucket * (uint64_t)B + (W > 1 ? wave_in_block * (uint32_t)(4 * G * R) : 0u);
+        // the wave's code tile: buckets first_bucket + q*BPW .. +BPW-1 (W == 1), or its share
+        const uint64_t tile_e0 = W == 1 ? (p.first_bucket + q * BPW) * (uint64_t)B : e0;
+        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) + (tile_e0 >> 3) * SB);
+        float* red_g = red_all + (W > 1 ? parity * 4 * W : 0);
+        float* red_w = red_g + (W > 1 ? 2 * W : 0);
+        const bool writes_meta = active && l == 0 && (W == 1 || wave_in_block == 0);
 
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
-#ifdef QSDP_EXP_AXPY
-        if (MODE == MODE_FUSED) {
-            float gv[R][4];
-            load_rows<G, R>(p.g + e0, l, gv);
-            load_rows<G, R>(p.x + e0, l, w);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) w[r][i] = fmaf(-p.lr, gv[r][i], w[r][i]);
-            if (active) store_rows<G, R>(p.x + e0, l, w);
-            continue;
-        }
-#endif
 
         if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
             float gv[R][4];
@@ -193,6 +210,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, w);
             float lo, hi;
             rows_minmax<G, R>(gv, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_g, wave_in_block);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg);
 #pragma unroll
             for (int cp = 0; cp < R / 2; ++cp) {
@@ -212,7 +230,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             }
             if constexpr (MODE == MODE_GRAD) {
                 store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
-                if (active && l == 0) {
+                if (writes_meta) {
                     p.meta[2 * bucket] = grid.lo;
                     p.meta[2 * bucket + 1] = grid.scale;
                 }
@@ -229,7 +247,10 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) lo = fminf(lo, w[r][i]);
-            lo = group_min<G>(lo) + 0.0f;
+            lo = group_min<G>(lo);
+            float unused_hi = lo;
+            block_combine_minmax<W>(lo, unused_hi, red_w, wave_in_block);
+            lo = lo + 0.0f;
             const float k0 = rintf(div_delta(lo, div) - xi);
             base = (k0 + xi) * p.delta;
             scale = p.delta;
@@ -242,6 +263,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         } else {
             float lo, hi;
             rows_minmax<G, R>(w, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw);
             base = fmaf(xi, grid.scale, grid.lo);
             scale = grid.scale;
@@ -253,7 +275,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 
         if (BITS != 0) {
             store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
-            if (active && l == 0) {
+            if (writes_meta) {
                 p.meta[2 * bucket] = base;
                 p.meta[2 * bucket + 1] = scale;
             }

@@ -1,13 +1,12 @@
 // Instantiations of the wave kernels for one bucket shape; compiled with
-// -DQSDP_G=<lanes per bucket> -DQSDP_R=<rows of 4*G elements> -DQSDP_B=<4*G*R>.
-#include <cstdlib>
-
+// -DQSDP_G=<lanes per bucket> -DQSDP_R=<rows of 4*G elements per wave> -DQSDP_W=<waves per
+// bucket> -DQSDP_B=<4*G*R*W>.
 #include "qsdp_launch.hpp"
 
-#if !defined(QSDP_G) || !defined(QSDP_R) || !defined(QSDP_B)
-#error "define QSDP_G, QSDP_R and QSDP_B"
+#if !defined(QSDP_G) || !defined(QSDP_R) || !defined(QSDP_W) || !defined(QSDP_B)
+#error "define QSDP_G, QSDP_R, QSDP_W and QSDP_B"
 #endif
-static_assert(QSDP_B == 4 * QSDP_G * QSDP_R, "bucket = 4 * G * R");
+static_assert(QSDP_B == 4 * QSDP_G * QSDP_R * QSDP_W, "bucket = 4 * G * R * W");
 
 #define QSDP_CAT2(a, b) a##b
 #define QSDP_CAT(a, b) QSDP_CAT2(a, b)
@@ -17,12 +16,9 @@ namespace {
 
 template <int MODE, int BITS>
 hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
-    unsigned block = 256;
-    if (const char* e = std::getenv("QSDP_DEBUG_BLOCK")) {
-        block = (unsigned)std::atoi(e);
-        grid = grid * (256 / block);
-    }
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS>), dim3(grid), dim3(block), 0, s, p);
+    // W == 1: 4 waves per workgroup, each on its own buckets; W > 1: W waves share a bucket
+    const unsigned block = QSDP_W == 1 ? 256u : 64u * QSDP_W;
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W>), dim3(grid), dim3(block), 0, s, p);
     return hipGetLastError();
 }
 
