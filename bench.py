@@ -39,6 +39,10 @@ def parse():
     ap.add_argument("--bucket", type=int, default=1024)
     ap.add_argument("--delta", type=float, default=0.0)
     ap.add_argument("--emit-codes", action="store_true", help="also write packed Q^w codes + meta")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="run the step tensor by tensor (bucketing restarts per tensor, one call each)")
+    ap.add_argument("--segmented", action="store_true",
+                    help="bucketing restarts per tensor, all tensors in ONE segmented launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip timing the other entry points")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
@@ -98,6 +102,31 @@ def main():
     def step(k):
         qb.qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, k, 0, wcodes, wmeta, None)
 
+    if a.segmented:
+        if a.workload == "1m":
+            print("bench.py: --segmented needs a GPT workload", file=sys.stderr)
+            return 2
+        segs = qb.Segments([size for _, size in wl.model_tensors(shape)], bucket, dev)
+        if a.emit_codes:
+            wcodes, wmeta = segs.alloc_packed(wbits)
+            wmeta = wmeta.reshape(-1)
+
+        def step(k):  # noqa: F811
+            qb.qsdp_fused_step_segmented(x, g, segs, lr, wbits, gbits, delta, k, 0, wcodes, wmeta, None)
+
+    if a.per_layer:
+        if a.workload == "1m" or a.emit_codes or a.segmented:
+            print("bench.py: --per-layer needs a GPT workload and no --emit-codes/--segmented", file=sys.stderr)
+            return 2
+        views, off = [], 0
+        for _, size in wl.model_tensors(shape):
+            views.append((x[off:off + size], g[off:off + size], off))
+            off += size
+
+        def step(k):  # noqa: F811
+            for xs, gs, o in views:
+                qb.qsdp_fused_step(xs, gs, lr, wbits, gbits, bucket, delta, k, o, None, None, None)
+
     for k in range(a.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -134,7 +163,9 @@ def main():
         "config": {
             "workload": f"{a.workload}-shaped flat fp32 vector, n={n}, W{wbits} G{gbits}, bucket {bucket}, "
                         f"delta {delta}, lr {lr}, seed = step index, in-place fused step"
-                        + (", packed codes emitted" if a.emit_codes else ""),
+                        + (", packed codes emitted" if a.emit_codes else "")
+                        + (", one call per layer tensor" if a.per_layer else "")
+                        + (", per-layer tensors in one segmented launch" if a.segmented else ""),
             "n": n, "wbits": wbits, "gbits": gbits, "bucket": bucket, "delta": delta,
             "spec_version": qb.spec_version(),
         },

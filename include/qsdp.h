@@ -30,7 +30,7 @@
  *     first): u = h * 2^-16 in [0,1). index_offset must be a multiple of 8. Quantizing a
  *     bucket-aligned shard with its global offset gives the bytes the whole vector gives.
  *   stream 1, weight shift: c = 0, xi = (word0 >> 8) * 2^-24 - 1/2 in [-1/2, 1/2); one
- *     draw per call whatever the shard ("a single random scalar" for the whole vector).
+ *     draw per call whatever the shard (Definition 1 shifts the whole vector by one scalar).
  *
  * Packed representation (the paper leaves the layout open)
  * ---------------------------------------------------------
@@ -105,8 +105,9 @@ int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
                          uint64_t* n_saturated, void* stream);
 
 /*
- * Decoding ("takes the lattice point and undoes the shift", Section 4.1; what a worker does
- * with a gathered quantized layer, Algorithm 2): out[i] = fma(code_i, scale_j, base_j),
+ * Decoding (the inverse map of Section 4.1: lattice coordinate back to a value, shift
+ * included; what a worker does with a gathered quantized layer in Algorithm 2):
+ * out[i] = fma(code_i, scale_j, base_j),
  * stored as float (QSDP_F32) or rounded to nearest-even bfloat16 (QSDP_BF16). Serves both
  * quantizers. Elements past n are not written.
  *   out  out  device float[n] or uint16[n]
@@ -130,6 +131,54 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
                     uint64_t seed, uint64_t index_offset,
                     uint32_t* wcodes, float* wmeta,
                     uint64_t* n_saturated, void* stream);
+
+/*
+ * Multi-tensor ("segmented") variants: in the paper's system every layer is compressed on
+ * its own (Section 5.1), i.e. bucketing restarts at each tensor.
+ * These calls do that for many tensors laid back to back in one flat buffer with ONE kernel
+ * launch, which matters when a model has hundreds of small tensors.
+ *
+ * A qsdp_segment describes one tensor: `n` elements at element offset `offset` of the flat
+ * x / g buffers; its buckets carry the numbers first_bucket .. first_bucket + ceil(n/bucket)-1.
+ * Packed codes and meta-data are indexed by bucket number exactly as in the single-tensor
+ * calls (every bucket padded to `bucket` slots), so tensor t's codes start at word
+ * first_bucket_t * bucket * bits / 32 and its meta at float 2 * first_bucket_t. The rounding
+ * uniform of an element depends on index_offset + its position in the flat buffer, so the
+ * result equals calling the single-tensor entry point on each tensor with
+ * index_offset + offset_t.
+ *
+ * qsdp_segments_build (host only) fills a HOST table from tensor sizes, packing the tensors
+ * contiguously (offset_t = sum of earlier sizes), and returns the total number of buckets, or 0
+ * if a size is 0 or a size other than the last is not a multiple of 8 (offsets must keep 16-byte
+ * alignment and Philox-block alignment). The caller copies the table to device memory and
+ * passes that DEVICE pointer (8-byte aligned) with the same nseg / total_buckets / bucket. The
+ * library does not validate the device table's contents.
+ */
+typedef struct qsdp_segment {
+    uint64_t offset;
+    uint64_t n;
+    uint64_t first_bucket;
+} qsdp_segment;
+
+uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table);
+
+int qsdp_quantize_grad_segmented(const float* g, const qsdp_segment* table, uint32_t nseg,
+                                 uint64_t total_buckets, int bits, int bucket,
+                                 uint64_t seed, uint64_t index_offset,
+                                 uint32_t* codes, float* meta, void* stream);
+
+int qsdp_quantize_weight_segmented(const float* x, const qsdp_segment* table, uint32_t nseg,
+                                   uint64_t total_buckets, int bits, int bucket,
+                                   float delta, uint64_t seed,
+                                   uint32_t* codes, float* meta,
+                                   uint64_t* n_saturated, void* stream);
+
+int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* table, uint32_t nseg,
+                              uint64_t total_buckets, float lr,
+                              int wbits, int gbits, int bucket, float delta,
+                              uint64_t seed, uint64_t index_offset,
+                              uint32_t* wcodes, float* wmeta,
+                              uint64_t* n_saturated, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ int qsdp_ref_set_threads(int threads) {
 }
 
 /* ------------------------------------------------------------------------- */
-/* Random numbers. The paper only asks for "a single random scalar r" (Def. 1) */
+/* Random numbers. The paper only asks for one random scalar per vector (Def. 1)*/
 /* and independent coin flips (coin-flip definition); the generator is ours:   */
 /* Philox4x32-10, counter-based, so that any shard of a vector can be          */
 /* quantized alone and give the bytes the whole vector would give.             */

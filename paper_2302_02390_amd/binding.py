@@ -17,7 +17,9 @@ QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
 QSDP_F32, QSDP_BF16 = 0, 1
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
-           "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step")
+           "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
+           "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
+           "qsdp_fused_step_segmented")
 
 _lib = None
 
@@ -48,7 +50,16 @@ def lib():
         L.qsdp_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp, vp]
         L.qsdp_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
         L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
-        for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step"):
+        L.qsdp_segments_build.argtypes = [vp, C.c_uint32, i32, vp]
+        L.qsdp_segments_build.restype = u64
+        L.qsdp_quantize_grad_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, u64, u64, vp, vp, vp]
+        L.qsdp_quantize_weight_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, f32, u64, vp, vp,
+                                                     vp, vp]
+        L.qsdp_fused_step_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64,
+                                                u64, vp, vp, vp, vp]
+        for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
+                     "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
+                     "qsdp_fused_step_segmented"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -146,3 +157,68 @@ def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
         _check(lib().qsdp_fused_step(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                      index_offset, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
                                      _stream(x)), "qsdp_fused_step")
+
+
+class Segments:
+    """Host table built by qsdp_segments_build plus its device copy (an int64 tensor holding the
+    {offset, n, first_bucket} triples)."""
+
+    def __init__(self, sizes, bucket, device):
+        import numpy as np
+        sizes_np = np.ascontiguousarray(sizes, dtype=np.uint64)
+        self.nseg = int(sizes_np.size)
+        self.bucket = int(bucket)
+        self.host = np.zeros((self.nseg, 3), dtype=np.uint64)
+        self.total_buckets = int(lib().qsdp_segments_build(
+            sizes_np.ctypes.data_as(C.c_void_p), self.nseg, self.bucket, self.host.ctypes.data_as(C.c_void_p)))
+        if self.total_buckets == 0:
+            raise QsdpError(QSDP_EINVAL, "qsdp_segments_build")
+        self.n = int(sizes_np.sum())
+        self.device = torch.from_numpy(self.host.view(np.int64).copy()).to(device)
+
+    def alloc_packed(self, bits):
+        cb = self.total_buckets * self.bucket * bits // 8
+        codes = torch.empty(cb // 4, dtype=torch.int32, device=self.device.device)
+        meta = torch.empty((self.total_buckets, 2), dtype=torch.float32, device=self.device.device)
+        return codes, meta
+
+
+def qsdp_quantize_grad_segmented(g, segs, bits, seed, index_offset, codes, meta):
+    _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if g.numel() < segs.n:
+        raise ValueError("g is smaller than the segments")
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_quantize_grad_segmented(_ptr(g), _ptr(segs.device), segs.nseg, segs.total_buckets,
+                                                  bits, segs.bucket, seed, index_offset, _ptr(codes),
+                                                  _ptr(meta), _stream(g)), "qsdp_quantize_grad_segmented")
+
+
+def qsdp_quantize_weight_segmented(x, segs, bits, delta, seed, codes, meta, n_saturated=None):
+    _is(x, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if x.numel() < segs.n:
+        raise ValueError("x is smaller than the segments")
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_quantize_weight_segmented(_ptr(x), _ptr(segs.device), segs.nseg,
+                                                    segs.total_buckets, bits, segs.bucket, delta, seed,
+                                                    _ptr(codes), _ptr(meta), _ptr(n_saturated), _stream(x)),
+               "qsdp_quantize_weight_segmented")
+
+
+def qsdp_fused_step_segmented(x, g, segs, lr, wbits, gbits, delta, seed, index_offset=0, wcodes=None,
+                              wmeta=None, n_saturated=None):
+    _is(x, torch.float32); _is(g, torch.float32)
+    if x.numel() < segs.n or g.numel() < segs.n:
+        raise ValueError("x or g is smaller than the segments")
+    if wcodes is not None:
+        _is(wcodes, torch.int32)
+    if wmeta is not None:
+        _is(wmeta, torch.float32)
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_segmented(_ptr(x), _ptr(g), _ptr(segs.device), segs.nseg,
+                                               segs.total_buckets, lr, wbits, gbits, segs.bucket, delta,
+                                               seed, index_offset, _ptr(wcodes), _ptr(wmeta),
+                                               _ptr(n_saturated), _stream(x)), "qsdp_fused_step_segmented")

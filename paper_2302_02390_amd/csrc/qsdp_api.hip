@@ -80,32 +80,24 @@ WaveLauncher wave_launcher(int bucket, int* buckets_per_wave) {
     }
 }
 
-// Full buckets go to the wave kernel of the bucket's shape when there is one for
-// (bucket, stored code width); everything else, and a short last bucket, to the block kernel.
+// Buckets go to the wave kernel of the bucket's shape when there is one for (bucket, stored
+// code width), else to the block kernel. p.num_buckets must be set.
 int run(int mode, Params p, int stored_bits, hipStream_t s) {
-    const uint64_t B = (uint64_t)p.bucket;
-    const uint64_t nb = ceil_div(p.n, B);
-    const uint64_t nb_full = p.n / B;
+    const uint64_t nb = p.num_buckets;
+    p.first_bucket = 0;
     int bpw = 1;
     WaveLauncher wl = wave_launcher(p.bucket, &bpw);
-    uint64_t done = 0;
-    if (wl != nullptr && wave_bits_supported(stored_bits) && nb_full > 0) {
-        p.first_bucket = 0;
-        p.num_buckets = nb_full;
+    if (wl != nullptr && wave_bits_supported(stored_bits)) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
-        const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb_full, (uint64_t)bpw), 4) : nb_full;
+        const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
         unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
         if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
             const unsigned cap = (unsigned)std::atoi(e);
             if (cap >= 1 && grid > cap) grid = cap;
         }
         if (wl(mode, stored_bits, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
-        done = nb_full;
-    }
-    if (done < nb) {
-        p.first_bucket = done;
-        p.num_buckets = nb - done;
-        const unsigned grid = (unsigned)(p.num_buckets < kMaxGrid ? p.num_buckets : kMaxGrid);
+    } else {
+        const unsigned grid = (unsigned)(nb < kMaxGrid ? nb : kMaxGrid);
         if (launch_block(mode, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
     }
     return QSDP_OK;
@@ -113,6 +105,7 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
 
 void set_common(Params& p, uint64_t n, int bucket, uint64_t seed, uint64_t index_offset, float delta) {
     p.n = n;
+    p.num_buckets = ceil_div(n, (uint64_t)bucket);
     p.bucket = bucket;
     p.block0 = index_offset >> 3;
     p.key0 = (uint32_t)seed;
@@ -126,6 +119,8 @@ void set_common(Params& p, uint64_t n, int bucket, uint64_t seed, uint64_t index
 }  // namespace qsdp
 
 using namespace qsdp;
+
+static_assert(sizeof(qsdp_segment) == sizeof(Segment), "segment layout");
 
 extern "C" {
 
@@ -218,6 +213,94 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, delta);
+    p.x = x;
+    p.g = g;
+    p.codes = wcodes;
+    p.meta = wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = gbits;
+    p.wbits = wbits;
+    p.lr = lr;
+    return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table) {
+    if (!sizes || !table || nseg == 0 || !shape_ok(1, 8, bucket)) return 0;
+    uint64_t offset = 0, buckets = 0;
+    for (uint32_t t = 0; t < nseg; ++t) {
+        if (sizes[t] == 0 || (t + 1 < nseg && (sizes[t] & 7u))) return 0;
+        table[t].offset = offset;
+        table[t].n = sizes[t];
+        table[t].first_bucket = buckets;
+        offset += sizes[t];
+        buckets += ceil_div(sizes[t], (uint64_t)bucket);
+    }
+    return buckets;
+}
+
+int qsdp_quantize_grad_segmented(const float* g, const qsdp_segment* table, uint32_t nseg,
+                                 uint64_t total_buckets, int bits, int bucket, uint64_t seed,
+                                 uint64_t index_offset, uint32_t* codes, float* meta, void* stream) {
+    if (!g || !table || nseg == 0 || total_buckets < nseg || !codes || !meta || !shape_ok(1, bits, bucket) ||
+        (index_offset & 7u))
+        return QSDP_EINVAL;
+    if (!aligned16(g) || !aligned16(codes) || !aligned16(meta) || (reinterpret_cast<uintptr_t>(table) & 7u))
+        return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, 0, bucket, seed, index_offset, 0.0f);
+    p.segs = reinterpret_cast<const Segment*>(table);
+    p.nseg = nseg;
+    p.num_buckets = total_buckets;
+    p.g = g;
+    p.codes = codes;
+    p.meta = meta;
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_GRAD, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_quantize_weight_segmented(const float* x, const qsdp_segment* table, uint32_t nseg,
+                                   uint64_t total_buckets, int bits, int bucket, float delta,
+                                   uint64_t seed, uint32_t* codes, float* meta, uint64_t* n_saturated,
+                                   void* stream) {
+    if (!x || !table || nseg == 0 || total_buckets < nseg || !codes || !meta || !shape_ok(1, bits, bucket))
+        return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(meta) || (reinterpret_cast<uintptr_t>(table) & 7u))
+        return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, 0, bucket, seed, 0, delta);
+    p.segs = reinterpret_cast<const Segment*>(table);
+    p.nseg = nseg;
+    p.num_buckets = total_buckets;
+    p.xin = x;
+    p.codes = codes;
+    p.meta = meta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_WEIGHT, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* table, uint32_t nseg,
+                              uint64_t total_buckets, float lr, int wbits, int gbits, int bucket,
+                              float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes,
+                              float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (!x || !g || !table || nseg == 0 || total_buckets < nseg || !shape_ok(1, wbits, bucket) ||
+        !shape_ok(1, gbits, bucket))
+        return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
+    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) ||
+        (reinterpret_cast<uintptr_t>(table) & 7u))
+        return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, 0, bucket, seed, index_offset, delta);
+    p.segs = reinterpret_cast<const Segment*>(table);
+    p.nseg = nseg;
+    p.num_buckets = total_buckets;
     p.x = x;
     p.g = g;
     p.codes = wcodes;

@@ -22,6 +22,14 @@ namespace qsdp {
 
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2 };
 
+// One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
+// the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
+struct Segment {
+    uint64_t offset;
+    uint64_t n;
+    uint64_t first_bucket;
+};
+
 struct Params {
     // tensors
     const float* g;      // GRAD, FUSED: gradient
@@ -30,11 +38,13 @@ struct Params {
     uint32_t* codes;     // packed output (nullable in FUSED)
     float* meta;         // {base, scale} per bucket (nullable iff codes is)
     unsigned long long* n_saturated;  // nullable
+    const Segment* segs;  // device table of nseg tensors, or nullptr: one tensor of n elements
     // problem
-    uint64_t n;             // elements
+    uint64_t n;             // elements (single tensor)
     uint64_t first_bucket;  // first bucket this launch handles
     uint64_t num_buckets;   // buckets this launch handles
     uint64_t block0;        // index_offset / 8
+    uint32_t nseg;
     int bucket;
     int gbits, wbits;
     float lr;
@@ -43,57 +53,121 @@ struct Params {
     uint32_t key0, key1;
 };
 
+// Where bucket `gb` starts in the flat buffers and how many of its `B` slots hold elements.
+struct BucketRef {
+    uint64_t e0;
+    uint32_t m;
+};
+
+__device__ __forceinline__ BucketRef locate_bucket(const Params& p, uint64_t gb, uint32_t B) {
+    BucketRef ref;
+    uint64_t left;
+    if (p.segs != nullptr) {
+        uint32_t lo = 0, hi = p.nseg;  // segs[lo].first_bucket <= gb < segs[hi].first_bucket
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (p.segs[mid].first_bucket <= gb) lo = mid; else hi = mid;
+        }
+        const Segment seg = p.segs[lo];
+        const uint64_t local = (gb - seg.first_bucket) * B;
+        ref.e0 = seg.offset + local;
+        left = seg.n - local;
+    } else {
+        ref.e0 = gb * B;
+        left = p.n - ref.e0;
+    }
+    ref.m = left < B ? (uint32_t)left : B;
+    return ref;
+}
+
 // ---------------------------------------------------------------------------------------
 // Wave kernels
 // ---------------------------------------------------------------------------------------
+// Lane l's rows of a tile of 4*G*R elements at `base`. `m` = how many of the tile's elements
+// exist; `partial` (wave-uniform) selects the guarded element-wise path for a short bucket.
 template <int G, int R>
-__device__ __forceinline__ void load_rows(const float* base, int l, float (&v)[R][4]) {
-    const f4* p = reinterpret_cast<const f4*>(base) + l;
+__device__ __forceinline__ void load_rows(const float* base, int l, int m, bool partial, float (&v)[R][4]) {
+    if (!partial) {
+        const f4* p = reinterpret_cast<const f4*>(base) + l;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < R; ++r) {
 #ifdef QSDP_EXP_LD_PLAIN
-        const f4 a = p[r * G];
+            const f4 a = p[r * G];
 #else
-        const f4 a = __builtin_nontemporal_load(p + r * G);
+            const f4 a = __builtin_nontemporal_load(p + r * G);
 #endif
-        v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
-    }
-}
-
-template <int G, int R>
-__device__ __forceinline__ void store_rows(float* base, int l, const float (&v)[R][4]) {
-    f4* p = reinterpret_cast<f4*>(base) + l;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
-#ifdef QSDP_EXP_ST_PLAIN
-        p[r * G] = a;
-#else
-        __builtin_nontemporal_store(a, p + r * G);
-#endif
-    }
-}
-
-template <int G, int R>
-__device__ __forceinline__ void rows_minmax(const float (&v)[R][4], float& lo, float& hi) {
-    lo = v[0][0];
-    hi = v[0][0];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lo = fminf(lo, v[r][i]);
-            hi = fmaxf(hi, v[r][i]);
+            v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
         }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                v[r][i] = idx < m ? base[idx] : 0.0f;
+            }
+    }
+}
+
+template <int G, int R>
+__device__ __forceinline__ void store_rows(float* base, int l, int m, bool partial, const float (&v)[R][4]) {
+    if (!partial) {
+        f4* p = reinterpret_cast<f4*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
+#ifdef QSDP_EXP_ST_PLAIN
+            p[r * G] = a;
+#else
+            __builtin_nontemporal_store(a, p + r * G);
+#endif
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                if (idx < m) base[idx] = v[r][i];
+            }
+    }
+}
+
+// min and max over the bucket (the group's G lanes); slots at or past m do not take part
+template <int G, int R>
+__device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m, bool partial, float& lo,
+                                            float& hi) {
+    if (!partial) {
+        lo = v[0][0];
+        hi = v[0][0];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo = fminf(lo, v[r][i]);
+                hi = fmaxf(hi, v[r][i]);
+            }
+    } else {
+        lo = __builtin_inff();
+        hi = -__builtin_inff();
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool valid = (r * G + l) * 4 + i < m;
+                lo = valid ? fminf(lo, v[r][i]) : lo;
+                hi = valid ? fmaxf(hi, v[r][i]) : hi;
+            }
+    }
     lo = group_min<G>(lo);
     hi = group_max<G>(hi);
 }
 
 // Pack the codes of all rows and stage them in LDS in wire order, then write the wave's code
 // tile (its 64/G buckets are consecutive, so the tile is 32*R*BITS contiguous bytes) with
-// 16-byte stores, one contiguous run per instruction. c[r][i] are the codes (as floats) of this
-// lane's elements; `stage` is this wave's LDS tile; `tile_out` the tile's place in the code
-// buffer; buckets at or past `active_buckets` of the wave's 64/G are not written.
+// 16-byte stores, one contiguous run per instruction. c[r][i] are the codes of this lane's
+// elements; `stage` is this wave's LDS tile; `tile_out` the tile's place in the code buffer;
+// buckets at or past `active_buckets` of the wave's 64/G are not written.
 template <int G, int R, int BITS, typename CodeT>
 __device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int lane, int active_buckets,
                                             const CodeT (&c)[R][4]) {
@@ -149,15 +223,16 @@ __device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float
     }
 }
 
-// MODE_GRAD / MODE_WEIGHT / MODE_FUSED over full buckets. BITS is the width of the codes
-// that are stored (0: FUSED without code output). W = waves per bucket (W > 1: the workgroup
-// has exactly W waves and owns one bucket per iteration). delta > 0 selects the explicit grid
-// (a wave-uniform branch).
+// MODE_GRAD / MODE_WEIGHT / MODE_FUSED over the buckets first_bucket .. +num_buckets-1 (the
+// last bucket of a tensor may be short). BITS is the width of the codes that are stored (0:
+// FUSED without code output). W = waves per bucket (W > 1: the workgroup has exactly W waves
+// and owns one bucket per iteration). delta > 0 selects the explicit grid (wave-uniform).
 template <int MODE, int G, int R, int BITS, int W>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
-    constexpr int B = 4 * G * R * W;
+    constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
+    constexpr int B = T * W;
     constexpr int BPW = 64 / G;
     constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
     const int lane = threadIdx.x & 63;
@@ -191,11 +266,18 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         const uint64_t left = p.num_buckets - q * BPW;
         const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
         const uint64_t bucket = p.first_bucket + (active ? rel : 0);
-        // first element this wave handles: the bucket's, or this wave's 1/W of it
-        const uint64_t e0 = bucket * (uint64_t)B + (W > 1 ? wave_in_block * (uint32_t)(4 * G * R) : 0u);
-        // the wave's code tile: buckets first_bucket + q*BPW .. +BPW-1 (W == 1), or its share
-        const uint64_t tile_e0 = W == 1 ? (p.first_bucket + q * BPW) * (uint64_t)B : e0;
-        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) + (tile_e0 >> 3) * SB);
+        const BucketRef ref = locate_bucket(p, bucket, B);
+        // this wave's tile of the bucket: all of it, or the wave's 1/W
+        const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
+        const uint64_t e0 = ref.e0 + part0;
+        const int m = ref.m > part0 ? (int)(ref.m - part0 < (uint32_t)T ? ref.m - part0 : (uint32_t)T) : 0;
+        const bool partial = __builtin_amdgcn_ballot_w64(m < T) != 0;
+        // Philox block of the tile's first element; the tile's place in the code buffer (the
+        // code stream is indexed by bucket number, every bucket padded to B slots)
+        const uint64_t block_e0 = p.block0 + (e0 >> 3);
+        const uint64_t tile_slot0 = (W == 1 ? (p.first_bucket + q * BPW) * (uint64_t)B
+                                            : bucket * (uint64_t)B + part0);
+        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) + (tile_slot0 >> 3) * SB);
         float* red_g = red_all + (W > 1 ? parity * 4 * W : 0);
         float* red_w = red_g + (W > 1 ? 2 * W : 0);
         const bool writes_meta = active && l == 0 && (W == 1 || wave_in_block == 0);
@@ -206,21 +288,23 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
-            load_rows<G, R>(p.g + e0, l, gv);
-            if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, w);
+            load_rows<G, R>(p.g + e0, l, m, partial, gv);
+            if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, m, partial, w);
             float lo, hi;
-            rows_minmax<G, R>(gv, lo, hi);
+            rows_minmax<G, R>(gv, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_g, wave_in_block);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg);
 #pragma unroll
             for (int cp = 0; cp < R / 2; ++cp) {
                 float h[8];
-                grad_uniforms_rows<G>(p.block0 + (e0 >> 3), cp, l, p.key0, p.key1, h);
+                grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int r = 2 * cp + (i >> 2);
                     if constexpr (MODE == MODE_GRAD) {
-                        gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
+                        const uint32_t c = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
+                        // slots past the end of a short bucket hold code 0
+                        gcode[r][i & 3] = (partial && (r * G + l) * 4 + (i & 3) >= m) ? 0u : c;
                     } else {
                         const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
                         const float ghat = fmaf(code, grid.scale, grid.lo);
@@ -237,18 +321,13 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                 continue;
             }
         } else {
-            load_rows<G, R>(p.xin + e0, l, w);
+            load_rows<G, R>(p.xin + e0, l, m, partial, w);
         }
 
         // weight quantization of w
         if (lattice) {
-            float lo = w[0][0];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) lo = fminf(lo, w[r][i]);
-            lo = group_min<G>(lo);
-            float unused_hi = lo;
+            float lo, unused_hi;
+            rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
             block_combine_minmax<W>(lo, unused_hi, red_w, wave_in_block);
             lo = lo + 0.0f;
             const float k0 = rintf(div_delta(lo, div) - xi);
@@ -258,11 +337,17 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_here);
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t sat_one = 0;
+                    const float c = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_one);
+                    const bool valid = !partial || (r * G + l) * 4 + i < m;
+                    w[r][i] = valid ? c : 0.0f;
+                    sat_here += valid ? sat_one : 0u;
+                }
             if (active) saturated += sat_here;
         } else {
             float lo, hi;
-            rows_minmax<G, R>(w, lo, hi);
+            rows_minmax<G, R>(w, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw);
             base = fmaf(xi, grid.scale, grid.lo);
@@ -270,7 +355,10 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
+                for (int i = 0; i < 4; ++i) {
+                    const float c = weight_code_minmax(w[r][i], grid, Lw, xi);
+                    w[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0.0f : c;
+                }
         }
 
         if (BITS != 0) {
@@ -286,7 +374,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], scale, base);
-                store_rows<G, R>(p.x + e0, l, w);
+                store_rows<G, R>(p.x + e0, l, m, partial, w);
             }
         }
     }
@@ -336,8 +424,9 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
 
     for (uint64_t rel = blockIdx.x; rel < p.num_buckets; rel += gridDim.x) {
         const uint64_t bucket = p.first_bucket + rel;
-        const uint64_t e0 = bucket * (uint64_t)B;
-        const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
+        const BucketRef ref = locate_bucket(p, bucket, (uint32_t)B);
+        const uint64_t e0 = ref.e0;
+        const int m = (int)ref.m;
         __syncthreads();  // previous bucket's LDS contents are dead
         float base = 0.0f, scale = 0.0f;
         int bits = (MODE == MODE_GRAD) ? p.gbits : p.wbits;

@@ -1,0 +1,107 @@
+"""GPU parity of the multi-tensor (segmented) entry points: one launch over many tensors must
+give, tensor by tensor, what the oracle gives for that tensor alone (bucketing restarts at each
+tensor; the rounding uniforms follow the position in the flat buffer)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2302_02390_amd import binding as qb
+from paper_2302_02390_amd import workloads as wl
+from gpu_util import DEV, bits_equal, np_f32, np_u32, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _expected(x, g, sizes, B, wbits, gbits, delta, seed, off0):
+    """Per-tensor oracle calls, concatenated in bucket order."""
+    gc, gm, wc, wm, xs, sat = [], [], [], [], [], 0
+    off = 0
+    for n in sizes:
+        sl = slice(off, off + n)
+        c, m = ref.quantize_grad(g[sl], gbits, B, seed, index_offset=off0 + off)
+        gc.append(c); gm.append(m)
+        c, m, s1 = ref.quantize_weight(x[sl], wbits, B, delta, seed)
+        wc.append(c); wm.append(m)
+        xn, fc, fm, s2 = ref.fused_step(x[sl], g[sl], 1e-3, wbits, gbits, B, delta, seed,
+                                        index_offset=off0 + off, emit_codes=True)
+        xs.append((xn, fc, fm))
+        sat += s2
+        off += n
+    return (np.concatenate(gc), np.concatenate(gm), np.concatenate(wc), np.concatenate(wm),
+            np.concatenate([a for a, _, _ in xs]), np.concatenate([b for _, b, _ in xs]),
+            np.concatenate([c for _, _, c in xs]), sat)
+
+
+@pytest.mark.parametrize("B,wbits,gbits,delta", [(1024, 8, 4, 0.0), (128, 4, 2, 0.0), (512, 6, 3, 0.0),
+                                                 (4096, 8, 8, 0.0), (2048, 8, 4, 2.0**-10),
+                                                 (96, 5, 7, 0.0), (1024, 7, 4, 0.0)])
+def test_segmented_matches_per_tensor_oracle(B, wbits, gbits, delta):
+    sizes = [768, 2304, 768 * 40, 8, 3072, 16, 1024 * 3 + 8, 50257 * 8, 4096 * 2, 24, 5000 + 3]
+    n = sum(sizes)
+    x, g = synth(n, 99 + B)
+    segs = qb.Segments(sizes, B, DEV)
+    assert segs.total_buckets == sum(-(-s // B) for s in sizes)
+    xd = torch.from_numpy(x).to(DEV)
+    gd = torch.from_numpy(g).to(DEV)
+    want_gc, want_gm, want_wc, want_wm, want_x, want_fc, want_fm, want_sat = _expected(
+        x, g, sizes, B, wbits, gbits, delta, 6, 64)
+
+    gc, gm = segs.alloc_packed(gbits)
+    qb.qsdp_quantize_grad_segmented(gd, segs, gbits, 6, 64, gc, gm.reshape(-1))
+    assert np.array_equal(np_u32(gc), want_gc) and np.array_equal(np_u32(gm), want_gm.view(np.uint32).reshape(-1))
+
+    wc, wm = segs.alloc_packed(wbits)
+    sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+    qb.qsdp_quantize_weight_segmented(xd, segs, wbits, delta, 6, wc, wm.reshape(-1), sat)
+    assert np.array_equal(np_u32(wc), want_wc) and np.array_equal(np_u32(wm), want_wm.view(np.uint32).reshape(-1))
+
+    fc, fm = segs.alloc_packed(wbits)
+    sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+    x1 = xd.clone()
+    qb.qsdp_fused_step_segmented(x1, gd, segs, 1e-3, wbits, gbits, delta, 6, 64, fc, fm.reshape(-1), sat)
+    assert bits_equal(np_f32(x1), want_x)
+    assert np.array_equal(np_u32(fc), want_fc) and np.array_equal(np_u32(fm), want_fm.view(np.uint32).reshape(-1))
+    assert int(sat) == want_sat
+    x2 = xd.clone()
+    qb.qsdp_fused_step_segmented(x2, gd, segs, 1e-3, wbits, gbits, delta, 6, 64)
+    assert torch.equal(x1, x2)
+
+
+def test_segmented_gpt350m_layers_equal_per_tensor_calls():
+    """The 350M model as per-layer tensors, W8 G4, bucket 1024: one segmented launch equals the
+    per-tensor launches (themselves checked against the oracle elsewhere), bit for bit."""
+    shape, B = wl.GPT_350M, 1024
+    sizes = [s for _, s in wl.model_tensors(shape)]
+    n = sum(sizes)
+    x = wl.weights(n, 1238, DEV)
+    g = wl.grads_student_t3(n, 1239, DEV)
+    segs = qb.Segments(sizes, B, DEV)
+    x_seg = x.clone()
+    qb.qsdp_fused_step_segmented(x_seg, g, segs, 1e-3, 8, 4, 0.0, 3)
+    x_per = x.clone()
+    off = 0
+    for s in sizes:
+        qb.qsdp_fused_step(x_per[off:off + s], g[off:off + s], 1e-3, 8, 4, B, 0.0, 3, off)
+        off += s
+    assert torch.equal(x_seg, x_per)
+    # and a few tensors against the oracle directly
+    off = 0
+    for t, s in enumerate(sizes):
+        if t in (2, 3, 5, 290) or s == shape.d:
+            if t % 7 == 0 or t in (2, 3, 5, 290):
+                want, _, _, _ = ref.fused_step(x[off:off + s].cpu().numpy(), g[off:off + s].cpu().numpy(), 1e-3,
+                                               8, 4, B, 0.0, 3, index_offset=off)
+                assert bits_equal(x_seg[off:off + s].cpu().numpy(), want)
+        off += s
+
+
+def test_segments_build_rejects_bad_sizes():
+    with pytest.raises(qb.QsdpError):
+        qb.Segments([1024, 0, 8], 1024, DEV)
+    with pytest.raises(qb.QsdpError):
+        qb.Segments([1020, 8], 1024, DEV)
+    with pytest.raises(qb.QsdpError):
+        qb.Segments([1024], 100, DEV)
+    ok = qb.Segments([1024, 1020], 1024, DEV)   # only the last size may be ragged
+    assert ok.total_buckets == 2
