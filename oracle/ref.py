@@ -20,7 +20,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # QSDP_REF_LIB: load another build of the oracle (the mutation tests plant mistakes in
+        # copies of the source to show that the pins catch them)
+        path = os.environ.get("QSDP_REF_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         u64, i32, f32, vp = C.c_uint64, C.c_int, C.c_float, C.c_void_p
         L.qsdp_ref_set_threads.argtypes = [i32]

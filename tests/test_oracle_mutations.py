@@ -1,0 +1,69 @@
+"""The pins must catch plausible mistakes. Each case plants ONE mistake in a copy of the oracle's
+source (on the CPU, never in the GPU path), builds it, and runs the pin tests against that build
+in a child process: at least one pin has to fail. An unmutated copy has to pass."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "qsdp_ref.c")
+
+# (name, text to replace, replacement, pin files expected to notice)
+MUTANTS = [
+    ("coin_flip_swapped", "(u[i] < frac ? 1 : 0)", "(u[i] >= frac ? 1 : 0)", ["test_oracle_grad.py"]),
+    ("levels_off_by_one", "float Lf = (float)((1 << bits) - 1);\n    float lo, hi, scale, inv;\n    bucket_stats(g,",
+     "float Lf = (float)(1 << bits);\n    float lo, hi, scale, inv;\n    bucket_stats(g,", ["test_oracle_grad.py"]),
+    ("floor_became_round", "float f = floorf(t);", "float f = rintf(t);", ["test_oracle_grad.py"]),
+    ("uniform_high_half_first", "(j % 2u) ? (w >> 16) : (w & 0xFFFFu)", "(j % 2u) ? (w & 0xFFFFu) : (w >> 16)",
+     ["test_oracle_rng.py"]),
+    ("philox_multipliers_swapped", "(uint64_t)0xD2511F53u * (uint64_t)c0", "(uint64_t)0xCD9E8D57u * (uint64_t)c0",
+     ["test_oracle_rng.py"]),
+    ("philox_nine_rounds", "round < 10", "round < 9", ["test_oracle_rng.py"]),
+    ("shift_sign_flipped", "float k = rintf(t - xi);", "float k = rintf(t + xi);", ["test_oracle_weight.py"]),
+    ("shift_missing_from_base", "*base_out = fmaf(xi, scale, lo);", "*base_out = lo;", ["test_oracle_weight.py"]),
+    ("lattice_shift_missing_from_base", "*base_out = (k0 + xi) * delta;", "*base_out = k0 * delta;",
+     ["test_oracle_weight.py"]),
+    ("lattice_saturation_not_counted", "*sat += 1u;", "", ["test_oracle_weight.py"]),
+    ("weight_shift_from_gradient_stream", "uint32_t ctr[4] = {0u, 0u, 1u, 0u};", "uint32_t ctr[4] = {0u, 0u, 0u, 0u};",
+     ["test_oracle_rng.py"]),
+    ("pack_bits_reversed", "words[p / 32] |= (uint32_t)1u << (p % 32);", "words[p / 32] |= (uint32_t)1u << (31 - p % 32);",
+     ["test_oracle_codec.py"]),
+    ("bf16_truncates", "bitsv += 0x7FFFu + ((bitsv >> 16) & 1u);", "", ["test_oracle_codec.py"]),
+    ("decode_not_fused", "out[i] = fmaf((float)code[i], scale, base);", "out[i] = (float)code[i] * scale + base;",
+     ["test_oracle_codec.py"]),
+    ("step_sign_flipped", "y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);", "y[i] = fmaf(lr, ghat[i], x[s + (uint64_t)i]);",
+     ["test_oracle_fused.py"]),
+    ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
+     "for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i];", ["test_oracle_fused.py"]),
+]
+
+
+def _build(tmp_path, name, text):
+    src = tmp_path / f"{name}.c"
+    src.write_text(text)
+    lib = tmp_path / f"lib{name}.so"
+    subprocess.run(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC",
+                    "-shared", "-I", os.path.join(ROOT, "oracle"), str(src), "-o", str(lib), "-lm"], check=True)
+    return str(lib)
+
+
+def _pins_pass(lib, files):
+    env = dict(os.environ, QSDP_REF_LIB=lib)
+    cmd = [sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"] + [
+        os.path.join(ROOT, "tests", f) for f in files]
+    return subprocess.run(cmd, env=env, cwd=ROOT, capture_output=True, text=True).returncode == 0
+
+
+def test_unmutated_copy_passes(tmp_path):
+    lib = _build(tmp_path, "plain", open(SRC).read())
+    assert _pins_pass(lib, ["test_oracle_rng.py", "test_oracle_codec.py"])
+
+
+@pytest.mark.parametrize("name,old,new,files", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new, files):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, "mutation site not found: the oracle changed, update this test"
+    lib = _build(tmp_path, name, text.replace(old, new, 1))
+    assert not _pins_pass(lib, files), f"no pin noticed the planted mistake '{name}'"
