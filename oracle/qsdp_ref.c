@@ -367,6 +367,32 @@ int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, in
     return QSDP_REF_OK;
 }
 
+/* Decode the slices of all peers and add them up in peer order, then scale. */
+int qsdp_ref_dequantize_add(const uint32_t* codes, uint64_t codes_stride_words, const float* meta,
+                            uint64_t meta_stride_floats, int npeers, uint64_t n, int bits,
+                            int bucket, float alpha, float* out) {
+    if (!codes || !meta || !out || npeers < 1 || !args_ok(n, bits, bucket) || !isfinite(alpha))
+        return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        uint8_t code[MAX_BUCKET];
+        float val[MAX_BUCKET], sum[MAX_BUCKET];
+        for (int p = 0; p < npeers; ++p) {
+            const uint32_t* pc = codes + (uint64_t)p * codes_stride_words;
+            const float* pm = meta + (uint64_t)p * meta_stride_floats;
+            unpack_bucket(pc + (uint64_t)j * (uint64_t)wpb, m, bits, code);
+            dequant_bucket(code, m, pm[2 * j], pm[2 * j + 1], val);
+            for (int i = 0; i < m; ++i) sum[i] = (p == 0) ? val[i] : sum[i] + val[i];
+        }
+        for (int i = 0; i < m; ++i) out[s + (uint64_t)i] = alpha * sum[i];
+    }
+    return QSDP_REF_OK;
+}
+
 /* x <- Q^w(x - lr * Q^g(g)): per bucket, quantize the gradient, decode it,
  * take the step, quantize the result, decode it (the iterate lives on the
  * quantization grid). The same seed drives both random streams. */

@@ -77,6 +77,14 @@ int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
                              uint32_t* codes, float* meta, uint64_t* n_saturated);
 int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                         int bucket, int out_dtype, void* out);
+/* Receive side of a quantized gradient exchange (Algorithm 2: every worker's quantized
+ * gradient slice arrives, the slices are decoded and summed before the weight update):
+ * out[i] = alpha * (((d_0[i] + d_1[i]) + d_2[i]) + ...), d_p = decoded slice of peer p, the
+ * sum taken in peer order with one binary32 rounding per addition. Peer p's codes start
+ * codes_stride_words words after peer p-1's, its meta meta_stride_floats floats after. */
+int qsdp_ref_dequantize_add(const uint32_t* codes, uint64_t codes_stride_words, const float* meta,
+                            uint64_t meta_stride_floats, int npeers, uint64_t n, int bits,
+                            int bucket, float alpha, float* out);
 int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr,
                         int wbits, int gbits, int bucket, float delta,
                         uint64_t seed, uint64_t index_offset,

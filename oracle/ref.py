@@ -48,6 +48,7 @@ def lib():
         L.qsdp_ref_quantize_grad.argtypes = [vp, u64, i32, i32, u64, u64, vp, vp]
         L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
         L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
+        L.qsdp_ref_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
         _lib = L
@@ -177,6 +178,17 @@ def dequantize(codes, meta, n, bits, bucket, out_dtype=F32):
     out = np.zeros(n, dtype=np.float32 if out_dtype == F32 else np.uint16)
     _check(lib().qsdp_ref_dequantize(_p(codes), _p(meta), n, bits, bucket, out_dtype, _p(out)),
            "dequantize")
+    return out
+
+
+def dequantize_add(codes, meta, npeers, n, bits, bucket, alpha):
+    """codes u32[npeers, words], meta f32[npeers, nb, 2] -> f32[n] = alpha * sum over peers."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint32).reshape(npeers, -1)
+    meta = np.ascontiguousarray(meta, dtype=np.float32).reshape(npeers, -1)
+    assert codes.shape[1] * 4 == codes_bytes(n, bits, bucket) and meta.shape[1] == 2 * _nb(n, bucket)
+    out = np.zeros(n, dtype=np.float32)
+    _check(lib().qsdp_ref_dequantize_add(_p(codes), codes.shape[1], _p(meta), meta.shape[1], npeers, n,
+                                         bits, bucket, float(alpha), _p(out)), "dequantize_add")
     return out
 
 

@@ -33,6 +33,10 @@ MUTANTS = [
     ("bf16_truncates", "bitsv += 0x7FFFu + ((bitsv >> 16) & 1u);", "", ["test_oracle_codec.py"]),
     ("decode_not_fused", "out[i] = fmaf((float)code[i], scale, base);", "out[i] = (float)code[i] * scale + base;",
      ["test_oracle_codec.py"]),
+    ("peer_sum_keeps_last_only", "sum[i] = (p == 0) ? val[i] : sum[i] + val[i];", "sum[i] = val[i];",
+     ["test_oracle_dequantize_add.py"]),
+    ("peer_sum_not_scaled", "out[s + (uint64_t)i] = alpha * sum[i];", "out[s + (uint64_t)i] = sum[i];",
+     ["test_oracle_dequantize_add.py"]),
     ("step_sign_flipped", "y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);", "y[i] = fmaf(lr, ghat[i], x[s + (uint64_t)i]);",
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
