@@ -25,7 +25,7 @@ BYTES_PER_PARAM = 12.0
 # HBM bytes per fused-step launch on the 1.3B workload from rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by the same counters on a plain copy kernel); see
 # profiles/fused_step_gpt1p3b.md.
-MEASURED_TRAFFIC_BYTES = 15788682854
+MEASURED_TRAFFIC_BYTES = 15788726884
 
 
 def parse():
@@ -229,6 +229,30 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
         2 + wbits / 8.0 + meta_b)
     run(f"dequantize_b{gbits}_bf16", lambda i: qb.qsdp_dequantize(gc, gm, n, gbits, bucket, out16),
         2 + gbits / 8.0 + meta_b)
+    del out16
+    # decode-and-sum of 8 peers' gradient slices on one GPU's 1/8 shard (the receive side of the
+    # quantized gradient exchange): the 8 slices are 8 quantizations of the shard with different seeds
+    peers = 8
+    m = (n // peers) // bucket * bucket
+    nbm = m // bucket
+    pc = torch.empty((peers, nbm * bucket * gbits // 32), dtype=torch.int32, device=dev)
+    pm = torch.empty((peers, nbm * 2), dtype=torch.float32, device=dev)
+    for p in range(peers):
+        qb.qsdp_quantize_grad(g[:m], gbits, bucket, 100 + p, 0, pc[p], pm[p])
+    acc = torch.empty(m, dtype=torch.float32, device=dev)
+    n_saved, n = n, m
+
+    def run_small(name, fn, bytes_per_param):
+        for i in range(3):
+            fn(i)
+        mean, _ = time_call(fn, 10, torch)
+        res[name] = {"ms": round(mean, 4), "GB/s": round(bytes_per_param * m / (mean * 1e-3) / 1e9, 1),
+                     "bytes_per_param": round(bytes_per_param, 4), "n": m}
+
+    run_small(f"dequantize_add_{peers}peers_b{gbits}",
+              lambda i: qb.qsdp_dequantize_add(pc, pm, peers, m, gbits, bucket, 1.0 / peers, acc),
+              peers * (gbits / 8.0 + meta_b) + 4)
+    n = n_saved
     return res
 
 

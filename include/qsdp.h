@@ -116,6 +116,22 @@ int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bi
                     int bucket, qsdp_dtype out_dtype, void* out, void* stream);
 
 /*
+ * Decode-and-sum, the receive side of a quantized gradient exchange (Algorithm 2: the
+ * quantized gradient slices of all workers reach the owner of a shard, which decodes and adds
+ * them before the weight update; codes with different per-bucket scales cannot be added in
+ * flight): out[i] = alpha * (((d_0[i] + d_1[i]) + d_2[i]) + ...), d_p = decoded slice of peer p
+ * (as qsdp_dequantize would give), summed in peer order with one rounding per addition; pass
+ * alpha = 1/npeers for the average. Peer p's packed codes start p * codes_stride_bytes after
+ * `codes`, its meta p * meta_stride_bytes after `meta` (a receive buffer with one slot per
+ * peer); strides are multiples of 4 and at least the size of one slice.
+ *   out  out  device float[n]
+ */
+int qsdp_dequantize_add(const uint32_t* codes, uint64_t codes_stride_bytes,
+                        const float* meta, uint64_t meta_stride_bytes, int npeers,
+                        uint64_t n, int bits, int bucket, float alpha,
+                        float* out, void* stream);
+
+/*
  * Fused quantized SGD step, in place: x <- Q^w(x - lr * Q^g(g)) (Section 3.3 / 4.1), one
  * pass over HBM (read x, read g, write x). Per bucket: Q^g of g with `gbits`, decoded in
  * registers; y = fma(-lr, ghat, x); Q^w of y with `wbits` (delta as in

@@ -18,7 +18,7 @@ QSDP_F32, QSDP_BF16 = 0, 1
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
-           "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
+           "qsdp_dequantize_add", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented")
 
 _lib = None
@@ -50,6 +50,8 @@ def lib():
         L.qsdp_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp, vp]
         L.qsdp_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
         L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
+        L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
+        L.qsdp_dequantize_add.restype = i32
         L.qsdp_segments_build.argtypes = [vp, C.c_uint32, i32, vp]
         L.qsdp_segments_build.restype = u64
         L.qsdp_quantize_grad_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, u64, u64, vp, vp, vp]
@@ -140,6 +142,19 @@ def qsdp_dequantize(codes, meta, n, bits, bucket, out):
     with torch.cuda.device(out.device):
         _check(lib().qsdp_dequantize(_ptr(codes), _ptr(meta), n, bits, bucket, dt, _ptr(out),
                                      _stream(out)), "qsdp_dequantize")
+
+
+def qsdp_dequantize_add(codes, meta, npeers, n, bits, bucket, alpha, out):
+    """codes int32[npeers, words], meta float32[npeers, nb*2] (row p = peer p's slice)."""
+    _is(codes, torch.int32); _is(meta, torch.float32); _is(out, torch.float32)
+    if codes.dim() != 2 or meta.dim() != 2 or codes.shape[0] != npeers or meta.shape[0] != npeers:
+        raise ValueError("codes and meta must be [npeers, ...]")
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize_add(_ptr(codes), codes.stride(0) * 4, _ptr(meta), meta.stride(0) * 4,
+                                         npeers, n, bits, bucket, alpha, _ptr(out), _stream(out)),
+               "qsdp_dequantize_add")
 
 
 def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, wcodes=None,

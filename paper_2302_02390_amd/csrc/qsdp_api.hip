@@ -20,17 +20,55 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
     return hipGetLastError();
 }
 
+// Which bucket-index scheme the decoder kernels use for this call (tile = elements per wave).
+static int bucket_indexing(const DequantParams& p, bool bf16) {
+    const uint32_t tile32 = (uint32_t)kDequantRows * 64u * (bf16 ? 8u : 4u) / 32u;
+    if (p.bucket32 % tile32 == 0) return BK_TILE_UNIFORM;
+    return p.bucket32_shift >= 0 ? BK_SHIFT : BK_DIVIDE;
+}
+
 namespace {
 template <int BITS>
 hipError_t dequant_go(bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
-    const bool pow2 = p.bucket32_shift >= 0;
-    if (bf16 && pow2) hipLaunchKernelGGL((dequant_kernel<BITS, true, true>), dim3(grid), dim3(256), 0, s, p);
-    else if (bf16) hipLaunchKernelGGL((dequant_kernel<BITS, true, false>), dim3(grid), dim3(256), 0, s, p);
-    else if (pow2) hipLaunchKernelGGL((dequant_kernel<BITS, false, true>), dim3(grid), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((dequant_kernel<BITS, false, false>), dim3(grid), dim3(256), 0, s, p);
+    const int bk = bucket_indexing(p, bf16);
+    if (bf16) {
+        if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, p);
+        else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_SHIFT>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, p);
+    } else {
+        if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, p);
+        else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_SHIFT>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, p);
+    }
     return hipGetLastError();
 }
 }  // namespace
+
+namespace {
+template <int BITS>
+hipError_t dequant_add_go(const DequantAddParams& p, unsigned grid, hipStream_t s) {
+    switch (bucket_indexing(p.d, false)) {
+        case BK_TILE_UNIFORM: hipLaunchKernelGGL((dequant_add_kernel<BITS, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, p); break;
+        case BK_SHIFT: hipLaunchKernelGGL((dequant_add_kernel<BITS, BK_SHIFT>), dim3(grid), dim3(256), 0, s, p); break;
+        default: hipLaunchKernelGGL((dequant_add_kernel<BITS, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, p); break;
+    }
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_dequant_add(int bits, const DequantAddParams& p, unsigned grid, hipStream_t s) {
+    switch (bits) {
+        case 1: return dequant_add_go<1>(p, grid, s);
+        case 2: return dequant_add_go<2>(p, grid, s);
+        case 3: return dequant_add_go<3>(p, grid, s);
+        case 4: return dequant_add_go<4>(p, grid, s);
+        case 5: return dequant_add_go<5>(p, grid, s);
+        case 6: return dequant_add_go<6>(p, grid, s);
+        case 7: return dequant_add_go<7>(p, grid, s);
+        case 8: return dequant_add_go<8>(p, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
     switch (bits) {
@@ -178,28 +216,58 @@ int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float
     return run(MODE_WEIGHT, p, bits, static_cast<hipStream_t>(stream));
 }
 
-int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
-                    qsdp_dtype out_dtype, void* out, void* stream) {
-    if (!codes || !meta || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
-    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
-    if (n >= (1ull << 37)) return QSDP_EINVAL;  // the decoder indexes buckets with 32-bit arithmetic
-    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
+static DequantParams decoder_params(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                                    int bucket, bool bf16, void* out, unsigned* grid) {
     DequantParams p = {};
     p.codes = codes;
     p.meta = meta;
     p.out = out;
     p.n = n;
     p.nwords = qsdp_codes_bytes(n, bits, bucket) / 4;
-    const uint64_t tile = (uint64_t)kDequantRows * 64u * (out_dtype == QSDP_BF16 ? 8u : 4u);
+    const uint64_t tile = (uint64_t)kDequantRows * 64u * (bf16 ? 8u : 4u);
     p.ntiles = ceil_div(n, tile);
     p.bucket32 = (uint32_t)bucket / 32u;
     p.bucket32_shift = -1;
     for (int sh = 0; sh < 9; ++sh)
         if (p.bucket32 == (1u << sh)) p.bucket32_shift = sh;
     const uint64_t blocks = ceil_div(p.ntiles, 4);
-    const unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+    *grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+    return p;
+}
+
+int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
+                    qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!codes || !meta || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (n >= (1ull << 37)) return QSDP_EINVAL;  // the decoder indexes buckets with 32-bit arithmetic
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
+    unsigned grid = 0;
+    const DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype == QSDP_BF16, out, &grid);
     if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_dequantize_add(const uint32_t* codes, uint64_t codes_stride_bytes, const float* meta,
+                        uint64_t meta_stride_bytes, int npeers, uint64_t n, int bits, int bucket,
+                        float alpha, float* out, void* stream) {
+    if (!codes || !meta || !out || npeers < 1 || !shape_ok(n, bits, bucket) || !std::isfinite(alpha))
+        return QSDP_EINVAL;
+    if (n >= (1ull << 37)) return QSDP_EINVAL;
+    if (npeers > 1 && (codes_stride_bytes < qsdp_codes_bytes(n, bits, bucket) ||
+                       meta_stride_bytes < qsdp_meta_bytes(n, bucket)))
+        return QSDP_EINVAL;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (codes_stride_bytes & 3u) ||
+        (meta_stride_bytes & 3u))
+        return QSDP_EALIGN;
+    DequantAddParams q = {};
+    unsigned grid = 0;
+    q.d = decoder_params(codes, meta, n, bits, bucket, false, out, &grid);
+    q.codes_stride_words = codes_stride_bytes / 4;
+    q.meta_stride_floats = meta_stride_bytes / 4;
+    q.npeers = npeers;
+    q.alpha = alpha;
+    if (launch_dequant_add(bits, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess) return QSDP_ELAUNCH;
     return QSDP_OK;
 }
 

@@ -572,11 +572,18 @@ __device__ __forceinline__ uint64_t load_bits(const uint32_t* codes, uint64_t bi
     }
 }
 
-template <bool POW2>
+// How a decoder lane finds the bucket of element e (32-bit arithmetic; the host checks
+// n < 2^37): by division, by shift (bucket a power of two), or once per wave tile when the
+// bucket size is a multiple of the tile (the index is then wave-uniform and the meta-data is
+// fetched with scalar loads, which keeps the vector memory pipeline for codes and output).
+enum BucketIndexing { BK_DIVIDE = 0, BK_SHIFT = 1, BK_TILE_UNIFORM = 2 };
+
+template <int BK>
 __device__ __forceinline__ uint64_t bucket_of(uint64_t e, const DequantParams& p) {
-    // e / bucket with 32-bit arithmetic (the host checks n < 2^37)
     const uint32_t e32 = (uint32_t)(e >> 5);
-    return POW2 ? (e32 >> p.bucket32_shift) : (e32 / p.bucket32);
+    if (BK == BK_SHIFT) return e32 >> p.bucket32_shift;
+    if (BK == BK_TILE_UNIFORM) return __builtin_amdgcn_readfirstlane(e32 / p.bucket32);
+    return e32 / p.bucket32;
 }
 
 template <int BITS, bool BF16>
@@ -609,7 +616,7 @@ __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e,
     }
 }
 
-template <int BITS, bool BF16, bool POW2>
+template <int BITS, bool BF16, int BK>
 __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
     constexpr int E = BF16 ? 8 : 4;
     constexpr int U = kDequantRows;
@@ -630,7 +637,7 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
             for (int u = 0; u < U; ++u) {
                 const uint64_t e = e0 + (uint64_t)(u * 64 * E);
                 bits[u] = load_bits<E * BITS>(p.codes, e * BITS, last_word);
-                const uint64_t bucket = bucket_of<POW2>(e, p);
+                const uint64_t bucket = bucket_of<BK>(e, p);
                 base[u] = p.meta[2 * bucket];
                 scale[u] = p.meta[2 * bucket + 1];
             }
@@ -643,10 +650,94 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
                 const uint64_t e = e0 + (uint64_t)(u * 64 * E);
                 if (e < p.n) {
                     const uint64_t bits = load_bits<E * BITS>(p.codes, e * BITS, last_word);
-                    const uint64_t bucket = bucket_of<POW2>(e, p);
+                    const uint64_t bucket = bucket_of<BK>(e, p);
                     decode_store<BITS, BF16>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
                                              e + E <= p.n);
                 }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Decode-and-sum of P peers' slices: out = alpha * (((d_0 + d_1) + d_2) + ...), d_p the decoded
+// slice of peer p. Same tiling as the decoder with fp32 output; peers are read in order.
+// ---------------------------------------------------------------------------------------
+struct DequantAddParams {
+    DequantParams d;             // d.codes / d.meta: peer 0; d.out: float[n]
+    uint64_t codes_stride_words;  // peer p's codes start p * stride words further
+    uint64_t meta_stride_floats;
+    int npeers;
+    float alpha;
+};
+
+template <int BITS, int BK>
+__global__ void __launch_bounds__(256) dequant_add_kernel(const DequantAddParams q) {
+    constexpr int E = 4;
+    constexpr int U = kDequantRows;
+    constexpr uint64_t T = (uint64_t)U * 64 * E;
+    const DequantParams& p = q.d;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t waves_per_block = blockDim.x >> 6;
+    const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
+    const uint64_t last_word = p.nwords - 1;
+    float* out = static_cast<float*>(p.out);
+    for (uint64_t tile = (uint64_t)blockIdx.x * waves_per_block + wave_in_block; tile < p.ntiles;
+         tile += nwaves) {
+        const uint64_t e0 = tile * T + (uint64_t)(lane * E);
+        const bool whole_tile = (tile + 1) * T <= p.n;  // wave-uniform
+        float sum[U][E];
+        uint64_t bucket[U];
+        bool in_range[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t e = e0 + (uint64_t)(u * 64 * E);
+            in_range[u] = whole_tile || e < p.n;
+            bucket[u] = bucket_of<BK>(in_range[u] ? e : 0, p);
+        }
+        // peers in groups of kPeerGroup: all loads of a group are issued before the first add
+        constexpr int kPeerGroup = 4;
+        for (int peer0 = 0; peer0 < q.npeers; peer0 += kPeerGroup) {
+            uint64_t bits[kPeerGroup][U];
+            float base[kPeerGroup][U], scale[kPeerGroup][U];
+#pragma unroll
+            for (int k = 0; k < kPeerGroup; ++k) {
+                // past the last peer: re-read the last one (in bounds), its values are not used
+                const int peer = peer0 + k < q.npeers ? peer0 + k : q.npeers - 1;
+                const uint32_t* codes = p.codes + (uint64_t)peer * q.codes_stride_words;
+                const float* meta = p.meta + (uint64_t)peer * q.meta_stride_floats;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint64_t e = in_range[u] ? e0 + (uint64_t)(u * 64 * E) : 0;
+                    bits[k][u] = load_bits<E * BITS>(codes, e * BITS, last_word);
+                    base[k][u] = meta[2 * bucket[u]];
+                    scale[k][u] = meta[2 * bucket[u] + 1];
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kPeerGroup; ++k) {
+                if (peer0 + k < q.npeers) {  // wave-uniform
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int i = 0; i < E; ++i) {
+                            const uint32_t c = (uint32_t)(bits[k][u] >> (i * BITS)) & ((1u << BITS) - 1u);
+                            const float d = fmaf((float)c, scale[k][u], base[k][u]);
+                            sum[u][i] = (peer0 + k == 0) ? d : sum[u][i] + d;
+                        }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t e = e0 + (uint64_t)(u * 64 * E);
+            if (whole_tile || e + E <= p.n) {
+                const f4 a = {q.alpha * sum[u][0], q.alpha * sum[u][1], q.alpha * sum[u][2], q.alpha * sum[u][3]};
+                __builtin_nontemporal_store(a, reinterpret_cast<f4*>(out + e));
+            } else if (e < p.n) {
+                for (int i = 0; i < E; ++i)
+                    if (e + i < p.n) out[e + i] = q.alpha * sum[u][i];
             }
         }
     }
