@@ -230,6 +230,10 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"dequantize_b{gbits}_bf16", lambda i: qb.qsdp_dequantize(gc, gm, n, gbits, bucket, out16),
         2 + gbits / 8.0 + meta_b)
     del out16
+    # the fused step with x resident as codes (wc, wm hold Q^w(x) from the call above)
+    run(f"fused_step_codes_W{wbits}G{gbits}",
+        lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i),
+        4 + 2 * (wbits / 8.0 + meta_b))
     # decode-and-sum of 8 peers' gradient slices on one GPU's 1/8 shard (the receive side of the
     # quantized gradient exchange): the 8 slices are 8 quantizations of the shard with different seeds
     peers = 8

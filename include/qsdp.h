@@ -149,6 +149,21 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
                     uint64_t* n_saturated, void* stream);
 
 /*
+ * The same step with the weights RESIDENT AS CODES: every iterate of the quantized iteration
+ * lies on its bucket grids (Section 4.1: the iterates live in the lattice domain), so
+ * (wcodes, wmeta) hold x_t exactly and the fp32 copy is redundant. The call decodes x_t in
+ * registers, takes the step and writes the codes and meta of x_{t+1} back in place:
+ * 4 + 2*wbits/8 bytes of HBM traffic per parameter instead of 12. Bit-identical to
+ * qsdp_dequantize followed by qsdp_fused_step with code output.
+ *   wcodes, wmeta  in/out  packed Q^w representation of x (as written by qsdp_quantize_weight
+ *                  or a fused step with the same wbits and bucket)
+ */
+int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
+                          int wbits, int gbits, int bucket, float delta,
+                          uint64_t seed, uint64_t index_offset,
+                          uint64_t* n_saturated, void* stream);
+
+/*
  * Multi-tensor ("segmented") variants: in the paper's system every layer is compressed on
  * its own (Section 5.1), i.e. bucketing restarts at each tensor.
  * These calls do that for many tensors laid back to back in one flat buffer with ONE kernel

@@ -91,6 +91,12 @@ int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr,
                         uint32_t* wcodes /* nullable */, float* wmeta /* nullable */,
                         uint64_t* n_saturated /* nullable */);
 
+/* The step on weights held as codes: decode (wcodes, wmeta), take the fused step, write the
+ * codes and meta of the result back. By definition the composition of the two routines. */
+int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
+                              int wbits, int gbits, int bucket, float delta,
+                              uint64_t seed, uint64_t index_offset, uint64_t* n_saturated);
+
 #ifdef __cplusplus
 }
 #endif

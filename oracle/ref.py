@@ -49,6 +49,7 @@ def lib():
         L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
         L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
         L.qsdp_ref_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp]
+        L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
         _lib = L
@@ -207,3 +208,17 @@ def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit
                                      float(delta), int(seed), int(index_offset),
                                      _p(wcodes), _p(wmeta), _p(sat)), "fused_step")
     return x, wcodes, wmeta, int(sat[0])
+
+
+def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0):
+    """Returns (new wcodes, new wmeta, n_saturated); inputs are not modified."""
+    g = _f32(g)
+    n = g.size
+    wcodes = np.ascontiguousarray(wcodes, dtype=np.uint32).reshape(-1).copy()
+    wmeta = np.ascontiguousarray(wmeta, dtype=np.float32).reshape(-1, 2).copy()
+    assert wcodes.size * 4 == codes_bytes(n, wbits, bucket) and wmeta.shape[0] == _nb(n, bucket)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_fused_step_codes(_p(wcodes), _p(wmeta), _p(g), n, float(lr), wbits, gbits, bucket,
+                                           float(delta), int(seed), int(index_offset), _p(sat)),
+           "fused_step_codes")
+    return wcodes, wmeta, int(sat[0])

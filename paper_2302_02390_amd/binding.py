@@ -18,7 +18,7 @@ QSDP_F32, QSDP_BF16 = 0, 1
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
-           "qsdp_dequantize_add", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
+           "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented")
 
 _lib = None
@@ -52,6 +52,8 @@ def lib():
         L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
         L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
         L.qsdp_dequantize_add.restype = i32
+        L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp]
+        L.qsdp_fused_step_codes.restype = i32
         L.qsdp_segments_build.argtypes = [vp, C.c_uint32, i32, vp]
         L.qsdp_segments_build.restype = u64
         L.qsdp_quantize_grad_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, u64, u64, vp, vp, vp]
@@ -172,6 +174,17 @@ def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
         _check(lib().qsdp_fused_step(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                      index_offset, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
                                      _stream(x)), "qsdp_fused_step")
+
+
+def qsdp_fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
+                          n_saturated=None):
+    _is(wcodes, torch.int32); _is(wmeta, torch.float32); _is(g, torch.float32)
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_fused_step_codes(_ptr(wcodes), _ptr(wmeta), _ptr(g), g.numel(), lr, wbits, gbits,
+                                           bucket, delta, seed, index_offset, _ptr(n_saturated), _stream(g)),
+               "qsdp_fused_step_codes")
 
 
 class Segments:

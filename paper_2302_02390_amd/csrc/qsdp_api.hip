@@ -15,6 +15,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_GRAD: hipLaunchKernelGGL(block_kernel<MODE_GRAD>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_WEIGHT: hipLaunchKernelGGL(block_kernel<MODE_WEIGHT>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -290,6 +291,25 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
     p.wbits = wbits;
     p.lr = lr;
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,
+                          int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                          uint64_t* n_saturated, void* stream) {
+    if (!wcodes || !wmeta || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket)) return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(wcodes) || !aligned16(wmeta) || !aligned16(g)) return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, index_offset, delta);
+    p.g = g;
+    p.codes = wcodes;
+    p.meta = wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = gbits;
+    p.wbits = wbits;
+    p.lr = lr;
+    return run(MODE_FUSED_CODES, p, wbits, static_cast<hipStream_t>(stream));
 }
 
 uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table) {

@@ -233,6 +233,26 @@ __device__ __forceinline__ void store_chunk(uint8_t* p, uint64_t v) {
     }
 }
 
+template <int BITS>
+__device__ __forceinline__ uint64_t load_chunk(const uint8_t* p) {
+    if (BITS == 8) {
+        u2 w = *reinterpret_cast<const u2*>(p);
+        return (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    } else if (BITS == 4) {
+        return *reinterpret_cast<const uint32_t*>(p);
+    } else if (BITS == 2) {
+        return *reinterpret_cast<const uint16_t*>(p);
+    } else if (BITS == 6) {
+        const uint16_t* q = reinterpret_cast<const uint16_t*>(p);
+        return (uint64_t)q[0] | ((uint64_t)q[1] << 16) | ((uint64_t)q[2] << 32);
+    } else {
+        uint64_t v = 0;
+#pragma unroll
+        for (int i = 0; i < BITS; ++i) v |= (uint64_t)p[i] << (8 * i);
+        return v;
+    }
+}
+
 // binary32 -> bfloat16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t bf16_bits(float v) {
     uint32_t b = __float_as_uint(v);

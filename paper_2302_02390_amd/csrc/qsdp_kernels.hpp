@@ -20,7 +20,10 @@
 
 namespace qsdp {
 
-enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2 };
+// MODE_FUSED_CODES: the fused step with the weights resident as packed codes + meta (the
+// iterate always lies on its bucket grids, so codes + meta hold it exactly): decode, step,
+// re-quantize, write codes + meta back in place; no fp32 copy of x is read or written.
+enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3 };
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
@@ -204,6 +207,49 @@ __device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int la
     __builtin_amdgcn_wave_barrier();
 }
 
+// The reverse of store_codes: stage the wave's code tile in LDS with 16-byte loads, then give
+// every lane the codes of its own elements (as floats). The even lane reads the chunk of row
+// 2cp (its own 4 codes, then its partner's), the odd lane that of row 2cp+1 (its partner's 4
+// codes, then its own); one DPP quad permute hands each lane the half it lacks.
+template <int G, int R, int BITS>
+__device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, int lane, int active_buckets,
+                                           float (&c)[R][4]) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;
+    constexpr uint32_t kHalfMask = (BITS == 8) ? 0xFFFFFFFFu : ((1u << (4 * BITS)) - 1u);
+    const int l = lane % G;
+    const int sub = lane / G;
+    const int odd = l & 1;
+    u4* staged = reinterpret_cast<u4*>(stage);
+#pragma unroll
+    for (int k0 = 0; k0 < kPieces; k0 += 64) {
+        const int k = k0 + lane;
+        if (k < kPieces && (k * 16) / kBucketBytes < active_buckets)
+            staged[k] = __builtin_nontemporal_load(tile_in + k);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int cp = 0; cp < R / 2; ++cp) {
+        const int chunk_index = ((2 * cp + odd) * G + (l - odd)) >> 1;
+        const uint64_t chunk = load_chunk<BITS>(stage + sub * kBucketBytes + chunk_index * BITS);
+        const uint32_t lo4 = (uint32_t)chunk & kHalfMask;
+        const uint32_t hi4 = (uint32_t)(chunk >> (4 * BITS)) & kHalfMask;
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(odd ? lo4 : hi4), 0xB1, 0xF, 0xF,
+                                                                    false);
+        const uint32_t q0 = odd ? recv : lo4;  // this lane's 4 codes of row 2cp
+        const uint32_t q1 = odd ? hi4 : recv;  // ... of row 2cp+1
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            c[2 * cp][i] = (float)((q0 >> (i * BITS)) & ((1u << BITS) - 1u));
+            c[2 * cp + 1][i] = (float)((q1 >> (i * BITS)) & ((1u << BITS) - 1u));
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Combine per-wave (lo, hi) across the W waves of a workgroup that share a bucket. `slot` is a
 // [2][W] LDS array that no other reduction uses; callers alternate two slots between loop
 // iterations so that a fast wave's next write cannot overtake a slow wave's read.
@@ -285,11 +331,21 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
+        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES) {
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
             load_rows<G, R>(p.g + e0, l, m, partial, gv);
             if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, m, partial, w);
+            if constexpr (MODE == MODE_FUSED_CODES) {
+                // x = decode(codes, meta) in registers
+                load_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
+                const float xbase = p.meta[2 * bucket];
+                const float xscale = p.meta[2 * bucket + 1];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], xscale, xbase);
+            }
             float lo, hi;
             rows_minmax<G, R>(gv, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_g, wave_in_block);
@@ -431,7 +487,13 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
         float base = 0.0f, scale = 0.0f;
         int bits = (MODE == MODE_GRAD) ? p.gbits : p.wbits;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED) {
+        // MODE_FUSED_CODES: the old iterate is decoded from the bucket's codes and meta
+        const int wpb_in = B * p.wbits / 32;
+        const uint32_t* old_words = (MODE == MODE_FUSED_CODES) ? p.codes + bucket * (uint64_t)wpb_in : nullptr;
+        const float old_base = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket] : 0.0f;
+        const float old_scale = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket + 1] : 0.0f;
+
+        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES) {
             float lo = __builtin_inff(), hi = -__builtin_inff();
             for (int i = tid; i < m; i += 256) {
                 const float v = p.g[e0 + i];
@@ -454,7 +516,17 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                     code[i] = (uint8_t)(uint32_t)c;
                 } else {
                     const float ghat = fmaf(c, grid.scale, grid.lo);
-                    val[i] = fmaf(-p.lr, ghat, p.x[e0 + i]);
+                    float xold;
+                    if (MODE == MODE_FUSED_CODES) {
+                        const int bit = i * p.wbits;
+                        uint64_t two = old_words[bit >> 5];
+                        if ((bit >> 5) + 1 < wpb_in) two |= (uint64_t)old_words[(bit >> 5) + 1] << 32;
+                        const uint32_t cw = (uint32_t)(two >> (bit & 31)) & ((1u << p.wbits) - 1u);
+                        xold = fmaf((float)cw, old_scale, old_base);
+                    } else {
+                        xold = p.x[e0 + i];
+                    }
+                    val[i] = fmaf(-p.lr, ghat, xold);
                 }
             }
             base = grid.lo;

@@ -85,3 +85,22 @@ def test_fused_shard_invariance_and_errors():
         ref.fused_step(x, g, 1e-3, 8, 4, B, -1.0, 0)
     with pytest.raises(ValueError):
         ref.fused_step(x, g, 1e-3, 9, 4, B, 0.0, 0)
+
+
+@pytest.mark.parametrize("wbits,gbits,bucket,delta", [(8, 4, 128, 0.0), (4, 8, 64, 0.0), (6, 3, 96, 0.0),
+                                                      (8, 4, 128, 2.0**-10)])
+def test_code_resident_iteration_equals_the_fp32_resident_one(wbits, gbits, bucket, delta):
+    """Every iterate lies on its bucket grids (the lattice domain of Section 4.1), so codes + meta
+    hold it exactly: iterating on the codes gives, step after step, the iterates of the fp32
+    iteration bit for bit."""
+    rng = np.random.default_rng(7)
+    n = 5 * bucket + 11
+    x_init = (rng.normal(size=n) * 0.02).astype(np.float32)
+    codes, meta, _ = ref.quantize_weight(x_init, wbits, bucket, delta, seed=100)
+    x = ref.dequantize(codes, meta, n, wbits, bucket)
+    for step in range(6):
+        g = (rng.standard_t(3, size=n) * 1e-3).astype(np.float32)
+        x, want_c, want_m, want_sat = ref.fused_step(x, g, 1e-2, wbits, gbits, bucket, delta, step, emit_codes=True)
+        codes, meta, sat = ref.fused_step_codes(codes, meta, g, 1e-2, wbits, gbits, bucket, delta, step)
+        assert np.array_equal(codes, want_c) and np.array_equal(meta, want_m) and sat == want_sat
+        assert np.array_equal(ref.dequantize(codes, meta, n, wbits, bucket), x)
