@@ -75,6 +75,15 @@ float qsdp_ref_weight_shift(uint64_t seed) {
     return (float)(out[0] >> 8) * 0x1p-24f - 0.5f;
 }
 
+/* Shift of the shared-shift gradient quantizer (stream id 2), same construction. */
+float qsdp_ref_grad_shift(uint64_t seed) {
+    uint32_t ctr[4] = {0u, 0u, 2u, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    qsdp_ref_philox4x32_10(ctr, key, out);
+    return (float)(out[0] >> 8) * 0x1p-24f - 0.5f;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Sizes and argument checks                                                   */
 /* ------------------------------------------------------------------------- */
@@ -106,8 +115,8 @@ size_t qsdp_ref_meta_bytes(uint64_t n, int bucket) {
  * own min and max). Signed zeros are canonicalised to +0 so that the stored
  * meta-data has one bit pattern. A bucket whose range is zero, not finite, or
  * so small that L/range overflows is treated as constant: scale = inv = 0. */
-static void bucket_stats(const float* v, int m, float Lf, float* lo_out, float* hi_out,
-                         float* scale_out, float* inv_out) {
+static void bucket_stats(const float* v, int m, float Lf, int symmetric, float* lo_out,
+                         float* hi_out, float* scale_out, float* inv_out) {
     float lo = v[0], hi = v[0];
     for (int i = 1; i < m; ++i) {
         if (v[i] < lo) lo = v[i];
@@ -115,6 +124,11 @@ static void bucket_stats(const float* v, int m, float Lf, float* lo_out, float* 
     }
     lo = lo + 0.0f;
     hi = hi + 0.0f;
+    if (symmetric) { /* grid over [-a, a], a = max |v| (the scaling of Section 3.2) */
+        float a = fmaxf(fabsf(lo), fabsf(hi));
+        lo = -a + 0.0f;
+        hi = a;
+    }
     float range = hi - lo;
     float scale = 0.0f, inv = 0.0f;
     if (range > 0.0f && isfinite(range)) {
@@ -130,11 +144,11 @@ static void bucket_stats(const float* v, int m, float Lf, float* lo_out, float* 
 /* Coin-flip quantizer in bucket coordinates t = (g - lo)/scale in [0, L]:
  * floor(t) with probability 1 - frac(t), floor(t)+1 with probability frac(t),
  * decided by u < frac(t) for u uniform in [0,1). */
-static void grad_bucket(const float* g, const float* u, int m, int bits, uint8_t* code,
-                        float* base_out, float* scale_out) {
+static void grad_bucket(const float* g, const float* u, int m, int bits, int symmetric,
+                        uint8_t* code, float* base_out, float* scale_out) {
     float Lf = (float)((1 << bits) - 1);
     float lo, hi, scale, inv;
-    bucket_stats(g, m, Lf, &lo, &hi, &scale, &inv);
+    bucket_stats(g, m, Lf, symmetric, &lo, &hi, &scale, &inv);
     for (int i = 0; i < m; ++i) {
         float t = (g[i] - lo) * inv;
         t = fminf(fmaxf(t, 0.0f), Lf);
@@ -151,11 +165,11 @@ static void grad_bucket(const float* g, const float* u, int m, int bits, uint8_t
  * shift r := lo + xi*scale, the nearest point of delta*Z + r to x is
  * r + scale*round((x - lo)/scale - xi). The clamp to [0, L] only acts on the
  * binary32 rounding of t - xi near L + 1/2 and on the tie at xi = -1/2. */
-static void weight_bucket_minmax(const float* x, int m, int bits, float xi, uint8_t* code,
-                                 float* base_out, float* scale_out) {
+static void weight_bucket_minmax(const float* x, int m, int bits, float xi, int symmetric,
+                                 uint8_t* code, float* base_out, float* scale_out) {
     float Lf = (float)((1 << bits) - 1);
     float lo, hi, scale, inv;
-    bucket_stats(x, m, Lf, &lo, &hi, &scale, &inv);
+    bucket_stats(x, m, Lf, symmetric, &lo, &hi, &scale, &inv);
     for (int i = 0; i < m; ++i) {
         float t = (x[i] - lo) * inv;
         float k = rintf(t - xi);
@@ -192,12 +206,34 @@ static void weight_bucket_lattice(const float* x, int m, int bits, float delta, 
     *scale_out = delta;
 }
 
-static void weight_bucket(const float* x, int m, int bits, float delta, float xi,
+static void weight_bucket(const float* x, int m, int bits, float delta, float xi, int symmetric,
                           uint8_t* code, float* base, float* scale, uint64_t* sat) {
     if (delta > 0.0f)
         weight_bucket_lattice(x, m, bits, delta, xi, code, base, scale, sat);
     else
-        weight_bucket_minmax(x, m, bits, xi, code, base, scale);
+        weight_bucket_minmax(x, m, bits, xi, symmetric, code, base, scale);
+}
+
+/* The variants of the two quantizers (flags of the *_ex entry points). */
+static int is_symmetric(uint32_t flags) { return (flags & QSDP_REF_FLAG_SYMMETRIC) != 0; }
+
+static float weight_shift_for(uint64_t seed, uint32_t flags) {
+    return (flags & QSDP_REF_FLAG_NO_SHIFT) ? 0.0f : qsdp_ref_weight_shift(seed);
+}
+
+static float grad_shift_for(uint64_t seed, uint32_t flags) {
+    return (flags & QSDP_REF_FLAG_NO_SHIFT) ? 0.0f : qsdp_ref_grad_shift(seed);
+}
+
+/* Gradient bucket under the flags: coin flips with the element uniforms u, or, with
+ * GRAD_SHIFT, the random-shift quantizer itself (the appendix notes that it is an unbiased
+ * quantizer in the sense required of Q^g), which draws nothing per element. */
+static void grad_bucket_flags(const float* g, const float* u, int m, int bits, uint32_t flags,
+                              float xi_g, uint8_t* code, float* base, float* scale) {
+    if (flags & QSDP_REF_FLAG_GRAD_SHIFT)
+        weight_bucket_minmax(g, m, bits, xi_g, is_symmetric(flags), code, base, scale);
+    else
+        grad_bucket(g, u, m, bits, is_symmetric(flags), code, base, scale);
 }
 
 /* Decoding: lattice point -> value, one fused multiply-add. */
@@ -252,19 +288,33 @@ static int bucket_len(uint64_t n, int bucket, uint64_t j) {
 
 int qsdp_ref_quantize_grad_u(const float* g, uint64_t n, int bits, int bucket, const float* u,
                              uint8_t* codes, float* meta) {
+    return qsdp_ref_quantize_grad_u_ex(g, n, bits, bucket, u, 0u, codes, meta);
+}
+
+int qsdp_ref_quantize_grad_u_ex(const float* g, uint64_t n, int bits, int bucket, const float* u,
+                                uint32_t flags, uint8_t* codes, float* meta) {
     if (!g || !u || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (flags & QSDP_REF_FLAG_GRAD_SHIFT) return QSDP_REF_EINVAL; /* no uniforms in that variant */
     int64_t nb = (int64_t)num_buckets(n, bucket);
 #pragma omp parallel for schedule(static) num_threads(g_threads)
     for (int64_t j = 0; j < nb; ++j) {
         uint64_t s = (uint64_t)j * (uint64_t)bucket;
         int m = bucket_len(n, bucket, (uint64_t)j);
-        grad_bucket(g + s, u + s, m, bits, codes + s, &meta[2 * j], &meta[2 * j + 1]);
+        grad_bucket(g + s, u + s, m, bits, is_symmetric(flags), codes + s, &meta[2 * j],
+                    &meta[2 * j + 1]);
     }
     return QSDP_REF_OK;
 }
 
 int qsdp_ref_quantize_weight_xi(const float* x, uint64_t n, int bits, int bucket, float delta,
                                 float xi, uint8_t* codes, float* meta, uint64_t* n_saturated) {
+    return qsdp_ref_quantize_weight_xi_ex(x, n, bits, bucket, delta, xi, 0u, codes, meta,
+                                          n_saturated);
+}
+
+int qsdp_ref_quantize_weight_xi_ex(const float* x, uint64_t n, int bits, int bucket, float delta,
+                                   float xi, uint32_t flags, uint8_t* codes, float* meta,
+                                   uint64_t* n_saturated) {
     if (!x || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
     if (!(delta >= 0.0f) || !isfinite(delta)) return QSDP_REF_EINVAL;
     int64_t nb = (int64_t)num_buckets(n, bucket);
@@ -274,8 +324,8 @@ int qsdp_ref_quantize_weight_xi(const float* x, uint64_t n, int bits, int bucket
         uint64_t s = (uint64_t)j * (uint64_t)bucket;
         int m = bucket_len(n, bucket, (uint64_t)j);
         uint64_t local = 0;
-        weight_bucket(x + s, m, bits, delta, xi, codes + s, &meta[2 * j], &meta[2 * j + 1],
-                      &local);
+        weight_bucket(x + s, m, bits, delta, xi, is_symmetric(flags), codes + s, &meta[2 * j],
+                      &meta[2 * j + 1], &local);
         sat += local;
     }
     if (n_saturated) *n_saturated += sat;
@@ -304,8 +354,14 @@ void qsdp_ref_unpack(const uint32_t* words, uint64_t n, int bits, int bucket, ui
 
 int qsdp_ref_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
                            uint64_t index_offset, uint32_t* codes, float* meta) {
+    return qsdp_ref_quantize_grad_ex(g, n, bits, bucket, seed, index_offset, 0u, codes, meta);
+}
+
+int qsdp_ref_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                              uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta) {
     if (!g || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
-    if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    if (index_offset % 8u != 0u || (flags & ~QSDP_REF_FLAG_ALL)) return QSDP_REF_EINVAL;
+    float xi_g = grad_shift_for(seed, flags);
     int64_t nb = (int64_t)num_buckets(n, bucket);
     int wpb = bucket * bits / 32;
 #pragma omp parallel for schedule(static) num_threads(g_threads)
@@ -315,7 +371,7 @@ int qsdp_ref_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uin
         float u[MAX_BUCKET];
         uint8_t code[MAX_BUCKET];
         for (int i = 0; i < m; ++i) u[i] = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
-        grad_bucket(g + s, u, m, bits, code, &meta[2 * j], &meta[2 * j + 1]);
+        grad_bucket_flags(g + s, u, m, bits, flags, xi_g, code, &meta[2 * j], &meta[2 * j + 1]);
         pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
     }
     return QSDP_REF_OK;
@@ -324,9 +380,16 @@ int qsdp_ref_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uin
 int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float delta,
                              uint64_t seed, uint32_t* codes, float* meta,
                              uint64_t* n_saturated) {
+    return qsdp_ref_quantize_weight_ex(x, n, bits, bucket, delta, seed, 0u, codes, meta,
+                                       n_saturated);
+}
+
+int qsdp_ref_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket, float delta,
+                                uint64_t seed, uint32_t flags, uint32_t* codes, float* meta,
+                                uint64_t* n_saturated) {
     if (!x || !codes || !meta || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
-    if (!(delta >= 0.0f) || !isfinite(delta)) return QSDP_REF_EINVAL;
-    float xi = qsdp_ref_weight_shift(seed);
+    if (!(delta >= 0.0f) || !isfinite(delta) || (flags & ~QSDP_REF_FLAG_ALL)) return QSDP_REF_EINVAL;
+    float xi = weight_shift_for(seed, flags);
     int64_t nb = (int64_t)num_buckets(n, bucket);
     int wpb = bucket * bits / 32;
     uint64_t sat = 0;
@@ -336,7 +399,8 @@ int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket, f
         int m = bucket_len(n, bucket, (uint64_t)j);
         uint8_t code[MAX_BUCKET];
         uint64_t local = 0;
-        weight_bucket(x + s, m, bits, delta, xi, code, &meta[2 * j], &meta[2 * j + 1], &local);
+        weight_bucket(x + s, m, bits, delta, xi, is_symmetric(flags), code, &meta[2 * j],
+                      &meta[2 * j + 1], &local);
         pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
         sat += local;
     }
@@ -399,12 +463,21 @@ int qsdp_ref_dequantize_add(const uint32_t* codes, uint64_t codes_stride_words, 
 int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits,
                         int bucket, float delta, uint64_t seed, uint64_t index_offset,
                         uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
-    if (!x || !g || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket))
+    return qsdp_ref_fused_step_ex(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, 0u,
+                                  wcodes, wmeta, n_saturated);
+}
+
+int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits,
+                           int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
+    if (!x || !g || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket) ||
+        (flags & ~QSDP_REF_FLAG_ALL))
         return QSDP_REF_EINVAL;
     if (!(delta >= 0.0f) || !isfinite(delta) || !isfinite(lr)) return QSDP_REF_EINVAL;
     if ((wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
     if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
-    float xi = qsdp_ref_weight_shift(seed);
+    float xi = weight_shift_for(seed, flags);
+    float xi_g = grad_shift_for(seed, flags);
     int64_t nb = (int64_t)num_buckets(n, bucket);
     int wpb = bucket * wbits / 32;
     uint64_t sat = 0;
@@ -417,10 +490,10 @@ int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr, int wbit
         float gbase, gscale, wbase, wscale;
         uint64_t local = 0;
         for (int i = 0; i < m; ++i) u[i] = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
-        grad_bucket(g + s, u, m, gbits, gcode, &gbase, &gscale);
+        grad_bucket_flags(g + s, u, m, gbits, flags, xi_g, gcode, &gbase, &gscale);
         dequant_bucket(gcode, m, gbase, gscale, ghat);
         for (int i = 0; i < m; ++i) y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);
-        weight_bucket(y, m, wbits, delta, xi, wcode, &wbase, &wscale, &local);
+        weight_bucket(y, m, wbits, delta, xi, is_symmetric(flags), wcode, &wbase, &wscale, &local);
         dequant_bucket(wcode, m, wbase, wscale, x + s);
         if (wcodes) {
             pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);

@@ -39,6 +39,20 @@ extern "C" {
 enum { QSDP_REF_OK = 0, QSDP_REF_EINVAL = -1 };
 enum { QSDP_REF_F32 = 0, QSDP_REF_BF16 = 1 };
 
+/* Quantizer variants the paper names as admissible (flags of the *_ex routines):
+ *  GRAD_SHIFT  gradients are quantized by random shift too (the appendix observes that the
+ *              shift-and-round operator meets the definition of an unbiased gradient quantizer):
+ *              one shift xi_g per call (stream 2), no per-element randomness;
+ *  NO_SHIFT    xi = 0 (and xi_g = 0): deterministic round-to-nearest;
+ *  SYMMETRIC   per-bucket grid over [-a, a], a = max |v| (the symmetric scaling of
+ *              Section 3.2) instead of [min, max]; ignored with an explicit delta. */
+enum {
+    QSDP_REF_FLAG_GRAD_SHIFT = 1,
+    QSDP_REF_FLAG_NO_SHIFT = 2,
+    QSDP_REF_FLAG_SYMMETRIC = 4,
+    QSDP_REF_FLAG_ALL = 7
+};
+
 /* Number of worker threads for the bucket loop (buckets are independent, so the
  * output does not depend on it). Default 1. Returns the value now in force. */
 int qsdp_ref_set_threads(int threads);
@@ -50,6 +64,7 @@ void qsdp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32
  * GLOBAL index is e, and the shift xi in [-1/2,1/2) of a weight quantization. */
 float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e);
 float qsdp_ref_weight_shift(uint64_t seed);
+float qsdp_ref_grad_shift(uint64_t seed);
 
 /* Sizes of the packed representation. */
 size_t qsdp_ref_codes_bytes(uint64_t n, int bits, int bucket);
@@ -63,6 +78,11 @@ int qsdp_ref_quantize_weight_xi(const float* x, uint64_t n, int bits, int bucket
                                 float delta, float xi,
                                 uint8_t* codes /* n */, float* meta /* 2*nb */,
                                 uint64_t* n_saturated /* nullable, incremented */);
+int qsdp_ref_quantize_grad_u_ex(const float* g, uint64_t n, int bits, int bucket, const float* u,
+                                uint32_t flags, uint8_t* codes, float* meta);
+int qsdp_ref_quantize_weight_xi_ex(const float* x, uint64_t n, int bits, int bucket, float delta,
+                                   float xi, uint32_t flags, uint8_t* codes, float* meta,
+                                   uint64_t* n_saturated);
 void qsdp_ref_pack(const uint8_t* codes, uint64_t n, int bits, int bucket, uint32_t* words);
 void qsdp_ref_unpack(const uint32_t* words, uint64_t n, int bits, int bucket, uint8_t* codes);
 uint16_t qsdp_ref_f32_to_bf16(float v);
@@ -77,6 +97,16 @@ int qsdp_ref_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
                              uint32_t* codes, float* meta, uint64_t* n_saturated);
 int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                         int bucket, int out_dtype, void* out);
+/* The same three operations with variant flags. */
+int qsdp_ref_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                              uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta);
+int qsdp_ref_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket, float delta,
+                                uint64_t seed, uint32_t flags, uint32_t* codes, float* meta,
+                                uint64_t* n_saturated);
+int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits,
+                           int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated);
+
 /* Receive side of a quantized gradient exchange (Algorithm 2: every worker's quantized
  * gradient slice arrives, the slices are decoded and summed before the weight update):
  * out[i] = alpha * (((d_0[i] + d_1[i]) + d_2[i]) + ...), d_p = decoded slice of peer p, the

@@ -13,6 +13,7 @@ import numpy as np
 from . import build as _build
 
 F32, BF16 = 0, 1
+FLAG_GRAD_SHIFT, FLAG_NO_SHIFT, FLAG_SYMMETRIC = 1, 2, 4
 
 _lib = None
 
@@ -33,6 +34,14 @@ def lib():
         L.qsdp_ref_grad_uniform.restype = f32
         L.qsdp_ref_weight_shift.argtypes = [u64]
         L.qsdp_ref_weight_shift.restype = f32
+        L.qsdp_ref_grad_shift.argtypes = [u64]
+        L.qsdp_ref_grad_shift.restype = f32
+        u32 = C.c_uint32
+        L.qsdp_ref_quantize_grad_u_ex.argtypes = [vp, u64, i32, i32, vp, u32, vp, vp]
+        L.qsdp_ref_quantize_weight_xi_ex.argtypes = [vp, u64, i32, i32, f32, f32, u32, vp, vp, vp]
+        L.qsdp_ref_quantize_grad_ex.argtypes = [vp, u64, i32, i32, u64, u64, u32, vp, vp]
+        L.qsdp_ref_quantize_weight_ex.argtypes = [vp, u64, i32, i32, f32, u64, u32, vp, vp, vp]
+        L.qsdp_ref_fused_step_ex.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, u32, vp, vp, vp]
         L.qsdp_ref_codes_bytes.argtypes = [u64, i32, i32]
         L.qsdp_ref_codes_bytes.restype = C.c_size_t
         L.qsdp_ref_meta_bytes.argtypes = [u64, i32]
@@ -90,6 +99,10 @@ def weight_shift(seed):
     return float(lib().qsdp_ref_weight_shift(int(seed)))
 
 
+def grad_shift(seed):
+    return float(lib().qsdp_ref_grad_shift(int(seed)))
+
+
 def codes_bytes(n, bits, bucket):
     return int(lib().qsdp_ref_codes_bytes(int(n), int(bits), int(bucket)))
 
@@ -102,27 +115,27 @@ def _nb(n, bucket):
     return (n + bucket - 1) // bucket
 
 
-def quantize_grad_u(g, bits, bucket, u):
+def quantize_grad_u(g, bits, bucket, u, flags=0):
     """Coin-flip quantizer with explicit uniforms. Returns (codes u8[n], meta f32[nb,2])."""
     g = _f32(g)
     u = _f32(u)
     n = g.size
     codes = np.zeros(n, dtype=np.uint8)
     meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
-    _check(lib().qsdp_ref_quantize_grad_u(_p(g), n, bits, bucket, _p(u), _p(codes), _p(meta)),
+    _check(lib().qsdp_ref_quantize_grad_u_ex(_p(g), n, bits, bucket, _p(u), flags, _p(codes), _p(meta)),
            "quantize_grad_u")
     return codes, meta
 
 
-def quantize_weight_xi(x, bits, bucket, delta, xi):
+def quantize_weight_xi(x, bits, bucket, delta, xi, flags=0):
     """Random-shift quantizer with explicit shift. Returns (codes u8[n], meta, n_saturated)."""
     x = _f32(x)
     n = x.size
     codes = np.zeros(n, dtype=np.uint8)
     meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
     sat = np.zeros(1, dtype=np.uint64)
-    _check(lib().qsdp_ref_quantize_weight_xi(_p(x), n, bits, bucket, float(delta), float(xi),
-                                             _p(codes), _p(meta), _p(sat)),
+    _check(lib().qsdp_ref_quantize_weight_xi_ex(_p(x), n, bits, bucket, float(delta), float(xi), flags,
+                                                _p(codes), _p(meta), _p(sat)),
            "quantize_weight_xi")
     return codes, meta, int(sat[0])
 
@@ -147,26 +160,26 @@ def f32_to_bf16(v):
     return int(lib().qsdp_ref_f32_to_bf16(float(v)))
 
 
-def quantize_grad(g, bits, bucket, seed, index_offset=0):
+def quantize_grad(g, bits, bucket, seed, index_offset=0, flags=0):
     """Returns (packed codes u32[...], meta f32[nb,2])."""
     g = _f32(g)
     n = g.size
     codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
     meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
-    _check(lib().qsdp_ref_quantize_grad(_p(g), n, bits, bucket, int(seed), int(index_offset),
-                                        _p(codes), _p(meta)), "quantize_grad")
+    _check(lib().qsdp_ref_quantize_grad_ex(_p(g), n, bits, bucket, int(seed), int(index_offset), flags,
+                                           _p(codes), _p(meta)), "quantize_grad")
     return codes, meta
 
 
-def quantize_weight(x, bits, bucket, delta, seed):
+def quantize_weight(x, bits, bucket, delta, seed, flags=0):
     """Returns (packed codes, meta, n_saturated)."""
     x = _f32(x)
     n = x.size
     codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
     meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
     sat = np.zeros(1, dtype=np.uint64)
-    _check(lib().qsdp_ref_quantize_weight(_p(x), n, bits, bucket, float(delta), int(seed),
-                                          _p(codes), _p(meta), _p(sat)), "quantize_weight")
+    _check(lib().qsdp_ref_quantize_weight_ex(_p(x), n, bits, bucket, float(delta), int(seed), flags,
+                                             _p(codes), _p(meta), _p(sat)), "quantize_weight")
     return codes, meta, int(sat[0])
 
 
@@ -193,7 +206,7 @@ def dequantize_add(codes, meta, npeers, n, bits, bucket, alpha):
     return out
 
 
-def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit_codes=False):
+def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit_codes=False, flags=0):
     """Returns (x_new f32[n], wcodes or None, wmeta or None, n_saturated). x is not modified."""
     x = _f32(x).copy()
     g = _f32(g)
@@ -204,9 +217,9 @@ def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit
         wcodes = np.zeros(codes_bytes(n, wbits, bucket) // 4, dtype=np.uint32)
         wmeta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
     sat = np.zeros(1, dtype=np.uint64)
-    _check(lib().qsdp_ref_fused_step(_p(x), _p(g), n, float(lr), wbits, gbits, bucket,
-                                     float(delta), int(seed), int(index_offset),
-                                     _p(wcodes), _p(wmeta), _p(sat)), "fused_step")
+    _check(lib().qsdp_ref_fused_step_ex(_p(x), _p(g), n, float(lr), wbits, gbits, bucket,
+                                        float(delta), int(seed), int(index_offset), flags,
+                                        _p(wcodes), _p(wmeta), _p(sat)), "fused_step")
     return x, wcodes, wmeta, int(sat[0])
 
 

@@ -37,6 +37,12 @@ MUTANTS = [
      ["test_oracle_dequantize_add.py"]),
     ("peer_sum_not_scaled", "out[s + (uint64_t)i] = alpha * sum[i];", "out[s + (uint64_t)i] = sum[i];",
      ["test_oracle_dequantize_add.py"]),
+    ("symmetric_grid_uses_max_only", "float a = fmaxf(fabsf(lo), fabsf(hi));", "float a = fabsf(hi);",
+     ["test_oracle_variants.py"]),
+    ("grad_shift_reuses_weight_stream", "uint32_t ctr[4] = {0u, 0u, 2u, 0u};", "uint32_t ctr[4] = {0u, 0u, 1u, 0u};",
+     ["test_oracle_variants.py"]),
+    ("no_shift_flag_ignored_for_weights", "return (flags & QSDP_REF_FLAG_NO_SHIFT) ? 0.0f : qsdp_ref_weight_shift(seed);",
+     "return qsdp_ref_weight_shift(seed);", ["test_oracle_variants.py"]),
     ("step_sign_flipped", "y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);", "y[i] = fmaf(lr, ghat[i], x[s + (uint64_t)i]);",
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
