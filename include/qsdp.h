@@ -149,6 +149,34 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
                     uint64_t* n_saturated, void* stream);
 
 /*
+ * Quantizer variants the paper names as admissible, selected by `flags` (0 = the default
+ * operators above; meta-data and wire format are unchanged, so qsdp_dequantize serves all):
+ *   QSDP_FLAG_GRAD_SHIFT  gradients are quantized by random shift as well (the appendix notes
+ *                         that the shift-and-round operator is an unbiased quantizer in the
+ *                         sense required of Q^g): one shift xi_g per call from Philox stream 2,
+ *                         code = clamp(round((g-lo)/scale - xi_g), 0, L), meta = {lo + xi_g*scale,
+ *                         scale}; nothing is drawn per element, index_offset has no effect.
+ *   QSDP_FLAG_NO_SHIFT    xi = 0 and xi_g = 0: deterministic round-to-nearest (biased).
+ *   QSDP_FLAG_SYMMETRIC   per-bucket grid over [-a, a], a = max |v| (the symmetric scaling of
+ *                         Section 3.2) instead of [min, max]; no effect with delta > 0.
+ * Other bits are rejected with QSDP_EINVAL.
+ */
+enum { QSDP_FLAG_GRAD_SHIFT = 1, QSDP_FLAG_NO_SHIFT = 2, QSDP_FLAG_SYMMETRIC = 4, QSDP_FLAG_ALL = 7 };
+
+int qsdp_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket,
+                          uint64_t seed, uint64_t index_offset, uint32_t flags,
+                          uint32_t* codes, float* meta, void* stream);
+int qsdp_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket,
+                            float delta, uint64_t seed, uint32_t flags,
+                            uint32_t* codes, float* meta,
+                            uint64_t* n_saturated, void* stream);
+int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
+                       int wbits, int gbits, int bucket, float delta,
+                       uint64_t seed, uint64_t index_offset, uint32_t flags,
+                       uint32_t* wcodes, float* wmeta,
+                       uint64_t* n_saturated, void* stream);
+
+/*
  * The same step with the weights RESIDENT AS CODES: every iterate of the quantized iteration
  * lies on its bucket grids (Section 4.1: the iterates live in the lattice domain), so
  * (wcodes, wmeta) hold x_t exactly and the fp32 copy is redundant. The call decodes x_t in

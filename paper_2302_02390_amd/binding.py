@@ -15,9 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libqsdp.so")
 
 QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
 QSDP_F32, QSDP_BF16 = 0, 1
+QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC = 1, 2, 4
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
+           "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented")
 
@@ -50,6 +52,12 @@ def lib():
         L.qsdp_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp, vp]
         L.qsdp_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
         L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
+        u32 = C.c_uint32
+        L.qsdp_quantize_grad_ex.argtypes = [vp, u64, i32, i32, u64, u64, u32, vp, vp, vp]
+        L.qsdp_quantize_weight_ex.argtypes = [vp, u64, i32, i32, f32, u64, u32, vp, vp, vp, vp]
+        L.qsdp_fused_step_ex.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, u32, vp, vp, vp, vp]
+        for name in ("qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex"):
+            getattr(L, name).restype = i32
         L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
         L.qsdp_dequantize_add.restype = i32
         L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp]
@@ -118,6 +126,37 @@ def qsdp_quantize_grad(g, bits, bucket, seed, index_offset, codes, meta):
     with torch.cuda.device(g.device):
         _check(lib().qsdp_quantize_grad(_ptr(g), g.numel(), bits, bucket, seed, index_offset,
                                         _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad")
+
+
+def qsdp_quantize_grad_ex(g, bits, bucket, seed, index_offset, flags, codes, meta):
+    _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_quantize_grad_ex(_ptr(g), g.numel(), bits, bucket, seed, index_offset, flags,
+                                           _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad_ex")
+
+
+def qsdp_quantize_weight_ex(x, bits, bucket, delta, seed, flags, codes, meta, n_saturated=None):
+    _is(x, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_quantize_weight_ex(_ptr(x), x.numel(), bits, bucket, delta, seed, flags, _ptr(codes),
+                                             _ptr(meta), _ptr(n_saturated), _stream(x)),
+               "qsdp_quantize_weight_ex")
+
+
+def qsdp_fused_step_ex(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes=None,
+                       wmeta=None, n_saturated=None):
+    _is(x, torch.float32); _is(g, torch.float32)
+    if g.numel() != x.numel():
+        raise ValueError("x and g differ in size")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_ex(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
+                                        index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
+                                        _stream(x)), "qsdp_fused_step_ex")
 
 
 def qsdp_quantize_weight(x, bits, bucket, delta, seed, codes, meta, n_saturated=None):

@@ -187,10 +187,17 @@ const char* qsdp_status_string(int status) {
 
 int qsdp_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
                        uint64_t index_offset, uint32_t* codes, float* meta, void* stream) {
-    if (!g || !codes || !meta || !shape_ok(n, bits, bucket) || (index_offset & 7u)) return QSDP_EINVAL;
+    return qsdp_quantize_grad_ex(g, n, bits, bucket, seed, index_offset, 0u, codes, meta, stream);
+}
+
+int qsdp_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                          uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta, void* stream) {
+    if (!g || !codes || !meta || !shape_ok(n, bits, bucket) || (index_offset & 7u) || (flags & ~QSDP_FLAG_ALL))
+        return QSDP_EINVAL;
     if (!aligned16(g) || !aligned16(codes) || !aligned16(meta)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, 0.0f);
+    p.flags = flags;
     p.g = g;
     p.codes = codes;
     p.meta = meta;
@@ -202,12 +209,19 @@ int qsdp_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_
 int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float delta,
                          uint64_t seed, uint32_t* codes, float* meta, uint64_t* n_saturated,
                          void* stream) {
-    if (!x || !codes || !meta || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    return qsdp_quantize_weight_ex(x, n, bits, bucket, delta, seed, 0u, codes, meta, n_saturated, stream);
+}
+
+int qsdp_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket, float delta,
+                            uint64_t seed, uint32_t flags, uint32_t* codes, float* meta,
+                            uint64_t* n_saturated, void* stream) {
+    if (!x || !codes || !meta || !shape_ok(n, bits, bucket) || (flags & ~QSDP_FLAG_ALL)) return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta)) return QSDP_EINVAL;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(meta)) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, 0, delta);
+    p.flags = flags;
     p.xin = x;
     p.codes = codes;
     p.meta = meta;
@@ -275,13 +289,22 @@ int qsdp_dequantize_add(const uint32_t* codes, uint64_t codes_stride_bytes, cons
 int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                     float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes, float* wmeta,
                     uint64_t* n_saturated, void* stream) {
-    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket)) return QSDP_EINVAL;
+    return qsdp_fused_step_ex(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, 0u, wcodes, wmeta,
+                              n_saturated, stream);
+}
+
+int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                       float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
+                       float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) || (flags & ~QSDP_FLAG_ALL))
+        return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
     if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta)) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, delta);
+    p.flags = flags;
     p.x = x;
     p.g = g;
     p.codes = wcodes;

@@ -51,11 +51,7 @@ __device__ __forceinline__ void grad_uniforms_rows(uint64_t bucket_block, int c,
     const int odd = l & 1;
     const uint64_t block = bucket_block + (uint64_t)(((2 * c + odd) * G + (l - odd)) >> 1);
     uint32_t w[4];
-#ifdef QSDP_EXP_NOPHILOX
-    w[0] = (uint32_t)block; w[1] = k0; w[2] = k1; w[3] = (uint32_t)(block >> 7);
-#else
     philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
-#endif
     const uint32_t send0 = odd ? w[0] : w[2];
     const uint32_t send1 = odd ? w[1] : w[3];
     const uint32_t recv0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send0, 0xB1, 0xF, 0xF, false);
@@ -68,10 +64,10 @@ __device__ __forceinline__ void grad_uniforms_rows(uint64_t bucket_block, int c,
     h[6] = (float)(b1 & 0xFFFFu); h[7] = (float)(b1 >> 16);
 }
 
-// The weight shift xi in [-1/2, 1/2): stream 1, counter 0.
-__device__ __forceinline__ float weight_shift(uint32_t k0, uint32_t k1) {
+// A shift xi in [-1/2, 1/2): counter 0 of stream 1 (weights) or 2 (shared-shift gradients).
+__device__ __forceinline__ float stream_shift(uint32_t stream, uint32_t k0, uint32_t k1) {
     uint32_t w[4];
-    philox4x32_10(0u, 0u, 1u, 0u, k0, k1, w);
+    philox4x32_10(0u, 0u, stream, 0u, k0, k1, w);
     return (float)(w[0] >> 8) * 0x1p-24f - 0.5f;
 }
 
@@ -127,9 +123,14 @@ struct MinMaxGrid {
     float lo, scale, inv;
 };
 
-__device__ __forceinline__ MinMaxGrid make_minmax_grid(float lo, float hi, float Lf) {
+__device__ __forceinline__ MinMaxGrid make_minmax_grid(float lo, float hi, float Lf, bool symmetric) {
     lo = lo + 0.0f;  // -0 -> +0: one bit pattern for the stored base
     hi = hi + 0.0f;
+    if (symmetric) {  // grid over [-a, a], a = max |v|
+        const float a = fmaxf(fabsf(lo), fabsf(hi));
+        lo = -a + 0.0f;
+        hi = a;
+    }
     const float range = hi - lo;
     const float inv = Lf / range;
     const float scale = range / Lf;

@@ -48,6 +48,7 @@ struct Params {
     uint64_t num_buckets;   // buckets this launch handles
     uint64_t block0;        // index_offset / 8
     uint32_t nseg;
+    uint32_t flags;  // FLAG_* variants
     int bucket;
     int gbits, wbits;
     float lr;
@@ -57,6 +58,23 @@ struct Params {
 };
 
 // Where bucket `gb` starts in the flat buffers and how many of its `B` slots hold elements.
+// Quantizer variants (same values as the QSDP_FLAG_* of the C header)
+enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u };
+
+struct Shifts {
+    float xi;    // weight shift
+    float xi_g;  // gradient shift (FLAG_GRAD_SHIFT)
+};
+
+__device__ __forceinline__ Shifts draw_shifts(const Params& p, bool weights) {
+    Shifts s = {0.0f, 0.0f};
+    if (!(p.flags & FLAG_NO_SHIFT)) {
+        if (weights) s.xi = stream_shift(1u, p.key0, p.key1);
+        if (p.flags & FLAG_GRAD_SHIFT) s.xi_g = stream_shift(2u, p.key0, p.key1);
+    }
+    return s;
+}
+
 struct BucketRef {
     uint64_t e0;
     uint32_t m;
@@ -94,11 +112,7 @@ __device__ __forceinline__ void load_rows(const float* base, int l, int m, bool 
         const f4* p = reinterpret_cast<const f4*>(base) + l;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-#ifdef QSDP_EXP_LD_PLAIN
-            const f4 a = p[r * G];
-#else
             const f4 a = __builtin_nontemporal_load(p + r * G);
-#endif
             v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
         }
     } else {
@@ -119,11 +133,7 @@ __device__ __forceinline__ void store_rows(float* base, int l, int m, bool parti
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
-#ifdef QSDP_EXP_ST_PLAIN
-            p[r * G] = a;
-#else
             __builtin_nontemporal_store(a, p + r * G);
-#endif
         }
     } else {
 #pragma unroll
@@ -302,8 +312,10 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     const float Lw = (float)((1 << p.wbits) - 1);
     const Divider div = {p.delta, p.inv_delta, p.delta_pow2 != 0};
     const bool lattice = p.delta > 0.0f;
-    float xi = 0.0f;
-    if (MODE != MODE_GRAD) xi = weight_shift(p.key0, p.key1);
+    const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
+    const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
+    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD);
+    const float xi = shifts.xi;
     uint32_t saturated = 0;
 
     for (uint64_t q = unit0; q < nunits; q += unit_stride, parity ^= 1u) {
@@ -349,29 +361,47 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             float lo, hi;
             rows_minmax<G, R>(gv, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_g, wave_in_block);
-            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg, symmetric);
+            // base of the decoded gradient: lo, or lo + xi_g * scale for the shared-shift variant
+            const float gbase = grad_shift ? fmaf(shifts.xi_g, grid.scale, grid.lo) : grid.lo;
+            if (grad_shift) {
+                // random-shift quantizer on the gradient: nothing is drawn per element
 #pragma unroll
-            for (int cp = 0; cp < R / 2; ++cp) {
-                float h[8];
-                grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int r = 2 * cp + (i >> 2);
-                    if constexpr (MODE == MODE_GRAD) {
-                        const uint32_t c = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
-                        // slots past the end of a short bucket hold code 0
-                        gcode[r][i & 3] = (partial && (r * G + l) * 4 + (i & 3) >= m) ? 0u : c;
-                    } else {
-                        const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
-                        const float ghat = fmaf(code, grid.scale, grid.lo);
-                        w[r][i & 3] = fmaf(-p.lr, ghat, w[r][i & 3]);
+                    for (int i = 0; i < 4; ++i) {
+                        const float code = weight_code_minmax(gv[r][i], grid, Lg, shifts.xi_g);
+                        if constexpr (MODE == MODE_GRAD) {
+                            gcode[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0u : (uint32_t)code;
+                        } else {
+                            const float ghat = fmaf(code, grid.scale, gbase);
+                            w[r][i] = fmaf(-p.lr, ghat, w[r][i]);
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int cp = 0; cp < R / 2; ++cp) {
+                    float h[8];
+                    grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = 2 * cp + (i >> 2);
+                        if constexpr (MODE == MODE_GRAD) {
+                            const uint32_t c = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
+                            // slots past the end of a short bucket hold code 0
+                            gcode[r][i & 3] = (partial && (r * G + l) * 4 + (i & 3) >= m) ? 0u : c;
+                        } else {
+                            const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
+                            const float ghat = fmaf(code, grid.scale, grid.lo);
+                            w[r][i & 3] = fmaf(-p.lr, ghat, w[r][i & 3]);
+                        }
                     }
                 }
             }
             if constexpr (MODE == MODE_GRAD) {
                 store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
                 if (writes_meta) {
-                    p.meta[2 * bucket] = grid.lo;
+                    p.meta[2 * bucket] = gbase;
                     p.meta[2 * bucket + 1] = grid.scale;
                 }
                 continue;
@@ -405,7 +435,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             float lo, hi;
             rows_minmax<G, R>(w, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
-            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw, symmetric);
             base = fmaf(xi, grid.scale, grid.lo);
             scale = grid.scale;
 #pragma unroll
@@ -474,8 +504,10 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
     const float Lw = (float)((1 << p.wbits) - 1);
     const Divider div = {p.delta, p.inv_delta, p.delta_pow2 != 0};
     const bool lattice = p.delta > 0.0f;
-    float xi = 0.0f;
-    if (MODE != MODE_GRAD) xi = weight_shift(p.key0, p.key1);
+    const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
+    const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
+    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD);
+    const float xi = shifts.xi;
     if (tid == 0) sat_block = 0;
 
     for (uint64_t rel = blockIdx.x; rel < p.num_buckets; rel += gridDim.x) {
@@ -502,20 +534,26 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                 hi = fmaxf(hi, v);
             }
             block_minmax(lo, hi, red);
-            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg, symmetric);
+            const float gbase = grad_shift ? fmaf(shifts.xi_g, grid.scale, grid.lo) : grid.lo;
             for (int i = tid; i < m; i += 256) {
-                const uint64_t e = (p.block0 << 3) + e0 + (uint64_t)i;
-                uint32_t w[4];
-                const uint64_t blk = e >> 3;
-                philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, p.key0, p.key1, w);
-                const uint32_t j = (uint32_t)(e & 7u);
-                const uint32_t word = w[j >> 1];
-                const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
-                const float c = grad_code(val[i], grid, Lg, h);
+                float c;
+                if (grad_shift) {
+                    c = weight_code_minmax(val[i], grid, Lg, shifts.xi_g);
+                } else {
+                    const uint64_t e = (p.block0 << 3) + e0 + (uint64_t)i;
+                    uint32_t w[4];
+                    const uint64_t blk = e >> 3;
+                    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, p.key0, p.key1, w);
+                    const uint32_t j = (uint32_t)(e & 7u);
+                    const uint32_t word = w[j >> 1];
+                    const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
+                    c = grad_code(val[i], grid, Lg, h);
+                }
                 if (MODE == MODE_GRAD) {
                     code[i] = (uint8_t)(uint32_t)c;
                 } else {
-                    const float ghat = fmaf(c, grid.scale, grid.lo);
+                    const float ghat = fmaf(c, grid.scale, gbase);
                     float xold;
                     if (MODE == MODE_FUSED_CODES) {
                         const int bit = i * p.wbits;
@@ -529,7 +567,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                     val[i] = fmaf(-p.lr, ghat, xold);
                 }
             }
-            base = grid.lo;
+            base = gbase;
             scale = grid.scale;
         } else {
             for (int i = tid; i < m; i += 256) val[i] = p.xin[e0 + i];
@@ -556,7 +594,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
             } else {
-                const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw);
+                const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw, symmetric);
                 base = fmaf(xi, grid.scale, grid.lo);
                 scale = grid.scale;
                 for (int i = tid; i < m; i += 256) {
