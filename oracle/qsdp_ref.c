@@ -519,3 +519,131 @@ int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, ui
     free(x);
     return rc;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Learned quantization levels (Section 5.2, Algorithm 1)                      */
+/* ------------------------------------------------------------------------- */
+
+int qsdp_ref_levels_uniform(int bits, float* levels) {
+    if (bits < 1 || bits > 8 || !levels) return QSDP_REF_EINVAL;
+    int K = 1 << bits;
+    for (int k = 0; k < K; ++k) levels[k] = (float)k / (float)(K - 1);
+    return QSDP_REF_OK;
+}
+
+static int levels_ok(const float* levels, int bits) {
+    int K = 1 << bits;
+    for (int k = 0; k < K; ++k) {
+        if (!(levels[k] >= 0.0f && levels[k] <= 1.0f)) return 0;
+        if (k > 0 && levels[k] < levels[k - 1]) return 0;
+    }
+    return 1;
+}
+
+/* Bucket-wise normalisation: z = (v - lo) * (1 / (hi - lo)); a degenerate bucket maps to 0. */
+static void normalize_bucket(const float* v, int m, float* z, float* lo_out, float* range_out) {
+    float lo, hi, scale_unused, inv_unused;
+    bucket_stats(v, m, 1.0f, 0, &lo, &hi, &scale_unused, &inv_unused);
+    float range = hi - lo;
+    float inv = 0.0f;
+    if (range > 0.0f && isfinite(range)) {
+        float t = 1.0f / range;
+        if (isfinite(t)) inv = t; else range = 0.0f;
+    } else {
+        range = 0.0f;
+    }
+    for (int i = 0; i < m; ++i) z[i] = (v[i] - lo) * inv;
+    *lo_out = lo;
+    *range_out = range;
+}
+
+/* Nearest level by the plain definition: smallest |z - q_k|, first index on ties. */
+static int closest_level(float z, const float* levels, int K) {
+    int best = 0;
+    float best_d = fabsf(z - levels[0]);
+    for (int k = 1; k < K; ++k) {
+        float d = fabsf(z - levels[k]);
+        if (d < best_d) {
+            best_d = d;
+            best = k;
+        }
+    }
+    return best;
+}
+
+int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                             uint32_t* codes, float* meta) {
+    if (!v || !levels || !codes || !meta || !args_ok(n, bits, bucket) || !levels_ok(levels, bits))
+        return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+    int K = 1 << bits;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float z[MAX_BUCKET];
+        uint8_t code[MAX_BUCKET];
+        normalize_bucket(v + s, m, z, &meta[2 * j], &meta[2 * j + 1]);
+        for (int i = 0; i < m; ++i) code[i] = (uint8_t)closest_level(z[i], levels, K);
+        pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
+    }
+    return QSDP_REF_OK;
+}
+
+int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                               int bucket, const float* levels, int out_dtype, void* out) {
+    if (!codes || !meta || !levels || !out || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
+    if (out_dtype != QSDP_REF_F32 && out_dtype != QSDP_REF_BF16) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        uint8_t code[MAX_BUCKET];
+        unpack_bucket(codes + (uint64_t)j * (uint64_t)wpb, m, bits, code);
+        for (int i = 0; i < m; ++i) {
+            float val = fmaf(levels[code[i]], meta[2 * j + 1], meta[2 * j]);
+            if (out_dtype == QSDP_REF_F32) ((float*)out)[s + (uint64_t)i] = val;
+            else ((uint16_t*)out)[s + (uint64_t)i] = qsdp_ref_f32_to_bf16(val);
+        }
+    }
+    return QSDP_REF_OK;
+}
+
+int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
+                        uint64_t max_batches, float* levels) {
+    if (!v || !levels || !args_ok(n, bits, bucket) || !levels_ok(levels, bits)) return QSDP_REF_EINVAL;
+    if (!(lr > 0.0f && lr < 1.0f)) return QSDP_REF_EINVAL;
+    uint64_t nb = num_buckets(n, bucket);
+    if (max_batches > 0 && max_batches < nb) nb = max_batches;
+    int K = 1 << bits;
+    /* keep[c] = (1 - lr)^c by repeated multiplication */
+    static double keep[MAX_BUCKET + 1];
+    double one_minus = 1.0 - (double)lr;
+    keep[0] = 1.0;
+    for (int c = 1; c <= bucket; ++c) keep[c] = keep[c - 1] * one_minus;
+    for (uint64_t j = 0; j < nb; ++j) {
+        uint64_t s = j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, j);
+        float z[MAX_BUCKET];
+        float lo, range;
+        normalize_bucket(v + s, m, z, &lo, &range);
+        int64_t sum[256];
+        uint32_t count[256];
+        for (int k = 0; k < K; ++k) { sum[k] = 0; count[k] = 0; }
+        for (int i = 0; i < m; ++i) {
+            int k = closest_level(z[i], levels, K);
+            sum[k] += (int64_t)(z[i] * 4294967296.0f); /* exact scaling, truncation */
+            count[k] += 1u;
+        }
+        for (int k = 0; k < K; ++k) {
+            if (count[k] == 0) continue;
+            double mean = ((double)sum[k] / (double)count[k]) * (1.0 / 4294967296.0);
+            double q = (double)levels[k];
+            levels[k] = (float)(q - (1.0 - keep[count[k]]) * (q - mean));
+        }
+    }
+    return QSDP_REF_OK;
+}

@@ -121,6 +121,27 @@ int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr,
                         uint32_t* wcodes /* nullable */, float* wmeta /* nullable */,
                         uint64_t* n_saturated /* nullable */);
 
+/* ---- Learned (non-uniform) quantization levels: Section 5.2, Algorithm 1, Appendix C ----
+ * A level table holds 2^bits positions in bucket-normalised coordinates z = (v - lo)/(hi - lo)
+ * in [0, 1], ascending. Encoding picks the NEAREST level (ties: the lowest index); decoding is
+ * a table lookup: v' = fma(levels[code], hi - lo, lo). meta = {lo, hi - lo}. The wire format
+ * of the codes is the one of the uniform quantizers.
+ *
+ * fit_levels is the level optimisation of Algorithm 1 in its batched form (batch = one bucket,
+ * the paper's batch size equals its bucket size): the values of a batch are normalised
+ * bucket-wise and assigned to their closest level with the levels frozen; then every level
+ * that received c > 0 values takes the c steps q <- q - lr*(q - v) of the algorithm towards
+ * the mean m of its values at once: q <- q - (1 - (1-lr)^c) * (q - m). Sums are exact
+ * (32.32 fixed point, order independent), the update is evaluated in binary64 and the level
+ * is stored in binary32. Batches are visited in order, first `max_batches` only if > 0. */
+int qsdp_ref_levels_uniform(int bits, float* levels /* 2^bits */);
+int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                             uint32_t* codes, float* meta);
+int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                               int bucket, const float* levels, int out_dtype, void* out);
+int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
+                        uint64_t max_batches, float* levels /* in: start, out: fitted */);
+
 /* The step on weights held as codes: decode (wcodes, wmeta), take the fused step, write the
  * codes and meta of the result back. By definition the composition of the two routines. */
 int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,

@@ -58,6 +58,10 @@ def lib():
         L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
         L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
         L.qsdp_ref_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp]
+        L.qsdp_ref_levels_uniform.argtypes = [i32, vp]
+        L.qsdp_ref_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp]
+        L.qsdp_ref_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp]
+        L.qsdp_ref_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp]
         L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
@@ -235,3 +239,40 @@ def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, in
                                            float(delta), int(seed), int(index_offset), _p(sat)),
            "fused_step_codes")
     return wcodes, wmeta, int(sat[0])
+
+
+def levels_uniform(bits):
+    lv = np.zeros(1 << bits, dtype=np.float32)
+    _check(lib().qsdp_ref_levels_uniform(bits, _p(lv)), "levels_uniform")
+    return lv
+
+
+def quantize_levels(v, bits, bucket, levels):
+    """Nearest-level encoding. Returns (packed codes, meta f32[nb,2] = {lo, hi-lo})."""
+    v = _f32(v)
+    levels = _f32(levels)
+    n = v.size
+    codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    _check(lib().qsdp_ref_quantize_levels(_p(v), n, bits, bucket, _p(levels), _p(codes), _p(meta)),
+           "quantize_levels")
+    return codes, meta
+
+
+def dequantize_levels(codes, meta, n, bits, bucket, levels, out_dtype=F32):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32).reshape(-1)
+    meta = np.ascontiguousarray(meta, dtype=np.float32).reshape(-1)
+    levels = _f32(levels)
+    out = np.zeros(n, dtype=np.float32 if out_dtype == F32 else np.uint16)
+    _check(lib().qsdp_ref_dequantize_levels(_p(codes), _p(meta), n, bits, bucket, _p(levels), out_dtype,
+                                            _p(out)), "dequantize_levels")
+    return out
+
+
+def fit_levels(v, bits, bucket, lr, levels, max_batches=0):
+    """Algorithm 1 (batched). Returns the fitted levels; `levels` is the start and is not modified."""
+    v = _f32(v)
+    lv = _f32(levels).copy()
+    _check(lib().qsdp_ref_fit_levels(_p(v), v.size, bits, bucket, float(lr), int(max_batches), _p(lv)),
+           "fit_levels")
+    return lv

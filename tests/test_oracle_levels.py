@@ -1,0 +1,120 @@
+"""Oracle pins, learned (non-uniform) quantization levels: Section 5.2, Algorithm 1, Appendix C."""
+import numpy as np
+import pytest
+
+from oracle import ref
+
+
+def _gauss(n, seed, scale=0.02):
+    return (np.random.default_rng(seed).normal(size=n) * scale).astype(np.float32)
+
+
+def _rel_l2(a, b):
+    return np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b.astype(np.float64))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+def test_uniform_levels_give_the_uniform_round_to_nearest_quantizer(bits):
+    """With levels k/L the nearest level is round((v-lo)/(hi-lo)*L): the deterministic uniform
+    quantizer, compared with a float64 computation away from rounding ties."""
+    B, L = 128, 2**bits - 1
+    v = _gauss(4 * B, bits)
+    lv = ref.levels_uniform(bits)
+    assert np.array_equal(lv, (np.arange(L + 1, dtype=np.float32) / np.float32(L)))
+    codes, meta = ref.quantize_levels(v, bits, B, lv)
+    vb = v.reshape(4, B).astype(np.float64)
+    lo = vb.min(1, keepdims=True)
+    rng_ = vb.max(1, keepdims=True) - lo
+    assert np.array_equal(meta[:, 0], v.reshape(4, B).min(1))
+    assert np.array_equal(meta[:, 1], v.reshape(4, B).max(1) - v.reshape(4, B).min(1))
+    t = (vb - lo) / rng_ * L
+    safe = np.abs(t - np.floor(t) - 0.5) > 1e-3
+    got = ref.unpack(codes, v.size, bits, B).reshape(4, B)
+    assert np.array_equal(got[safe], np.rint(t)[safe].astype(np.uint8))
+    assert safe.mean() > 0.98
+
+
+def test_nearest_level_by_brute_force_and_ties_and_decode_lookup():
+    bits, B = 3, 32
+    levels = np.array([0.0, 0.07, 0.2, 0.35, 0.5, 0.5, 0.8, 1.0], dtype=np.float32)  # a duplicate on purpose
+    v = np.linspace(-1.0, 3.0, B, dtype=np.float32)
+    v[5] = -1.0 + 4.0 * 0.135                       # exactly between 0.07 and 0.2 -> lower index
+    codes, meta = ref.quantize_levels(v, bits, B, levels)
+    got = ref.unpack(codes, B, bits, B)
+    z = ((v - np.float32(-1.0)) * (np.float32(1.0) / np.float32(4.0))).astype(np.float32)
+    want = np.array([int(np.argmin(np.abs(zi - levels))) for zi in z])   # argmin takes the first minimum
+    assert np.array_equal(got, want)
+    assert 5 not in got                              # the duplicate's second copy is never chosen
+    out = ref.dequantize_levels(codes, meta, B, bits, B, levels)
+    assert np.array_equal(out, (levels[got].astype(np.float64) * 4.0 - 1.0).astype(np.float32))
+    # decoding error is at most half the widest gap between levels
+    assert np.all(np.abs(out - v) <= 4.0 * 0.15 + 1e-6)
+
+
+def test_levels_must_be_sorted_in_unit_interval():
+    v = np.zeros(64, np.float32)
+    for bad in ([0.0, 0.5, 0.4, 1.0], [0.0, 0.2, 0.5, 1.5], [-0.1, 0.2, 0.5, 1.0]):
+        with pytest.raises(ValueError):
+            ref.quantize_levels(v, 2, 64, np.array(bad, np.float32))
+
+
+def test_one_batch_update_matches_the_sequential_steps_of_the_algorithm():
+    """Algorithm 1 moves the chosen level by q <- q - lr*(q - v) for every value. With all the
+    values of a level equal, c such steps are q - (1-(1-lr)^c)(q - v): the batched rule, exactly."""
+    bits, B, lr = 2, 32, 0.05
+    levels = np.array([0.0, 0.3, 0.6, 1.0], np.float32)
+    # one bucket: 0 and 1 pin the normalisation; 10 values at 0.25 (level 1), 7 at 0.7 (level 2)
+    v = np.array([0.0, 1.0] + [0.25] * 10 + [0.7] * 7 + [0.0] * 13, np.float32)
+    got = ref.fit_levels(v, bits, B, lr, levels)
+    q = levels.astype(np.float64).copy()
+    for val in v:                                    # the printed algorithm, frozen assignment
+        k = int(np.argmin(np.abs(np.float32(val) - levels)))
+        q[k] = q[k] - lr * (q[k] - np.float64(np.float32(val)))
+    assert np.allclose(got, q, rtol=0, atol=2e-7)
+    assert got[1] < levels[1] and got[2] > levels[2] and got[3] == pytest.approx(1.0 - (1 - 0.95) * 0, abs=1e-7)
+
+
+def test_fitted_levels_stay_sorted_and_lower_the_error_on_gaussian_data():
+    """Appendix C: learned levels have a consistently lower compression error than uniform ones,
+    the more so the fewer the bits."""
+    B = 1024
+    v = _gauss(400 * B, 3)
+    test = _gauss(100 * B, 4)
+    gains = {}
+    for bits in (2, 3, 4, 6):
+        uni = ref.levels_uniform(bits)
+        fit = ref.fit_levels(v, bits, B, 0.01, uni)
+        assert np.all(np.diff(fit) > 0) and fit[0] >= 0 and fit[-1] <= 1
+        e_uni = _rel_l2(ref.dequantize_levels(*ref.quantize_levels(test, bits, B, uni), test.size, bits, B, uni), test)
+        e_fit = _rel_l2(ref.dequantize_levels(*ref.quantize_levels(test, bits, B, fit), test.size, bits, B, fit), test)
+        gains[bits] = e_uni / e_fit
+        assert e_fit < e_uni
+    assert gains[2] > 1.3 and gains[3] > 1.2 and gains[2] > gains[6]
+
+
+def test_fit_converges_to_the_known_optimum_for_uniform_data():
+    """For values uniform on an interval the optimal K-level quantizer has its levels at the
+    centres (k+1/2)/K of K equal cells (Lloyd's condition: each level is the mean of its cell)."""
+    bits, B = 2, 1024
+    rng = np.random.default_rng(5)
+    v = rng.random(600 * B).astype(np.float32)
+    v[::B] = 0.0
+    v[1::B] = 1.0                                     # every bucket spans [0, 1]
+    fit = ref.fit_levels(v, bits, B, 0.01, ref.levels_uniform(bits))
+    assert np.allclose(fit, (np.arange(4) + 0.5) / 4, atol=0.01)
+    # a fixed point up to the noise of a batch mean (sd of a cell mean over ~256 values = 0.0045)
+    again = ref.fit_levels(v[:50 * B], bits, B, 0.01, fit)
+    assert np.allclose(again, fit, atol=0.02)
+
+
+def test_max_batches_and_empty_cells():
+    bits, B = 3, 64
+    v = _gauss(10 * B, 6)
+    lv = ref.levels_uniform(bits)
+    a = ref.fit_levels(v, bits, B, 0.01, lv, max_batches=3)
+    b = ref.fit_levels(v[:3 * B], bits, B, 0.01, lv)
+    assert np.array_equal(a, b)
+    # a level nobody is assigned to does not move
+    two = np.array([0.0, 1.0] * 32, np.float32)
+    c = ref.fit_levels(two, bits, B, 0.1, lv)
+    assert np.array_equal(c[1:-1], lv[1:-1])

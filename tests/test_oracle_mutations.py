@@ -43,6 +43,13 @@ MUTANTS = [
      ["test_oracle_variants.py"]),
     ("no_shift_flag_ignored_for_weights", "return (flags & QSDP_REF_FLAG_NO_SHIFT) ? 0.0f : qsdp_ref_weight_shift(seed);",
      "return qsdp_ref_weight_shift(seed);", ["test_oracle_variants.py"]),
+    ("closest_level_takes_last_minimum", "if (d < best_d) {", "if (d <= best_d) {", ["test_oracle_levels.py"]),
+    ("level_update_moves_away", "levels[k] = (float)(q - (1.0 - keep[count[k]]) * (q - mean));",
+     "levels[k] = (float)(q + (1.0 - keep[count[k]]) * (q - mean));", ["test_oracle_levels.py"]),
+    ("level_update_single_step", "levels[k] = (float)(q - (1.0 - keep[count[k]]) * (q - mean));",
+     "levels[k] = (float)(q - (1.0 - keep[1]) * (q - mean));", ["test_oracle_levels.py"]),
+    ("level_decode_ignores_table", "float val = fmaf(levels[code[i]], meta[2 * j + 1], meta[2 * j]);",
+     "float val = fmaf((float)code[i], meta[2 * j + 1], meta[2 * j]);", ["test_oracle_levels.py"]),
     ("step_sign_flipped", "y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);", "y[i] = fmaf(lr, ghat[i], x[s + (uint64_t)i]);",
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
