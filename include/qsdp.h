@@ -192,6 +192,36 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
                           uint64_t* n_saturated, void* stream);
 
 /*
+ * Learned (non-uniform) quantization levels: Section 5.2, Algorithm 1, Appendix C.
+ * A level table is 2^bits floats in bucket-normalised coordinates z = (v-lo)/(hi-lo) in
+ * [0,1], ascending (DEVICE memory, 4-byte aligned; the library does not validate its contents;
+ * unsorted levels give unspecified codes but no fault). Per bucket meta = {lo, hi-lo}.
+ *   qsdp_levels_uniform     host only: fills a HOST array with k/(2^bits-1), the usual start.
+ *   qsdp_quantize_levels    code = index of the NEAREST level to z (ties and equal levels: the
+ *                           lowest index); deterministic. Wire format as for the other codes.
+ *   qsdp_dequantize_levels  out = fma(levels[code], hi-lo, lo), fp32 or bf16.
+ *   qsdp_fit_levels         the level optimisation of Algorithm 1 in batched form, batch = one
+ *                           bucket, visited in order (the first max_batches only, if > 0): the
+ *                           values of a batch are normalised and assigned to their nearest
+ *                           level with the levels frozen; every level that received c > 0
+ *                           values takes its c steps of rate lr towards the mean m of those
+ *                           values at once: q <- q - (1-(1-lr)^c)(q-m). Sums are exact (32.32
+ *                           fixed point), the update is evaluated in binary64: the result is
+ *                           reproducible bit for bit. Runs as ONE workgroup (each batch starts
+ *                           from the levels the previous one left); it is a rare, offline-like
+ *                           call (the paper runs it a few times per training), not a hot path.
+ *                           0 < lr < 1. `levels` is read as the start and overwritten.
+ */
+int qsdp_levels_uniform(int bits, float* levels);
+int qsdp_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                         uint32_t* codes, float* meta, void* stream);
+int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
+                           int bucket, const float* levels, qsdp_dtype out_dtype,
+                           void* out, void* stream);
+int qsdp_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
+                    uint64_t max_batches, float* levels, void* stream);
+
+/*
  * Multi-tensor ("segmented") variants: in the paper's system every layer is compressed on
  * its own (Section 5.1), i.e. bucketing restarts at each tensor.
  * These calls do that for many tensors laid back to back in one flat buffer with ONE kernel

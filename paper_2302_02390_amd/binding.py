@@ -20,6 +20,7 @@ QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC = 1, 2, 4
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
+           "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented")
 
@@ -57,6 +58,12 @@ def lib():
         L.qsdp_quantize_weight_ex.argtypes = [vp, u64, i32, i32, f32, u64, u32, vp, vp, vp, vp]
         L.qsdp_fused_step_ex.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, u32, vp, vp, vp, vp]
         for name in ("qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex"):
+            getattr(L, name).restype = i32
+        L.qsdp_levels_uniform.argtypes = [i32, vp]
+        L.qsdp_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp]
+        L.qsdp_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp, vp]
+        L.qsdp_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp]
+        for name in ("qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels"):
             getattr(L, name).restype = i32
         L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
         L.qsdp_dequantize_add.restype = i32
@@ -183,6 +190,47 @@ def qsdp_dequantize(codes, meta, n, bits, bucket, out):
     with torch.cuda.device(out.device):
         _check(lib().qsdp_dequantize(_ptr(codes), _ptr(meta), n, bits, bucket, dt, _ptr(out),
                                      _stream(out)), "qsdp_dequantize")
+
+
+def levels_uniform(bits, device):
+    """The uniform starting table k/(2^bits-1) as a device tensor."""
+    import numpy as np
+    host = np.zeros(1 << bits, dtype=np.float32)
+    _check(lib().qsdp_levels_uniform(bits, host.ctypes.data_as(C.c_void_p)), "qsdp_levels_uniform")
+    return torch.from_numpy(host).to(device)
+
+
+def qsdp_quantize_levels(v, bits, bucket, levels, codes, meta):
+    _is(v, torch.float32); _is(levels, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if levels.numel() != (1 << bits):
+        raise ValueError("levels must hold 2^bits entries")
+    with torch.cuda.device(v.device):
+        _check(lib().qsdp_quantize_levels(_ptr(v), v.numel(), bits, bucket, _ptr(levels), _ptr(codes), _ptr(meta),
+                                          _stream(v)), "qsdp_quantize_levels")
+
+
+def qsdp_dequantize_levels(codes, meta, n, bits, bucket, levels, out):
+    _is(codes, torch.int32); _is(meta, torch.float32); _is(levels, torch.float32)
+    if levels.numel() != (1 << bits):
+        raise ValueError("levels must hold 2^bits entries")
+    dt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16}.get(out.dtype)
+    if dt is None:
+        raise TypeError("out must be float32 or bfloat16")
+    _is(out, out.dtype)
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize_levels(_ptr(codes), _ptr(meta), n, bits, bucket, _ptr(levels), dt, _ptr(out),
+                                            _stream(out)), "qsdp_dequantize_levels")
+
+
+def qsdp_fit_levels(v, bits, bucket, lr, levels, max_batches=0):
+    _is(v, torch.float32); _is(levels, torch.float32)
+    if levels.numel() != (1 << bits):
+        raise ValueError("levels must hold 2^bits entries")
+    with torch.cuda.device(v.device):
+        _check(lib().qsdp_fit_levels(_ptr(v), v.numel(), bits, bucket, lr, max_batches, _ptr(levels), _stream(v)),
+               "qsdp_fit_levels")
 
 
 def qsdp_dequantize_add(codes, meta, npeers, n, bits, bucket, alpha, out):

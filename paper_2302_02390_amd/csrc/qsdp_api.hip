@@ -16,6 +16,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_WEIGHT: hipLaunchKernelGGL(block_kernel<MODE_WEIGHT>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -29,18 +30,21 @@ static int bucket_indexing(const DequantParams& p, bool bf16) {
 }
 
 namespace {
+template <int BITS, bool BF16, bool LUT>
+void dequant_launch(int bk, const DequantParams& p, unsigned grid, hipStream_t s) {
+    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_TILE_UNIFORM, LUT>), dim3(grid), dim3(256), 0, s, p);
+    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_SHIFT, LUT>), dim3(grid), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_DIVIDE, LUT>), dim3(grid), dim3(256), 0, s, p);
+}
+
 template <int BITS>
 hipError_t dequant_go(bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
     const int bk = bucket_indexing(p, bf16);
-    if (bf16) {
-        if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, p);
-        else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_SHIFT>), dim3(grid), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((dequant_kernel<BITS, true, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, p);
-    } else {
-        if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, p);
-        else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_SHIFT>), dim3(grid), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((dequant_kernel<BITS, false, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, p);
-    }
+    const bool lut = p.levels != nullptr;
+    if (bf16 && lut) dequant_launch<BITS, true, true>(bk, p, grid, s);
+    else if (bf16) dequant_launch<BITS, true, false>(bk, p, grid, s);
+    else if (lut) dequant_launch<BITS, false, true>(bk, p, grid, s);
+    else dequant_launch<BITS, false, false>(bk, p, grid, s);
     return hipGetLastError();
 }
 }  // namespace
@@ -69,6 +73,21 @@ hipError_t launch_dequant_add(int bits, const DequantAddParams& p, unsigned grid
         case 8: return dequant_add_go<8>(p, grid, s);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_fit_levels(const FitParams& p, hipStream_t s) {
+    switch (p.bits) {
+        case 1: hipLaunchKernelGGL(fit_levels_kernel<1>, dim3(1), dim3(256), 0, s, p); break;
+        case 2: hipLaunchKernelGGL(fit_levels_kernel<2>, dim3(1), dim3(256), 0, s, p); break;
+        case 3: hipLaunchKernelGGL(fit_levels_kernel<3>, dim3(1), dim3(256), 0, s, p); break;
+        case 4: hipLaunchKernelGGL(fit_levels_kernel<4>, dim3(1), dim3(256), 0, s, p); break;
+        case 5: hipLaunchKernelGGL(fit_levels_kernel<5>, dim3(1), dim3(256), 0, s, p); break;
+        case 6: hipLaunchKernelGGL(fit_levels_kernel<6>, dim3(1), dim3(256), 0, s, p); break;
+        case 7: hipLaunchKernelGGL(fit_levels_kernel<7>, dim3(1), dim3(256), 0, s, p); break;
+        case 8: hipLaunchKernelGGL(fit_levels_kernel<8>, dim3(1), dim3(256), 0, s, p); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
@@ -260,6 +279,61 @@ int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bi
     const DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype == QSDP_BF16, out, &grid);
     if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_levels_uniform(int bits, float* levels) {
+    if (bits < 1 || bits > 8 || !levels) return QSDP_EINVAL;
+    const int K = 1 << bits;
+    for (int k = 0; k < K; ++k) levels[k] = (float)k / (float)(K - 1);
+    return QSDP_OK;
+}
+
+int qsdp_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                         uint32_t* codes, float* meta, void* stream) {
+    if (!v || !levels || !codes || !meta || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    if (!aligned16(v) || !aligned16(codes) || !aligned16(meta) || (reinterpret_cast<uintptr_t>(levels) & 3u))
+        return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, 0, 0, 0.0f);
+    p.xin = v;
+    p.levels = levels;
+    p.codes = codes;
+    p.meta = meta;
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_LEVELS, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
+                           const float* levels, qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!codes || !meta || !levels || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (n >= (1ull << 37)) return QSDP_EINVAL;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (reinterpret_cast<uintptr_t>(levels) & 3u))
+        return QSDP_EALIGN;
+    unsigned grid = 0;
+    DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype == QSDP_BF16, out, &grid);
+    p.levels = levels;
+    if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr, uint64_t max_batches,
+                    float* levels, void* stream) {
+    if (!v || !levels || !shape_ok(n, bits, bucket) || !(lr > 0.0f && lr < 1.0f)) return QSDP_EINVAL;
+    if (!aligned16(v) || (reinterpret_cast<uintptr_t>(levels) & 3u)) return QSDP_EALIGN;
+    FitParams p = {};
+    p.v = v;
+    p.levels = levels;
+    p.n = n;
+    p.num_batches = ceil_div(n, (uint64_t)bucket);
+    if (max_batches > 0 && max_batches < p.num_batches) p.num_batches = max_batches;
+    p.bucket = bucket;
+    p.bits = bits;
+    p.lr = lr;
+    if (launch_fit_levels(p, static_cast<hipStream_t>(stream)) != hipSuccess) return QSDP_ELAUNCH;
     return QSDP_OK;
 }
 

@@ -195,6 +195,25 @@ __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, 
     return c;
 }
 
+// Nearest of the K = 2^BITS ascending levels `lv` (in LDS) to z; ties and equal levels resolve
+// to the lowest index. Branch-free lower bound over the power-of-two table, then the closer of
+// the two neighbours.
+template <int BITS>
+__device__ __forceinline__ int nearest_level(float z, const float* lv) {
+    constexpr int K = 1 << BITS;
+    int j = 0;  // ends as the number of levels < z among the first K-1, i.e. a lower bound
+#pragma unroll
+    for (int step = K / 2; step >= 1; step >>= 1)
+        if (lv[j + step - 1] < z) j += step;
+    // levels[j-1] < z <= levels[j] (with j in [0, K-1]; if all of the first K-1 are < z, j = K-1)
+    const int lo_idx = j > 0 ? j - 1 : 0;
+    const float d_lo = fabsf(z - lv[lo_idx]);
+    const float d_hi = fabsf(z - lv[j]);
+    int c = d_hi < d_lo ? j : lo_idx;
+    while (c > 0 && lv[c - 1] == lv[c]) --c;  // first among equal levels (rare)
+    return c;
+}
+
 // ---------------------------------------------------------------------------------------
 // Packing: 4 consecutive codes of a lane, 8 consecutive codes (a chunk) = BITS bytes
 // ---------------------------------------------------------------------------------------

@@ -23,7 +23,9 @@ namespace qsdp {
 // MODE_FUSED_CODES: the fused step with the weights resident as packed codes + meta (the
 // iterate always lies on its bucket grids, so codes + meta hold it exactly): decode, step,
 // re-quantize, write codes + meta back in place; no fp32 copy of x is read or written.
-enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3 };
+// MODE_LEVELS: nearest-level encoding against a table of learned (non-uniform) levels in
+// bucket-normalised coordinates.
+enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4 };
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
@@ -37,7 +39,8 @@ struct Params {
     // tensors
     const float* g;      // GRAD, FUSED: gradient
     float* x;            // FUSED: in/out weights
-    const float* xin;    // WEIGHT: weights to quantize
+    const float* xin;    // WEIGHT, LEVELS: values to quantize
+    const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]
     uint32_t* codes;     // packed output (nullable in FUSED)
     float* meta;         // {base, scale} per bucket (nullable iff codes is)
     unsigned long long* n_saturated;  // nullable
@@ -307,6 +310,11 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (BITS ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
+    __shared__ float level_table[MODE == MODE_LEVELS ? (1 << SB) : 1];
+    if constexpr (MODE == MODE_LEVELS) {
+        for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_table[k] = p.levels[k];
+        __syncthreads();
+    }
 
     const float Lg = (float)((1 << p.gbits) - 1);
     const float Lw = (float)((1 << p.wbits) - 1);
@@ -314,7 +322,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     const bool lattice = p.delta > 0.0f;
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
-    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD);
+    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
@@ -411,7 +419,22 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         }
 
         // weight quantization of w
-        if (lattice) {
+        if constexpr (MODE == MODE_LEVELS) {
+            float lo, hi;
+            rows_minmax<G, R>(w, l, m, partial, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);  // scale = hi - lo, inv = 1/(hi - lo)
+            base = grid.lo;
+            scale = grid.scale;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float z = (w[r][i] - grid.lo) * grid.inv;
+                    const float c = (float)nearest_level<SB>(z, level_table);
+                    w[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0.0f : c;
+                }
+        } else if (lattice) {
             float lo, unused_hi;
             rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
             block_combine_minmax<W>(lo, unused_hi, red_w, wave_in_block);
@@ -506,7 +529,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
     const bool lattice = p.delta > 0.0f;
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
-    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD);
+    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
     if (tid == 0) sat_block = 0;
 
@@ -582,7 +605,26 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
             }
             block_minmax(lo, hi, red);
             unsigned int sat_here = 0;
-            if (lattice) {
+            if (MODE == MODE_LEVELS) {
+                const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);
+                base = grid.lo;
+                scale = grid.scale;
+                const int K = 1 << p.wbits;
+                for (int i = tid; i < m; i += 256) {
+                    const float z = (val[i] - grid.lo) * grid.inv;
+                    // plain scan: nearest level, first index on ties (the table is in global memory)
+                    int best = 0;
+                    float best_d = fabsf(z - p.levels[0]);
+                    for (int k = 1; k < K; ++k) {
+                        const float d = fabsf(z - p.levels[k]);
+                        if (d < best_d) {
+                            best_d = d;
+                            best = k;
+                        }
+                    }
+                    code[i] = (uint8_t)best;
+                }
+            } else if (lattice) {
                 lo = lo + 0.0f;
                 const float k0 = rintf(div_delta(lo, div) - xi);
                 base = (k0 + xi) * p.delta;
@@ -643,6 +685,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
 struct DequantParams {
     const uint32_t* codes;
     const float* meta;
+    const float* levels;  // learned-level table (2^bits floats) or nullptr
     void* out;
     uint64_t n;
     uint64_t nwords;  // 32-bit words in the code buffer
@@ -696,15 +739,17 @@ __device__ __forceinline__ uint64_t bucket_of(uint64_t e, const DequantParams& p
     return e32 / p.bucket32;
 }
 
-template <int BITS, bool BF16>
+// `lut` = the level table in LDS (learned levels: the code indexes it), or nullptr (uniform
+// levels: the code is the level).
+template <int BITS, bool BF16, bool LUT>
 __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e, uint64_t bits, float base,
-                                             float scale, bool whole) {
+                                             float scale, bool whole, const float* lut) {
     constexpr int E = BF16 ? 8 : 4;
     float o[E];
 #pragma unroll
     for (int i = 0; i < E; ++i) {
         const uint32_t c = (uint32_t)(bits >> (i * BITS)) & ((1u << BITS) - 1u);
-        o[i] = fmaf((float)c, scale, base);
+        o[i] = fmaf(LUT ? lut[c] : (float)c, scale, base);
     }
     if (whole) {
         if (BF16) {
@@ -726,11 +771,16 @@ __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e,
     }
 }
 
-template <int BITS, bool BF16, int BK>
+template <int BITS, bool BF16, int BK, bool LUT>
 __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
     constexpr int E = BF16 ? 8 : 4;
     constexpr int U = kDequantRows;
     constexpr uint64_t T = (uint64_t)U * 64 * E;
+    __shared__ float lut[LUT ? (1 << BITS) : 1];
+    if (LUT) {
+        for (int k = threadIdx.x; k < (1 << BITS); k += blockDim.x) lut[k] = p.levels[k];
+        __syncthreads();
+    }
     const int lane = threadIdx.x & 63;
     const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t waves_per_block = blockDim.x >> 6;
@@ -753,7 +803,7 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                decode_store<BITS, BF16>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true);
+                decode_store<BITS, BF16, LUT>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true, lut);
         } else {
             // last, partial tile
             for (int u = 0; u < U; ++u) {
@@ -761,8 +811,8 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
                 if (e < p.n) {
                     const uint64_t bits = load_bits<E * BITS>(p.codes, e * BITS, last_word);
                     const uint64_t bucket = bucket_of<BK>(e, p);
-                    decode_store<BITS, BF16>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
-                                             e + E <= p.n);
+                    decode_store<BITS, BF16, LUT>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
+                                                  e + E <= p.n, lut);
                 }
             }
         }
@@ -851,6 +901,76 @@ __global__ void __launch_bounds__(256) dequant_add_kernel(const DequantAddParams
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Level fitting (Algorithm 1 in batched form): ONE workgroup walks the buckets in order, since
+// every batch starts from the levels the previous one left. Per bucket: stage the values in
+// LDS, block min/max, assign every value to its nearest level (levels frozen), accumulate
+// exact 32.32 fixed-point sums and counts per level with LDS atomics (order independent, so the
+// result is reproducible), then level k takes its count_k steps of rate lr towards the mean
+// of its values at once, in binary64: q <- q - (1 - (1-lr)^c)(q - mean).
+// ---------------------------------------------------------------------------------------
+struct FitParams {
+    const float* v;
+    float* levels;  // in/out, 2^bits floats
+    uint64_t n;
+    uint64_t num_batches;
+    int bucket;
+    int bits;
+    float lr;
+};
+
+template <int BITS>
+__global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
+    constexpr int K = 1 << BITS;
+    __shared__ float val[kMaxBucket];
+    __shared__ float lv[K];
+    __shared__ long long sum[K];
+    __shared__ unsigned int count[K];
+    __shared__ float red[8];
+    const int tid = threadIdx.x;
+    const int B = p.bucket;
+    for (int k = tid; k < K; k += 256) lv[k] = p.levels[k];
+    const double one_minus = 1.0 - (double)p.lr;
+    for (uint64_t j = 0; j < p.num_batches; ++j) {
+        const uint64_t e0 = j * (uint64_t)B;
+        const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
+        __syncthreads();  // previous batch's level update and LDS reads are complete
+        float lo = __builtin_inff(), hi = -__builtin_inff();
+        for (int i = tid; i < m; i += 256) {
+            const float x = p.v[e0 + i];
+            val[i] = x;
+            lo = fminf(lo, x);
+            hi = fmaxf(hi, x);
+        }
+        for (int k = tid; k < K; k += 256) {
+            sum[k] = 0;
+            count[k] = 0u;
+        }
+        block_minmax(lo, hi, red);  // contains the barriers that publish sum/count = 0 too
+        const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);
+        for (int i = tid; i < m; i += 256) {
+            const float z = (val[i] - grid.lo) * grid.inv;
+            const int k = nearest_level<BITS>(z, lv);
+            atomicAdd(reinterpret_cast<unsigned long long*>(&sum[k]),
+                      (unsigned long long)(long long)(z * 4294967296.0f));
+            atomicAdd(&count[k], 1u);
+        }
+        __syncthreads();
+        for (int k = tid; k < K; k += 256) {
+            const unsigned int c = count[k];
+            if (c != 0u) {
+                double keep = 1.0;
+                for (unsigned int t = 0; t < c; ++t) keep *= one_minus;  // (1 - lr)^c, same order as the oracle
+                const double mean = ((double)sum[k] / (double)c) * (1.0 / 4294967296.0);
+                const double q = (double)lv[k];
+                lv[k] = (float)(q - (1.0 - keep) * (q - mean));
+            }
+        }
+    }
+    __syncthreads();
+    for (int k = tid; k < K; k += 256) p.levels[k] = lv[k];
 }
 
 }  // namespace qsdp

@@ -45,6 +45,7 @@ hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, u
             if (bits == 0) return go<MODE_FUSED, 0>(p, grid, s);
             return by_bits<MODE_FUSED>(bits, p, grid, s);
         case MODE_FUSED_CODES: return by_bits<MODE_FUSED_CODES>(bits, p, grid, s);
+        case MODE_LEVELS: return by_bits<MODE_LEVELS>(bits, p, grid, s);
         default: return hipErrorInvalidValue;
     }
 }
