@@ -647,3 +647,59 @@ int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float 
     }
     return QSDP_REF_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* AdamW inside the quantized iteration (Appendix A names the optimizer)       */
+/* ------------------------------------------------------------------------- */
+
+int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, uint64_t n, float lr,
+                              float beta1, float beta2, float eps, float weight_decay, float bias1,
+                              float bias2, int wbits, int gbits, int bucket, float delta,
+                              uint64_t seed, uint64_t index_offset, uint32_t flags,
+                              uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
+    if (!x || !g || !mom || !var || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket) ||
+        (flags & ~QSDP_REF_FLAG_ALL))
+        return QSDP_REF_EINVAL;
+    if (!(delta >= 0.0f) || !isfinite(delta) || !isfinite(lr)) return QSDP_REF_EINVAL;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
+          bias2 > 0.0f && isfinite(weight_decay)))
+        return QSDP_REF_EINVAL;
+    if ((wcodes == NULL) != (wmeta == NULL) || index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    float xi = weight_shift_for(seed, flags);
+    float xi_g = grad_shift_for(seed, flags);
+    float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * wbits / 32;
+    uint64_t sat = 0;
+#pragma omp parallel for schedule(static) num_threads(g_threads) reduction(+ : sat)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float u[MAX_BUCKET], ghat[MAX_BUCKET], y[MAX_BUCKET];
+        uint8_t gcode[MAX_BUCKET], wcode[MAX_BUCKET];
+        float gbase, gscale, wbase, wscale;
+        uint64_t local = 0;
+        for (int i = 0; i < m; ++i) u[i] = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
+        grad_bucket_flags(g + s, u, m, gbits, flags, xi_g, gcode, &gbase, &gscale);
+        dequant_bucket(gcode, m, gbase, gscale, ghat);
+        for (int i = 0; i < m; ++i) {
+            uint64_t e = s + (uint64_t)i;
+            float mi = fmaf(beta1, mom[e], omb1 * ghat[i]);
+            float vi = fmaf(beta2, var[e], (omb2 * ghat[i]) * ghat[i]);
+            mom[e] = mi;
+            var[e] = vi;
+            float upd = (mi / bias1) / (sqrtf(vi / bias2) + eps);
+            y[i] = fmaf(-lr, fmaf(weight_decay, x[e], upd), x[e]);
+        }
+        weight_bucket(y, m, wbits, delta, xi, is_symmetric(flags), wcode, &wbase, &wscale, &local);
+        dequant_bucket(wcode, m, wbase, wscale, x + s);
+        if (wcodes) {
+            pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);
+            wmeta[2 * j] = wbase;
+            wmeta[2 * j + 1] = wscale;
+        }
+        sat += local;
+    }
+    if (n_saturated) *n_saturated += sat;
+    return QSDP_REF_OK;
+}

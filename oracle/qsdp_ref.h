@@ -121,6 +121,19 @@ int qsdp_ref_fused_step(float* x, const float* g, uint64_t n, float lr,
                         uint32_t* wcodes /* nullable */, float* wmeta /* nullable */,
                         uint64_t* n_saturated /* nullable */);
 
+/* AdamW-flavoured quantized step (the optimizer of the paper's experiments, Appendix A, in
+ * place of plain SGD inside the quantized iteration): per bucket ghat = decode(Q^g(g)); then per
+ * element, all in binary32 in this order:
+ *   m <- fma(beta1, m, (1-beta1)*ghat);  v <- fma(beta2, v, ((1-beta2)*ghat)*ghat);
+ *   upd = (m / bias1) / (sqrt(v / bias2) + eps);  y = fma(-lr, fma(weight_decay, x, upd), x);
+ * then x <- decode(Q^w(y)). bias1 = 1-beta1^t and bias2 = 1-beta2^t are passed in by the caller.
+ * m and v are updated in place. flags, delta, seeds as in qsdp_ref_fused_step_ex. */
+int qsdp_ref_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr,
+                              float beta1, float beta2, float eps, float weight_decay, float bias1,
+                              float bias2, int wbits, int gbits, int bucket, float delta,
+                              uint64_t seed, uint64_t index_offset, uint32_t flags,
+                              uint32_t* wcodes, float* wmeta, uint64_t* n_saturated);
+
 /* ---- Learned (non-uniform) quantization levels: Section 5.2, Algorithm 1, Appendix C ----
  * A level table holds 2^bits positions in bucket-normalised coordinates z = (v - lo)/(hi - lo)
  * in [0, 1], ascending. Encoding picks the NEAREST level (ties: the lowest index); decoding is

@@ -58,6 +58,8 @@ def lib():
         L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
         L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
         L.qsdp_ref_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp]
+        L.qsdp_ref_fused_adamw_step.argtypes = [vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, f32, f32, i32, i32,
+                                                i32, f32, u64, u64, u32, vp, vp, vp]
         L.qsdp_ref_levels_uniform.argtypes = [i32, vp]
         L.qsdp_ref_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp]
         L.qsdp_ref_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp]
@@ -276,3 +278,21 @@ def fit_levels(v, bits, bucket, lr, levels, max_batches=0):
     _check(lib().qsdp_ref_fit_levels(_p(v), v.size, bits, bucket, float(lr), int(max_batches), _p(lv)),
            "fit_levels")
     return lv
+
+
+def fused_adamw_step(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket,
+                     delta, seed, index_offset=0, flags=0, emit_codes=False):
+    """Returns (x_new, m_new, v_new, wcodes, wmeta, n_saturated); inputs are not modified."""
+    x = _f32(x).copy(); m = _f32(m).copy(); v = _f32(v).copy()
+    g = _f32(g)
+    n = x.size
+    wcodes = wmeta = None
+    if emit_codes:
+        wcodes = np.zeros(codes_bytes(n, wbits, bucket) // 4, dtype=np.uint32)
+        wmeta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_fused_adamw_step(_p(x), _p(g), _p(m), _p(v), n, float(lr), float(beta1), float(beta2),
+                                           float(eps), float(weight_decay), float(bias1), float(bias2), wbits,
+                                           gbits, bucket, float(delta), int(seed), int(index_offset), flags,
+                                           _p(wcodes), _p(wmeta), _p(sat)), "fused_adamw_step")
+    return x, m, v, wcodes, wmeta, int(sat[0])
