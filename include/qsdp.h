@@ -177,6 +177,26 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
                        uint64_t* n_saturated, void* stream);
 
 /*
+ * The quantized step with AdamW (the optimizer of the paper's experiments, Appendix A: betas
+ * 0.9 / 0.95, eps 1e-8) between the two quantizers in place of the plain SGD update, one pass
+ * over HBM: read x, g, m, v; write x, m, v (28 bytes per parameter). Per bucket
+ * ghat = decode(Q^g(g)), then per element, in binary32 and in this order:
+ *   m <- fma(beta1, m, (1-beta1)*ghat);   v <- fma(beta2, v, ((1-beta2)*ghat)*ghat);
+ *   u = (m / bias1) / (sqrt(v / bias2) + eps);   y = fma(-lr, fma(weight_decay, x, u), x);
+ * then x <- decode(Q^w(y)). bias1 = 1 - beta1^t and bias2 = 1 - beta2^t (t = step number from
+ * 1) are computed by the caller. 0 <= beta < 1, eps > 0, bias > 0.
+ *   m, v  in/out  device float[n], the moment estimates (start at 0)
+ * flags as in the *_ex entry points; the other arguments as in qsdp_fused_step.
+ */
+int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr,
+                          float beta1, float beta2, float eps, float weight_decay,
+                          float bias1, float bias2,
+                          int wbits, int gbits, int bucket, float delta,
+                          uint64_t seed, uint64_t index_offset, uint32_t flags,
+                          uint32_t* wcodes, float* wmeta,
+                          uint64_t* n_saturated, void* stream);
+
+/*
  * The same step with the weights RESIDENT AS CODES: every iterate of the quantized iteration
  * lies on its bucket grids (Section 4.1: the iterates live in the lattice domain), so
  * (wcodes, wmeta) hold x_t exactly and the fp32 copy is redundant. The call decodes x_t in

@@ -21,7 +21,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
-           "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
+           "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented")
 
 _lib = None
@@ -65,6 +65,9 @@ def lib():
         L.qsdp_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp]
         for name in ("qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels"):
             getattr(L, name).restype = i32
+        L.qsdp_fused_adamw_step.argtypes = [vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, f32, f32, i32, i32, i32,
+                                            f32, u64, u64, u32, vp, vp, vp, vp]
+        L.qsdp_fused_adamw_step.restype = i32
         L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
         L.qsdp_dequantize_add.restype = i32
         L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp]
@@ -261,6 +264,22 @@ def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
         _check(lib().qsdp_fused_step(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                      index_offset, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
                                      _stream(x)), "qsdp_fused_step")
+
+
+def qsdp_fused_adamw_step(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket,
+                          delta, seed, index_offset=0, flags=0, wcodes=None, wmeta=None, n_saturated=None):
+    for t in (x, g, m, v):
+        _is(t, torch.float32)
+    if not (g.numel() == x.numel() == m.numel() == v.numel()):
+        raise ValueError("x, g, m, v differ in size")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_adamw_step(_ptr(x), _ptr(g), _ptr(m), _ptr(v), x.numel(), lr, beta1, beta2, eps,
+                                           weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed,
+                                           index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
+                                           _stream(x)), "qsdp_fused_adamw_step")
 
 
 def qsdp_fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,

@@ -17,6 +17,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p); break;
         case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -388,6 +389,46 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits
     p.wbits = wbits;
     p.lr = lr;
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, float bias1, float bias2, int wbits,
+                          int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                          uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (!x || !g || !m || !v || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
+        (flags & ~QSDP_FLAG_ALL))
+        return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
+          bias2 > 0.0f && std::isfinite(weight_decay)))
+        return QSDP_EINVAL;
+    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(m) || !aligned16(v) || !aligned16(wcodes) ||
+        !aligned16(wmeta))
+        return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, index_offset, delta);
+    p.flags = flags;
+    p.x = x;
+    p.g = g;
+    p.mom = m;
+    p.var = v;
+    p.codes = wcodes;
+    p.meta = wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = gbits;
+    p.wbits = wbits;
+    p.lr = lr;
+    p.beta1 = beta1;
+    p.beta2 = beta2;
+    p.omb1 = 1.0f - beta1;
+    p.omb2 = 1.0f - beta2;
+    p.eps = eps;
+    p.weight_decay = weight_decay;
+    p.bias1 = bias1;
+    p.bias2 = bias2;
+    return run(MODE_ADAMW, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
 int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,

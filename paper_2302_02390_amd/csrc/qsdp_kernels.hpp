@@ -25,7 +25,10 @@ namespace qsdp {
 // re-quantize, write codes + meta back in place; no fp32 copy of x is read or written.
 // MODE_LEVELS: nearest-level encoding against a table of learned (non-uniform) levels in
 // bucket-normalised coordinates.
-enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4 };
+// MODE_ADAMW: the fused step with AdamW (moments m, v in fp32, updated in place) between the
+// two quantizers instead of the plain SGD update.
+enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
+            MODE_ADAMW = 5 };
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
@@ -41,6 +44,9 @@ struct Params {
     float* x;            // FUSED: in/out weights
     const float* xin;    // WEIGHT, LEVELS: values to quantize
     const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]
+    float* mom;          // ADAMW: first moment, in/out
+    float* var;          // ADAMW: second moment, in/out
+    float beta1, beta2, omb1, omb2, eps, weight_decay, bias1, bias2;  // ADAMW
     uint32_t* codes;     // packed output (nullable in FUSED)
     float* meta;         // {base, scale} per bucket (nullable iff codes is)
     unsigned long long* n_saturated;  // nullable
@@ -59,6 +65,21 @@ struct Params {
     int delta_pow2;
     uint32_t key0, key1;
 };
+
+// The value that gets weight-quantized: x - lr * ghat, or the AdamW update (binary32, in the
+// order m <- fma(b1, m, (1-b1) g); v <- fma(b2, v, ((1-b2) g) g); u = (m/c1) / (sqrt(v/c2) + eps);
+// y = fma(-lr, fma(wd, x, u), x)).
+template <int MODE>
+__device__ __forceinline__ float step_value(const Params& p, float x, float ghat, float& mom, float& var) {
+    if constexpr (MODE == MODE_ADAMW) {
+        mom = fmaf(p.beta1, mom, p.omb1 * ghat);
+        var = fmaf(p.beta2, var, (p.omb2 * ghat) * ghat);
+        const float upd = (mom / p.bias1) / (sqrtf(var / p.bias2) + p.eps);
+        return fmaf(-p.lr, fmaf(p.weight_decay, x, upd), x);
+    } else {
+        return fmaf(-p.lr, ghat, x);
+    }
+}
 
 // Where bucket `gb` starts in the flat buffers and how many of its `B` slots hold elements.
 // Quantizer variants (same values as the QSDP_FLAG_* of the C header)
@@ -351,11 +372,16 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES) {
+        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
+            float mom[R][4], var[R][4];  // MODE_ADAMW only
             load_rows<G, R>(p.g + e0, l, m, partial, gv);
-            if (MODE == MODE_FUSED) load_rows<G, R>(p.x + e0, l, m, partial, w);
+            if (MODE == MODE_FUSED || MODE == MODE_ADAMW) load_rows<G, R>(p.x + e0, l, m, partial, w);
+            if constexpr (MODE == MODE_ADAMW) {
+                load_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                load_rows<G, R>(p.var + e0, l, m, partial, var);
+            }
             if constexpr (MODE == MODE_FUSED_CODES) {
                 // x = decode(codes, meta) in registers
                 load_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
@@ -383,7 +409,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                             gcode[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0u : (uint32_t)code;
                         } else {
                             const float ghat = fmaf(code, grid.scale, gbase);
-                            w[r][i] = fmaf(-p.lr, ghat, w[r][i]);
+                            w[r][i] = step_value<MODE>(p, w[r][i], ghat, mom[r][i], var[r][i]);
                         }
                     }
             } else {
@@ -401,9 +427,15 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                         } else {
                             const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
                             const float ghat = fmaf(code, grid.scale, grid.lo);
-                            w[r][i & 3] = fmaf(-p.lr, ghat, w[r][i & 3]);
+                            w[r][i & 3] = step_value<MODE>(p, w[r][i & 3], ghat, mom[r][i & 3], var[r][i & 3]);
                         }
                     }
+                }
+            }
+            if constexpr (MODE == MODE_ADAMW) {
+                if (active) {
+                    store_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                    store_rows<G, R>(p.var + e0, l, m, partial, var);
                 }
             }
             if constexpr (MODE == MODE_GRAD) {
@@ -478,7 +510,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             }
         }
         if (active) {
-            if (MODE == MODE_FUSED) {
+            if (MODE == MODE_FUSED || MODE == MODE_ADAMW) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -548,7 +580,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
         const float old_base = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket] : 0.0f;
         const float old_scale = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket + 1] : 0.0f;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES) {
+        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
             float lo = __builtin_inff(), hi = -__builtin_inff();
             for (int i = tid; i < m; i += 256) {
                 const float v = p.g[e0 + i];
@@ -587,7 +619,16 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                     } else {
                         xold = p.x[e0 + i];
                     }
-                    val[i] = fmaf(-p.lr, ghat, xold);
+                    float mom = 0.0f, var = 0.0f;
+                    if (MODE == MODE_ADAMW) {
+                        mom = p.mom[e0 + i];
+                        var = p.var[e0 + i];
+                    }
+                    val[i] = step_value<MODE>(p, xold, ghat, mom, var);
+                    if (MODE == MODE_ADAMW) {
+                        p.mom[e0 + i] = mom;
+                        p.var[e0 + i] = var;
+                    }
                 }
             }
             base = gbase;
@@ -632,7 +673,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_lattice(val[i], div, xi, k0, Lw, sat_here);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW) p.x[e0 + i] = fmaf(c, scale, base);
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
             } else {
@@ -642,7 +683,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_minmax(val[i], grid, Lw, xi);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW) p.x[e0 + i] = fmaf(c, scale, base);
                 }
             }
         }
