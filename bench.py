@@ -234,6 +234,17 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"fused_step_codes_W{wbits}G{gbits}",
         lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i),
         4 + 2 * (wbits / 8.0 + meta_b))
+    run(f"fused_step_codes_W{wbits}G{gbits}_shared_shift_gradients",
+        lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i, 0, None,
+                                           qb.QSDP_FLAG_GRAD_SHIFT), 4 + 2 * (wbits / 8.0 + meta_b))
+    # AdamW between the quantizers (moments in fp32): read x, g, m, v; write x, m, v
+    mom = torch.zeros(n, dtype=torch.float32, device=dev)
+    var = torch.zeros(n, dtype=torch.float32, device=dev)
+    xa = x.clone()
+    run(f"fused_adamw_step_W{wbits}G{gbits}",
+        lambda i: qb.qsdp_fused_adamw_step(xa, g, mom, var, 2e-4, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** (i + 1),
+                                           1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i), 28.0)
+    del mom, var, xa
     # decode-and-sum of 8 peers' gradient slices on one GPU's 1/8 shard (the receive side of the
     # quantized gradient exchange): the 8 slices are 8 quantizations of the shard with different seeds
     peers = 8

@@ -202,13 +202,13 @@ int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t
  * (wcodes, wmeta) hold x_t exactly and the fp32 copy is redundant. The call decodes x_t in
  * registers, takes the step and writes the codes and meta of x_{t+1} back in place:
  * 4 + 2*wbits/8 bytes of HBM traffic per parameter instead of 12. Bit-identical to
- * qsdp_dequantize followed by qsdp_fused_step with code output.
+ * qsdp_dequantize followed by qsdp_fused_step_ex with code output and the same flags.
  *   wcodes, wmeta  in/out  packed Q^w representation of x (as written by qsdp_quantize_weight
  *                  or a fused step with the same wbits and bucket)
  */
 int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
                           int wbits, int gbits, int bucket, float delta,
-                          uint64_t seed, uint64_t index_offset,
+                          uint64_t seed, uint64_t index_offset, uint32_t flags,
                           uint64_t* n_saturated, void* stream);
 
 /*

@@ -508,14 +508,14 @@ int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int w
 
 int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
                               int wbits, int gbits, int bucket, float delta, uint64_t seed,
-                              uint64_t index_offset, uint64_t* n_saturated) {
+                              uint64_t index_offset, uint32_t flags, uint64_t* n_saturated) {
     if (!wcodes || !wmeta || !g || !args_ok(n, wbits, bucket)) return QSDP_REF_EINVAL;
     float* x = (float*)malloc((size_t)n * sizeof(float));
     if (!x) return QSDP_REF_EINVAL;
     int rc = qsdp_ref_dequantize(wcodes, wmeta, n, wbits, bucket, QSDP_REF_F32, x);
     if (rc == QSDP_REF_OK)
-        rc = qsdp_ref_fused_step(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, wcodes,
-                                 wmeta, n_saturated);
+        rc = qsdp_ref_fused_step_ex(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags,
+                                    wcodes, wmeta, n_saturated);
     free(x);
     return rc;
 }

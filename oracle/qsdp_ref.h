@@ -159,7 +159,8 @@ int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float 
  * codes and meta of the result back. By definition the composition of the two routines. */
 int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
                               int wbits, int gbits, int bucket, float delta,
-                              uint64_t seed, uint64_t index_offset, uint64_t* n_saturated);
+                              uint64_t seed, uint64_t index_offset, uint32_t flags,
+                              uint64_t* n_saturated);
 
 #ifdef __cplusplus
 }

@@ -64,7 +64,7 @@ def lib():
         L.qsdp_ref_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp]
         L.qsdp_ref_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp]
         L.qsdp_ref_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp]
-        L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp]
+        L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
         _lib = L
@@ -229,7 +229,7 @@ def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit
     return x, wcodes, wmeta, int(sat[0])
 
 
-def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0):
+def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, flags=0):
     """Returns (new wcodes, new wmeta, n_saturated); inputs are not modified."""
     g = _f32(g)
     n = g.size
@@ -238,7 +238,7 @@ def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, in
     assert wcodes.size * 4 == codes_bytes(n, wbits, bucket) and wmeta.shape[0] == _nb(n, bucket)
     sat = np.zeros(1, dtype=np.uint64)
     _check(lib().qsdp_ref_fused_step_codes(_p(wcodes), _p(wmeta), _p(g), n, float(lr), wbits, gbits, bucket,
-                                           float(delta), int(seed), int(index_offset), _p(sat)),
+                                           float(delta), int(seed), int(index_offset), flags, _p(sat)),
            "fused_step_codes")
     return wcodes, wmeta, int(sat[0])
 

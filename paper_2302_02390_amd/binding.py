@@ -70,7 +70,7 @@ def lib():
         L.qsdp_fused_adamw_step.restype = i32
         L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
         L.qsdp_dequantize_add.restype = i32
-        L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp]
+        L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp]
         L.qsdp_fused_step_codes.restype = i32
         L.qsdp_segments_build.argtypes = [vp, C.c_uint32, i32, vp]
         L.qsdp_segments_build.restype = u64
@@ -283,14 +283,14 @@ def qsdp_fused_adamw_step(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1
 
 
 def qsdp_fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
-                          n_saturated=None):
+                          n_saturated=None, flags=0):
     _is(wcodes, torch.int32); _is(wmeta, torch.float32); _is(g, torch.float32)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_fused_step_codes(_ptr(wcodes), _ptr(wmeta), _ptr(g), g.numel(), lr, wbits, gbits,
-                                           bucket, delta, seed, index_offset, _ptr(n_saturated), _stream(g)),
-               "qsdp_fused_step_codes")
+                                           bucket, delta, seed, index_offset, flags, _ptr(n_saturated),
+                                           _stream(g)), "qsdp_fused_step_codes")
 
 
 class Segments:

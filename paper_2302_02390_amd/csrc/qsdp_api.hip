@@ -433,13 +433,16 @@ int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t
 
 int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
-                          uint64_t* n_saturated, void* stream) {
-    if (!wcodes || !wmeta || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket)) return QSDP_EINVAL;
+                          uint32_t flags, uint64_t* n_saturated, void* stream) {
+    if (!wcodes || !wmeta || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
+        (flags & ~QSDP_FLAG_ALL))
+        return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr) || (index_offset & 7u)) return QSDP_EINVAL;
     if (!aligned16(wcodes) || !aligned16(wmeta) || !aligned16(g)) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, delta);
+    p.flags = flags;
     p.g = g;
     p.codes = wcodes;
     p.meta = wmeta;

@@ -12,9 +12,10 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("bucket", [32, 96, 128, 512, 1024, 2048, 4096])
-@pytest.mark.parametrize("wbits,gbits,delta", [(8, 4, 0.0), (4, 8, 0.0), (6, 3, 0.0), (2, 2, 0.0), (3, 6, 0.0),
-                                               (5, 4, 0.0), (7, 1, 0.0), (1, 8, 0.0), (8, 4, 2.0**-10)])
-def test_fused_step_codes_bit_exact(wbits, gbits, delta, bucket):
+@pytest.mark.parametrize("wbits,gbits,delta,flags", [(8, 4, 0.0, 0), (4, 8, 0.0, 0), (6, 3, 0.0, 0), (2, 2, 0.0, 0),
+                                                     (3, 6, 0.0, 0), (5, 4, 0.0, 0), (7, 1, 0.0, 0), (1, 8, 0.0, 0),
+                                                     (8, 4, 2.0**-10, 0), (8, 4, 0.0, 1), (6, 4, 0.0, 5)])
+def test_fused_step_codes_bit_exact(wbits, gbits, delta, flags, bucket):
     n = 7 * bucket + bucket // 2 + 5
     x, g = synth(n, 300 + wbits * 10 + gbits)
     c0, m0, _ = ref.quantize_weight(x, wbits, bucket, delta, seed=50)
@@ -24,8 +25,8 @@ def test_fused_step_codes_bit_exact(wbits, gbits, delta, bucket):
     sat = torch.zeros(1, dtype=torch.int64, device=DEV)
     hc, hm = c0, m0
     for step in range(3):
-        qb.qsdp_fused_step_codes(codes, meta, gd, 1e-2, wbits, gbits, bucket, delta, step, 0, sat)
-        hc, hm, hs = ref.fused_step_codes(hc, hm, g, 1e-2, wbits, gbits, bucket, delta, step)
+        qb.qsdp_fused_step_codes(codes, meta, gd, 1e-2, wbits, gbits, bucket, delta, step, 0, sat, flags)
+        hc, hm, hs = ref.fused_step_codes(hc, hm, g, 1e-2, wbits, gbits, bucket, delta, step, flags=flags)
         assert np.array_equal(np_u32(codes), hc), step
         assert np.array_equal(np_u32(meta), hm.view(np.uint32).reshape(-1)), step
 
