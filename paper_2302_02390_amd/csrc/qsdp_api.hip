@@ -109,6 +109,18 @@ namespace {
 
 constexpr unsigned kMaxGrid = 1u << 20;
 
+// Workgroups to launch for `blocks` units of work: all of them up to kMaxGrid, the kernels stride
+// beyond that. QSDP_DEBUG_MAXGRID (the library's one debug switch) lowers the cap so that the
+// striding paths can be exercised on small inputs.
+unsigned capped_grid(uint64_t blocks) {
+    unsigned cap = kMaxGrid;
+    if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
+        const long v = std::atol(e);
+        if (v >= 1 && v < (long)kMaxGrid) cap = (unsigned)v;
+    }
+    return (unsigned)(blocks < cap ? blocks : cap);
+}
+
 bool shape_ok(uint64_t n, int bits, int bucket) {
     return n >= 1 && bits >= 1 && bits <= 8 && bucket >= 32 && bucket <= kMaxBucket && bucket % 32 == 0;
 }
@@ -149,15 +161,9 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
     if (wl != nullptr && wave_bits_supported(stored_bits)) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
-        unsigned grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
-        if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
-            const unsigned cap = (unsigned)std::atoi(e);
-            if (cap >= 1 && grid > cap) grid = cap;
-        }
-        if (wl(mode, stored_bits, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
+        if (wl(mode, stored_bits, p, capped_grid(blocks), s) != hipSuccess) return QSDP_ELAUNCH;
     } else {
-        const unsigned grid = (unsigned)(nb < kMaxGrid ? nb : kMaxGrid);
-        if (launch_block(mode, p, grid, s) != hipSuccess) return QSDP_ELAUNCH;
+        if (launch_block(mode, p, capped_grid(nb), s) != hipSuccess) return QSDP_ELAUNCH;
     }
     return QSDP_OK;
 }
@@ -266,7 +272,7 @@ static DequantParams decoder_params(const uint32_t* codes, const float* meta, ui
     for (int sh = 0; sh < 9; ++sh)
         if (p.bucket32 == (1u << sh)) p.bucket32_shift = sh;
     const uint64_t blocks = ceil_div(p.ntiles, 4);
-    *grid = (unsigned)(blocks < kMaxGrid ? blocks : kMaxGrid);
+    *grid = capped_grid(blocks);
     return p;
 }
 
