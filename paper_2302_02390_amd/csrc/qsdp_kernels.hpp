@@ -1,19 +1,22 @@
 // Kernels of the QSDP codec for gfx950.
 //
 // Two families share the element arithmetic of qsdp_device.hpp:
-//   * wave kernels: a bucket is owned by an aligned group of G lanes of one wave and never
-//     leaves registers: one pass over HBM, no LDS, no barrier. The bucket is cut into R rows
+//   * wave kernels: a bucket is owned by an aligned group of G lanes of one wave and its values
+//     never leave registers: one pass over HBM, no barrier (LDS only stages the packed codes so
+//     that they are written with 16-byte stores). The bucket is cut into R rows
 //     of 4*G elements; lane l of the group holds elements (r*G + l)*4 .. +3 of every row r, so
 //     each load/store instruction of a wave touches whole contiguous 16*G-byte segments.
 //     Bucket size B = 4*G*R, R even. A Philox block (8 elements) and a packed code chunk
 //     (8 codes = BITS bytes) span the lane pair (l even, l+1) of one row: for each row pair
 //     (2c, 2c+1) the even lane owns the block/chunk of row 2c and the odd lane that of row
 //     2c+1, and the pair swaps halves with one DPP quad permute. A wave handles 64/G buckets
-//     at a time; waves stride over the full buckets of the vector. Buckets larger than one
+//     at a time, one wave per such group (waves stride only past 2^20 workgroups); a short last
+//     bucket takes a guarded element-wise path of the same kernel. Buckets larger than one
 //     wave's tile are shared by the W waves of a workgroup (B = 4*G*R*W, G = 64): each wave
 //     owns a contiguous 1/W of the bucket and the waves combine their min/max through LDS.
 //   * block kernel: one 256-thread workgroup per bucket, staged in LDS; any bucket size, any
-//     bits, short last bucket. Used for the shapes the wave kernels do not cover.
+//     bits. Used for the shapes the wave kernels do not cover.
+// Decoders, the decode-and-sum kernel and the level-fitting kernel follow at the end.
 #pragma once
 
 #include "qsdp_device.hpp"
@@ -81,7 +84,6 @@ __device__ __forceinline__ float step_value(const Params& p, float x, float ghat
     }
 }
 
-// Where bucket `gb` starts in the flat buffers and how many of its `B` slots hold elements.
 // Quantizer variants (same values as the QSDP_FLAG_* of the C header)
 enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u };
 
@@ -99,6 +101,8 @@ __device__ __forceinline__ Shifts draw_shifts(const Params& p, bool weights) {
     return s;
 }
 
+// Where a bucket starts in the flat buffers (element index) and how many of its B slots hold
+// elements; for a segmented call the bucket's tensor is found by binary search in the table.
 struct BucketRef {
     uint64_t e0;
     uint32_t m;
@@ -303,10 +307,11 @@ __device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float
     }
 }
 
-// MODE_GRAD / MODE_WEIGHT / MODE_FUSED over the buckets first_bucket .. +num_buckets-1 (the
-// last bucket of a tensor may be short). BITS is the width of the codes that are stored (0:
-// FUSED without code output). W = waves per bucket (W > 1: the workgroup has exactly W waves
-// and owns one bucket per iteration). delta > 0 selects the explicit grid (wave-uniform).
+// Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
+// be short). BITS is the width of the codes that are stored (0: FUSED / ADAMW without code
+// output). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
+// per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
+// wave-uniform branches).
 template <int MODE, int G, int R, int BITS, int W>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
