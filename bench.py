@@ -45,6 +45,9 @@ def parse():
                     help="bucketing restarts per tensor, all tensors in ONE segmented launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip timing the other entry points")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline run: the bits / bucket / delta sweep and the layer-by-layer "
+                         "decode to bf16 on the chosen workload; still one JSON line (key 'sweep')")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device copy of the weight vector a few times (a kernel of "
@@ -101,6 +104,10 @@ def main():
 
     def step(k):
         qb.qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, k, 0, wcodes, wmeta, None)
+
+    if a.sweep:
+        print(json.dumps(sweep(torch, qb, wl, x, g, n, a.workload, dev)))
+        return 0
 
     if a.segmented:
         if a.workload == "1m":
@@ -199,6 +206,64 @@ def main():
                                            bytes_per_param)
     print(json.dumps(out))
     return 0
+
+
+def sweep(torch, qb, wl, x, g, n, workload, dev):
+    """Fused step over gradient bits x weight bits x bucket, the explicit-delta pairings, the
+    quantizers, and the decode of the transformer blocks to bf16 one by one (median of 10 calls)."""
+    def med(fn, iters=10):
+        for i in range(2):
+            fn(i)
+        return time_call(fn, iters, torch)[1]
+
+    rows = []
+    for B in (128, 512, 1024, 4096):
+        for gb in (2, 3, 4, 6, 8):
+            for wb in (4, 6, 8):
+                t = med(lambda i: qb.qsdp_fused_step(x, g, 1e-3, wb, gb, B, 0.0, i))
+                rows.append({"call": "fused_step", "bucket": B, "gbits": gb, "wbits": wb, "ms": round(t, 4),
+                             "GB/s": round(12.0 * n / t / 1e6, 1)})
+    for d, wb in ((2.0 ** -6, 4), (2.0 ** -8, 6), (2.0 ** -10, 8)):
+        sat = torch.zeros(1, dtype=torch.int64, device=dev)
+        t = med(lambda i: qb.qsdp_fused_step(x, g, 1e-3, wb, 4, 1024, d, i, 0, None, None, sat))
+        rows.append({"call": "fused_step", "bucket": 1024, "gbits": 4, "wbits": wb, "delta": d, "ms": round(t, 4),
+                     "GB/s": round(12.0 * n / t / 1e6, 1), "saturated_per_call": int(sat) // 12})
+    for B in (128, 1024, 4096):
+        for b in (2, 3, 4, 6, 8):
+            c, m = qb.alloc_packed(n, b, B, dev)
+            bp = 4 + b / 8.0 + 8.0 / B
+            t = med(lambda i: qb.qsdp_quantize_grad(g, b, B, i, 0, c, m.reshape(-1)))
+            rows.append({"call": "quantize_grad", "bucket": B, "bits": b, "ms": round(t, 4),
+                         "GB/s": round(bp * n / t / 1e6, 1)})
+            t = med(lambda i: qb.qsdp_quantize_weight(x, b, B, 0.0, i, c, m.reshape(-1)))
+            rows.append({"call": "quantize_weight", "bucket": B, "bits": b, "ms": round(t, 4),
+                         "GB/s": round(bp * n / t / 1e6, 1)})
+            del c, m
+    layer = None
+    if workload != "1m":
+        shape = {"gpt-1.3b": wl.GPT_1P3B, "gpt-350m": wl.GPT_350M, "gpt-125m": wl.GPT_125M}[workload]
+        blk = wl.block_numel(shape.d)
+        start = (wl.VOCAB + wl.N_CTX) * shape.d
+        out = torch.empty(blk, dtype=torch.bfloat16, device=dev)
+        packed = []
+        for layer_id in range(shape.layers):
+            c, m = qb.alloc_packed(blk, 8, 1024, dev)
+            qb.qsdp_quantize_weight(x[start + layer_id * blk: start + (layer_id + 1) * blk], 8, 1024, 0.0, layer_id, c,
+                                    m.reshape(-1))
+            packed.append((c, m.reshape(-1)))
+
+        def all_layers(i):
+            for c, m in packed:
+                qb.qsdp_dequantize(c, m, blk, 8, 1024, out)
+
+        t_all = med(all_layers, 5)
+        t_one = med(lambda i: qb.qsdp_dequantize(packed[0][0], packed[0][1], blk, 8, 1024, out))
+        bp = 2 + 1 + 8.0 / 1024
+        layer = {"block_elements": blk, "layers": shape.layers, "ms_one_block": round(t_one, 4),
+                 "GB/s_one_block": round(bp * blk / t_one / 1e6, 1), "ms_all_blocks": round(t_all, 4),
+                 "GB/s_all_blocks": round(bp * blk * shape.layers / t_all / 1e6, 1)}
+    return {"metric": "sweep of the codec entry points (algorithmic GB/s)", "workload": workload, "n": n,
+            "data": "synthetic", "sweep": rows, "layerwise_dequantize_to_bf16": layer}
 
 
 def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
