@@ -237,3 +237,47 @@ def test_config5_layerwise_dequantize_to_bf16(gpt1p3b):
             assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), want)
             ids = sample_bucket_ids(blk // B, 32, layer)
             check_quantized_buckets("weight", xs, wc, wm, 8, B, 0.0, layer, ids, blk)
+
+
+def test_more_than_2_to_32_elements():
+    """Maximum sizes: a vector of 2^32 + 3*1024 + 5 elements (17 GB of fp32). Element indices,
+    Philox counters and code offsets pass 32 bits, the grid passes 2^20 workgroups (so waves
+    stride), and the vector ends in a short bucket. Buckets around the 2^32 boundary, the last
+    ones and random ones are recomputed by the oracle."""
+    B = 1024
+    n = (1 << 32) + 3 * B + 5
+    nb_full = n // B
+    g = torch.empty(n, dtype=torch.float32, device=DEV)
+    for s in range(0, n, 1 << 28):                       # fill in chunks: bounded temporaries
+        e = min(n, s + (1 << 28))
+        g[s:e].normal_(0.0, 1e-3, generator=torch.Generator(device=DEV).manual_seed(s >> 28))
+    ids = np.unique(np.concatenate([sample_bucket_ids(nb_full, 40, 11),
+                                    np.array([(1 << 22) - 1, 1 << 22, (1 << 22) + 1, nb_full - 2, nb_full - 1])]))
+    gc, gm = qb.alloc_packed(n, 4, B, DEV)
+    qb.qsdp_quantize_grad(g, 4, B, 3, 0, gc, gm.reshape(-1))
+    check_quantized_buckets("grad", g, gc, gm, 4, B, 0.0, 3, ids, n)
+    # decode the gradient back (bf16) and compare the sampled buckets and the tail
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    qb.qsdp_dequantize(gc, gm.reshape(-1), n, 4, B, out)
+    crow = u32(gather_rows(gc, ids, B * 4 // 32))
+    mrow = gather_rows(gm.reshape(-1), ids, 2)
+    orow = gather_rows(out.view(torch.int16), ids, B).view(np.uint16)
+    for r in range(len(ids)):
+        assert np.array_equal(orow[r], ref.dequantize(crow[r], mrow[r], B, 4, B, ref.BF16))
+    tail = n - nb_full * B
+    wt = ref.dequantize(u32(gc[nb_full * (B * 4 // 32):].cpu().numpy()), gm[nb_full:].cpu().numpy(), tail, 4, B, ref.BF16)
+    assert np.array_equal(out[nb_full * B:].view(torch.int16).cpu().numpy().view(np.uint16), wt)
+    del out, gc, gm
+    # fused step in place on x (another 17 GB)
+    x = torch.empty(n, dtype=torch.float32, device=DEV)
+    for s in range(0, n, 1 << 28):
+        e = min(n, s + (1 << 28))
+        x[s:e].normal_(0.0, 0.02, generator=torch.Generator(device=DEV).manual_seed(100 + (s >> 28)))
+    xb, gb = gather_rows(x, ids, B), gather_rows(g, ids, B)
+    tx, tg = x[nb_full * B:].cpu().numpy(), g[nb_full * B:].cpu().numpy()
+    qb.qsdp_fused_step(x, g, 1e-3, 8, 4, B, 0.0, 4)
+    check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, 8, 4, 0.0, 4)
+    want_tail, _, _, _ = ref.fused_step(tx, tg, 1e-3, 8, 4, B, 0.0, 4, index_offset=nb_full * B)
+    assert bits_equal(x[nb_full * B:].cpu().numpy(), want_tail)
+    del x, g
+    torch.cuda.empty_cache()
