@@ -204,6 +204,16 @@ __device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m
     hi = group_max<G>(hi);
 }
 
+// Slots at or past m (a short bucket) carry code 0. Only called on the guarded path.
+template <int G, int R, typename CodeT>
+__device__ __forceinline__ void zero_slots_past_end(CodeT (&c)[R][4], int l, int m) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((r * G + l) * 4 + i >= m) c[r][i] = CodeT(0);
+}
+
 // Pack the codes of all rows and stage them in LDS in wire order, then write the wave's code
 // tile (its 64/G buckets are consecutive, so the tile is 32*R*BITS contiguous bytes) with
 // 16-byte stores, one contiguous run per instruction. c[r][i] are the codes of this lane's
@@ -411,7 +421,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                     for (int i = 0; i < 4; ++i) {
                         const float code = weight_code_minmax(gv[r][i], grid, Lg, shifts.xi_g);
                         if constexpr (MODE == MODE_GRAD) {
-                            gcode[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0u : (uint32_t)code;
+                            gcode[r][i] = (uint32_t)code;
                         } else {
                             const float ghat = fmaf(code, grid.scale, gbase);
                             w[r][i] = step_value<MODE>(p, w[r][i], ghat, mom[r][i], var[r][i]);
@@ -426,9 +436,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                     for (int i = 0; i < 8; ++i) {
                         const int r = 2 * cp + (i >> 2);
                         if constexpr (MODE == MODE_GRAD) {
-                            const uint32_t c = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
-                            // slots past the end of a short bucket hold code 0
-                            gcode[r][i & 3] = (partial && (r * G + l) * 4 + (i & 3) >= m) ? 0u : c;
+                            gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
                         } else {
                             const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
                             const float ghat = fmaf(code, grid.scale, grid.lo);
@@ -444,6 +452,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
                 }
             }
             if constexpr (MODE == MODE_GRAD) {
+                if (partial) zero_slots_past_end<G, R>(gcode, l, m);
                 store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
                 if (writes_meta) {
                     p.meta[2 * bucket] = gbase;
@@ -468,8 +477,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float z = (w[r][i] - grid.lo) * grid.inv;
-                    const float c = (float)nearest_level<SB>(z, level_table);
-                    w[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0.0f : c;
+                    w[r][i] = (float)nearest_level<SB>(z, level_table);
                 }
         } else if (lattice) {
             float lo, unused_hi;
@@ -480,16 +488,23 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
             base = (k0 + xi) * p.delta;
             scale = p.delta;
             uint32_t sat_here = 0;
+            if (!partial) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    uint32_t sat_one = 0;
-                    const float c = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_one);
-                    const bool valid = !partial || (r * G + l) * 4 + i < m;
-                    w[r][i] = valid ? c : 0.0f;
-                    sat_here += valid ? sat_one : 0u;
-                }
+                    for (int i = 0; i < 4; ++i) w[r][i] = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_here);
+            } else {  // short bucket: slots past the end neither count as saturated nor carry a code
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        uint32_t sat_one = 0;
+                        const float c = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_one);
+                        const bool valid = (r * G + l) * 4 + i < m;
+                        w[r][i] = valid ? c : 0.0f;
+                        sat_here += valid ? sat_one : 0u;
+                    }
+            }
             if (active) saturated += sat_here;
         } else {
             float lo, hi;
@@ -501,11 +516,9 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float c = weight_code_minmax(w[r][i], grid, Lw, xi);
-                    w[r][i] = (partial && (r * G + l) * 4 + i >= m) ? 0.0f : c;
-                }
+                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
         }
+        if (partial && BITS != 0) zero_slots_past_end<G, R>(w, l, m);
 
         if (BITS != 0) {
             store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
