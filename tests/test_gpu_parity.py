@@ -214,3 +214,32 @@ def test_config1_all_entry_points():
     out, _, _, _ = gpu_fused_step(x, g, 1e-3, 8, 8, B, 0.0, seed=0)
     want, _, _, _ = ref.fused_step(x, g, 1e-3, 8, 8, B, 0.0, 0)
     assert close(np_f32(out), want) and bits_equal(np_f32(out), want)
+
+
+def test_non_finite_inputs_do_not_disturb_their_neighbours():
+    """Non-finite inputs are a precondition violation with unspecified codes, but memory addresses
+    never depend on the data: the call completes, buckets without such values are unaffected."""
+    B = 1024
+    n = 8 * B
+    x, g = synth(n, 9100)
+    gbad, xbad = g.copy(), x.copy()
+    gbad[3 * B + 5] = np.nan
+    gbad[5 * B + 7] = np.inf
+    xbad[3 * B + 9] = -np.inf
+    clean = [0, 1, 2, 4, 6, 7]
+    codes, meta = gpu_quantize_grad(gbad, 4, B, seed=1)
+    wc, wm = ref.quantize_grad(g, 4, B, seed=1)
+    wpb = B * 4 // 32
+    got = np_u32(codes).reshape(8, wpb)
+    assert np.array_equal(got[clean], wc.reshape(8, wpb)[clean])
+    out, _, _, _ = gpu_fused_step(xbad, gbad, 1e-3, 8, 4, B, 0.0, seed=2)
+    want, _, _, _ = ref.fused_step(x, g, 1e-3, 8, 4, B, 0.0, 2)
+    assert bits_equal(np_f32(out).reshape(8, B)[clean], want.reshape(8, B)[clean])
+    lv = torch.from_numpy(ref.levels_uniform(4)).to(DEV)
+    c2, m2 = qb.alloc_packed(n, 4, B, DEV)
+    qb.qsdp_quantize_levels(torch.from_numpy(xbad).to(DEV), 4, B, lv, c2, m2.reshape(-1))
+    o2 = torch.empty(n, dtype=torch.float32, device=DEV)
+    qb.qsdp_dequantize_levels(c2, m2.reshape(-1), n, 4, B, lv, o2)
+    torch.cuda.synchronize()
+    wc2, wm2 = ref.quantize_levels(x, 4, B, ref.levels_uniform(4))
+    assert np.array_equal(np_u32(c2).reshape(8, wpb)[clean], wc2.reshape(8, wpb)[clean])
