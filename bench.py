@@ -200,6 +200,8 @@ def main():
 
     if not a.no_extras:
         out["other_entry_points"] = extras(torch, qb, x, g, n, wbits, gbits, bucket, dev)
+        if a.segmented:
+            out["segmented_entry_points"] = segmented_extras(torch, qb, x, n, segs, wbits, bucket, dev)
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x0_head, g[: x0_head.numel()], lr, wbits, gbits, bucket, delta,
@@ -266,6 +268,30 @@ def sweep(torch, qb, wl, x, g, n, workload, dev):
             "data": "synthetic", "sweep": rows, "layerwise_dequantize_to_bf16": layer}
 
 
+def segmented_extras(torch, qb, x, n, segs, wbits, bucket, dev):
+    """Encode and decode of all layer tensors in one segmented launch each (algorithmic GB/s over
+    the n real elements; the padding slots of short tensors are not counted)."""
+    res = {}
+    meta_b = 8.0 / bucket
+    wc, wm = segs.alloc_packed(wbits)
+    wm = wm.reshape(-1)
+    out16 = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    out32 = torch.empty(n, dtype=torch.float32, device=dev)
+    for name, fn, bpp in (
+            (f"quantize_weight_segmented_b{wbits}",
+             lambda i: qb.qsdp_quantize_weight_segmented(x, segs, wbits, 0.0, i, wc, wm), 4 + wbits / 8.0 + meta_b),
+            (f"dequantize_segmented_b{wbits}_bf16",
+             lambda i: qb.qsdp_dequantize_segmented(wc, wm, segs, wbits, out16), 2 + wbits / 8.0 + meta_b),
+            (f"dequantize_segmented_b{wbits}_f32",
+             lambda i: qb.qsdp_dequantize_segmented(wc, wm, segs, wbits, out32), 4 + wbits / 8.0 + meta_b)):
+        for i in range(3):
+            fn(i)
+        mean, _ = time_call(fn, 10, torch)
+        res[name] = {"ms": round(mean, 4), "GB/s": round(bpp * n / (mean * 1e-3) / 1e9, 1),
+                     "bytes_per_param": round(bpp, 4), "tensors": segs.nseg}
+    return res
+
+
 def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     """Algorithmic GB/s of the other entry points on the same tensors (not part of `value`)."""
     res = {}
@@ -316,7 +342,7 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     m = (n // peers) // bucket * bucket
     nbm = m // bucket
     pc = torch.empty((peers, nbm * bucket * gbits // 32), dtype=torch.int32, device=dev)
-    pm = torch.empty((peers, nbm * 2), dtype=torch.float32, device=dev)
+    pm = torch.empty((peers, (nbm * 2 + 3) // 4 * 4), dtype=torch.float32, device=dev)  # rows stay 16-byte aligned
     for p in range(peers):
         qb.qsdp_quantize_grad(g[:m], gbits, bucket, 100 + p, 0, pc[p], pm[p])
     acc = torch.empty(m, dtype=torch.float32, device=dev)

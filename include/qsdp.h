@@ -289,6 +289,17 @@ int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* tabl
                               uint32_t* wcodes, float* wmeta,
                               uint64_t* n_saturated, void* stream);
 
+/*
+ * Decoding of a multi-tensor code buffer (what a worker does with a gathered set of quantized
+ * layers, Algorithm 2, in one launch): tensor t's elements are decoded from the codes and meta
+ * of its buckets, as qsdp_dequantize would from word first_bucket_t * bucket * bits / 32, into
+ * out[offset_t .. offset_t + n_t). Padding slots are skipped. total_buckets * bucket < 2^37.
+ *   out  out  device float[] or uint16[] covering every tensor's range of the flat buffer
+ */
+int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qsdp_segment* table,
+                              uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
+                              qsdp_dtype out_dtype, void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

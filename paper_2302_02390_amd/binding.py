@@ -22,7 +22,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-           "qsdp_fused_step_segmented")
+           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented")
 
 _lib = None
 
@@ -81,7 +81,7 @@ def lib():
                                                 u64, vp, vp, vp, vp]
         for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
                      "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-                     "qsdp_fused_step_segmented"):
+                     "qsdp_fused_step_segmented", "qsdp_dequantize_segmented"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -356,3 +356,22 @@ def qsdp_fused_step_segmented(x, g, segs, lr, wbits, gbits, delta, seed, index_o
                                                segs.total_buckets, lr, wbits, gbits, segs.bucket, delta,
                                                seed, index_offset, _ptr(wcodes), _ptr(wmeta),
                                                _ptr(n_saturated), _stream(x)), "qsdp_fused_step_segmented")
+
+
+def qsdp_dequantize_segmented(codes, meta, segs, bits, out):
+    _is(codes, torch.int32); _is(meta, torch.float32)
+    if out.dtype == torch.float32:
+        dt = QSDP_F32
+    elif out.dtype == torch.bfloat16:
+        dt = QSDP_BF16
+    else:
+        raise TypeError("out must be float32 or bfloat16")
+    _is(out, out.dtype)
+    if out.numel() < segs.n:
+        raise ValueError("out is smaller than the segments")
+    if codes.numel() * 32 < segs.total_buckets * segs.bucket * bits or meta.numel() < 2 * segs.total_buckets:
+        raise ValueError("codes or meta is smaller than the segments")
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize_segmented(_ptr(codes), _ptr(meta), _ptr(segs.device), segs.nseg,
+                                               segs.total_buckets, bits, segs.bucket, dt, _ptr(out),
+                                               _stream(out)), "qsdp_dequantize_segmented")

@@ -12,12 +12,12 @@ namespace qsdp {
 
 hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s) {
     switch (mode) {
-        case MODE_GRAD: hipLaunchKernelGGL(block_kernel<MODE_GRAD>, dim3(grid), dim3(256), 0, s, p); break;
-        case MODE_WEIGHT: hipLaunchKernelGGL(block_kernel<MODE_WEIGHT>, dim3(grid), dim3(256), 0, s, p); break;
-        case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p); break;
-        case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p); break;
-        case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p); break;
-        case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p); break;
+        case MODE_GRAD: hipLaunchKernelGGL(block_kernel<MODE_GRAD>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_WEIGHT: hipLaunchKernelGGL(block_kernel<MODE_WEIGHT>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_FUSED: hipLaunchKernelGGL(block_kernel<MODE_FUSED>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -72,6 +72,37 @@ hipError_t launch_dequant_add(int bits, const DequantAddParams& p, unsigned grid
         case 6: return dequant_add_go<6>(p, grid, s);
         case 7: return dequant_add_go<7>(p, grid, s);
         case 8: return dequant_add_go<8>(p, grid, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+template <int BITS, bool BF16>
+void dequant_seg_launch(int bk, const DequantSegParams& q, unsigned grid, hipStream_t s) {
+    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, q, q.segs);
+    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_SHIFT>), dim3(grid), dim3(256), 0, s, q, q.segs);
+    else hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, q, q.segs);
+}
+
+template <int BITS>
+hipError_t dequant_seg_go(bool bf16, const DequantSegParams& q, unsigned grid, hipStream_t s) {
+    const int bk = bucket_indexing(q.d, bf16);
+    if (bf16) dequant_seg_launch<BITS, true>(bk, q, grid, s);
+    else dequant_seg_launch<BITS, false>(bk, q, grid, s);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_dequant_seg(int bits, bool bf16, const DequantSegParams& q, unsigned grid, hipStream_t s) {
+    switch (bits) {
+        case 1: return dequant_seg_go<1>(bf16, q, grid, s);
+        case 2: return dequant_seg_go<2>(bf16, q, grid, s);
+        case 3: return dequant_seg_go<3>(bf16, q, grid, s);
+        case 4: return dequant_seg_go<4>(bf16, q, grid, s);
+        case 5: return dequant_seg_go<5>(bf16, q, grid, s);
+        case 6: return dequant_seg_go<6>(bf16, q, grid, s);
+        case 7: return dequant_seg_go<7>(bf16, q, grid, s);
+        case 8: return dequant_seg_go<8>(bf16, q, grid, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -545,6 +576,26 @@ int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* tabl
     p.wbits = wbits;
     p.lr = lr;
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qsdp_segment* table,
+                              uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
+                              qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!codes || !meta || !table || !out || nseg == 0 || total_buckets < nseg || !shape_ok(1, bits, bucket))
+        return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (total_buckets >= (1ull << 37) / (uint64_t)bucket) return QSDP_EINVAL;  // 32-bit bucket indexing
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (reinterpret_cast<uintptr_t>(table) & 7u))
+        return QSDP_EALIGN;
+    unsigned grid = 0;
+    DequantSegParams q = {};
+    q.d = decoder_params(codes, meta, total_buckets * (uint64_t)bucket, bits, bucket, out_dtype == QSDP_BF16, out,
+                         &grid);
+    q.segs = reinterpret_cast<const Segment*>(table);
+    q.nseg = nseg;
+    if (launch_dequant_seg(bits, out_dtype == QSDP_BF16, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QSDP_ELAUNCH;
+    return QSDP_OK;
 }
 
 }  // extern "C"

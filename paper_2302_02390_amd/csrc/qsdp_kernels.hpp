@@ -101,23 +101,42 @@ __device__ __forceinline__ Shifts draw_shifts(const Params& p, bool weights) {
     return s;
 }
 
+// The tensor of a segmented call that owns bucket `gb`, given a WAVE-UNIFORM bucket gb0 <= gb
+// (the first bucket the wave works on): binary search for gb0, then a per-lane walk forward that
+// is taken only where the wave's buckets straddle tensors. The table is a __restrict__ kernel
+// argument so that the uniform search compiles to scalar loads; through the vector memory path
+// every probe would cost a round trip behind the streaming traffic.
+__device__ __forceinline__ Segment find_segment(const Segment* __restrict__ segs, uint32_t nseg, uint64_t gb0,
+                                                uint64_t gb) {
+    uint32_t lo = 0, hi = nseg;  // segs[lo].first_bucket <= gb0 < segs[hi].first_bucket
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (segs[mid].first_bucket <= gb0) lo = mid; else hi = mid;
+    }
+    Segment seg = segs[lo];
+    uint64_t next_first = lo + 1 < nseg ? segs[lo + 1].first_bucket : ~0ull;
+    uint32_t idx = lo;
+    while (gb >= next_first) {
+        ++idx;
+        seg = segs[idx];
+        next_first = idx + 1 < nseg ? segs[idx + 1].first_bucket : ~0ull;
+    }
+    return seg;
+}
+
 // Where a bucket starts in the flat buffers (element index) and how many of its B slots hold
-// elements; for a segmented call the bucket's tensor is found by binary search in the table.
+// elements. gb0: a wave-uniform bucket <= gb (see find_segment).
 struct BucketRef {
     uint64_t e0;
     uint32_t m;
 };
 
-__device__ __forceinline__ BucketRef locate_bucket(const Params& p, uint64_t gb, uint32_t B) {
+__device__ __forceinline__ BucketRef locate_bucket(const Params& p, const Segment* __restrict__ segs, uint64_t gb0,
+                                                   uint64_t gb, uint32_t B) {
     BucketRef ref;
     uint64_t left;
-    if (p.segs != nullptr) {
-        uint32_t lo = 0, hi = p.nseg;  // segs[lo].first_bucket <= gb < segs[hi].first_bucket
-        while (hi - lo > 1) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (p.segs[mid].first_bucket <= gb) lo = mid; else hi = mid;
-        }
-        const Segment seg = p.segs[lo];
+    if (segs != nullptr) {
+        const Segment seg = find_segment(segs, p.nseg, gb0, gb);
         const uint64_t local = (gb - seg.first_bucket) * B;
         ref.e0 = seg.offset + local;
         left = seg.n - local;
@@ -323,7 +342,7 @@ __device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
 template <int MODE, int G, int R, int BITS, int W>
-__global__ void __launch_bounds__(256) wave_kernel(const Params p) {
+__global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
@@ -367,8 +386,9 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p) {
         const bool active = rel < p.num_buckets;
         const uint64_t left = p.num_buckets - q * BPW;
         const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
-        const uint64_t bucket = p.first_bucket + (active ? rel : 0);
-        const BucketRef ref = locate_bucket(p, bucket, B);
+        const uint64_t bucket0 = p.first_bucket + q * BPW;  // wave-uniform
+        const uint64_t bucket = active ? p.first_bucket + rel : bucket0;
+        const BucketRef ref = locate_bucket(p, segs, bucket0, bucket, B);
         // this wave's tile of the bucket: all of it, or the wave's 1/W
         const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
         const uint64_t e0 = ref.e0 + part0;
@@ -565,7 +585,7 @@ __device__ __forceinline__ void block_minmax(float& lo, float& hi, float* red /*
 }
 
 template <int MODE>
-__global__ void __launch_bounds__(256) block_kernel(const Params p) {
+__global__ void __launch_bounds__(256) block_kernel(const Params p, const Segment* __restrict__ segs) {
     __shared__ float val[kMaxBucket];
     __shared__ uint8_t code[kMaxBucket];
     __shared__ float red[8];
@@ -585,7 +605,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p) {
 
     for (uint64_t rel = blockIdx.x; rel < p.num_buckets; rel += gridDim.x) {
         const uint64_t bucket = p.first_bucket + rel;
-        const BucketRef ref = locate_bucket(p, bucket, (uint32_t)B);
+        const BucketRef ref = locate_bucket(p, segs, bucket, bucket, (uint32_t)B);
         const uint64_t e0 = ref.e0;
         const int m = (int)ref.m;
         __syncthreads();  // previous bucket's LDS contents are dead
@@ -802,7 +822,7 @@ __device__ __forceinline__ uint64_t bucket_of(uint64_t e, const DequantParams& p
 // levels: the code is the level).
 template <int BITS, bool BF16, bool LUT>
 __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e, uint64_t bits, float base,
-                                             float scale, bool whole, const float* lut) {
+                                             float scale, bool whole, const float* lut, uint64_t limit) {
     constexpr int E = BF16 ? 8 : 4;
     float o[E];
 #pragma unroll
@@ -822,7 +842,7 @@ __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e,
         }
     } else {
         for (int i = 0; i < E; ++i) {
-            if (e + i < p.n) {
+            if (e + i < limit) {
                 if (BF16) static_cast<uint16_t*>(p.out)[e + i] = (uint16_t)bf16_bits(o[i]);
                 else static_cast<float*>(p.out)[e + i] = o[i];
             }
@@ -856,13 +876,18 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
             for (int u = 0; u < U; ++u) {
                 const uint64_t e = e0 + (uint64_t)(u * 64 * E);
                 bits[u] = load_bits<E * BITS>(p.codes, e * BITS, last_word);
-                const uint64_t bucket = bucket_of<BK>(e, p);
-                base[u] = p.meta[2 * bucket];
-                scale[u] = p.meta[2 * bucket + 1];
+                if (BK == BK_TILE_UNIFORM && u > 0) {  // the whole tile lies in one bucket
+                    base[u] = base[0];
+                    scale[u] = scale[0];
+                } else {
+                    const uint64_t bucket = bucket_of<BK>(e, p);
+                    base[u] = p.meta[2 * bucket];
+                    scale[u] = p.meta[2 * bucket + 1];
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                decode_store<BITS, BF16, LUT>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true, lut);
+                decode_store<BITS, BF16, LUT>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true, lut, p.n);
         } else {
             // last, partial tile
             for (int u = 0; u < U; ++u) {
@@ -871,7 +896,77 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
                     const uint64_t bits = load_bits<E * BITS>(p.codes, e * BITS, last_word);
                     const uint64_t bucket = bucket_of<BK>(e, p);
                     decode_store<BITS, BF16, LUT>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
-                                                  e + E <= p.n, lut);
+                                                  e + E <= p.n, lut, p.n);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Decoder for a multi-tensor code buffer: slot s of the padded code stream (bucket s / B of the
+// whole buffer) belongs to the tensor whose bucket range holds that bucket and lands at element
+// seg.offset + (s - seg.first_bucket * B) of the flat output, if the tensor has that element.
+// Same tiling as dequant_kernel over SLOTS (p.n = number of slots). The tensor of a tile's
+// first slot is found by a wave-uniform search (scalar loads, see find_segment). A tile that
+// lies inside that tensor's elements (the common case) is decoded without per-lane control
+// flow; a tile that reaches a tensor's padding or the next tensor goes lane by lane, each lane
+// walking on from the tile's tensor to its own.
+// ---------------------------------------------------------------------------------------
+struct DequantSegParams {
+    DequantParams d;  // d.n: slots (total buckets * bucket); d.out: the flat output
+    const Segment* segs;
+    uint32_t nseg;
+};
+
+template <int BITS, bool BF16, int BK>
+__global__ void __launch_bounds__(256) dequant_seg_kernel(const DequantSegParams q,
+                                                          const Segment* __restrict__ segs) {
+    const DequantParams& p = q.d;
+    constexpr int E = BF16 ? 8 : 4;
+    constexpr int U = kDequantRows;
+    constexpr uint64_t T = (uint64_t)U * 64 * E;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t waves_per_block = blockDim.x >> 6;
+    const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
+    const uint64_t last_word = p.nwords - 1;
+    const uint64_t B = (uint64_t)p.bucket32 * 32u;
+    for (uint64_t tile = (uint64_t)blockIdx.x * waves_per_block + wave_in_block; tile < p.ntiles;
+         tile += nwaves) {
+        const uint64_t s0 = tile * T;
+        const uint64_t bucket0 = (uint32_t)(s0 >> 5) / p.bucket32;  // wave-uniform
+        const Segment seg0 = find_segment(segs, q.nseg, bucket0, bucket0);
+        const uint64_t e0 = seg0.offset + (s0 - seg0.first_bucket * B);  // element of slot s0
+        const uint64_t end0 = seg0.offset + seg0.n;
+        if (e0 + T <= end0) {
+            uint64_t bits[U];
+            float base[U], scale[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t s = s0 + (uint64_t)(u * 64 * E + lane * E);
+                bits[u] = load_bits<E * BITS>(p.codes, s * BITS, last_word);
+                const uint64_t bucket = BK == BK_TILE_UNIFORM ? bucket0 : bucket_of<BK>(s, p);
+                base[u] = p.meta[2 * bucket];
+                scale[u] = p.meta[2 * bucket + 1];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                decode_store<BITS, BF16, false>(p, e0 + (uint64_t)(u * 64 * E + lane * E), bits[u], base[u], scale[u],
+                                                true, nullptr, end0);
+        } else {
+            for (int u = 0; u < U; ++u) {
+                const uint64_t s = s0 + (uint64_t)(u * 64 * E + lane * E);
+                if (s < p.n) {
+                    const uint64_t bucket = bucket_of<BK>(s, p);
+                    const Segment seg = find_segment(segs, q.nseg, bucket0, bucket);
+                    const uint64_t e = seg.offset + (s - seg.first_bucket * B);
+                    const uint64_t end = seg.offset + seg.n;
+                    if (e < end) {
+                        const uint64_t bits = load_bits<E * BITS>(p.codes, s * BITS, last_word);
+                        decode_store<BITS, BF16, false>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
+                                                        e + E <= end, nullptr, end);
+                    }
                 }
             }
         }
@@ -913,7 +1008,8 @@ __global__ void __launch_bounds__(256) dequant_add_kernel(const DequantAddParams
         for (int u = 0; u < U; ++u) {
             const uint64_t e = e0 + (uint64_t)(u * 64 * E);
             in_range[u] = whole_tile || e < p.n;
-            bucket[u] = bucket_of<BK>(in_range[u] ? e : 0, p);
+            // tile-uniform: the whole tile lies in the bucket of its first element (lane 0, row 0)
+            bucket[u] = (BK == BK_TILE_UNIFORM && u > 0) ? bucket[0] : bucket_of<BK>(in_range[u] ? e : 0, p);
         }
         // peers in groups of kPeerGroup: all loads of a group are issued before the first add
         constexpr int kPeerGroup = 4;

@@ -18,7 +18,7 @@ template <int MODE, int BITS>
 hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
     // W == 1: 4 waves per workgroup, each on its own buckets; W > 1: W waves share a bucket
     const unsigned block = QSDP_W == 1 ? 256u : 64u * QSDP_W;
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W>), dim3(grid), dim3(block), 0, s, p);
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W>), dim3(grid), dim3(block), 0, s, p, p.segs);
     return hipGetLastError();
 }
 

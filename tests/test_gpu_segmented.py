@@ -105,3 +105,53 @@ def test_segments_build_rejects_bad_sizes():
         qb.Segments([1024], 100, DEV)
     ok = qb.Segments([1024, 1020], 1024, DEV)   # only the last size may be ragged
     assert ok.total_buckets == 2
+
+
+@pytest.mark.parametrize("B,bits", [(1024, 8), (512, 4), (128, 2), (4096, 8), (2048, 3), (96, 5), (1024, 7),
+                                    (256, 6), (160, 1)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dequantize_segmented_matches_per_tensor_oracle(B, bits, dtype):
+    """One launch decodes every tensor's buckets into its range of the flat buffer; padding slots
+    of short tensors are skipped and nothing outside a tensor's range is written."""
+    sizes = [768, 2304, 768 * 40, 8, 3072, 16, 1024 * 3 + 8, 50257 * 8, 4096 * 2, 24, 5000 + 3]
+    n = sum(sizes)
+    x, _ = synth(n, 512 + B + bits)
+    segs = qb.Segments(sizes, B, DEV)
+    codes, meta = segs.alloc_packed(bits)
+    qb.qsdp_quantize_weight_segmented(torch.from_numpy(x).to(DEV), segs, bits, 0.0, 11, codes, meta.reshape(-1))
+    pad = 64
+    out = torch.full((n + pad,), -7.0, dtype=dtype, device=DEV)
+    qb.qsdp_dequantize_segmented(codes, meta.reshape(-1), segs, bits, out)
+    got = out.cpu()
+    assert torch.all(got[n:] == -7.0)
+    off = 0
+    want = []
+    for s in sizes:
+        c, m, _ = ref.quantize_weight(x[off:off + s], bits, B, 0.0, 11)
+        want.append(ref.dequantize(c, m, s, bits, B, ref.BF16 if dtype == torch.bfloat16 else ref.F32))
+        off += s
+    want = np.concatenate(want)
+    if dtype == torch.float32:
+        assert bits_equal(got[:n].numpy(), want)
+    else:
+        assert np.array_equal(got[:n].view(torch.int16).numpy().view(np.uint16), want)
+
+
+def test_dequantize_segmented_gpt350m_equals_per_tensor_calls():
+    shape, B = wl.GPT_350M, 1024
+    sizes = [s for _, s in wl.model_tensors(shape)]
+    n = sum(sizes)
+    x = wl.weights(n, 1240, DEV)
+    segs = qb.Segments(sizes, B, DEV)
+    codes, meta = segs.alloc_packed(8)
+    qb.qsdp_quantize_weight_segmented(x, segs, 8, 0.0, 5, codes, meta.reshape(-1))
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    qb.qsdp_dequantize_segmented(codes, meta.reshape(-1), segs, 8, out)
+    per = torch.empty_like(out)
+    host = segs.host
+    wpb = B * 8 // 32
+    for off, s, fb in host.tolist():
+        nb = -(-s // B)
+        qb.qsdp_dequantize(codes[fb * wpb:(fb + nb) * wpb], meta[fb:fb + nb].clone().reshape(-1), s, 8, B,
+                           per[off:off + s])
+    assert torch.equal(out.view(torch.int16), per.view(torch.int16))
