@@ -56,6 +56,25 @@ def build(jobs=None, verbose=False):
     return LIB
 
 
+def build_client(verbose=False):
+    """The plain C example client (examples/qsdp_client.c) against the built library, with gcc."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "examples", "qsdp_client.c")
+    out = os.path.join(root, "examples", "qsdp_client")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(root, "include"),
+           "-I", os.path.join(rocm, "include"), src, "-L", HERE, "-lqsdp", "-L", os.path.join(rocm, "lib"),
+           "-lamdhip64", "-Wl,-rpath,$ORIGIN/../paper_2302_02390_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"),
+           "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(out)
+    return out
+
+
 if __name__ == "__main__":
     build(verbose=True)
+    build_client(verbose=True)
     sys.exit(0)

@@ -56,3 +56,15 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.qsdp_fused_step(ok, ok, 10, float("inf"), 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step(ok, odd, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EALIGN
     assert qb.status_string(qb.QSDP_EALIGN).startswith("pointer")
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/qsdp.h is a C header: it compiles as strict C11 and every declared function can be
+    named from C."""
+    import subprocess
+    names = [n for n in _declared_symbols()]
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "qsdp.h"\n' + "const void* table[] = {" +
+                   ", ".join(f"(const void*)(uintptr_t){n}" for n in names) + "};\n")
+    subprocess.run(["gcc", "-std=c11", "-pedantic-errors", "-Wall", "-Werror", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
