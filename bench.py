@@ -359,6 +359,23 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
               lambda i: qb.qsdp_dequantize_add(pc, pm, peers, m, gbits, bucket, 1.0 / peers, acc),
               peers * (gbits / 8.0 + meta_b) + 4)
     n = n_saved
+    del pc, pm, acc
+    # decode of a gathered layer: the vector as 8 peers' weight shards, each quantized on its own, one
+    # slot [codes | meta] per peer in a single receive buffer, decoded to bf16 in one launch
+    shard = -(-(n // peers) // bucket) * bucket
+    npeers = -(-n // shard)
+    cw = shard * wbits // 32
+    mw = (2 * (shard // bucket) + 3) // 4 * 4
+    recv = torch.empty((npeers, cw + mw), dtype=torch.int32, device=dev)
+    slot_codes, slot_meta = recv[:, :cw], recv.view(torch.float32)[:, cw:]
+    for p in range(npeers):
+        xs = x[p * shard:min((p + 1) * shard, n)]
+        mlen = 2 * (-(-xs.numel() // bucket))
+        qb.qsdp_quantize_weight(xs, wbits, bucket, 0.0, 7, slot_codes[p], slot_meta[p, :mlen])
+    out16 = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    run(f"dequantize_gathered_{npeers}slots_b{wbits}_bf16",
+        lambda i: qb.qsdp_dequantize_gathered(slot_codes, slot_meta, npeers, n, shard, wbits, bucket, out16),
+        2 + wbits / 8.0 + meta_b)
     return res
 
 

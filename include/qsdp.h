@@ -116,6 +116,25 @@ int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bi
                     int bucket, qsdp_dtype out_dtype, void* out, void* stream);
 
 /*
+ * Decoding of a gathered layer (Algorithm 2: after the all-gather of the quantized weight
+ * shards a worker holds one slot per peer and decodes the whole layer, twice per micro-batch;
+ * the highest-volume call of the scheme): peer p's slot holds the packed codes and meta of
+ * elements [p*shard, min((p+1)*shard, n)) of the layer, quantized on their own by
+ * qsdp_quantize_weight (or a fused step); `shard` is a multiple of `bucket`, so the buckets are
+ * those of the unsharded layer, and npeers = ceil(n / shard). One launch writes
+ * out[0..n) = what qsdp_dequantize gives slot by slot. Peer p's codes start
+ * p * codes_stride_bytes after `codes`, its meta p * meta_stride_bytes after `meta` (strides:
+ * multiples of 16, at least the size of a full shard's codes / meta; a receive buffer whose
+ * slots hold codes followed by meta is addressed with equal strides). shard < 2^37,
+ * npeers <= 65535.
+ *   out  out  device float[n] or uint16[n]
+ */
+int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes,
+                             const float* meta, uint64_t meta_stride_bytes, int npeers,
+                             uint64_t n, uint64_t shard, int bits, int bucket,
+                             qsdp_dtype out_dtype, void* out, void* stream);
+
+/*
  * Decode-and-sum, the receive side of a quantized gradient exchange (Algorithm 2: the
  * quantized gradient slices of all workers reach the owner of a shard, which decodes and adds
  * them before the weight update; codes with different per-bucket scales cannot be added in

@@ -22,7 +22,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented")
+           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered")
 
 _lib = None
 
@@ -79,9 +79,11 @@ def lib():
                                                      vp, vp]
         L.qsdp_fused_step_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64,
                                                 u64, vp, vp, vp, vp]
+        L.qsdp_dequantize_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, i32, vp, vp]
+        L.qsdp_dequantize_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, i32, vp, vp]
         for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
                      "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-                     "qsdp_fused_step_segmented", "qsdp_dequantize_segmented"):
+                     "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -119,6 +121,12 @@ def _check(status, what):
 def _is(t, dtype):
     if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"expected a contiguous {dtype} tensor on the GPU")
+
+
+def _is_rows(t, dtype):
+    """A 2-D tensor whose rows are contiguous (the rows themselves may be strided apart)."""
+    if not (t.is_cuda and t.dtype == dtype and t.dim() == 2 and (t.shape[1] == 1 or t.stride(1) == 1)):
+        raise TypeError(f"expected a {dtype} GPU tensor [rows, row length] with contiguous rows")
 
 
 def alloc_packed(n, bits, bucket, device):
@@ -375,3 +383,24 @@ def qsdp_dequantize_segmented(codes, meta, segs, bits, out):
         _check(lib().qsdp_dequantize_segmented(_ptr(codes), _ptr(meta), _ptr(segs.device), segs.nseg,
                                                segs.total_buckets, bits, segs.bucket, dt, _ptr(out),
                                                _stream(out)), "qsdp_dequantize_segmented")
+
+
+def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out):
+    """codes int32[npeers, >= words of a shard], meta float32[npeers, >= 2 * buckets of a shard]
+    (row p = peer p's slot; rows may be views into one receive buffer); out float32/bfloat16[n]."""
+    _is_rows(codes, torch.int32); _is_rows(meta, torch.float32)
+    if out.dtype == torch.float32:
+        dt = QSDP_F32
+    elif out.dtype == torch.bfloat16:
+        dt = QSDP_BF16
+    else:
+        raise TypeError("out must be float32 or bfloat16")
+    _is(out, out.dtype)
+    if codes.shape[0] != npeers or meta.shape[0] != npeers:
+        raise ValueError("codes and meta must be [npeers, ...]")
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize_gathered(_ptr(codes), codes.stride(0) * 4, _ptr(meta), meta.stride(0) * 4,
+                                              npeers, n, shard, bits, bucket, dt, _ptr(out), _stream(out)),
+               "qsdp_dequantize_gathered")

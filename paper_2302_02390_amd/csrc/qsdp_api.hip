@@ -32,14 +32,14 @@ static int bucket_indexing(const DequantParams& p, bool bf16) {
 
 namespace {
 template <int BITS, bool BF16, bool LUT>
-void dequant_launch(int bk, const DequantParams& p, unsigned grid, hipStream_t s) {
-    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_TILE_UNIFORM, LUT>), dim3(grid), dim3(256), 0, s, p);
-    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_SHIFT, LUT>), dim3(grid), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_DIVIDE, LUT>), dim3(grid), dim3(256), 0, s, p);
+void dequant_launch(int bk, const DequantParams& p, dim3 grid, hipStream_t s) {
+    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_TILE_UNIFORM, LUT>), grid, dim3(256), 0, s, p);
+    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_SHIFT, LUT>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((dequant_kernel<BITS, BF16, BK_DIVIDE, LUT>), grid, dim3(256), 0, s, p);
 }
 
 template <int BITS>
-hipError_t dequant_go(bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
+hipError_t dequant_go(bool bf16, const DequantParams& p, dim3 grid, hipStream_t s) {
     const int bk = bucket_indexing(p, bf16);
     const bool lut = p.levels != nullptr;
     if (bf16 && lut) dequant_launch<BITS, true, true>(bk, p, grid, s);
@@ -122,7 +122,7 @@ hipError_t launch_fit_levels(const FitParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, unsigned grid, hipStream_t s) {
+hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, dim3 grid, hipStream_t s) {
     switch (bits) {
         case 1: return dequant_go<1>(bf16, p, grid, s);
         case 2: return dequant_go<2>(bf16, p, grid, s);
@@ -304,6 +304,9 @@ static DequantParams decoder_params(const uint32_t* codes, const float* meta, ui
         if (p.bucket32 == (1u << sh)) p.bucket32_shift = sh;
     const uint64_t blocks = ceil_div(p.ntiles, 4);
     *grid = capped_grid(blocks);
+    p.n_last = p.n;
+    p.nwords_last = p.nwords;
+    p.ntiles_last = p.ntiles;
     return p;
 }
 
@@ -594,6 +597,34 @@ int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qs
     q.segs = reinterpret_cast<const Segment*>(table);
     q.nseg = nseg;
     if (launch_dequant_seg(bits, out_dtype == QSDP_BF16, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes, const float* meta,
+                             uint64_t meta_stride_bytes, int npeers, uint64_t n, uint64_t shard, int bits,
+                             int bucket, qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!codes || !meta || !out || !shape_ok(n, bits, bucket) || npeers < 1 || npeers > 65535) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (shard == 0 || shard % (uint64_t)bucket != 0 || ceil_div(n, shard) != (uint64_t)npeers) return QSDP_EINVAL;
+    if (shard >= (1ull << 37)) return QSDP_EINVAL;
+    if ((codes_stride_bytes & 15u) || (meta_stride_bytes & 15u)) return QSDP_EALIGN;
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
+    const uint64_t first = npeers > 1 ? shard : n;  // elements of every slot but the last
+    if (npeers > 1 && (codes_stride_bytes < qsdp_codes_bytes(shard, bits, bucket) ||
+                       meta_stride_bytes < qsdp_meta_bytes(shard, bucket)))
+        return QSDP_EINVAL;
+    const bool bf16 = out_dtype == QSDP_BF16;
+    unsigned grid = 0, grid_last = 0;
+    DequantParams p = decoder_params(codes, meta, first, bits, bucket, bf16, out, &grid);
+    const DequantParams last = decoder_params(codes, meta, n - (uint64_t)(npeers - 1) * shard, bits, bucket, bf16, out,
+                                              &grid_last);
+    p.n_last = last.n;
+    p.nwords_last = last.nwords;
+    p.ntiles_last = last.ntiles;
+    p.codes_stride_words = codes_stride_bytes / 4;
+    p.meta_stride_floats = meta_stride_bytes / 4;
+    if (launch_dequant(bits, bf16, p, dim3(grid, (unsigned)npeers), static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
 }

@@ -771,6 +771,12 @@ struct DequantParams {
     uint64_t ntiles;  // wave tiles of U*64*E elements
     uint32_t bucket32;      // bucket / 32
     int bucket32_shift;     // log2(bucket / 32) if that is a power of two, else -1 (division)
+    // Gathered buffers (dequant_kernel only, one blockIdx.y per peer slot): peer p's codes start
+    // p * codes_stride_words after `codes`, its meta p * meta_stride_floats after `meta`, its
+    // elements p * n after `out`; n / nwords / ntiles describe every slot but the last, the
+    // *_last fields the last one (for a plain call: the only one).
+    uint64_t codes_stride_words, meta_stride_floats;
+    uint64_t n_last, nwords_last, ntiles_last;
 };
 
 #ifndef QSDP_DEQ_ROWS
@@ -864,39 +870,47 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
     const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t waves_per_block = blockDim.x >> 6;
     const uint64_t nwaves = (uint64_t)gridDim.x * waves_per_block;
-    const uint64_t last_word = p.nwords - 1;
-    for (uint64_t tile = (uint64_t)blockIdx.x * waves_per_block + wave_in_block; tile < p.ntiles;
-         tile += nwaves) {
+    // the slot this workgroup decodes (the whole buffer for a plain call)
+    const uint64_t peer = blockIdx.y;
+    const bool last_peer = peer + 1 == gridDim.y;
+    const uint32_t* codes = p.codes + peer * p.codes_stride_words;
+    const float* meta = p.meta + peer * p.meta_stride_floats;
+    const uint64_t out0 = peer * p.n;
+    const uint64_t n = last_peer ? p.n_last : p.n;
+    const uint64_t ntiles = last_peer ? p.ntiles_last : p.ntiles;
+    const uint64_t last_word = (last_peer ? p.nwords_last : p.nwords) - 1;
+    for (uint64_t tile = (uint64_t)blockIdx.x * waves_per_block + wave_in_block; tile < ntiles; tile += nwaves) {
         const uint64_t e0 = tile * T + (uint64_t)(lane * E);
-        if ((tile + 1) * T <= p.n) {
+        if ((tile + 1) * T <= n) {
             // whole tile in range (wave-uniform): all loads first, no per-lane control flow
             uint64_t bits[U];
             float base[U], scale[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint64_t e = e0 + (uint64_t)(u * 64 * E);
-                bits[u] = load_bits<E * BITS>(p.codes, e * BITS, last_word);
+                bits[u] = load_bits<E * BITS>(codes, e * BITS, last_word);
                 if (BK == BK_TILE_UNIFORM && u > 0) {  // the whole tile lies in one bucket
                     base[u] = base[0];
                     scale[u] = scale[0];
                 } else {
                     const uint64_t bucket = bucket_of<BK>(e, p);
-                    base[u] = p.meta[2 * bucket];
-                    scale[u] = p.meta[2 * bucket + 1];
+                    base[u] = meta[2 * bucket];
+                    scale[u] = meta[2 * bucket + 1];
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                decode_store<BITS, BF16, LUT>(p, e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true, lut, p.n);
+                decode_store<BITS, BF16, LUT>(p, out0 + e0 + (uint64_t)(u * 64 * E), bits[u], base[u], scale[u], true,
+                                              lut, out0 + n);
         } else {
             // last, partial tile
             for (int u = 0; u < U; ++u) {
                 const uint64_t e = e0 + (uint64_t)(u * 64 * E);
-                if (e < p.n) {
-                    const uint64_t bits = load_bits<E * BITS>(p.codes, e * BITS, last_word);
+                if (e < n) {
+                    const uint64_t bits = load_bits<E * BITS>(codes, e * BITS, last_word);
                     const uint64_t bucket = bucket_of<BK>(e, p);
-                    decode_store<BITS, BF16, LUT>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
-                                                  e + E <= p.n, lut, p.n);
+                    decode_store<BITS, BF16, LUT>(p, out0 + e, bits, meta[2 * bucket], meta[2 * bucket + 1],
+                                                  e + E <= n, lut, out0 + n);
                 }
             }
         }

@@ -10,6 +10,9 @@ from oracle import ref
 from paper_2302_02390_amd import binding as qb
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+C_INT_DEFAULT = ctypes.c_int   # what ctypes assumes when restype was never set
+INT_RETURNING = {n for n in qb.EXPORTS if n not in ("qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
+                                                    "qsdp_segments_build", "qsdp_spec_version")}
 
 
 def _declared_symbols():
@@ -68,3 +71,19 @@ def test_header_is_plain_c(tmp_path):
                    ", ".join(f"(const void*)(uintptr_t){n}" for n in names) + "};\n")
     subprocess.run(["gcc", "-std=c11", "-pedantic-errors", "-Wall", "-Werror", "-fsyntax-only",
                     "-I", os.path.join(ROOT, "include"), str(src)], check=True)
+
+
+def test_binding_declares_the_signature_of_every_export():
+    """ctypes guesses int for undeclared arguments, which truncates 64-bit sizes and pointers:
+    every exported function must have its argument and result types set, and the number of
+    arguments must match the header's declaration."""
+    L = qb.lib()
+    text = open(os.path.join(ROOT, "include", "qsdp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    for name in qb.EXPORTS:
+        fn = getattr(L, name)
+        assert fn.argtypes is not None, name
+        decl = re.search(r"\b" + name + r"\s*\(([^)]*)\)", text).group(1).strip()
+        nargs = 0 if decl in ("", "void") else decl.count(",") + 1
+        assert len(fn.argtypes) == nargs, (name, len(fn.argtypes), nargs)
+        assert fn.restype is not C_INT_DEFAULT or name in INT_RETURNING, name
