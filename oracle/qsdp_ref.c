@@ -520,6 +520,37 @@ int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, ui
     return rc;
 }
 
+/* The shard owner's update in Algorithm 2 with P workers: the quantized gradient slices of all
+ * peers are decoded and averaged (as qsdp_ref_dequantize_add does, peers in order), the SGD step
+ * is taken with that average, and the new weights are quantized by Q^w (what the next weight
+ * gather transmits) and decoded:
+ *   ghat = alpha * (((d_0 + d_1) + d_2) + ...);  y = fma(-lr, ghat, x);  x <- decode(Q^w(y)).
+ * No Q^g is applied here: the gradients arrive already quantized by their senders. */
+int qsdp_ref_recv_step(float* x, const uint32_t* gcodes, uint64_t codes_stride_words, const float* gmeta,
+                       uint64_t meta_stride_floats, int npeers, uint64_t n, float alpha, float lr,
+                       int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
+                       uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
+    if (!x || !args_ok(n, wbits, bucket) || (flags & ~(QSDP_REF_FLAG_NO_SHIFT | QSDP_REF_FLAG_SYMMETRIC)))
+        return QSDP_REF_EINVAL;
+    if (!isfinite(lr) || (wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
+    float* ghat = (float*)malloc((size_t)n * sizeof(float));
+    uint32_t* codes = wcodes ? wcodes : (uint32_t*)malloc(qsdp_ref_codes_bytes(n, wbits, bucket));
+    float* meta = wmeta ? wmeta : (float*)malloc(qsdp_ref_meta_bytes(n, bucket));
+    int rc = (ghat && codes && meta) ? QSDP_REF_OK : QSDP_REF_EINVAL;
+    if (rc == QSDP_REF_OK)
+        rc = qsdp_ref_dequantize_add(gcodes, codes_stride_words, gmeta, meta_stride_floats, npeers, n, gbits,
+                                     bucket, alpha, ghat);
+    if (rc == QSDP_REF_OK) {
+        for (uint64_t i = 0; i < n; ++i) ghat[i] = fmaf(-lr, ghat[i], x[i]); /* y, in place */
+        rc = qsdp_ref_quantize_weight_ex(ghat, n, wbits, bucket, delta, seed, flags, codes, meta, n_saturated);
+    }
+    if (rc == QSDP_REF_OK) rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);
+    free(ghat);
+    if (!wcodes) free(codes);
+    if (!wmeta) free(meta);
+    return rc;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Learned quantization levels (Section 5.2, Algorithm 1)                      */
 /* ------------------------------------------------------------------------- */

@@ -162,6 +162,16 @@ int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, ui
                               uint64_t seed, uint64_t index_offset, uint32_t flags,
                               uint64_t* n_saturated);
 
+/* The shard owner's update with P workers (Algorithm 2): decode-and-average the peers'
+ * quantized gradient slices, take the SGD step, quantize the new weights with Q^w and decode:
+ * ghat = alpha * (((d_0 + d_1) + ...)); y = fma(-lr, ghat, x); x <- decode(Q^w(y)).
+ * By definition the composition of qsdp_ref_dequantize_add, the fma and qsdp_ref_quantize_weight_ex
+ * + qsdp_ref_dequantize. flags: NO_SHIFT, SYMMETRIC. */
+int qsdp_ref_recv_step(float* x, const uint32_t* gcodes, uint64_t codes_stride_words, const float* gmeta,
+                       uint64_t meta_stride_floats, int npeers, uint64_t n, float alpha, float lr,
+                       int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
+                       uint32_t* wcodes, float* wmeta, uint64_t* n_saturated);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,6 +60,13 @@ MUTANTS = [
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
      "for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i];", ["test_oracle_fused.py"]),
+    ("recv_step_sign_flipped", "ghat[i] = fmaf(-lr, ghat[i], x[i]); /* y, in place */",
+     "ghat[i] = fmaf(lr, ghat[i], x[i]); /* y, in place */", ["test_oracle_recv_step.py"]),
+    ("recv_step_average_dropped", "npeers, n, gbits,\n                                     bucket, alpha, ghat);",
+     "npeers, n, gbits,\n                                     bucket, 1.0f, ghat);", ["test_oracle_recv_step.py"]),
+    ("recv_step_skips_weight_quantizer",
+     "if (rc == QSDP_REF_OK) rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);",
+     "if (rc == QSDP_REF_OK) memcpy(x, ghat, (size_t)n * sizeof(float));", ["test_oracle_recv_step.py"]),
 ]
 
 
