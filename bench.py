@@ -358,6 +358,14 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run_small(f"dequantize_add_{peers}peers_b{gbits}",
               lambda i: qb.qsdp_dequantize_add(pc, pm, peers, m, gbits, bucket, 1.0 / peers, acc),
               peers * (gbits / 8.0 + meta_b) + 4)
+    # the same receive side fused with the update and Q^w (codes of the new weights emitted)
+    xs = x[:m].clone()
+    sc, sm = qb.alloc_packed(m, wbits, bucket, dev)
+    run_small(f"recv_step_{peers}peers_W{wbits}G{gbits}",
+              lambda i: qb.qsdp_recv_step(xs, pc, pm, peers, 1.0 / peers, 1e-3, wbits, gbits, bucket, 0.0, i, 0,
+                                          sc, sm.reshape(-1)),
+              8 + peers * (gbits / 8.0 + meta_b) + wbits / 8.0 + meta_b)
+    del xs, sc, sm
     n = n_saved
     del pc, pm, acc
     # decode of a gathered layer: the vector as 8 peers' weight shards, each quantized on its own, one

@@ -168,6 +168,24 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
                     uint64_t* n_saturated, void* stream);
 
 /*
+ * The shard owner's step with P workers (Algorithm 2: the quantized gradient slices of all
+ * workers reach the owner of a shard, which averages them, updates its weights and quantizes
+ * them for the next weight gather), fused into one pass: read x and the P code slices, write x
+ * (and the packed Q^w codes): 8 + P * gbits/8 (+ wbits/8) bytes per parameter instead of the
+ * 16 + P * gbits/8 of qsdp_dequantize_add followed by a separate update.
+ *   ghat = alpha * (((d_0 + d_1) + d_2) + ...)   as qsdp_dequantize_add computes it
+ *   y = fma(-lr, ghat, x);   x <- decode(Q^w(y)) as in qsdp_fused_step (delta, seed, wcodes,
+ *   wmeta, n_saturated as there). No Q^g is applied: the slices were quantized by their senders.
+ * gcodes / gmeta and their strides as in qsdp_dequantize_add, except that the code stride is a
+ * multiple of 16 bytes; flags: QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC.
+ */
+int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
+                   const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, uint64_t n,
+                   float alpha, float lr, int wbits, int gbits, int bucket, float delta,
+                   uint64_t seed, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                   uint64_t* n_saturated, void* stream);
+
+/*
  * Quantizer variants the paper names as admissible, selected by `flags` (0 = the default
  * operators above; meta-data and wire format are unchanged, so qsdp_dequantize serves all):
  *   QSDP_FLAG_GRAD_SHIFT  gradients are quantized by random shift as well (the appendix notes

@@ -22,7 +22,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered")
+           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step")
 
 _lib = None
 
@@ -81,6 +81,9 @@ def lib():
                                                 u64, vp, vp, vp, vp]
         L.qsdp_dequantize_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, i32, vp, vp]
         L.qsdp_dequantize_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, i32, vp, vp]
+        L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
+                                     vp, vp, vp, vp]
+        L.qsdp_recv_step.restype = i32
         for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
                      "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
                      "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered"):
@@ -404,3 +407,18 @@ def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out):
         _check(lib().qsdp_dequantize_gathered(_ptr(codes), codes.stride(0) * 4, _ptr(meta), meta.stride(0) * 4,
                                               npeers, n, shard, bits, bucket, dt, _ptr(out), _stream(out)),
                "qsdp_dequantize_gathered")
+
+
+def qsdp_recv_step(x, gcodes, gmeta, npeers, alpha, lr, wbits, gbits, bucket, delta, seed, flags=0, wcodes=None,
+                   wmeta=None, n_saturated=None):
+    """gcodes int32[npeers, words], gmeta float32[npeers, nb*2] (row k = peer k's slice)."""
+    _is(x, torch.float32); _is_rows(gcodes, torch.int32); _is_rows(gmeta, torch.float32)
+    if gcodes.shape[0] != npeers or gmeta.shape[0] != npeers:
+        raise ValueError("gcodes and gmeta must be [npeers, ...]")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_recv_step(_ptr(x), _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta), gmeta.stride(0) * 4,
+                                    npeers, x.numel(), alpha, lr, wbits, gbits, bucket, delta, seed, flags,
+                                    _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)), "qsdp_recv_step")

@@ -18,6 +18,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_RECV: hipLaunchKernelGGL(block_kernel<MODE_RECV>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -183,13 +184,15 @@ WaveLauncher wave_launcher(int bucket, int* buckets_per_wave) {
 }
 
 // Buckets go to the wave kernel of the bucket's shape when there is one for (bucket, stored
-// code width), else to the block kernel. p.num_buckets must be set.
+// code width; for MODE_RECV also the width of the peers' codes), else to the block kernel.
+// p.num_buckets must be set.
 int run(int mode, Params p, int stored_bits, hipStream_t s) {
     const uint64_t nb = p.num_buckets;
     p.first_bucket = 0;
     int bpw = 1;
     WaveLauncher wl = wave_launcher(p.bucket, &bpw);
-    if (wl != nullptr && wave_bits_supported(stored_bits)) {
+    const bool peer_bits_ok = mode != MODE_RECV || (p.gbits != 0 && wave_bits_supported(p.gbits));
+    if (wl != nullptr && wave_bits_supported(stored_bits) && peer_bits_ok) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
         if (wl(mode, stored_bits, p, capped_grid(blocks), s) != hipSuccess) return QSDP_ELAUNCH;
@@ -627,6 +630,42 @@ int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes,
     if (launch_dequant(bits, bf16, p, dim3(grid, (unsigned)npeers), static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
+}
+
+int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes, const float* gmeta,
+                   uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha, float lr, int wbits,
+                   int gbits, int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
+                   float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (!x || !gcodes || !gmeta || npeers < 1 || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
+        (flags & ~(uint32_t)(QSDP_FLAG_NO_SHIFT | QSDP_FLAG_SYMMETRIC)))
+        return QSDP_EINVAL;
+    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr) || !std::isfinite(alpha)) return QSDP_EINVAL;
+    if ((wcodes == nullptr) != (wmeta == nullptr)) return QSDP_EINVAL;
+    if (npeers > 1 && (gcodes_stride_bytes < qsdp_codes_bytes(n, gbits, bucket) ||
+                       gmeta_stride_bytes < qsdp_meta_bytes(n, bucket)))
+        return QSDP_EINVAL;
+    if ((gcodes_stride_bytes & 15u) || (gmeta_stride_bytes & 3u)) return QSDP_EALIGN;
+    if (!aligned16(x) || !aligned16(gcodes) || !aligned16(wcodes) || !aligned16(wmeta) ||
+        (reinterpret_cast<uintptr_t>(gmeta) & 3u))
+        return QSDP_EALIGN;
+    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, 0, delta);
+    p.flags = flags;
+    p.x = x;
+    p.peer_codes = gcodes;
+    p.peer_meta = gmeta;
+    p.peer_codes_stride_words = gcodes_stride_bytes / 4;
+    p.peer_meta_stride_floats = gmeta_stride_bytes / 4;
+    p.npeers = npeers;
+    p.alpha = alpha;
+    p.codes = wcodes;
+    p.meta = wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.gbits = gbits;
+    p.wbits = wbits;
+    p.lr = lr;
+    return run(MODE_RECV, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

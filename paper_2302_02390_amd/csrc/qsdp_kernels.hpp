@@ -30,8 +30,10 @@ namespace qsdp {
 // bucket-normalised coordinates.
 // MODE_ADAMW: the fused step with AdamW (moments m, v in fp32, updated in place) between the
 // two quantizers instead of the plain SGD update.
+// MODE_RECV: the shard owner's step with P workers: the gradient is the scaled sum of the
+// decoded slices of all peers (no Q^g here), then the SGD step and Q^w as in MODE_FUSED.
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
-            MODE_ADAMW = 5 };
+            MODE_ADAMW = 5, MODE_RECV = 6 };
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
@@ -54,6 +56,13 @@ struct Params {
     float* meta;         // {base, scale} per bucket (nullable iff codes is)
     unsigned long long* n_saturated;  // nullable
     const Segment* segs;  // device table of nseg tensors, or nullptr: one tensor of n elements
+    // RECV: peer k's packed gradient codes (gbits wide) start k * peer_codes_stride_words after
+    // peer_codes, its meta k * peer_meta_stride_floats after peer_meta; ghat = alpha * sum
+    const uint32_t* peer_codes;
+    const float* peer_meta;
+    uint64_t peer_codes_stride_words, peer_meta_stride_floats;
+    int npeers;
+    float alpha;
     // problem
     uint64_t n;             // elements (single tensor)
     uint64_t first_bucket;  // first bucket this launch handles
@@ -274,26 +283,30 @@ __device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int la
     __builtin_amdgcn_wave_barrier();
 }
 
-// The reverse of store_codes: stage the wave's code tile in LDS with 16-byte loads, then give
-// every lane the codes of its own elements (as floats). The even lane reads the chunk of row
-// 2cp (its own 4 codes, then its partner's), the odd lane that of row 2cp+1 (its partner's 4
-// codes, then its own); one DPP quad permute hands each lane the half it lacks.
+// The reverse of store_codes, in two phases so that several tiles can be in flight: fetch the
+// wave's code tile with 16-byte loads (one piece per lane: 2*R*BITS <= 64 pieces), then stage
+// it in LDS and give every lane the codes of its own elements (as floats). The even lane reads
+// the chunk of row 2cp (its own 4 codes, then its partner's), the odd lane that of row 2cp+1
+// (its partner's 4 codes, then its own); one DPP quad permute hands each lane the half it lacks.
 template <int G, int R, int BITS>
-__device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, int lane, int active_buckets,
-                                           float (&c)[R][4]) {
+__device__ __forceinline__ u4 fetch_code_tile(const u4* tile_in, int lane, int active_buckets) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;
+    static_assert(kPieces <= 64, "one 16-byte piece per lane");
+    u4 piece = {0u, 0u, 0u, 0u};
+    if (lane < kPieces && (lane * 16) / kBucketBytes < active_buckets) piece = __builtin_nontemporal_load(tile_in + lane);
+    return piece;
+}
+
+template <int G, int R, int BITS>
+__device__ __forceinline__ void unstage_codes(uint8_t* stage, u4 piece, int lane, float (&c)[R][4]) {
     constexpr int kBucketBytes = 4 * G * R * BITS / 8;
     constexpr int kPieces = 2 * R * BITS;
     constexpr uint32_t kHalfMask = (BITS == 8) ? 0xFFFFFFFFu : ((1u << (4 * BITS)) - 1u);
     const int l = lane % G;
     const int sub = lane / G;
     const int odd = l & 1;
-    u4* staged = reinterpret_cast<u4*>(stage);
-#pragma unroll
-    for (int k0 = 0; k0 < kPieces; k0 += 64) {
-        const int k = k0 + lane;
-        if (k < kPieces && (k * 16) / kBucketBytes < active_buckets)
-            staged[k] = __builtin_nontemporal_load(tile_in + k);
-    }
+    if (lane < kPieces) reinterpret_cast<u4*>(stage)[lane] = piece;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -315,6 +328,12 @@ __device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, in
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+}
+
+template <int G, int R, int BITS>
+__device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, int lane, int active_buckets,
+                                           float (&c)[R][4]) {
+    unstage_codes<G, R, BITS>(stage, fetch_code_tile<G, R, BITS>(tile_in, lane, active_buckets), lane, c);
 }
 
 // Combine per-wave (lo, hi) across the W waves of a workgroup that share a bucket. `slot` is a
@@ -341,14 +360,16 @@ __device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float
 // output). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
-template <int MODE, int G, int R, int BITS, int W>
+template <int MODE, int G, int R, int BITS, int W, int GB = 0>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
+    static_assert((MODE == MODE_RECV) == (GB != 0), "GB = width of the peers' gradient codes (MODE_RECV only)");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
     constexpr int B = T * W;
     constexpr int BPW = 64 / G;
     constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
+    constexpr int GBW = GB ? GB : 8;     // only used when GB != 0
     const int lane = threadIdx.x & 63;
     const int sub = lane / G;
     const int l = lane % G;
@@ -359,10 +380,12 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const uint64_t unit_stride = W == 1 ? (uint64_t)gridDim.x * waves_per_block : gridDim.x;
     const uint64_t nunits = (p.num_buckets + BPW - 1) / BPW;
 
-    // LDS staging tile of the packed codes: 32*R*BITS bytes per wave, up to 4 waves per block
-    constexpr int kTileBytes = 32 * R * SB;
-    __shared__ u4 stage_all[BITS ? 4 * kTileBytes / 16 : 1];
-    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (BITS ? wave_in_block * kTileBytes : 0);
+    // LDS staging tile of the packed codes (stored, or read from the peers): 32*R*bits bytes per
+    // wave, up to 4 waves per block
+    constexpr int kStageBits = (BITS > GB) ? BITS : GB;
+    constexpr int kTileBytes = 32 * R * (kStageBits ? kStageBits : 8);
+    __shared__ u4 stage_all[kStageBits ? 4 * kTileBytes / 16 : 1];
+    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStageBits ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
     __shared__ float level_table[MODE == MODE_LEVELS ? (1 << SB) : 1];
@@ -480,6 +503,46 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 }
                 continue;
             }
+        } else if constexpr (MODE == MODE_RECV) {
+            // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k; the tiles of
+            // up to kPeerGroup peers are in flight before the first is unpacked
+            load_rows<G, R>(p.x + e0, l, m, partial, w);
+            constexpr int kPeerGroup = 4;
+            const u4* gtile = reinterpret_cast<const u4*>(reinterpret_cast<const uint8_t*>(p.peer_codes) +
+                                                          (tile_slot0 >> 3) * GBW);
+            const uint64_t stride_u4 = p.peer_codes_stride_words >> 2;
+            float sum[R][4];
+            for (int peer0 = 0; peer0 < p.npeers; peer0 += kPeerGroup) {
+                u4 piece[kPeerGroup];
+                float gbase[kPeerGroup], gscale[kPeerGroup];
+#pragma unroll
+                for (int k = 0; k < kPeerGroup; ++k) {
+                    // past the last peer: re-read the last one (in bounds), its values are not used
+                    const uint64_t peer = peer0 + k < p.npeers ? peer0 + k : p.npeers - 1;
+                    piece[k] = fetch_code_tile<G, R, GBW>(gtile + peer * stride_u4, lane, active_buckets);
+                    const float* pm = p.peer_meta + peer * p.peer_meta_stride_floats;
+                    gbase[k] = pm[2 * bucket];
+                    gscale[k] = pm[2 * bucket + 1];
+                }
+#pragma unroll
+                for (int k = 0; k < kPeerGroup; ++k) {
+                    if (peer0 + k < p.npeers) {  // wave-uniform
+                        float c[R][4];
+                        unstage_codes<G, R, GBW>(stage, piece[k], lane, c);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float d = fmaf(c[r][i], gscale[k], gbase[k]);
+                                sum[r][i] = (peer0 + k == 0) ? d : sum[r][i] + d;
+                            }
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[r][i] = fmaf(-p.lr, p.alpha * sum[r][i], w[r][i]);
         } else {
             load_rows<G, R>(p.xin + e0, l, m, partial, w);
         }
@@ -548,7 +611,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             }
         }
         if (active) {
-            if (MODE == MODE_FUSED || MODE == MODE_ADAMW) {
+            if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -671,6 +734,24 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
             }
             base = gbase;
             scale = grid.scale;
+        } else if (MODE == MODE_RECV) {
+            const int wpb_g = B * p.gbits / 32;
+            const int bit_mask = (1 << p.gbits) - 1;
+            for (int i = tid; i < m; i += 256) {
+                const int bit = i * p.gbits;
+                float sum = 0.0f;
+                for (int peer = 0; peer < p.npeers; ++peer) {
+                    const uint32_t* words = p.peer_codes + (uint64_t)peer * p.peer_codes_stride_words +
+                                            bucket * (uint64_t)wpb_g;
+                    const float* pm = p.peer_meta + (uint64_t)peer * p.peer_meta_stride_floats;
+                    uint64_t two = words[bit >> 5];
+                    if ((bit >> 5) + 1 < wpb_g) two |= (uint64_t)words[(bit >> 5) + 1] << 32;
+                    const uint32_t c = (uint32_t)(two >> (bit & 31)) & (uint32_t)bit_mask;
+                    const float d = fmaf((float)c, pm[2 * bucket + 1], pm[2 * bucket]);
+                    sum = (peer == 0) ? d : sum + d;
+                }
+                val[i] = fmaf(-p.lr, p.alpha * sum, p.x[e0 + i]);
+            }
         } else {
             for (int i = tid; i < m; i += 256) val[i] = p.xin[e0 + i];
         }
@@ -711,7 +792,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_lattice(val[i], div, xi, k0, Lw, sat_here);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) p.x[e0 + i] = fmaf(c, scale, base);
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
             } else {
@@ -721,7 +802,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_minmax(val[i], grid, Lw, xi);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) p.x[e0 + i] = fmaf(c, scale, base);
                 }
             }
         }
