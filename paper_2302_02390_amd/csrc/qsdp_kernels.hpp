@@ -893,8 +893,8 @@ __device__ __forceinline__ uint64_t load_bits(const uint32_t* codes, uint64_t bi
 
 // How a decoder lane finds the bucket of element e (32-bit arithmetic; the host checks
 // n < 2^37): by division, by shift (bucket a power of two), or once per wave tile when the
-// bucket size is a multiple of the tile (the index is then wave-uniform and the meta-data is
-// fetched with scalar loads, which keeps the vector memory pipeline for codes and output).
+// bucket size is a multiple of the tile (the index is then wave-uniform: one meta-data fetch per
+// tile, every lane reading the same 8 bytes, issued together with the code loads).
 enum BucketIndexing { BK_DIVIDE = 0, BK_SHIFT = 1, BK_TILE_UNIFORM = 2 };
 
 template <int BK>
