@@ -199,6 +199,18 @@ def main():
         del y
 
     if not a.no_extras:
+        # what the runtime's own streaming kernels reach on this machine, for context: a device-to-device copy of the
+        # weight vector (read 4n + write 4n bytes) and a fill (write 4n bytes)
+        y = torch.empty_like(x)
+        for _ in range(2):
+            y.copy_(x)
+            y.zero_()
+        copy_ms, _ = time_call(lambda i: y.copy_(x), 5, torch)
+        fill_ms, _ = time_call(lambda i: y.zero_(), 5, torch)
+        del y
+        out["attainable"] = {"device_copy_GB/s": round(8.0 * n / (copy_ms * 1e-3) / 1e9, 1),
+                             "device_fill_GB/s": round(4.0 * n / (fill_ms * 1e-3) / 1e9, 1),
+                             "fused_step_vs_device_copy": round(achieved / (8.0 * n / (copy_ms * 1e-3) / 1e9), 3)}
         out["other_entry_points"] = extras(torch, qb, x, g, n, wbits, gbits, bucket, dev)
         if a.segmented:
             out["segmented_entry_points"] = segmented_extras(torch, qb, x, n, segs, wbits, bucket, dev)
