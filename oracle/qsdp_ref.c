@@ -471,11 +471,12 @@ int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int w
                            int bucket, float delta, uint64_t seed, uint64_t index_offset,
                            uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
     if (!x || !g || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket) ||
-        (flags & ~QSDP_REF_FLAG_ALL))
+        (flags & ~(QSDP_REF_FLAG_ALL | QSDP_REF_FLAG_KEEP_MASTER)))
         return QSDP_REF_EINVAL;
     if (!(delta >= 0.0f) || !isfinite(delta) || !isfinite(lr)) return QSDP_REF_EINVAL;
     if ((wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
     if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    int keep_master = (flags & QSDP_REF_FLAG_KEEP_MASTER) != 0;
     float xi = weight_shift_for(seed, flags);
     float xi_g = grad_shift_for(seed, flags);
     int64_t nb = (int64_t)num_buckets(n, bucket);
@@ -494,7 +495,11 @@ int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int w
         dequant_bucket(gcode, m, gbase, gscale, ghat);
         for (int i = 0; i < m; ++i) y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);
         weight_bucket(y, m, wbits, delta, xi, is_symmetric(flags), wcode, &wbase, &wscale, &local);
-        dequant_bucket(wcode, m, wbase, wscale, x + s);
+        if (keep_master) {
+            for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i]; /* the partition stays unquantized */
+        } else {
+            dequant_bucket(wcode, m, wbase, wscale, x + s);
+        }
         if (wcodes) {
             pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);
             wmeta[2 * j] = wbase;
@@ -509,7 +514,8 @@ int qsdp_ref_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int w
 int qsdp_ref_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr,
                               int wbits, int gbits, int bucket, float delta, uint64_t seed,
                               uint64_t index_offset, uint32_t flags, uint64_t* n_saturated) {
-    if (!wcodes || !wmeta || !g || !args_ok(n, wbits, bucket)) return QSDP_REF_EINVAL;
+    if (!wcodes || !wmeta || !g || !args_ok(n, wbits, bucket) || (flags & ~QSDP_REF_FLAG_ALL))
+        return QSDP_REF_EINVAL; /* KEEP_MASTER: there is no full-precision partition here */
     float* x = (float*)malloc((size_t)n * sizeof(float));
     if (!x) return QSDP_REF_EINVAL;
     int rc = qsdp_ref_dequantize(wcodes, wmeta, n, wbits, bucket, QSDP_REF_F32, x);
@@ -530,7 +536,8 @@ int qsdp_ref_recv_step(float* x, const uint32_t* gcodes, uint64_t codes_stride_w
                        uint64_t meta_stride_floats, int npeers, uint64_t n, float alpha, float lr,
                        int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
                        uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
-    if (!x || !args_ok(n, wbits, bucket) || (flags & ~(QSDP_REF_FLAG_NO_SHIFT | QSDP_REF_FLAG_SYMMETRIC)))
+    if (!x || !args_ok(n, wbits, bucket) ||
+        (flags & ~(QSDP_REF_FLAG_NO_SHIFT | QSDP_REF_FLAG_SYMMETRIC | QSDP_REF_FLAG_KEEP_MASTER)))
         return QSDP_REF_EINVAL;
     if (!isfinite(lr) || (wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
     float* ghat = (float*)malloc((size_t)n * sizeof(float));
@@ -542,9 +549,15 @@ int qsdp_ref_recv_step(float* x, const uint32_t* gcodes, uint64_t codes_stride_w
                                      bucket, alpha, ghat);
     if (rc == QSDP_REF_OK) {
         for (uint64_t i = 0; i < n; ++i) ghat[i] = fmaf(-lr, ghat[i], x[i]); /* y, in place */
-        rc = qsdp_ref_quantize_weight_ex(ghat, n, wbits, bucket, delta, seed, flags, codes, meta, n_saturated);
+        rc = qsdp_ref_quantize_weight_ex(ghat, n, wbits, bucket, delta, seed,
+                                         flags & ~(uint32_t)QSDP_REF_FLAG_KEEP_MASTER, codes, meta, n_saturated);
     }
-    if (rc == QSDP_REF_OK) rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);
+    if (rc == QSDP_REF_OK) {
+        if (flags & QSDP_REF_FLAG_KEEP_MASTER)
+            memcpy(x, ghat, (size_t)n * sizeof(float)); /* x <- y: the partition stays unquantized */
+        else
+            rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);
+    }
     free(ghat);
     if (!wcodes) free(codes);
     if (!wmeta) free(meta);
@@ -689,7 +702,7 @@ int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, 
                               uint64_t seed, uint64_t index_offset, uint32_t flags,
                               uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
     if (!x || !g || !mom || !var || !args_ok(n, wbits, bucket) || !args_ok(n, gbits, bucket) ||
-        (flags & ~QSDP_REF_FLAG_ALL))
+        (flags & ~(QSDP_REF_FLAG_ALL | QSDP_REF_FLAG_KEEP_MASTER)))
         return QSDP_REF_EINVAL;
     if (!(delta >= 0.0f) || !isfinite(delta) || !isfinite(lr)) return QSDP_REF_EINVAL;
     if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
@@ -723,7 +736,11 @@ int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, 
             y[i] = fmaf(-lr, fmaf(weight_decay, x[e], upd), x[e]);
         }
         weight_bucket(y, m, wbits, delta, xi, is_symmetric(flags), wcode, &wbase, &wscale, &local);
-        dequant_bucket(wcode, m, wbase, wscale, x + s);
+        if (flags & QSDP_REF_FLAG_KEEP_MASTER) {
+            for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i]; /* the partition stays unquantized */
+        } else {
+            dequant_bucket(wcode, m, wbase, wscale, x + s);
+        }
         if (wcodes) {
             pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);
             wmeta[2 * j] = wbase;

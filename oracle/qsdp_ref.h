@@ -45,12 +45,17 @@ enum { QSDP_REF_F32 = 0, QSDP_REF_BF16 = 1 };
  *              one shift xi_g per call (stream 2), no per-element randomness;
  *  NO_SHIFT    xi = 0 (and xi_g = 0): deterministic round-to-nearest;
  *  SYMMETRIC   per-bucket grid over [-a, a], a = max |v| (the symmetric scaling of
- *              Section 3.2) instead of [min, max]; ignored with an explicit delta. */
+ *              Section 3.2) instead of [min, max]; ignored with an explicit delta.
+ * For the step routines only (fused_step_ex, fused_adamw_step, recv_step):
+ *  KEEP_MASTER the weight partition stays in full precision, as in Algorithm 2 where
+ *              WeightUpdate acts on w_p and QuantizeWeights only produces what is transmitted:
+ *              x <- y (the updated value itself) while wcodes / wmeta still receive Q^w(y). */
 enum {
     QSDP_REF_FLAG_GRAD_SHIFT = 1,
     QSDP_REF_FLAG_NO_SHIFT = 2,
     QSDP_REF_FLAG_SYMMETRIC = 4,
-    QSDP_REF_FLAG_ALL = 7
+    QSDP_REF_FLAG_ALL = 7, /* the quantizer variants */
+    QSDP_REF_FLAG_KEEP_MASTER = 8
 };
 
 /* Number of worker threads for the bucket loop (buckets are independent, so the

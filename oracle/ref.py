@@ -13,7 +13,7 @@ import numpy as np
 from . import build as _build
 
 F32, BF16 = 0, 1
-FLAG_GRAD_SHIFT, FLAG_NO_SHIFT, FLAG_SYMMETRIC = 1, 2, 4
+FLAG_GRAD_SHIFT, FLAG_NO_SHIFT, FLAG_SYMMETRIC, FLAG_KEEP_MASTER = 1, 2, 4, 8
 
 _lib = None
 

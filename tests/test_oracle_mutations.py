@@ -60,13 +60,18 @@ MUTANTS = [
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
      "for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i];", ["test_oracle_fused.py"]),
+    ("keep_master_still_quantizes", "for (int i = 0; i < m; ++i) x[s + (uint64_t)i] = y[i]; /* the partition stays unquantized */\n        } else {\n            dequant_bucket(wcode, m, wbase, wscale, x + s);\n        }\n        if (wcodes) {\n            pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);\n            wmeta[2 * j] = wbase;\n            wmeta[2 * j + 1] = wscale;\n        }\n        sat += local;\n    }\n    if (n_saturated) *n_saturated += sat;\n    return QSDP_REF_OK;\n}\n\nint qsdp_ref_fused_step_codes(",
+     "dequant_bucket(wcode, m, wbase, wscale, x + s);\n        } else {\n            dequant_bucket(wcode, m, wbase, wscale, x + s);\n        }\n        if (wcodes) {\n            pack_bucket(wcode, m, wbits, bucket, wcodes + (uint64_t)j * (uint64_t)wpb);\n            wmeta[2 * j] = wbase;\n            wmeta[2 * j + 1] = wscale;\n        }\n        sat += local;\n    }\n    if (n_saturated) *n_saturated += sat;\n    return QSDP_REF_OK;\n}\n\nint qsdp_ref_fused_step_codes(",
+     ["test_oracle_keep_master.py"]),
+    ("keep_master_recv_copies_old_weights", "memcpy(x, ghat, (size_t)n * sizeof(float)); /* x <- y: the partition stays unquantized */",
+     "(void)0;", ["test_oracle_keep_master.py"]),
     ("recv_step_sign_flipped", "ghat[i] = fmaf(-lr, ghat[i], x[i]); /* y, in place */",
      "ghat[i] = fmaf(lr, ghat[i], x[i]); /* y, in place */", ["test_oracle_recv_step.py"]),
     ("recv_step_average_dropped", "npeers, n, gbits,\n                                     bucket, alpha, ghat);",
      "npeers, n, gbits,\n                                     bucket, 1.0f, ghat);", ["test_oracle_recv_step.py"]),
     ("recv_step_skips_weight_quantizer",
-     "if (rc == QSDP_REF_OK) rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);",
-     "if (rc == QSDP_REF_OK) memcpy(x, ghat, (size_t)n * sizeof(float));", ["test_oracle_recv_step.py"]),
+     "        else\n            rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);",
+     "        else\n            memcpy(x, ghat, (size_t)n * sizeof(float));", ["test_oracle_recv_step.py"]),
 ]
 
 
