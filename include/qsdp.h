@@ -177,7 +177,7 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr,
  *   y = fma(-lr, ghat, x);   x <- decode(Q^w(y)) as in qsdp_fused_step (delta, seed, wcodes,
  *   wmeta, n_saturated as there). No Q^g is applied: the slices were quantized by their senders.
  * gcodes / gmeta and their strides as in qsdp_dequantize_add, except that the code stride is a
- * multiple of 16 bytes; flags: QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC.
+ * multiple of 16 bytes; flags: QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC, QSDP_FLAG_KEEP_MASTER.
  */
 int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
                    const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, uint64_t n,
@@ -196,9 +196,19 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
  *   QSDP_FLAG_NO_SHIFT    xi = 0 and xi_g = 0: deterministic round-to-nearest (biased).
  *   QSDP_FLAG_SYMMETRIC   per-bucket grid over [-a, a], a = max |v| (the symmetric scaling of
  *                         Section 3.2) instead of [min, max]; no effect with delta > 0.
- * Other bits are rejected with QSDP_EINVAL.
+ * For the entry points that update a weight partition in place (qsdp_fused_step_ex,
+ * qsdp_fused_adamw_step, qsdp_recv_step) there is also
+ *   QSDP_FLAG_KEEP_MASTER the partition stays in full precision, as in Algorithm 2 where the
+ *                         weight update acts on w_p and the weight quantizer only produces what is
+ *                         transmitted: x receives the updated value y itself instead of
+ *                         decode(Q^w(y)); wcodes / wmeta / n_saturated are unchanged.
+ * Other bits, and bits an entry point has no use for, are rejected with QSDP_EINVAL.
  */
-enum { QSDP_FLAG_GRAD_SHIFT = 1, QSDP_FLAG_NO_SHIFT = 2, QSDP_FLAG_SYMMETRIC = 4, QSDP_FLAG_ALL = 7 };
+enum {
+    QSDP_FLAG_GRAD_SHIFT = 1, QSDP_FLAG_NO_SHIFT = 2, QSDP_FLAG_SYMMETRIC = 4,
+    QSDP_FLAG_ALL = 7, /* the quantizer variants */
+    QSDP_FLAG_KEEP_MASTER = 8
+};
 
 int qsdp_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket,
                           uint64_t seed, uint64_t index_offset, uint32_t flags,

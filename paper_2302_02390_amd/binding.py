@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libqsdp.so")
 
 QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
 QSDP_F32, QSDP_BF16 = 0, 1
-QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC = 1, 2, 4
+QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC, QSDP_FLAG_KEEP_MASTER = 1, 2, 4, 8
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
            "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",

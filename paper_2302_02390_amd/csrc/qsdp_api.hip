@@ -414,7 +414,8 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                        float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, uint64_t* n_saturated, void* stream) {
-    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) || (flags & ~QSDP_FLAG_ALL))
+    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
+        (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
@@ -439,7 +440,7 @@ int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!x || !g || !m || !v || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
-        (flags & ~QSDP_FLAG_ALL))
+        (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
@@ -637,7 +638,7 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
                    int gbits, int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
                    float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!x || !gcodes || !gmeta || npeers < 1 || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
-        (flags & ~(uint32_t)(QSDP_FLAG_NO_SHIFT | QSDP_FLAG_SYMMETRIC)))
+        (flags & ~(uint32_t)(QSDP_FLAG_NO_SHIFT | QSDP_FLAG_SYMMETRIC | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr) || !std::isfinite(alpha)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr)) return QSDP_EINVAL;

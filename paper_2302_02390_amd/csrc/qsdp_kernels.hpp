@@ -94,7 +94,8 @@ __device__ __forceinline__ float step_value(const Params& p, float x, float ghat
 }
 
 // Quantizer variants (same values as the QSDP_FLAG_* of the C header)
-enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u };
+// FLAG_KEEP_MASTER (step modes): x receives the updated value itself, the codes still Q^w of it
+enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u, FLAG_KEEP_MASTER = 8u };
 
 struct Shifts {
     float xi;    // weight shift
@@ -400,6 +401,8 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const bool lattice = p.delta > 0.0f;
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
+    constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV;
+    const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
     const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
     uint32_t saturated = 0;
@@ -547,6 +550,9 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             load_rows<G, R>(p.xin + e0, l, m, partial, w);
         }
 
+        // the full-precision partition keeps the updated value itself (stored before w turns into codes)
+        if (kWritesX && keep_master && active) store_rows<G, R>(p.x + e0, l, m, partial, w);
+
         // weight quantization of w
         if constexpr (MODE == MODE_LEVELS) {
             float lo, hi;
@@ -610,8 +616,8 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 p.meta[2 * bucket + 1] = scale;
             }
         }
-        if (active) {
-            if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) {
+        if (active && !keep_master) {
+            if (kWritesX) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -662,6 +668,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
     const bool lattice = p.delta > 0.0f;
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
+    const bool keep_master = (p.flags & FLAG_KEEP_MASTER) != 0;
     const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
     if (tid == 0) sat_block = 0;
@@ -792,7 +799,8 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_lattice(val[i], div, xi, k0, Lw, sat_here);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV)
+                        p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
             } else {
@@ -802,7 +810,8 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_minmax(val[i], grid, Lw, xi);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV) p.x[e0 + i] = fmaf(c, scale, base);
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV)
+                        p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
                 }
             }
         }

@@ -74,7 +74,7 @@ def test_adamw_argument_errors():
     z = torch.zeros(1024, dtype=torch.float32, device=DEV)
     base = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, bias1=0.1, bias2=0.05, wbits=8,
                 gbits=4, bucket=1024, delta=0.0, seed=0)
-    for kw in (dict(beta1=1.0), dict(eps=0.0), dict(bias2=0.0), dict(flags=8), dict(wbits=9)):
+    for kw in (dict(beta1=1.0), dict(eps=0.0), dict(bias2=0.0), dict(flags=16), dict(wbits=9)):
         a = dict(base)
         a.update(kw)
         with pytest.raises(qb.QsdpError) as e:
