@@ -36,10 +36,13 @@ def layout(n, workers, bucket, wbits, gbits):
     }
 
 
-def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=0, trace=None):
+def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=0, trace=None, keep_master=False):
     """x0: float32[n] initial weights on the GPU; targets: float32[P, n] (worker p pulls towards
     targets[p]). Returns (final master weights float32[n], [loss after every step]). `trace`, if
-    given, receives (step, decoded weights) before every update."""
+    given, receives (step, decoded weights) before every update. keep_master: the owners' shards stay
+    in full precision (Algorithm 2 as written) instead of living on the quantization grid (the
+    iteration the paper analyses)."""
+    flags = qb.QSDP_FLAG_KEEP_MASTER if keep_master else 0
     dev = x0.device
     workers, n = targets.shape
     lay = layout(n, workers, bucket, wbits, gbits)
@@ -76,7 +79,7 @@ def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=
             slices = gcodes[:, s * lay["gwords"]: s * lay["gwords"] + gw]                                # 4
             metas = gmeta[:, s * lay["mfloats"]: s * lay["mfloats"] + 2 * nb]
             qb.qsdp_recv_step(x[a:b], slices, metas, workers, 1.0 / workers, lr, wbits, gbits, bucket, delta,
-                              seed0 + t, 0, slot_codes[s, :nb * bucket * wbits // 32], slot_meta[s, :2 * nb])  # 5
+                              seed0 + t, flags, slot_codes[s, :nb * bucket * wbits // 32], slot_meta[s, :2 * nb])  # 5
         losses.append(float(0.5 * ((x.double() - mean_target) ** 2).sum()))
     return x, losses
 

@@ -18,7 +18,7 @@ import virtual_workers as vw  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 
-def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0):
+def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0, flags=0):
     P, n = targets.shape
     lay = vw.layout(n, P, B, wbits, gbits)
     shard = lay["shard"]
@@ -42,7 +42,7 @@ def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0):
             cs = np.stack([c[s * lay["gwords"]: s * lay["gwords"] + gw] for c, _ in grads])
             ms = np.stack([m.reshape(-1)[s * lay["mfloats"]: s * lay["mfloats"] + 2 * nb] for _, m in grads])
             x[a:b], wc, wm, _ = ref.recv_step(x[a:b], cs, ms, P, 1.0 / P, lr, wbits, gbits, B, delta, seed0 + t,
-                                              emit_codes=True)
+                                              flags=flags, emit_codes=True)
             slots[s] = (wc, wm)
     return x, decoded
 
@@ -52,15 +52,18 @@ def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0):
     (5 * 384 - 50, 5, 4, 8, 128, 0.0),
     (3 * 4096 + 9, 3, 8, 4, 512, 2.0 ** -9),
 ])
-def test_virtual_workers_match_the_cpu_twin(n, P, wbits, gbits, B, delta):
+@pytest.mark.parametrize("keep_master", [False, True])
+def test_virtual_workers_match_the_cpu_twin(n, P, wbits, gbits, B, delta, keep_master):
     rng = np.random.default_rng(n)
     x0 = (0.02 * rng.standard_normal(n)).astype(np.float32)
     targets = (0.02 * rng.standard_normal((P, n)) + 0.01).astype(np.float32)
     steps, lr, seed0 = 4, 0.25, 7
     seen = []
     x_gpu, losses = vw.run(torch.from_numpy(x0).to(DEV), torch.from_numpy(targets).to(DEV), steps, lr, wbits,
-                           gbits, B, delta, seed0, trace=lambda t, w: seen.append(w.cpu().numpy()))
-    x_cpu, decoded = cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0)
+                           gbits, B, delta, seed0, trace=lambda t, w: seen.append(w.cpu().numpy()),
+                           keep_master=keep_master)
+    x_cpu, decoded = cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0,
+                              ref.FLAG_KEEP_MASTER if keep_master else 0)
     for t in range(steps):
         assert bits_equal(seen[t], decoded[t]), t
     assert bits_equal(x_gpu.cpu().numpy(), x_cpu)
