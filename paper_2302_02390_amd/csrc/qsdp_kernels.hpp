@@ -15,7 +15,8 @@
 //     wave's tile are shared by the W waves of a workgroup (B = 4*G*R*W, G = 64): each wave
 //     owns a contiguous 1/W of the bucket and the waves combine their min/max through LDS.
 //   * block kernel: one 256-thread workgroup per bucket, staged in LDS; any bucket size, any
-//     bits. Used for the shapes the wave kernels do not cover.
+//     bits. Used for the bucket sizes the wave kernels are not instantiated for (several times
+//     slower: the values make a round trip through LDS and the codes are packed bit by bit).
 // Decoders, the decode-and-sum kernel and the level-fitting kernel follow at the end.
 #pragma once
 

@@ -9,10 +9,8 @@
 
 namespace qsdp {
 
-// Code widths the wave kernels are instantiated for (0 = fused step without code output).
-inline bool wave_bits_supported(int bits) {
-    return bits == 0 || bits == 2 || bits == 3 || bits == 4 || bits == 6 || bits == 8;
-}
+// Code widths the wave kernels are instantiated for (0 = a step without code output).
+inline bool wave_bits_supported(int bits) { return bits >= 0 && bits <= 8; }
 
 // One launcher per instantiated bucket size. `bits` is the width of the codes stored.
 #define QSDP_DECLARE_WAVE(B) \

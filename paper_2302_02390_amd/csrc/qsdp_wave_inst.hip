@@ -25,10 +25,13 @@ hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
 template <int MODE>
 hipError_t by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
     switch (bits) {
+        case 1: return go<MODE, 1>(p, grid, s);
         case 2: return go<MODE, 2>(p, grid, s);
         case 3: return go<MODE, 3>(p, grid, s);
         case 4: return go<MODE, 4>(p, grid, s);
+        case 5: return go<MODE, 5>(p, grid, s);
         case 6: return go<MODE, 6>(p, grid, s);
+        case 7: return go<MODE, 7>(p, grid, s);
         case 8: return go<MODE, 8>(p, grid, s);
         default: return hipErrorInvalidValue;
     }
@@ -47,10 +50,13 @@ template <int GB>
 hipError_t recv_by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
     switch (bits) {
         case 0: return go_recv<GB, 0>(p, grid, s);
+        case 1: return go_recv<GB, 1>(p, grid, s);
         case 2: return go_recv<GB, 2>(p, grid, s);
         case 3: return go_recv<GB, 3>(p, grid, s);
         case 4: return go_recv<GB, 4>(p, grid, s);
+        case 5: return go_recv<GB, 5>(p, grid, s);
         case 6: return go_recv<GB, 6>(p, grid, s);
+        case 7: return go_recv<GB, 7>(p, grid, s);
         case 8: return go_recv<GB, 8>(p, grid, s);
         default: return hipErrorInvalidValue;
     }
@@ -58,10 +64,13 @@ hipError_t recv_by_bits(int bits, const Params& p, unsigned grid, hipStream_t s)
 
 hipError_t recv(int bits, const Params& p, unsigned grid, hipStream_t s) {
     switch (p.gbits) {
+        case 1: return recv_by_bits<1>(bits, p, grid, s);
         case 2: return recv_by_bits<2>(bits, p, grid, s);
         case 3: return recv_by_bits<3>(bits, p, grid, s);
         case 4: return recv_by_bits<4>(bits, p, grid, s);
+        case 5: return recv_by_bits<5>(bits, p, grid, s);
         case 6: return recv_by_bits<6>(bits, p, grid, s);
+        case 7: return recv_by_bits<7>(bits, p, grid, s);
         case 8: return recv_by_bits<8>(bits, p, grid, s);
         default: return hipErrorInvalidValue;
     }

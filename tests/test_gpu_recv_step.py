@@ -41,9 +41,9 @@ CASES = [
     (5 * 4096 + 4095, 2, 2, 8, 4096, 0.0, qb.QSDP_FLAG_NO_SHIFT),
     (20 * 1024 + 300, 8, 8, 4, 1024, 2.0 ** -10, 0),
     (20 * 1024 + 300, 6, 4, 4, 1024, 2.0 ** -10, 0),       # saturating lattice
-    (11 * 96 + 40, 4, 5, 7, 96, 0.0, 0),                   # generic bucket, odd widths: block kernel
-    (6 * 1024 + 1, 3, 7, 4, 1024, 0.0, 0),                 # odd weight width: block kernel
-    (6 * 1024 + 1, 3, 8, 5, 1024, 0.0, 0),                 # odd gradient width: block kernel
+    (11 * 96 + 40, 4, 5, 7, 96, 0.0, 0),                   # generic bucket size: block kernel
+    (6 * 1024 + 1, 3, 7, 4, 1024, 0.0, 0),                 # odd weight width
+    (6 * 1024 + 1, 3, 8, 5, 1024, 0.0, 0),                 # odd gradient width
     (100, 2, 8, 4, 1024, 0.0, 0),                          # less than one bucket
 ]
 
