@@ -48,6 +48,10 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline run: the bits / bucket / delta sweep and the layer-by-layer "
                          "decode to bf16 on the chosen workload; still one JSON line (key 'sweep')")
+    ap.add_argument("--levels-report", action="store_true",
+                    help="instead of the headline run: relative L2 compression error of uniform and fitted "
+                         "(learned) levels at 2..6 bits on the chosen workload, with the fit and codec timings; "
+                         "one JSON line (key 'levels')")
     ap.add_argument("--cpu-sample", type=int, default=1 << 29)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device copy of the weight vector a few times (a kernel of "
@@ -107,6 +111,10 @@ def main():
 
     if a.sweep:
         print(json.dumps(sweep(torch, qb, wl, x, g, n, a.workload, dev)))
+        return 0
+
+    if a.levels_report:
+        print(json.dumps(levels_report(torch, qb, x, g, n, a.workload, bucket, dev)))
         return 0
 
     if a.segmented:
@@ -220,6 +228,42 @@ def main():
                                            bytes_per_param)
     print(json.dumps(out))
     return 0
+
+
+def levels_report(torch, qb, x, g, n, workload, bucket, dev):
+    """Learned (non-uniform) levels against the uniform table: relative L2 error |decode(encode(v)) - v| / |v| of
+    the deterministic nearest-level codec on the weights and on the gradients, levels fitted on the first 4096
+    buckets (rate 0.01, one pass), codec applied to the whole vector. The norms are torch reductions (measurement
+    only)."""
+    rows = []
+    fit_buckets = 4096
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    for name, v in (("weights", x), ("gradients", g)):
+        vnorm = float(torch.linalg.vector_norm(v.double()))
+        for bits in (2, 3, 4, 5, 6):
+            codes, meta = qb.alloc_packed(n, bits, bucket, dev)
+            meta = meta.reshape(-1)
+            uniform = qb.levels_uniform(bits, dev)
+            fitted = uniform.clone()
+            fit_ms, _ = time_call(lambda i: qb.qsdp_fit_levels(v, bits, bucket, 0.01, fitted, fit_buckets), 1, torch)
+            row = {"tensor": name, "bits": bits, "fit_ms": round(fit_ms, 3), "fit_batches": fit_buckets}
+            for label, table in (("uniform", uniform), ("fitted", fitted)):
+                enc_ms, _ = time_call(lambda i: qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta), 3, torch)
+                dec_ms, _ = time_call(lambda i: qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out), 3,
+                                      torch)
+                err = float(torch.linalg.vector_norm((out - v).double())) / vnorm
+                # the quantity the fit minimises: rms error in bucket-normalised coordinates (full buckets only)
+                nbf = n // bucket
+                rng = meta.view(-1, 2)[:nbf, 1].double().clamp_min(1e-30)
+                zerr = ((out[:nbf * bucket] - v[:nbf * bucket]).view(nbf, bucket).double() / rng[:, None])
+                row[label] = {"rel_l2_error": round(err, 6), "normalised_rms_error": round(float(zerr.pow(2).mean().sqrt()), 6),
+                              "encode_ms": round(enc_ms, 4), "decode_ms": round(dec_ms, 4)}
+                del zerr
+            row["error_ratio_fitted_over_uniform"] = round(row["fitted"]["rel_l2_error"] / row["uniform"]["rel_l2_error"], 4)
+            rows.append(row)
+            del codes, meta
+    return {"metric": "relative L2 compression error, uniform vs fitted levels", "workload": workload, "n": n,
+            "bucket": bucket, "data": "synthetic", "levels": rows}
 
 
 def sweep(torch, qb, wl, x, g, n, workload, dev):
