@@ -696,6 +696,19 @@ int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float 
 /* AdamW inside the quantized iteration (Appendix A names the optimizer)       */
 /* ------------------------------------------------------------------------- */
 
+/* One element of AdamW with decoupled weight decay, in binary32 and in this order:
+ *   m <- fma(beta1, m, (1-beta1) g);  v <- fma(beta2, v, ((1-beta2) g) g);
+ *   u = (m / bias1) / (sqrt(v / bias2) + eps);  returns y = fma(-lr, fma(wd, x, u), x). */
+static float adamw_element(float x, float ghat, float* mom, float* var, float lr, float beta1, float beta2,
+                           float omb1, float omb2, float eps, float weight_decay, float bias1, float bias2) {
+    float mi = fmaf(beta1, *mom, omb1 * ghat);
+    float vi = fmaf(beta2, *var, (omb2 * ghat) * ghat);
+    *mom = mi;
+    *var = vi;
+    float upd = (mi / bias1) / (sqrtf(vi / bias2) + eps);
+    return fmaf(-lr, fmaf(weight_decay, x, upd), x);
+}
+
 int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, uint64_t n, float lr,
                               float beta1, float beta2, float eps, float weight_decay, float bias1,
                               float bias2, int wbits, int gbits, int bucket, float delta,
@@ -728,12 +741,8 @@ int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, 
         dequant_bucket(gcode, m, gbase, gscale, ghat);
         for (int i = 0; i < m; ++i) {
             uint64_t e = s + (uint64_t)i;
-            float mi = fmaf(beta1, mom[e], omb1 * ghat[i]);
-            float vi = fmaf(beta2, var[e], (omb2 * ghat[i]) * ghat[i]);
-            mom[e] = mi;
-            var[e] = vi;
-            float upd = (mi / bias1) / (sqrtf(vi / bias2) + eps);
-            y[i] = fmaf(-lr, fmaf(weight_decay, x[e], upd), x[e]);
+            y[i] = adamw_element(x[e], ghat[i], &mom[e], &var[e], lr, beta1, beta2, omb1, omb2, eps, weight_decay,
+                                 bias1, bias2);
         }
         weight_bucket(y, m, wbits, delta, xi, is_symmetric(flags), wcode, &wbase, &wscale, &local);
         if (flags & QSDP_REF_FLAG_KEEP_MASTER) {
@@ -750,4 +759,48 @@ int qsdp_ref_fused_adamw_step(float* x, const float* g, float* mom, float* var, 
     }
     if (n_saturated) *n_saturated += sat;
     return QSDP_REF_OK;
+}
+
+/* The shard owner's update with P workers and AdamW (what the paper's experiments run:
+ * Algorithm 2 with the optimizer of Appendix A): ghat = the scaled sum of the decoded peer slices
+ * as in qsdp_ref_recv_step, then adamw_element per element, then Q^w of the result; x receives
+ * its decode, or the value itself with KEEP_MASTER. */
+int qsdp_ref_recv_adamw_step(float* x, float* mom, float* var, const uint32_t* gcodes,
+                             uint64_t codes_stride_words, const float* gmeta, uint64_t meta_stride_floats,
+                             int npeers, uint64_t n, float alpha, float lr, float beta1, float beta2, float eps,
+                             float weight_decay, float bias1, float bias2, int wbits, int gbits, int bucket,
+                             float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                             uint64_t* n_saturated) {
+    if (!x || !mom || !var || !args_ok(n, wbits, bucket) ||
+        (flags & ~(QSDP_REF_FLAG_NO_SHIFT | QSDP_REF_FLAG_SYMMETRIC | QSDP_REF_FLAG_KEEP_MASTER)))
+        return QSDP_REF_EINVAL;
+    if (!isfinite(lr) || (wcodes == NULL) != (wmeta == NULL)) return QSDP_REF_EINVAL;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
+          bias2 > 0.0f && isfinite(weight_decay)))
+        return QSDP_REF_EINVAL;
+    float* y = (float*)malloc((size_t)n * sizeof(float));
+    uint32_t* codes = wcodes ? wcodes : (uint32_t*)malloc(qsdp_ref_codes_bytes(n, wbits, bucket));
+    float* meta = wmeta ? wmeta : (float*)malloc(qsdp_ref_meta_bytes(n, bucket));
+    int rc = (y && codes && meta) ? QSDP_REF_OK : QSDP_REF_EINVAL;
+    if (rc == QSDP_REF_OK)
+        rc = qsdp_ref_dequantize_add(gcodes, codes_stride_words, gmeta, meta_stride_floats, npeers, n, gbits,
+                                     bucket, alpha, y); /* y holds ghat for now */
+    if (rc == QSDP_REF_OK) {
+        float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+        for (uint64_t i = 0; i < n; ++i)
+            y[i] = adamw_element(x[i], y[i], &mom[i], &var[i], lr, beta1, beta2, omb1, omb2, eps, weight_decay,
+                                 bias1, bias2);
+        rc = qsdp_ref_quantize_weight_ex(y, n, wbits, bucket, delta, seed,
+                                         flags & ~(uint32_t)QSDP_REF_FLAG_KEEP_MASTER, codes, meta, n_saturated);
+    }
+    if (rc == QSDP_REF_OK) {
+        if (flags & QSDP_REF_FLAG_KEEP_MASTER)
+            memcpy(x, y, (size_t)n * sizeof(float));
+        else
+            rc = qsdp_ref_dequantize(codes, meta, n, wbits, bucket, QSDP_REF_F32, x);
+    }
+    free(y);
+    if (!wcodes) free(codes);
+    if (!wmeta) free(meta);
+    return rc;
 }

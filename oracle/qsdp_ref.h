@@ -177,6 +177,15 @@ int qsdp_ref_recv_step(float* x, const uint32_t* gcodes, uint64_t codes_stride_w
                        int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
                        uint32_t* wcodes, float* wmeta, uint64_t* n_saturated);
 
+/* The same with AdamW (Appendix A) in place of the SGD step: ghat as above, then per element
+ * m, v, y as in qsdp_ref_fused_adamw_step, then Q^w(y). flags: NO_SHIFT, SYMMETRIC, KEEP_MASTER. */
+int qsdp_ref_recv_adamw_step(float* x, float* mom, float* var, const uint32_t* gcodes,
+                             uint64_t codes_stride_words, const float* gmeta, uint64_t meta_stride_floats,
+                             int npeers, uint64_t n, float alpha, float lr, float beta1, float beta2, float eps,
+                             float weight_decay, float bias1, float bias2, int wbits, int gbits, int bucket,
+                             float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                             uint64_t* n_saturated);
+
 #ifdef __cplusplus
 }
 #endif

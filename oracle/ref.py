@@ -67,6 +67,8 @@ def lib():
         L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
+        L.qsdp_ref_recv_adamw_step.argtypes = [vp, vp, vp, vp, u64, vp, u64, i32, u64, f32, f32, f32, f32, f32, f32,
+                                               f32, f32, i32, i32, i32, f32, u64, u32, vp, vp, vp]
         L.qsdp_ref_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, u32,
                                          vp, vp, vp]
         _lib = L
@@ -262,6 +264,27 @@ def recv_step(x, gcodes, gmeta, npeers, alpha, lr, wbits, gbits, bucket, delta, 
                                     float(alpha), float(lr), wbits, gbits, bucket, float(delta), int(seed), flags,
                                     _p(wcodes), _p(wmeta), _p(sat)), "recv_step")
     return x, wcodes, wmeta, int(sat[0])
+
+
+def recv_adamw_step(x, m, v, gcodes, gmeta, npeers, alpha, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits,
+                    gbits, bucket, delta, seed, flags=0, emit_codes=False):
+    """Returns (x_new, m_new, v_new, wcodes or None, wmeta or None, n_saturated); inputs are not modified."""
+    x = _f32(x).copy(); m = _f32(m).copy(); v = _f32(v).copy()
+    n = x.size
+    gcodes = np.ascontiguousarray(gcodes, dtype=np.uint32).reshape(npeers, -1)
+    gmeta = np.ascontiguousarray(gmeta, dtype=np.float32).reshape(npeers, -1)
+    assert gcodes.shape[1] * 4 == codes_bytes(n, gbits, bucket) and gmeta.shape[1] == 2 * _nb(n, bucket)
+    wcodes = wmeta = None
+    if emit_codes:
+        wcodes = np.zeros(codes_bytes(n, wbits, bucket) // 4, dtype=np.uint32)
+        wmeta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_recv_adamw_step(_p(x), _p(m), _p(v), _p(gcodes), gcodes.shape[1], _p(gmeta),
+                                          gmeta.shape[1], npeers, n, float(alpha), float(lr), float(beta1),
+                                          float(beta2), float(eps), float(weight_decay), float(bias1), float(bias2),
+                                          wbits, gbits, bucket, float(delta), int(seed), flags, _p(wcodes), _p(wmeta),
+                                          _p(sat)), "recv_adamw_step")
+    return x, m, v, wcodes, wmeta, int(sat[0])
 
 
 def levels_uniform(bits):

@@ -50,12 +50,16 @@ MUTANTS = [
      "levels[k] = (float)(q - (1.0 - keep[1]) * (q - mean));", ["test_oracle_levels.py"]),
     ("level_decode_ignores_table", "float val = fmaf(levels[code[i]], meta[2 * j + 1], meta[2 * j]);",
      "float val = fmaf((float)code[i], meta[2 * j + 1], meta[2 * j]);", ["test_oracle_levels.py"]),
-    ("adamw_second_moment_not_squared", "float vi = fmaf(beta2, var[e], (omb2 * ghat[i]) * ghat[i]);",
-     "float vi = fmaf(beta2, var[e], omb2 * ghat[i]);", ["test_oracle_adamw.py"]),
+    ("adamw_second_moment_not_squared", "float vi = fmaf(beta2, *var, (omb2 * ghat) * ghat);",
+     "float vi = fmaf(beta2, *var, omb2 * ghat);", ["test_oracle_adamw.py"]),
     ("adamw_bias_corrections_swapped", "float upd = (mi / bias1) / (sqrtf(vi / bias2) + eps);",
      "float upd = (mi / bias2) / (sqrtf(vi / bias1) + eps);", ["test_oracle_adamw.py"]),
-    ("adamw_decay_dropped", "y[i] = fmaf(-lr, fmaf(weight_decay, x[e], upd), x[e]);", "y[i] = fmaf(-lr, upd, x[e]);",
+    ("adamw_decay_dropped", "return fmaf(-lr, fmaf(weight_decay, x, upd), x);", "return fmaf(-lr, upd, x);",
      ["test_oracle_adamw.py"]),
+    ("recv_adamw_uses_unscaled_sum", "bucket, alpha, y); /* y holds ghat for now */",
+     "bucket, 1.0f, y); /* y holds ghat for now */", ["test_oracle_recv_adamw.py"]),
+    ("recv_adamw_moments_swapped", "y[i] = adamw_element(x[i], y[i], &mom[i], &var[i], lr,",
+     "y[i] = adamw_element(x[i], y[i], &var[i], &mom[i], lr,", ["test_oracle_recv_adamw.py"]),
     ("step_sign_flipped", "y[i] = fmaf(-lr, ghat[i], x[s + (uint64_t)i]);", "y[i] = fmaf(lr, ghat[i], x[s + (uint64_t)i]);",
      ["test_oracle_fused.py"]),
     ("step_skips_weight_quantizer", "dequant_bucket(wcode, m, wbase, wscale, x + s);",
