@@ -421,7 +421,15 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
               lambda i: qb.qsdp_recv_step(xs, pc, pm, peers, 1.0 / peers, 1e-3, wbits, gbits, bucket, 0.0, i, 0,
                                           sc, sm.reshape(-1)),
               8 + peers * (gbits / 8.0 + meta_b) + wbits / 8.0 + meta_b)
-    del xs, sc, sm
+    # ... and with AdamW on the full-precision partition (Algorithm 2's weight update as the experiments run it)
+    mom = torch.zeros(m, dtype=torch.float32, device=dev)
+    var = torch.zeros(m, dtype=torch.float32, device=dev)
+    run_small(f"recv_adamw_step_{peers}peers_W{wbits}G{gbits}_keep_master",
+              lambda i: qb.qsdp_recv_adamw_step(xs, mom, var, pc, pm, peers, 1.0 / peers, 2e-4, 0.9, 0.95, 1e-8, 0.0,
+                                                1 - 0.9 ** (i + 1), 1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i,
+                                                qb.QSDP_FLAG_KEEP_MASTER, sc, sm.reshape(-1)),
+              24 + peers * (gbits / 8.0 + meta_b) + wbits / 8.0 + meta_b)
+    del xs, sc, sm, mom, var
     n = n_saved
     del pc, pm, acc
     # decode of a gathered layer: the vector as 8 peers' weight shards, each quantized on its own, one

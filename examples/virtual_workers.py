@@ -9,8 +9,9 @@ Per step, for a layer of n parameters sharded P ways (shard = a multiple of the 
      f_p(w) = 1/2 |w - t_p|^2, so g_p = w - t_p; plain torch arithmetic, not part of the library);
   3. every worker quantizes its whole gradient with qsdp_quantize_grad (its own seed);
   4. gradient exchange: owner s needs slice s of every worker's codes, a strided view here;
-  5. owner s runs qsdp_recv_step: decode-and-average the P slices, SGD step on its fp32 master
-     shard, Q^w of the result, whose codes go straight into its slot of the gather buffer.
+  5. owner s runs qsdp_recv_step (or qsdp_recv_adamw_step): decode-and-average the P slices, SGD
+     (AdamW) step on its fp32 master shard, Q^w of the result, whose codes go straight into its
+     slot of the gather buffer.
 
     python examples/virtual_workers.py            # prints the loss per step
 """
@@ -36,12 +37,14 @@ def layout(n, workers, bucket, wbits, gbits):
     }
 
 
-def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=0, trace=None, keep_master=False):
+def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=0, trace=None, keep_master=False,
+        adamw=None):
     """x0: float32[n] initial weights on the GPU; targets: float32[P, n] (worker p pulls towards
     targets[p]). Returns (final master weights float32[n], [loss after every step]). `trace`, if
     given, receives (step, decoded weights) before every update. keep_master: the owners' shards stay
     in full precision (Algorithm 2 as written) instead of living on the quantization grid (the
-    iteration the paper analyses)."""
+    iteration the paper analyses). adamw: None for the SGD step, or (beta1, beta2, eps, weight_decay) for the
+    owners' AdamW (moments live with the master shards)."""
     flags = qb.QSDP_FLAG_KEEP_MASTER if keep_master else 0
     dev = x0.device
     workers, n = targets.shape
@@ -62,6 +65,8 @@ def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=
     gcodes = torch.zeros((workers, nb_all * bucket * gbits // 32), dtype=torch.int32, device=dev)
     gmeta = torch.zeros((workers, (2 * nb_all + 3) // 4 * 4), dtype=torch.float32, device=dev)
     w = torch.empty(n, dtype=torch.float32, device=dev)
+    mom = torch.zeros(n, dtype=torch.float32, device=dev) if adamw else None
+    var = torch.zeros(n, dtype=torch.float32, device=dev) if adamw else None
     mean_target = targets.double().mean(dim=0)
     losses = []
     for t in range(steps):
@@ -78,8 +83,15 @@ def run(x0, targets, steps, lr, wbits=8, gbits=4, bucket=1024, delta=0.0, seed0=
             gw = nb * bucket * gbits // 32
             slices = gcodes[:, s * lay["gwords"]: s * lay["gwords"] + gw]                                # 4
             metas = gmeta[:, s * lay["mfloats"]: s * lay["mfloats"] + 2 * nb]
-            qb.qsdp_recv_step(x[a:b], slices, metas, workers, 1.0 / workers, lr, wbits, gbits, bucket, delta,
-                              seed0 + t, flags, slot_codes[s, :nb * bucket * wbits // 32], slot_meta[s, :2 * nb])  # 5
+            out_codes, out_meta = slot_codes[s, :nb * bucket * wbits // 32], slot_meta[s, :2 * nb]
+            if adamw:                                                                                    # 5
+                b1, b2, eps, wd = adamw
+                qb.qsdp_recv_adamw_step(x[a:b], mom[a:b], var[a:b], slices, metas, workers, 1.0 / workers, lr, b1, b2,
+                                        eps, wd, 1.0 - b1 ** (t + 1), 1.0 - b2 ** (t + 1), wbits, gbits, bucket, delta,
+                                        seed0 + t, flags, out_codes, out_meta)
+            else:
+                qb.qsdp_recv_step(x[a:b], slices, metas, workers, 1.0 / workers, lr, wbits, gbits, bucket, delta,
+                                  seed0 + t, flags, out_codes, out_meta)
         losses.append(float(0.5 * ((x.double() - mean_target) ** 2).sum()))
     return x, losses
 

@@ -186,6 +186,22 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
                    uint64_t* n_saturated, void* stream);
 
 /*
+ * The same with AdamW (Appendix A) in place of the SGD update, which is what the paper's
+ * experiments run on every shard: ghat as in qsdp_recv_step, then per element m, v, u, y as in
+ * qsdp_fused_adamw_step (defined below), then Q^w(y). Reads x, m, v and the P code slices,
+ * writes x, m, v (and the packed codes): 24 + P * gbits/8 (+ wbits/8) bytes per parameter.
+ * With QSDP_FLAG_KEEP_MASTER this is Algorithm 2's weight update as written: AdamW on the
+ * full-precision partition, the codes being what the next weight gather transmits.
+ */
+int qsdp_recv_adamw_step(float* x, float* m, float* v, const uint32_t* gcodes,
+                         uint64_t gcodes_stride_bytes, const float* gmeta,
+                         uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha,
+                         float lr, float beta1, float beta2, float eps, float weight_decay,
+                         float bias1, float bias2, int wbits, int gbits, int bucket, float delta,
+                         uint64_t seed, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                         uint64_t* n_saturated, void* stream);
+
+/*
  * Quantizer variants the paper names as admissible, selected by `flags` (0 = the default
  * operators above; meta-data and wire format are unchanged, so qsdp_dequantize serves all):
  *   QSDP_FLAG_GRAD_SHIFT  gradients are quantized by random shift as well (the appendix notes
@@ -197,7 +213,7 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
  *   QSDP_FLAG_SYMMETRIC   per-bucket grid over [-a, a], a = max |v| (the symmetric scaling of
  *                         Section 3.2) instead of [min, max]; no effect with delta > 0.
  * For the entry points that update a weight partition in place (qsdp_fused_step_ex,
- * qsdp_fused_adamw_step, qsdp_recv_step) there is also
+ * qsdp_fused_adamw_step, qsdp_recv_step, qsdp_recv_adamw_step) there is also
  *   QSDP_FLAG_KEEP_MASTER the partition stays in full precision, as in Algorithm 2 where the
  *                         weight update acts on w_p and the weight quantizer only produces what is
  *                         transmitted: x receives the updated value y itself instead of

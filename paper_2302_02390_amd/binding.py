@@ -22,7 +22,8 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step")
+           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
+           "qsdp_recv_adamw_step")
 
 _lib = None
 
@@ -84,6 +85,9 @@ def lib():
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
+        L.qsdp_recv_adamw_step.argtypes = [vp, vp, vp, vp, u64, vp, u64, i32, u64, f32, f32, f32, f32, f32, f32, f32,
+                                           f32, i32, i32, i32, f32, u64, C.c_uint32, vp, vp, vp, vp]
+        L.qsdp_recv_adamw_step.restype = i32
         for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
                      "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
                      "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered"):
@@ -422,3 +426,24 @@ def qsdp_recv_step(x, gcodes, gmeta, npeers, alpha, lr, wbits, gbits, bucket, de
         _check(lib().qsdp_recv_step(_ptr(x), _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta), gmeta.stride(0) * 4,
                                     npeers, x.numel(), alpha, lr, wbits, gbits, bucket, delta, seed, flags,
                                     _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)), "qsdp_recv_step")
+
+
+def qsdp_recv_adamw_step(x, m, v, gcodes, gmeta, npeers, alpha, lr, beta1, beta2, eps, weight_decay, bias1, bias2,
+                         wbits, gbits, bucket, delta, seed, flags=0, wcodes=None, wmeta=None, n_saturated=None):
+    """As qsdp_recv_step with the AdamW update; m, v float32[n] moment estimates, updated in place."""
+    for t in (x, m, v):
+        _is(t, torch.float32)
+    if not (x.numel() == m.numel() == v.numel()):
+        raise ValueError("x, m, v differ in size")
+    _is_rows(gcodes, torch.int32); _is_rows(gmeta, torch.float32)
+    if gcodes.shape[0] != npeers or gmeta.shape[0] != npeers:
+        raise ValueError("gcodes and gmeta must be [npeers, ...]")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_recv_adamw_step(_ptr(x), _ptr(m), _ptr(v), _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta),
+                                          gmeta.stride(0) * 4, npeers, x.numel(), alpha, lr, beta1, beta2, eps,
+                                          weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed, flags,
+                                          _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)),
+               "qsdp_recv_adamw_step")

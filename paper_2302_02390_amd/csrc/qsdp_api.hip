@@ -19,6 +19,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_RECV: hipLaunchKernelGGL(block_kernel<MODE_RECV>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_RECV_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_RECV_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -191,7 +192,7 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
     p.first_bucket = 0;
     int bpw = 1;
     WaveLauncher wl = wave_launcher(p.bucket, &bpw);
-    const bool peer_bits_ok = mode != MODE_RECV || (p.gbits != 0 && wave_bits_supported(p.gbits));
+    const bool peer_bits_ok = !mode_is_recv(mode) || (p.gbits != 0 && wave_bits_supported(p.gbits));
     if (wl != nullptr && wave_bits_supported(stored_bits) && peer_bits_ok) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
@@ -633,10 +634,17 @@ int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes,
     return QSDP_OK;
 }
 
-int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes, const float* gmeta,
-                   uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha, float lr, int wbits,
-                   int gbits, int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
-                   float* wmeta, uint64_t* n_saturated, void* stream) {
+// Argument checks and parameter block shared by the two receive-side steps; `adam`: the AdamW
+// scalars (nullptr for the SGD step).
+struct AdamScalars {
+    float *m, *v;
+    float beta1, beta2, eps, weight_decay, bias1, bias2;
+};
+
+static int recv_step_common(const AdamScalars* adam, float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
+                            const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha,
+                            float lr, int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
+                            uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!x || !gcodes || !gmeta || npeers < 1 || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
         (flags & ~(uint32_t)(QSDP_FLAG_NO_SHIFT | QSDP_FLAG_SYMMETRIC | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
@@ -645,10 +653,15 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
     if (npeers > 1 && (gcodes_stride_bytes < qsdp_codes_bytes(n, gbits, bucket) ||
                        gmeta_stride_bytes < qsdp_meta_bytes(n, bucket)))
         return QSDP_EINVAL;
+    if (adam && (!adam->m || !adam->v ||
+                 !(adam->beta1 >= 0.0f && adam->beta1 < 1.0f && adam->beta2 >= 0.0f && adam->beta2 < 1.0f &&
+                   adam->eps > 0.0f && adam->bias1 > 0.0f && adam->bias2 > 0.0f && std::isfinite(adam->weight_decay))))
+        return QSDP_EINVAL;
     if ((gcodes_stride_bytes & 15u) || (gmeta_stride_bytes & 3u)) return QSDP_EALIGN;
     if (!aligned16(x) || !aligned16(gcodes) || !aligned16(wcodes) || !aligned16(wmeta) ||
         (reinterpret_cast<uintptr_t>(gmeta) & 3u))
         return QSDP_EALIGN;
+    if (adam && (!aligned16(adam->m) || !aligned16(adam->v))) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, 0, delta);
@@ -666,7 +679,37 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    return run(MODE_RECV, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+    if (adam) {
+        p.mom = adam->m;
+        p.var = adam->v;
+        p.beta1 = adam->beta1;
+        p.beta2 = adam->beta2;
+        p.omb1 = 1.0f - adam->beta1;
+        p.omb2 = 1.0f - adam->beta2;
+        p.eps = adam->eps;
+        p.weight_decay = adam->weight_decay;
+        p.bias1 = adam->bias1;
+        p.bias2 = adam->bias2;
+    }
+    return run(adam ? MODE_RECV_ADAMW : MODE_RECV, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes, const float* gmeta,
+                   uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha, float lr, int wbits,
+                   int gbits, int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
+                   float* wmeta, uint64_t* n_saturated, void* stream) {
+    return recv_step_common(nullptr, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha, lr,
+                            wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
+}
+
+int qsdp_recv_adamw_step(float* x, float* m, float* v, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
+                         const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha,
+                         float lr, float beta1, float beta2, float eps, float weight_decay, float bias1,
+                         float bias2, int wbits, int gbits, int bucket, float delta, uint64_t seed,
+                         uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    return recv_step_common(&adam, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha, lr,
+                            wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
 }
 
 }  // extern "C"

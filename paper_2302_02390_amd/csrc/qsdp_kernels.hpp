@@ -33,8 +33,12 @@ namespace qsdp {
 // two quantizers instead of the plain SGD update.
 // MODE_RECV: the shard owner's step with P workers: the gradient is the scaled sum of the
 // decoded slices of all peers (no Q^g here), then the SGD step and Q^w as in MODE_FUSED.
+// MODE_RECV_ADAMW: the same with the AdamW update of MODE_ADAMW in place of the SGD step.
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
-            MODE_ADAMW = 5, MODE_RECV = 6 };
+            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7 };
+
+constexpr bool mode_is_recv(int mode) { return mode == MODE_RECV || mode == MODE_RECV_ADAMW; }
+constexpr bool mode_is_adamw(int mode) { return mode == MODE_ADAMW || mode == MODE_RECV_ADAMW; }
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.
@@ -84,7 +88,7 @@ struct Params {
 // y = fma(-lr, fma(wd, x, u), x)).
 template <int MODE>
 __device__ __forceinline__ float step_value(const Params& p, float x, float ghat, float& mom, float& var) {
-    if constexpr (MODE == MODE_ADAMW) {
+    if constexpr (mode_is_adamw(MODE)) {
         mom = fmaf(p.beta1, mom, p.omb1 * ghat);
         var = fmaf(p.beta2, var, (p.omb2 * ghat) * ghat);
         const float upd = (mom / p.bias1) / (sqrtf(var / p.bias2) + p.eps);
@@ -366,7 +370,7 @@ template <int MODE, int G, int R, int BITS, int W, int GB = 0>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
-    static_assert((MODE == MODE_RECV) == (GB != 0), "GB = width of the peers' gradient codes (MODE_RECV only)");
+    static_assert(mode_is_recv(MODE) == (GB != 0), "GB = width of the peers' gradient codes (receive-side modes only)");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
     constexpr int B = T * W;
     constexpr int BPW = 64 / G;
@@ -402,7 +406,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const bool lattice = p.delta > 0.0f;
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
-    constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV;
+    constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE);
     const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
     const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
@@ -507,10 +511,15 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 }
                 continue;
             }
-        } else if constexpr (MODE == MODE_RECV) {
+        } else if constexpr (mode_is_recv(MODE)) {
             // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k; the tiles of
             // up to kPeerGroup peers are in flight before the first is unpacked
             load_rows<G, R>(p.x + e0, l, m, partial, w);
+            float mom[R][4], var[R][4];  // MODE_RECV_ADAMW only
+            if constexpr (MODE == MODE_RECV_ADAMW) {
+                load_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                load_rows<G, R>(p.var + e0, l, m, partial, var);
+            }
             constexpr int kPeerGroup = 4;
             const u4* gtile = reinterpret_cast<const u4*>(reinterpret_cast<const uint8_t*>(p.peer_codes) +
                                                           (tile_slot0 >> 3) * GBW);
@@ -546,7 +555,14 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[r][i] = fmaf(-p.lr, p.alpha * sum[r][i], w[r][i]);
+                for (int i = 0; i < 4; ++i)
+                    w[r][i] = step_value<MODE>(p, w[r][i], p.alpha * sum[r][i], mom[r][i], var[r][i]);
+            if constexpr (MODE == MODE_RECV_ADAMW) {
+                if (active) {
+                    store_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                    store_rows<G, R>(p.var + e0, l, m, partial, var);
+                }
+            }
         } else {
             load_rows<G, R>(p.xin + e0, l, m, partial, w);
         }
@@ -742,7 +758,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
             }
             base = gbase;
             scale = grid.scale;
-        } else if (MODE == MODE_RECV) {
+        } else if (mode_is_recv(MODE)) {
             const int wpb_g = B * p.gbits / 32;
             const int bit_mask = (1 << p.gbits) - 1;
             for (int i = tid; i < m; i += 256) {
@@ -758,7 +774,16 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     const float d = fmaf((float)c, pm[2 * bucket + 1], pm[2 * bucket]);
                     sum = (peer == 0) ? d : sum + d;
                 }
-                val[i] = fmaf(-p.lr, p.alpha * sum, p.x[e0 + i]);
+                float mom = 0.0f, var = 0.0f;
+                if (MODE == MODE_RECV_ADAMW) {
+                    mom = p.mom[e0 + i];
+                    var = p.var[e0 + i];
+                }
+                val[i] = step_value<MODE>(p, p.x[e0 + i], p.alpha * sum, mom, var);
+                if (MODE == MODE_RECV_ADAMW) {
+                    p.mom[e0 + i] = mom;
+                    p.var[e0 + i] = var;
+                }
             }
         } else {
             for (int i = tid; i < m; i += 256) val[i] = p.xin[e0 + i];
@@ -800,7 +825,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_lattice(val[i], div, xi, k0, Lw, sat_here);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV)
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE))
                         p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
@@ -811,7 +836,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 for (int i = tid; i < m; i += 256) {
                     const float c = weight_code_minmax(val[i], grid, Lw, xi);
                     code[i] = (uint8_t)(uint32_t)c;
-                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || MODE == MODE_RECV)
+                    if (MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE))
                         p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
                 }
             }

@@ -18,12 +18,13 @@ import virtual_workers as vw  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 
-def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0, flags=0):
+def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0, flags=0, adamw=None):
     P, n = targets.shape
     lay = vw.layout(n, P, B, wbits, gbits)
     shard = lay["shard"]
     bounds = [(s * shard, min((s + 1) * shard, n)) for s in range(P)]
     x = x0.copy()
+    mom, var = np.zeros(n, np.float32), np.zeros(n, np.float32)
     slots = []
     for a, b in bounds:
         c, m, _ = ref.quantize_weight(x[a:b], wbits, B, delta, seed0)
@@ -41,8 +42,14 @@ def cpu_twin(x0, targets, steps, lr, wbits, gbits, B, delta, seed0, flags=0):
             gw = nb * B * gbits // 32
             cs = np.stack([c[s * lay["gwords"]: s * lay["gwords"] + gw] for c, _ in grads])
             ms = np.stack([m.reshape(-1)[s * lay["mfloats"]: s * lay["mfloats"] + 2 * nb] for _, m in grads])
-            x[a:b], wc, wm, _ = ref.recv_step(x[a:b], cs, ms, P, 1.0 / P, lr, wbits, gbits, B, delta, seed0 + t,
-                                              flags=flags, emit_codes=True)
+            if adamw:
+                b1, b2, eps, wd = adamw
+                x[a:b], mom[a:b], var[a:b], wc, wm, _ = ref.recv_adamw_step(
+                    x[a:b], mom[a:b], var[a:b], cs, ms, P, 1.0 / P, lr, b1, b2, eps, wd, 1.0 - b1 ** (t + 1),
+                    1.0 - b2 ** (t + 1), wbits, gbits, B, delta, seed0 + t, flags=flags, emit_codes=True)
+            else:
+                x[a:b], wc, wm, _ = ref.recv_step(x[a:b], cs, ms, P, 1.0 / P, lr, wbits, gbits, B, delta, seed0 + t,
+                                                  flags=flags, emit_codes=True)
             slots[s] = (wc, wm)
     return x, decoded
 
@@ -85,3 +92,17 @@ def test_virtual_workers_converge_to_the_grid_floor():
     assert losses[-1] / n < 1e-6
     tail = losses[-10:]
     assert max(tail) < 1.5 * min(tail)
+
+
+def test_virtual_workers_with_adamw_match_the_cpu_twin():
+    """The experiments' configuration in miniature: AdamW on full-precision owner shards, W8 G4."""
+    n, P, B = 6 * 1024 + 100, 3, 1024
+    rng = np.random.default_rng(12)
+    x0 = (0.02 * rng.standard_normal(n)).astype(np.float32)
+    targets = (0.02 * rng.standard_normal((P, n)) + 0.01).astype(np.float32)
+    adamw = (0.9, 0.95, 1e-8, 0.01)
+    x_gpu, losses = vw.run(torch.from_numpy(x0).to(DEV), torch.from_numpy(targets).to(DEV), 5, 2e-3, 8, 4, B, 0.0, 3,
+                           keep_master=True, adamw=adamw)
+    x_cpu, _ = cpu_twin(x0, targets, 5, 2e-3, 8, 4, B, 0.0, 3, ref.FLAG_KEEP_MASTER, adamw)
+    assert bits_equal(x_gpu.cpu().numpy(), x_cpu)
+    assert losses[-1] < losses[0]
