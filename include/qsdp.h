@@ -303,6 +303,13 @@ int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n,
                            void* out, void* stream);
 int qsdp_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
                     uint64_t max_batches, float* levels, void* stream);
+/* qsdp_dequantize_gathered for slots that were encoded with qsdp_quantize_levels (all slots with
+ * the same level table): out = what qsdp_dequantize_levels gives slot by slot. */
+int qsdp_dequantize_levels_gathered(const uint32_t* codes, uint64_t codes_stride_bytes,
+                                    const float* meta, uint64_t meta_stride_bytes, int npeers,
+                                    uint64_t n, uint64_t shard, int bits, int bucket,
+                                    const float* levels, qsdp_dtype out_dtype, void* out,
+                                    void* stream);
 
 /*
  * Multi-tensor ("segmented") variants: in the paper's system every layer is compressed on

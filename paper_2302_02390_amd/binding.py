@@ -23,7 +23,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
-           "qsdp_recv_adamw_step")
+           "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered")
 
 _lib = None
 
@@ -82,6 +82,8 @@ def lib():
                                                 u64, vp, vp, vp, vp]
         L.qsdp_dequantize_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, i32, vp, vp]
         L.qsdp_dequantize_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, i32, vp, vp]
+        L.qsdp_dequantize_levels_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, vp, i32, vp, vp]
+        L.qsdp_dequantize_levels_gathered.restype = i32
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
@@ -392,9 +394,10 @@ def qsdp_dequantize_segmented(codes, meta, segs, bits, out):
                                                _stream(out)), "qsdp_dequantize_segmented")
 
 
-def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out):
+def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out, levels=None):
     """codes int32[npeers, >= words of a shard], meta float32[npeers, >= 2 * buckets of a shard]
-    (row p = peer p's slot; rows may be views into one receive buffer); out float32/bfloat16[n]."""
+    (row p = peer p's slot; rows may be views into one receive buffer); out float32/bfloat16[n].
+    levels: the table the slots were encoded with by qsdp_quantize_levels, or None for uniform codes."""
     _is_rows(codes, torch.int32); _is_rows(meta, torch.float32)
     if out.dtype == torch.float32:
         dt = QSDP_F32
@@ -408,6 +411,15 @@ def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out):
     if out.numel() < n:
         raise ValueError("out is too small")
     with torch.cuda.device(out.device):
+        if levels is not None:
+            _is(levels, torch.float32)
+            if levels.numel() != (1 << bits):
+                raise ValueError("levels must hold 2^bits entries")
+            _check(lib().qsdp_dequantize_levels_gathered(_ptr(codes), codes.stride(0) * 4, _ptr(meta),
+                                                         meta.stride(0) * 4, npeers, n, shard, bits, bucket,
+                                                         _ptr(levels), dt, _ptr(out), _stream(out)),
+                   "qsdp_dequantize_levels_gathered")
+            return
         _check(lib().qsdp_dequantize_gathered(_ptr(codes), codes.stride(0) * 4, _ptr(meta), meta.stride(0) * 4,
                                               npeers, n, shard, bits, bucket, dt, _ptr(out), _stream(out)),
                "qsdp_dequantize_gathered")

@@ -606,9 +606,10 @@ int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qs
     return QSDP_OK;
 }
 
-int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes, const float* meta,
-                             uint64_t meta_stride_bytes, int npeers, uint64_t n, uint64_t shard, int bits,
-                             int bucket, qsdp_dtype out_dtype, void* out, void* stream) {
+static int dequantize_gathered_common(const float* levels, const uint32_t* codes, uint64_t codes_stride_bytes,
+                                      const float* meta, uint64_t meta_stride_bytes, int npeers, uint64_t n,
+                                      uint64_t shard, int bits, int bucket, qsdp_dtype out_dtype, void* out,
+                                      void* stream) {
     if (!codes || !meta || !out || !shape_ok(n, bits, bucket) || npeers < 1 || npeers > 65535) return QSDP_EINVAL;
     if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
     if (shard == 0 || shard % (uint64_t)bucket != 0 || ceil_div(n, shard) != (uint64_t)npeers) return QSDP_EINVAL;
@@ -629,9 +630,27 @@ int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes,
     p.ntiles_last = last.ntiles;
     p.codes_stride_words = codes_stride_bytes / 4;
     p.meta_stride_floats = meta_stride_bytes / 4;
+    p.levels = levels;
     if (launch_dequant(bits, bf16, p, dim3(grid, (unsigned)npeers), static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
+}
+
+int qsdp_dequantize_gathered(const uint32_t* codes, uint64_t codes_stride_bytes, const float* meta,
+                             uint64_t meta_stride_bytes, int npeers, uint64_t n, uint64_t shard, int bits,
+                             int bucket, qsdp_dtype out_dtype, void* out, void* stream) {
+    return dequantize_gathered_common(nullptr, codes, codes_stride_bytes, meta, meta_stride_bytes, npeers, n, shard,
+                                      bits, bucket, out_dtype, out, stream);
+}
+
+int qsdp_dequantize_levels_gathered(const uint32_t* codes, uint64_t codes_stride_bytes, const float* meta,
+                                    uint64_t meta_stride_bytes, int npeers, uint64_t n, uint64_t shard, int bits,
+                                    int bucket, const float* levels, qsdp_dtype out_dtype, void* out,
+                                    void* stream) {
+    if (!levels) return QSDP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(levels) & 3u) return QSDP_EALIGN;
+    return dequantize_gathered_common(levels, codes, codes_stride_bytes, meta, meta_stride_bytes, npeers, n, shard,
+                                      bits, bucket, out_dtype, out, stream);
 }
 
 // Argument checks and parameter block shared by the two receive-side steps; `adam`: the AdamW

@@ -100,3 +100,29 @@ def test_gathered_decode_rejects_bad_arguments():
     with pytest.raises(qb.QsdpError):
         qb.qsdp_dequantize_gathered(small, m, 2, 8192, 4096, 8, 1024, out)  # slots closer than a shard's codes
     qb.qsdp_dequantize_gathered(c, m, 2, 8192, 4096, 8, 1024, out)          # the valid form of the same call
+
+
+@pytest.mark.parametrize("bits,dtype", [(3, torch.float32), (5, torch.bfloat16)])
+def test_gathered_decode_with_a_learned_level_table(bits, dtype):
+    n, shard, B = 5 * 2048 + 700, 2048, 1024
+    npeers = -(-n // shard)
+    x, _ = synth(n, 404)
+    levels = ref.fit_levels(x[:4 * B], bits, B, 0.05, ref.levels_uniform(bits))
+    cw, mw = ref.codes_bytes(shard, bits, B) // 4, ref.meta_bytes(shard, B) // 4
+    codes = torch.zeros((npeers, (cw + 3) // 4 * 4), dtype=torch.int32, device=DEV)
+    meta = torch.zeros((npeers, (mw + 3) // 4 * 4), dtype=torch.float32, device=DEV)
+    want = []
+    for p in range(npeers):
+        xs = x[p * shard: min((p + 1) * shard, n)]
+        c, m = ref.quantize_levels(xs, bits, B, levels)
+        codes[p, :c.size] = torch.from_numpy(c.view(np.int32)).to(DEV)
+        meta[p, :m.size] = torch.from_numpy(m.reshape(-1)).to(DEV)
+        want.append(ref.dequantize_levels(c, m, xs.size, bits, B, levels,
+                                          ref.BF16 if dtype == torch.bfloat16 else ref.F32))
+    want = np.concatenate(want)
+    out = torch.empty(n, dtype=dtype, device=DEV)
+    qb.qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, B, out, torch.from_numpy(levels).to(DEV))
+    if dtype == torch.float32:
+        assert bits_equal(out.cpu().numpy(), want)
+    else:
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), want)
