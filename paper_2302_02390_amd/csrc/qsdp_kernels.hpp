@@ -1194,7 +1194,10 @@ __global__ void __launch_bounds__(256) dequant_add_kernel(const DequantAddParams
 // LDS, block min/max, assign every value to its nearest level (levels frozen), accumulate
 // exact 32.32 fixed-point sums and counts per level with LDS atomics (order independent, so the
 // result is reproducible), then level k takes its count_k steps of rate lr towards the mean
-// of its values at once, in binary64: q <- q - (1 - (1-lr)^c)(q - mean).
+// of its values at once, in binary64: q <- q - (1 - (1-lr)^c)(q - mean). The chain of batches is
+// kept short: the next batch's values are fetched while the current one is processed, the
+// powers (1-lr)^c come from an LDS table filled once by repeated multiplication (the order in
+// which single steps compound), and small level tables are accumulated per wave.
 // ---------------------------------------------------------------------------------------
 struct FitParams {
     const float* v;
@@ -1209,46 +1212,92 @@ struct FitParams {
 template <int BITS>
 __global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
     constexpr int K = 1 << BITS;
+    constexpr int kCopies = K <= 16 ? 4 : 1;  // small tables: one accumulator set per wave (fewer atomic collisions)
+    constexpr int kKeepMax = 2048;            // (1 - lr)^c is tabulated up to this count
+    constexpr int kPre = 8;                   // values per thread fetched one batch ahead (buckets up to 2048)
     __shared__ float val[kMaxBucket];
     __shared__ float lv[K];
-    __shared__ long long sum[K];
-    __shared__ unsigned int count[K];
+    __shared__ long long sum[kCopies][K];
+    __shared__ unsigned int count[kCopies][K];
+    __shared__ double keep_tab[kKeepMax + 1];
     __shared__ float red[8];
     const int tid = threadIdx.x;
+    const int copy = kCopies == 1 ? 0 : (tid >> 6);
     const int B = p.bucket;
+    const bool prefetch = B <= 256 * kPre;
     for (int k = tid; k < K; k += 256) lv[k] = p.levels[k];
     const double one_minus = 1.0 - (double)p.lr;
+    if (tid == 0) {
+        // (1 - lr)^c by repeated multiplication, the order in which c single steps compound
+        double keep = 1.0;
+        keep_tab[0] = 1.0;
+        const int top = B < kKeepMax ? B : kKeepMax;
+        for (int c = 1; c <= top; ++c) {
+            keep *= one_minus;
+            keep_tab[c] = keep;
+        }
+    }
+    float nxt[kPre];
+    auto fetch = [&](uint64_t j) {
+        const uint64_t e0 = j * (uint64_t)B;
+        const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) {
+            const int i = tid + 256 * q;
+            nxt[q] = i < m ? p.v[e0 + i] : 0.0f;
+        }
+    };
+    if (prefetch && p.num_batches > 0) fetch(0);
     for (uint64_t j = 0; j < p.num_batches; ++j) {
         const uint64_t e0 = j * (uint64_t)B;
         const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
-        __syncthreads();  // previous batch's level update and LDS reads are complete
+        __syncthreads();  // previous batch's level update and LDS reads are complete (and keep_tab is written)
         float lo = __builtin_inff(), hi = -__builtin_inff();
-        for (int i = tid; i < m; i += 256) {
-            const float x = p.v[e0 + i];
-            val[i] = x;
-            lo = fminf(lo, x);
-            hi = fmaxf(hi, x);
+        if (prefetch) {
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) {
+                const int i = tid + 256 * q;
+                if (i < m) {
+                    val[i] = nxt[q];
+                    lo = fminf(lo, nxt[q]);
+                    hi = fmaxf(hi, nxt[q]);
+                }
+            }
+            if (j + 1 < p.num_batches) fetch(j + 1);  // in flight while this batch is processed
+        } else {
+            for (int i = tid; i < m; i += 256) {
+                const float x = p.v[e0 + i];
+                val[i] = x;
+                lo = fminf(lo, x);
+                hi = fmaxf(hi, x);
+            }
         }
-        for (int k = tid; k < K; k += 256) {
-            sum[k] = 0;
-            count[k] = 0u;
+        for (int k = tid; k < kCopies * K; k += 256) {
+            (&sum[0][0])[k] = 0;
+            (&count[0][0])[k] = 0u;
         }
         block_minmax(lo, hi, red);  // contains the barriers that publish sum/count = 0 too
         const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);
         for (int i = tid; i < m; i += 256) {
             const float z = (val[i] - grid.lo) * grid.inv;
             const int k = nearest_level<BITS>(z, lv);
-            atomicAdd(reinterpret_cast<unsigned long long*>(&sum[k]),
+            atomicAdd(reinterpret_cast<unsigned long long*>(&sum[copy][k]),
                       (unsigned long long)(long long)(z * 4294967296.0f));
-            atomicAdd(&count[k], 1u);
+            atomicAdd(&count[copy][k], 1u);
         }
         __syncthreads();
         for (int k = tid; k < K; k += 256) {
-            const unsigned int c = count[k];
+            unsigned int c = 0;
+            long long total = 0;  // exact integer sums: any order of accumulation gives the same value
+#pragma unroll
+            for (int w = 0; w < kCopies; ++w) {
+                c += count[w][k];
+                total += sum[w][k];
+            }
             if (c != 0u) {
-                double keep = 1.0;
-                for (unsigned int t = 0; t < c; ++t) keep *= one_minus;  // (1 - lr)^c, same order as the oracle
-                const double mean = ((double)sum[k] / (double)c) * (1.0 / 4294967296.0);
+                double keep = keep_tab[c < (unsigned)kKeepMax ? c : (unsigned)kKeepMax];
+                for (unsigned int t = kKeepMax; t < c; ++t) keep *= one_minus;
+                const double mean = ((double)total / (double)c) * (1.0 / 4294967296.0);
                 const double q = (double)lv[k];
                 lv[k] = (float)(q - (1.0 - keep) * (q - mean));
             }
