@@ -370,6 +370,45 @@ int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qs
                               uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
                               qsdp_dtype out_dtype, void* out, void* stream);
 
+/*
+ * The receive-side steps for a partition that holds many tensors, each bucketed on its own
+ * (Section 5.1): x (and m, v) are the flat buffers the segment table describes; the peers'
+ * gradient codes and meta, like wcodes / wmeta, are indexed by bucket number as in the other
+ * segmented calls (peer k's slot starts k * stride after gcodes / gmeta and holds
+ * total_buckets * bucket code slots). Equal to qsdp_recv_step / qsdp_recv_adamw_step tensor by
+ * tensor; n_saturated accumulates over all tensors. qsdp_fused_adamw_step_segmented and
+ * qsdp_fused_step_codes_segmented are the multi-tensor forms of those two single-worker steps
+ * (gradient uniforms follow index_offset + the position in the flat buffer, as in
+ * qsdp_fused_step_segmented).
+ */
+int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v,
+                                    const qsdp_segment* table, uint32_t nseg,
+                                    uint64_t total_buckets, float lr, float beta1, float beta2,
+                                    float eps, float weight_decay, float bias1, float bias2,
+                                    int wbits, int gbits, int bucket, float delta, uint64_t seed,
+                                    uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
+                                    float* wmeta, uint64_t* n_saturated, void* stream);
+int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float* g,
+                                    const qsdp_segment* table, uint32_t nseg,
+                                    uint64_t total_buckets, float lr, int wbits, int gbits,
+                                    int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                                    uint32_t flags, uint64_t* n_saturated, void* stream);
+int qsdp_recv_step_segmented(float* x, const qsdp_segment* table, uint32_t nseg,
+                             uint64_t total_buckets, const uint32_t* gcodes,
+                             uint64_t gcodes_stride_bytes, const float* gmeta,
+                             uint64_t gmeta_stride_bytes, int npeers, float alpha, float lr,
+                             int wbits, int gbits, int bucket, float delta, uint64_t seed,
+                             uint32_t flags, uint32_t* wcodes, float* wmeta,
+                             uint64_t* n_saturated, void* stream);
+int qsdp_recv_adamw_step_segmented(float* x, float* m, float* v, const qsdp_segment* table,
+                                   uint32_t nseg, uint64_t total_buckets, const uint32_t* gcodes,
+                                   uint64_t gcodes_stride_bytes, const float* gmeta,
+                                   uint64_t gmeta_stride_bytes, int npeers, float alpha, float lr,
+                                   float beta1, float beta2, float eps, float weight_decay,
+                                   float bias1, float bias2, int wbits, int gbits, int bucket,
+                                   float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
+                                   float* wmeta, uint64_t* n_saturated, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
-           "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered")
+           "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
+           "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented")
 
 _lib = None
 
@@ -84,6 +85,19 @@ def lib():
         L.qsdp_dequantize_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, i32, vp, vp]
         L.qsdp_dequantize_levels_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, vp, i32, vp, vp]
         L.qsdp_dequantize_levels_gathered.restype = i32
+        L.qsdp_recv_step_segmented.argtypes = [vp, vp, C.c_uint32, u64, vp, u64, vp, u64, i32, f32, f32, i32, i32, i32,
+                                               f32, u64, C.c_uint32, vp, vp, vp, vp]
+        L.qsdp_recv_step_segmented.restype = i32
+        L.qsdp_recv_adamw_step_segmented.argtypes = [vp, vp, vp, vp, C.c_uint32, u64, vp, u64, vp, u64, i32, f32, f32,
+                                                     f32, f32, f32, f32, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
+                                                     vp, vp, vp, vp]
+        L.qsdp_recv_adamw_step_segmented.restype = i32
+        L.qsdp_fused_adamw_step_segmented.argtypes = [vp, vp, vp, vp, vp, C.c_uint32, u64, f32, f32, f32, f32, f32, f32,
+                                                      f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp, vp, vp]
+        L.qsdp_fused_adamw_step_segmented.restype = i32
+        L.qsdp_fused_step_codes_segmented.argtypes = [vp, vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64, u64,
+                                                      C.c_uint32, vp, vp]
+        L.qsdp_fused_step_codes_segmented.restype = i32
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
@@ -459,3 +473,66 @@ def qsdp_recv_adamw_step(x, m, v, gcodes, gmeta, npeers, alpha, lr, beta1, beta2
                                           weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed, flags,
                                           _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)),
                "qsdp_recv_adamw_step")
+
+
+def qsdp_recv_step_segmented(x, segs, gcodes, gmeta, npeers, alpha, lr, wbits, gbits, delta, seed, flags=0,
+                             wcodes=None, wmeta=None, n_saturated=None, adamw=None):
+    """The receive-side step over the tensors of `segs` in one launch. adamw: None, or
+    (m, v, beta1, beta2, eps, weight_decay, bias1, bias2) for the AdamW form."""
+    _is(x, torch.float32); _is_rows(gcodes, torch.int32); _is_rows(gmeta, torch.float32)
+    if x.numel() < segs.n:
+        raise ValueError("x is smaller than the segments")
+    if gcodes.shape[0] != npeers or gmeta.shape[0] != npeers:
+        raise ValueError("gcodes and gmeta must be [npeers, ...]")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        if adamw is None:
+            _check(lib().qsdp_recv_step_segmented(_ptr(x), _ptr(segs.device), segs.nseg, segs.total_buckets,
+                                                  _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta),
+                                                  gmeta.stride(0) * 4, npeers, alpha, lr, wbits, gbits, segs.bucket,
+                                                  delta, seed, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
+                                                  _stream(x)), "qsdp_recv_step_segmented")
+        else:
+            m, v, b1, b2, eps, wd, c1, c2 = adamw
+            _is(m, torch.float32); _is(v, torch.float32)
+            if m.numel() < segs.n or v.numel() < segs.n:
+                raise ValueError("m or v is smaller than the segments")
+            _check(lib().qsdp_recv_adamw_step_segmented(_ptr(x), _ptr(m), _ptr(v), _ptr(segs.device), segs.nseg,
+                                                        segs.total_buckets, _ptr(gcodes), gcodes.stride(0) * 4,
+                                                        _ptr(gmeta), gmeta.stride(0) * 4, npeers, alpha, lr, b1, b2,
+                                                        eps, wd, c1, c2, wbits, gbits, segs.bucket, delta, seed, flags,
+                                                        _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)),
+                   "qsdp_recv_adamw_step_segmented")
+
+
+def qsdp_fused_adamw_step_segmented(x, g, m, v, segs, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits,
+                                    delta, seed, index_offset=0, flags=0, wcodes=None, wmeta=None, n_saturated=None):
+    for t in (x, g, m, v):
+        _is(t, torch.float32)
+        if t.numel() < segs.n:
+            raise ValueError("a tensor is smaller than the segments")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_adamw_step_segmented(_ptr(x), _ptr(g), _ptr(m), _ptr(v), _ptr(segs.device), segs.nseg,
+                                                     segs.total_buckets, lr, beta1, beta2, eps, weight_decay, bias1,
+                                                     bias2, wbits, gbits, segs.bucket, delta, seed, index_offset, flags,
+                                                     _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated), _stream(x)),
+               "qsdp_fused_adamw_step_segmented")
+
+
+def qsdp_fused_step_codes_segmented(wcodes, wmeta, g, segs, lr, wbits, gbits, delta, seed, index_offset=0, flags=0,
+                                    n_saturated=None):
+    _is(wcodes, torch.int32); _is(wmeta, torch.float32); _is(g, torch.float32)
+    if g.numel() < segs.n:
+        raise ValueError("g is smaller than the segments")
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_fused_step_codes_segmented(_ptr(wcodes), _ptr(wmeta), _ptr(g), _ptr(segs.device), segs.nseg,
+                                                     segs.total_buckets, lr, wbits, gbits, segs.bucket, delta, seed,
+                                                     index_offset, flags, _ptr(n_saturated), _stream(g)),
+               "qsdp_fused_step_codes_segmented")

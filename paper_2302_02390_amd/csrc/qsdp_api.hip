@@ -220,6 +220,51 @@ void set_common(Params& p, uint64_t n, int bucket, uint64_t seed, uint64_t index
 
 using namespace qsdp;
 
+// A multi-tensor call's segment table (device pointer) as the segmented entry points receive it.
+struct SegmentTable {
+    const qsdp_segment* table;
+    uint32_t nseg;
+    uint64_t total_buckets;
+};
+
+// The AdamW moments and scalars of the AdamW-flavoured steps.
+struct AdamScalars {
+    float *m, *v;
+    float beta1, beta2, eps, weight_decay, bias1, bias2;
+};
+
+static bool adam_ok(const AdamScalars& a) {
+    return a.m && a.v && a.beta1 >= 0.0f && a.beta1 < 1.0f && a.beta2 >= 0.0f && a.beta2 < 1.0f && a.eps > 0.0f &&
+           a.bias1 > 0.0f && a.bias2 > 0.0f && std::isfinite(a.weight_decay);
+}
+
+static void set_adam(Params& p, const AdamScalars& a) {
+    p.mom = a.m;
+    p.var = a.v;
+    p.beta1 = a.beta1;
+    p.beta2 = a.beta2;
+    p.omb1 = 1.0f - a.beta1;
+    p.omb2 = 1.0f - a.beta2;
+    p.eps = a.eps;
+    p.weight_decay = a.weight_decay;
+    p.bias1 = a.bias1;
+    p.bias2 = a.bias2;
+}
+
+// Validates a segment table argument; on success *n is replaced by the number of code slots.
+static int segments_ok(const SegmentTable& segs, int bucket, uint64_t* n) {
+    if (!segs.table || segs.nseg == 0 || segs.total_buckets < segs.nseg || bucket <= 0) return QSDP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(segs.table) & 7u) return QSDP_EALIGN;
+    *n = segs.total_buckets * (uint64_t)bucket;
+    return QSDP_OK;
+}
+
+static void set_segments(Params& p, const SegmentTable& segs) {
+    p.segs = reinterpret_cast<const Segment*>(segs.table);
+    p.nseg = segs.nseg;
+    p.num_buckets = segs.total_buckets;
+}
+
 static_assert(sizeof(qsdp_segment) == sizeof(Segment), "segment layout");
 
 extern "C" {
@@ -436,49 +481,68 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
-int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr, float beta1,
-                          float beta2, float eps, float weight_decay, float bias1, float bias2, int wbits,
-                          int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
-                          uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
-    if (!x || !g || !m || !v || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
+static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g, const AdamScalars& adam, uint64_t n,
+                              float lr, int wbits, int gbits, int bucket, float delta, uint64_t seed,
+                              uint64_t index_offset, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                              uint64_t* n_saturated, void* stream) {
+    if (segs) {
+        const int rc = segments_ok(*segs, bucket, &n);
+        if (rc != QSDP_OK) return rc;
+    }
+    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) || !adam_ok(adam) ||
         (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
-    if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f && eps > 0.0f && bias1 > 0.0f &&
-          bias2 > 0.0f && std::isfinite(weight_decay)))
-        return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(m) || !aligned16(v) || !aligned16(wcodes) ||
+    if (!aligned16(x) || !aligned16(g) || !aligned16(adam.m) || !aligned16(adam.v) || !aligned16(wcodes) ||
         !aligned16(wmeta))
         return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
-    set_common(p, n, bucket, seed, index_offset, delta);
+    set_common(p, segs ? 0 : n, bucket, seed, index_offset, delta);
+    if (segs) set_segments(p, *segs);
     p.flags = flags;
     p.x = x;
     p.g = g;
-    p.mom = m;
-    p.var = v;
     p.codes = wcodes;
     p.meta = wmeta;
     p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    p.beta1 = beta1;
-    p.beta2 = beta2;
-    p.omb1 = 1.0f - beta1;
-    p.omb2 = 1.0f - beta2;
-    p.eps = eps;
-    p.weight_decay = weight_decay;
-    p.bias1 = bias1;
-    p.bias2 = bias2;
+    set_adam(p, adam);
     return run(MODE_ADAMW, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
-int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,
+int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, float bias1, float bias2, int wbits,
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
-                          uint32_t flags, uint64_t* n_saturated, void* stream) {
+                          uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    return fused_adamw_common(nullptr, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags,
+                              wcodes, wmeta, n_saturated, stream);
+}
+
+int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v, const qsdp_segment* table,
+                                    uint32_t nseg, uint64_t total_buckets, float lr, float beta1, float beta2,
+                                    float eps, float weight_decay, float bias1, float bias2, int wbits, int gbits,
+                                    int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                                    uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated,
+                                    void* stream) {
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    const SegmentTable segs = {table, nseg, total_buckets};
+    return fused_adamw_common(&segs, x, g, adam, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+                              wmeta, n_saturated, stream);
+}
+
+static int fused_step_codes_common(const SegmentTable* segs, uint32_t* wcodes, float* wmeta, const float* g,
+                                   uint64_t n, float lr, int wbits, int gbits, int bucket, float delta,
+                                   uint64_t seed, uint64_t index_offset, uint32_t flags, uint64_t* n_saturated,
+                                   void* stream) {
+    if (segs) {
+        const int rc = segments_ok(*segs, bucket, &n);
+        if (rc != QSDP_OK) return rc;
+    }
     if (!wcodes || !wmeta || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
         (flags & ~QSDP_FLAG_ALL))
         return QSDP_EINVAL;
@@ -486,7 +550,8 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
     if (!aligned16(wcodes) || !aligned16(wmeta) || !aligned16(g)) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
-    set_common(p, n, bucket, seed, index_offset, delta);
+    set_common(p, segs ? 0 : n, bucket, seed, index_offset, delta);
+    if (segs) set_segments(p, *segs);
     p.flags = flags;
     p.g = g;
     p.codes = wcodes;
@@ -496,6 +561,22 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
     p.wbits = wbits;
     p.lr = lr;
     return run(MODE_FUSED_CODES, p, wbits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,
+                          int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                          uint32_t flags, uint64_t* n_saturated, void* stream) {
+    return fused_step_codes_common(nullptr, wcodes, wmeta, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset,
+                                   flags, n_saturated, stream);
+}
+
+int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float* g, const qsdp_segment* table,
+                                    uint32_t nseg, uint64_t total_buckets, float lr, int wbits, int gbits,
+                                    int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                                    uint32_t flags, uint64_t* n_saturated, void* stream) {
+    const SegmentTable segs = {table, nseg, total_buckets};
+    return fused_step_codes_common(&segs, wcodes, wmeta, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset,
+                                   flags, n_saturated, stream);
 }
 
 uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table) {
@@ -653,17 +734,15 @@ int qsdp_dequantize_levels_gathered(const uint32_t* codes, uint64_t codes_stride
                                       bits, bucket, out_dtype, out, stream);
 }
 
-// Argument checks and parameter block shared by the two receive-side steps; `adam`: the AdamW
-// scalars (nullptr for the SGD step).
-struct AdamScalars {
-    float *m, *v;
-    float beta1, beta2, eps, weight_decay, bias1, bias2;
-};
-
-static int recv_step_common(const AdamScalars* adam, float* x, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
+static int recv_step_common(const AdamScalars* adam, const SegmentTable* segs, float* x, const uint32_t* gcodes,
+                            uint64_t gcodes_stride_bytes,
                             const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha,
                             float lr, int wbits, int gbits, int bucket, float delta, uint64_t seed, uint32_t flags,
                             uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (segs) {  // multi-tensor call: the slots of all buckets count as the "vector" for the size checks
+        const int rc = segments_ok(*segs, bucket, &n);
+        if (rc != QSDP_OK) return rc;
+    }
     if (!x || !gcodes || !gmeta || npeers < 1 || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
         (flags & ~(uint32_t)(QSDP_FLAG_NO_SHIFT | QSDP_FLAG_SYMMETRIC | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
@@ -672,10 +751,7 @@ static int recv_step_common(const AdamScalars* adam, float* x, const uint32_t* g
     if (npeers > 1 && (gcodes_stride_bytes < qsdp_codes_bytes(n, gbits, bucket) ||
                        gmeta_stride_bytes < qsdp_meta_bytes(n, bucket)))
         return QSDP_EINVAL;
-    if (adam && (!adam->m || !adam->v ||
-                 !(adam->beta1 >= 0.0f && adam->beta1 < 1.0f && adam->beta2 >= 0.0f && adam->beta2 < 1.0f &&
-                   adam->eps > 0.0f && adam->bias1 > 0.0f && adam->bias2 > 0.0f && std::isfinite(adam->weight_decay))))
-        return QSDP_EINVAL;
+    if (adam && !adam_ok(*adam)) return QSDP_EINVAL;
     if ((gcodes_stride_bytes & 15u) || (gmeta_stride_bytes & 3u)) return QSDP_EALIGN;
     if (!aligned16(x) || !aligned16(gcodes) || !aligned16(wcodes) || !aligned16(wmeta) ||
         (reinterpret_cast<uintptr_t>(gmeta) & 3u))
@@ -683,7 +759,8 @@ static int recv_step_common(const AdamScalars* adam, float* x, const uint32_t* g
     if (adam && (!aligned16(adam->m) || !aligned16(adam->v))) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
-    set_common(p, n, bucket, seed, 0, delta);
+    set_common(p, segs ? 0 : n, bucket, seed, 0, delta);
+    if (segs) set_segments(p, *segs);
     p.flags = flags;
     p.x = x;
     p.peer_codes = gcodes;
@@ -698,18 +775,7 @@ static int recv_step_common(const AdamScalars* adam, float* x, const uint32_t* g
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    if (adam) {
-        p.mom = adam->m;
-        p.var = adam->v;
-        p.beta1 = adam->beta1;
-        p.beta2 = adam->beta2;
-        p.omb1 = 1.0f - adam->beta1;
-        p.omb2 = 1.0f - adam->beta2;
-        p.eps = adam->eps;
-        p.weight_decay = adam->weight_decay;
-        p.bias1 = adam->bias1;
-        p.bias2 = adam->bias2;
-    }
+    if (adam) set_adam(p, *adam);
     return run(adam ? MODE_RECV_ADAMW : MODE_RECV, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
@@ -717,7 +783,8 @@ int qsdp_recv_step(float* x, const uint32_t* gcodes, uint64_t gcodes_stride_byte
                    uint64_t gmeta_stride_bytes, int npeers, uint64_t n, float alpha, float lr, int wbits,
                    int gbits, int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
                    float* wmeta, uint64_t* n_saturated, void* stream) {
-    return recv_step_common(nullptr, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha, lr,
+    return recv_step_common(nullptr, nullptr, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha,
+                            lr,
                             wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
 }
 
@@ -727,8 +794,32 @@ int qsdp_recv_adamw_step(float* x, float* m, float* v, const uint32_t* gcodes, u
                          float bias2, int wbits, int gbits, int bucket, float delta, uint64_t seed,
                          uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
-    return recv_step_common(&adam, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha, lr,
+    return recv_step_common(&adam, nullptr, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, n, alpha,
+                            lr,
                             wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
+}
+
+int qsdp_recv_step_segmented(float* x, const qsdp_segment* table, uint32_t nseg, uint64_t total_buckets,
+                             const uint32_t* gcodes, uint64_t gcodes_stride_bytes, const float* gmeta,
+                             uint64_t gmeta_stride_bytes, int npeers, float alpha, float lr, int wbits, int gbits,
+                             int bucket, float delta, uint64_t seed, uint32_t flags, uint32_t* wcodes,
+                             float* wmeta, uint64_t* n_saturated, void* stream) {
+    const SegmentTable segs = {table, nseg, total_buckets};
+    return recv_step_common(nullptr, &segs, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, 0, alpha,
+                            lr, wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
+}
+
+int qsdp_recv_adamw_step_segmented(float* x, float* m, float* v, const qsdp_segment* table, uint32_t nseg,
+                                   uint64_t total_buckets, const uint32_t* gcodes, uint64_t gcodes_stride_bytes,
+                                   const float* gmeta, uint64_t gmeta_stride_bytes, int npeers, float alpha,
+                                   float lr, float beta1, float beta2, float eps, float weight_decay,
+                                   float bias1, float bias2, int wbits, int gbits, int bucket, float delta,
+                                   uint64_t seed, uint32_t flags, uint32_t* wcodes, float* wmeta,
+                                   uint64_t* n_saturated, void* stream) {
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    const SegmentTable segs = {table, nseg, total_buckets};
+    return recv_step_common(&adam, &segs, x, gcodes, gcodes_stride_bytes, gmeta, gmeta_stride_bytes, npeers, 0, alpha,
+                            lr, wbits, gbits, bucket, delta, seed, flags, wcodes, wmeta, n_saturated, stream);
 }
 
 }  // extern "C"

@@ -155,3 +155,102 @@ def test_dequantize_segmented_gpt350m_equals_per_tensor_calls():
         qb.qsdp_dequantize(codes[fb * wpb:(fb + nb) * wpb], meta[fb:fb + nb].clone().reshape(-1), s, 8, B,
                            per[off:off + s])
     assert torch.equal(out.view(torch.int16), per.view(torch.int16))
+
+
+@pytest.mark.parametrize("B,wbits,gbits,delta,flags", [(1024, 8, 4, 0.0, 0), (128, 5, 2, 0.0, qb.QSDP_FLAG_KEEP_MASTER),
+                                                       (512, 6, 3, 2.0 ** -9, 0), (2048, 8, 4, 0.0, 0),
+                                                       (96, 5, 7, 0.0, qb.QSDP_FLAG_KEEP_MASTER)])
+@pytest.mark.parametrize("adamw", [False, True])
+def test_recv_steps_segmented_match_per_tensor_oracle(B, wbits, gbits, delta, flags, adamw):
+    """The receive-side steps (SGD and AdamW) over many tensors in one launch, against the oracle's
+    single-tensor routines applied tensor by tensor."""
+    sizes = [768, 2304, 768 * 24, 8, 3072, 16, 1024 * 3 + 8, 4096 * 2, 24, 5000 + 3]
+    n, P = sum(sizes), 4
+    x, _ = synth(n, 321 + B)
+    peers_g = [synth(n, 700 + 11 * p)[1] for p in range(P)]
+    segs = qb.Segments(sizes, B, DEV)
+    b1, b2, eps, wd, lr, c1, c2 = 0.9, 0.95, 1e-8, 0.05, 1e-2, 0.1, 0.05
+    m0 = (1e-4 * np.arange(n) / n).astype(np.float32)
+    v0 = (1e-8 * (1 + np.arange(n) % 7)).astype(np.float32)
+    want_x, want_m, want_v, want_c, want_meta, gcs, gms, want_sat = [], [], [], [], [], [[] for _ in range(P)], \
+        [[] for _ in range(P)], 0
+    off = 0
+    for s in sizes:
+        sl = slice(off, off + s)
+        cs, ms = [], []
+        for p in range(P):
+            c, mm = ref.quantize_grad(peers_g[p][sl], gbits, B, 60 + p, index_offset=off)
+            cs.append(c); ms.append(mm.reshape(-1))
+            gcs[p].append(c); gms[p].append(mm.reshape(-1))
+        cs, ms = np.stack(cs), np.stack(ms)
+        if adamw:
+            xs, mo, vo, wc, wm, sat = ref.recv_adamw_step(x[sl], m0[sl], v0[sl], cs, ms, P, 1.0 / P, lr, b1, b2, eps, wd,
+                                                          c1, c2, wbits, gbits, B, delta, 8, flags, emit_codes=True)
+            want_m.append(mo); want_v.append(vo)
+        else:
+            xs, wc, wm, sat = ref.recv_step(x[sl], cs, ms, P, 1.0 / P, lr, wbits, gbits, B, delta, 8, flags,
+                                            emit_codes=True)
+        want_x.append(xs); want_c.append(wc); want_meta.append(wm.reshape(-1)); want_sat += sat
+        off += s
+    gc_np = np.stack([np.concatenate(a) for a in gcs])
+    gm_np = np.stack([np.concatenate(a) for a in gms])
+    row = -(-gc_np.shape[1] // 4) * 4
+    gc = torch.zeros((P, row), dtype=torch.int32, device=DEV)
+    gc[:, :gc_np.shape[1]] = torch.from_numpy(gc_np.view(np.int32)).to(DEV)
+    gm = torch.from_numpy(gm_np).to(DEV)
+    xd = torch.from_numpy(x).to(DEV)
+    md, vd = torch.from_numpy(m0).to(DEV), torch.from_numpy(v0).to(DEV)
+    wc, wm = segs.alloc_packed(wbits)
+    sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+    qb.qsdp_recv_step_segmented(xd, segs, gc[:, :gc_np.shape[1]], gm, P, 1.0 / P, lr, wbits, gbits, delta, 8, flags, wc,
+                                wm.reshape(-1), sat, adamw=(md, vd, b1, b2, eps, wd, c1, c2) if adamw else None)
+    assert bits_equal(np_f32(xd), np.concatenate(want_x))
+    if adamw:
+        assert bits_equal(np_f32(md), np.concatenate(want_m)) and bits_equal(np_f32(vd), np.concatenate(want_v))
+    assert np.array_equal(np_u32(wc), np.concatenate(want_c))
+    assert np.array_equal(np_u32(wm).reshape(-1), np.concatenate(want_meta).view(np.uint32))
+    assert int(sat) == want_sat
+
+
+@pytest.mark.parametrize("B,wbits,gbits,delta", [(1024, 8, 4, 0.0), (128, 5, 2, 0.0), (2048, 8, 4, 2.0 ** -10),
+                                                 (96, 5, 7, 0.0)])
+def test_adamw_and_code_resident_steps_segmented(B, wbits, gbits, delta):
+    """The multi-tensor forms of the single-worker AdamW step and of the code-resident step equal the
+    oracle's single-tensor routines applied tensor by tensor (index_offset + position in the buffer)."""
+    sizes = [768, 2304, 768 * 24, 8, 3072, 16, 1024 * 3 + 8, 4096 * 2, 24, 5000 + 3]
+    n = sum(sizes)
+    x, g = synth(n, 611 + B)
+    segs = qb.Segments(sizes, B, DEV)
+    b1, b2, eps, wd, lr, c1, c2 = 0.9, 0.95, 1e-8, 0.05, 1e-3, 0.1, 0.05
+    m0 = (1e-4 * np.arange(n) / n).astype(np.float32)
+    v0 = (1e-8 * (1 + np.arange(n) % 7)).astype(np.float32)
+    # AdamW
+    want = {"x": [], "m": [], "v": [], "c": [], "meta": []}
+    codes0, meta0, cwant, mwant = [], [], [], []
+    off = 0
+    for s in sizes:
+        sl = slice(off, off + s)
+        xs, mo, vo, wc, wm, _ = ref.fused_adamw_step(x[sl], g[sl], m0[sl], v0[sl], lr, b1, b2, eps, wd, c1, c2, wbits,
+                                                     gbits, B, delta, 5, index_offset=64 + off, emit_codes=True)
+        for k, a in zip(("x", "m", "v", "c", "meta"), (xs, mo, vo, wc, wm.reshape(-1))):
+            want[k].append(a)
+        c0, mm0, _ = ref.quantize_weight(x[sl], wbits, B, delta, 9)
+        codes0.append(c0); meta0.append(mm0.reshape(-1))
+        c1_, m1_, _ = ref.fused_step_codes(c0, mm0, g[sl], lr, wbits, gbits, B, delta, 5, index_offset=64 + off)
+        cwant.append(c1_); mwant.append(m1_.reshape(-1))
+        off += s
+    xd, gd = torch.from_numpy(x).to(DEV), torch.from_numpy(g).to(DEV)
+    md, vd = torch.from_numpy(m0).to(DEV), torch.from_numpy(v0).to(DEV)
+    wc, wm = segs.alloc_packed(wbits)
+    qb.qsdp_fused_adamw_step_segmented(xd, gd, md, vd, segs, lr, b1, b2, eps, wd, c1, c2, wbits, gbits, delta, 5, 64, 0,
+                                       wc, wm.reshape(-1))
+    assert bits_equal(np_f32(xd), np.concatenate(want["x"]))
+    assert bits_equal(np_f32(md), np.concatenate(want["m"])) and bits_equal(np_f32(vd), np.concatenate(want["v"]))
+    assert np.array_equal(np_u32(wc), np.concatenate(want["c"]))
+    assert np.array_equal(np_u32(wm).reshape(-1), np.concatenate(want["meta"]).view(np.uint32))
+    # code-resident step
+    rc = torch.from_numpy(np.concatenate(codes0).view(np.int32)).to(DEV)
+    rm = torch.from_numpy(np.concatenate(meta0)).to(DEV)
+    qb.qsdp_fused_step_codes_segmented(rc, rm, gd, segs, lr, wbits, gbits, delta, 5, 64)
+    assert np.array_equal(np_u32(rc), np.concatenate(cwant))
+    assert np.array_equal(np_u32(rm), np.concatenate(mwant).view(np.uint32))
