@@ -152,6 +152,32 @@ def _is_rows(t, dtype):
         raise TypeError(f"expected a {dtype} GPU tensor [rows, row length] with contiguous rows")
 
 
+def _need(t, numel, what):
+    if t.numel() < numel:
+        raise ValueError(f"{what} holds {t.numel()} elements, {numel} are needed")
+
+
+def _packed_ok(codes, meta, n, bits, bucket):
+    """The packed buffers are large enough for n elements (the C ABI takes raw pointers and cannot
+    check this itself). Invalid n / bits / bucket are left to the library to report."""
+    cb, mb = codes_bytes(n, bits, bucket), meta_bytes(n, bucket)
+    if cb and mb:
+        if codes is not None:
+            _need(codes, cb // 4, "codes")
+        if meta is not None:
+            _need(meta, mb // 4, "meta")
+
+
+def _rows_ok(codes, meta, n, bits, bucket):
+    """Every row (peer slot) of the 2-D buffers is large enough for n elements."""
+    cb, mb = codes_bytes(n, bits, bucket), meta_bytes(n, bucket)
+    if cb and mb:
+        if codes.shape[1] < cb // 4:
+            raise ValueError(f"code rows hold {codes.shape[1]} words, {cb // 4} are needed")
+        if meta.shape[1] < mb // 4:
+            raise ValueError(f"meta rows hold {meta.shape[1]} floats, {mb // 4} are needed")
+
+
 def alloc_packed(n, bits, bucket, device):
     """Empty (codes uint32-as-int32[...], meta float32[nb, 2]) buffers of the right size."""
     cb, mb = codes_bytes(n, bits, bucket), meta_bytes(n, bucket)
@@ -164,6 +190,7 @@ def alloc_packed(n, bits, bucket, device):
 
 def qsdp_quantize_grad(g, bits, bucket, seed, index_offset, codes, meta):
     _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    _packed_ok(codes, meta, g.numel(), bits, bucket)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_quantize_grad(_ptr(g), g.numel(), bits, bucket, seed, index_offset,
                                         _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad")
@@ -171,6 +198,7 @@ def qsdp_quantize_grad(g, bits, bucket, seed, index_offset, codes, meta):
 
 def qsdp_quantize_grad_ex(g, bits, bucket, seed, index_offset, flags, codes, meta):
     _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    _packed_ok(codes, meta, g.numel(), bits, bucket)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_quantize_grad_ex(_ptr(g), g.numel(), bits, bucket, seed, index_offset, flags,
                                            _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad_ex")
@@ -178,6 +206,7 @@ def qsdp_quantize_grad_ex(g, bits, bucket, seed, index_offset, flags, codes, met
 
 def qsdp_quantize_weight_ex(x, bits, bucket, delta, seed, flags, codes, meta, n_saturated=None):
     _is(x, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    _packed_ok(codes, meta, x.numel(), bits, bucket)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
     with torch.cuda.device(x.device):
@@ -194,6 +223,7 @@ def qsdp_fused_step_ex(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_fused_step_ex(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                         index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
@@ -202,6 +232,7 @@ def qsdp_fused_step_ex(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset
 
 def qsdp_quantize_weight(x, bits, bucket, delta, seed, codes, meta, n_saturated=None):
     _is(x, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    _packed_ok(codes, meta, x.numel(), bits, bucket)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
     with torch.cuda.device(x.device):
@@ -221,6 +252,7 @@ def qsdp_dequantize(codes, meta, n, bits, bucket, out):
     _is(out, out.dtype)
     if out.numel() < n:
         raise ValueError("out is too small")
+    _packed_ok(codes, meta, n, bits, bucket)
     with torch.cuda.device(out.device):
         _check(lib().qsdp_dequantize(_ptr(codes), _ptr(meta), n, bits, bucket, dt, _ptr(out),
                                      _stream(out)), "qsdp_dequantize")
@@ -238,6 +270,7 @@ def qsdp_quantize_levels(v, bits, bucket, levels, codes, meta):
     _is(v, torch.float32); _is(levels, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
     if levels.numel() != (1 << bits):
         raise ValueError("levels must hold 2^bits entries")
+    _packed_ok(codes, meta, v.numel(), bits, bucket)
     with torch.cuda.device(v.device):
         _check(lib().qsdp_quantize_levels(_ptr(v), v.numel(), bits, bucket, _ptr(levels), _ptr(codes), _ptr(meta),
                                           _stream(v)), "qsdp_quantize_levels")
@@ -253,6 +286,7 @@ def qsdp_dequantize_levels(codes, meta, n, bits, bucket, levels, out):
     _is(out, out.dtype)
     if out.numel() < n:
         raise ValueError("out is too small")
+    _packed_ok(codes, meta, n, bits, bucket)
     with torch.cuda.device(out.device):
         _check(lib().qsdp_dequantize_levels(_ptr(codes), _ptr(meta), n, bits, bucket, _ptr(levels), dt, _ptr(out),
                                             _stream(out)), "qsdp_dequantize_levels")
@@ -274,6 +308,7 @@ def qsdp_dequantize_add(codes, meta, npeers, n, bits, bucket, alpha, out):
         raise ValueError("codes and meta must be [npeers, ...]")
     if out.numel() < n:
         raise ValueError("out is too small")
+    _rows_ok(codes, meta, n, bits, bucket)
     with torch.cuda.device(out.device):
         _check(lib().qsdp_dequantize_add(_ptr(codes), codes.stride(0) * 4, _ptr(meta), meta.stride(0) * 4,
                                          npeers, n, bits, bucket, alpha, _ptr(out), _stream(out)),
@@ -291,6 +326,7 @@ def qsdp_fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0,
         _is(wmeta, torch.float32)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_fused_step(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                      index_offset, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
@@ -306,6 +342,7 @@ def qsdp_fused_adamw_step(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_fused_adamw_step(_ptr(x), _ptr(g), _ptr(m), _ptr(v), x.numel(), lr, beta1, beta2, eps,
                                            weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed,
@@ -318,6 +355,7 @@ def qsdp_fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, see
     _is(wcodes, torch.int32); _is(wmeta, torch.float32); _is(g, torch.float32)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
+    _packed_ok(wcodes, wmeta, g.numel(), wbits, bucket)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_fused_step_codes(_ptr(wcodes), _ptr(wmeta), _ptr(g), g.numel(), lr, wbits, gbits,
                                            bucket, delta, seed, index_offset, flags, _ptr(n_saturated),
@@ -341,6 +379,16 @@ class Segments:
         self.n = int(sizes_np.sum())
         self.device = torch.from_numpy(self.host.view(np.int64).copy()).to(device)
 
+    def check_packed(self, codes, meta, bits, rows=False):
+        """codes / meta (or every row of them, for per-peer buffers) cover all buckets of the table."""
+        words, floats = self.total_buckets * self.bucket * bits // 32, 2 * self.total_buckets
+        for t, need, what in ((codes, words, "codes"), (meta, floats, "meta")):
+            if t is None:
+                continue
+            have = t.shape[1] if rows else t.numel()
+            if have < need:
+                raise ValueError(f"{what} holds {have} elements{' per row' if rows else ''}, {need} are needed")
+
     def alloc_packed(self, bits):
         cb = self.total_buckets * self.bucket * bits // 8
         codes = torch.empty(cb // 4, dtype=torch.int32, device=self.device.device)
@@ -352,6 +400,7 @@ def qsdp_quantize_grad_segmented(g, segs, bits, seed, index_offset, codes, meta)
     _is(g, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
     if g.numel() < segs.n:
         raise ValueError("g is smaller than the segments")
+    segs.check_packed(codes, meta, bits)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_quantize_grad_segmented(_ptr(g), _ptr(segs.device), segs.nseg, segs.total_buckets,
                                                   bits, segs.bucket, seed, index_offset, _ptr(codes),
@@ -364,6 +413,7 @@ def qsdp_quantize_weight_segmented(x, segs, bits, delta, seed, codes, meta, n_sa
         raise ValueError("x is smaller than the segments")
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
+    segs.check_packed(codes, meta, bits)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_quantize_weight_segmented(_ptr(x), _ptr(segs.device), segs.nseg,
                                                     segs.total_buckets, bits, segs.bucket, delta, seed,
@@ -382,6 +432,7 @@ def qsdp_fused_step_segmented(x, g, segs, lr, wbits, gbits, delta, seed, index_o
         _is(wmeta, torch.float32)
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
+    segs.check_packed(wcodes, wmeta, wbits)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_fused_step_segmented(_ptr(x), _ptr(g), _ptr(segs.device), segs.nseg,
                                                segs.total_buckets, lr, wbits, gbits, segs.bucket, delta,
@@ -424,6 +475,7 @@ def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out, l
         raise ValueError("codes and meta must be [npeers, ...]")
     if out.numel() < n:
         raise ValueError("out is too small")
+    _rows_ok(codes, meta, min(n, shard) if shard > 0 else n, bits, bucket)
     with torch.cuda.device(out.device):
         if levels is not None:
             _is(levels, torch.float32)
@@ -448,6 +500,8 @@ def qsdp_recv_step(x, gcodes, gmeta, npeers, alpha, lr, wbits, gbits, bucket, de
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    _rows_ok(gcodes, gmeta, x.numel(), gbits, bucket)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_recv_step(_ptr(x), _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta), gmeta.stride(0) * 4,
                                     npeers, x.numel(), alpha, lr, wbits, gbits, bucket, delta, seed, flags,
@@ -467,6 +521,8 @@ def qsdp_recv_adamw_step(x, m, v, gcodes, gmeta, npeers, alpha, lr, beta1, beta2
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    _rows_ok(gcodes, gmeta, x.numel(), gbits, bucket)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_recv_adamw_step(_ptr(x), _ptr(m), _ptr(v), _ptr(gcodes), gcodes.stride(0) * 4, _ptr(gmeta),
                                           gmeta.stride(0) * 4, npeers, x.numel(), alpha, lr, beta1, beta2, eps,
@@ -487,6 +543,8 @@ def qsdp_recv_step_segmented(x, segs, gcodes, gmeta, npeers, alpha, lr, wbits, g
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    segs.check_packed(gcodes, gmeta, gbits, rows=True)
+    segs.check_packed(wcodes, wmeta, wbits)
     with torch.cuda.device(x.device):
         if adamw is None:
             _check(lib().qsdp_recv_step_segmented(_ptr(x), _ptr(segs.device), segs.nseg, segs.total_buckets,
@@ -516,6 +574,7 @@ def qsdp_fused_adamw_step_segmented(x, g, m, v, segs, lr, beta1, beta2, eps, wei
     for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
         if t is not None:
             _is(t, dt)
+    segs.check_packed(wcodes, wmeta, wbits)
     with torch.cuda.device(x.device):
         _check(lib().qsdp_fused_adamw_step_segmented(_ptr(x), _ptr(g), _ptr(m), _ptr(v), _ptr(segs.device), segs.nseg,
                                                      segs.total_buckets, lr, beta1, beta2, eps, weight_decay, bias1,
@@ -531,6 +590,7 @@ def qsdp_fused_step_codes_segmented(wcodes, wmeta, g, segs, lr, wbits, gbits, de
         raise ValueError("g is smaller than the segments")
     if n_saturated is not None:
         _is(n_saturated, torch.int64)
+    segs.check_packed(wcodes, wmeta, wbits)
     with torch.cuda.device(g.device):
         _check(lib().qsdp_fused_step_codes_segmented(_ptr(wcodes), _ptr(wmeta), _ptr(g), _ptr(segs.device), segs.nseg,
                                                      segs.total_buckets, lr, wbits, gbits, segs.bucket, delta, seed,

@@ -97,8 +97,12 @@ def test_gathered_decode_rejects_bad_arguments():
     with pytest.raises(qb.QsdpError):
         qb.qsdp_dequantize_gathered(c, m, 2, 8192, 2048, 8, 1024, out)      # npeers != ceil(n / shard)
     small = torch.zeros((2, 512), dtype=torch.int32, device=DEV)
-    with pytest.raises(qb.QsdpError):
+    with pytest.raises(ValueError):                                         # caught by the binding's size check
         qb.qsdp_dequantize_gathered(small, m, 2, 8192, 4096, 8, 1024, out)  # slots closer than a shard's codes
+    wide = torch.zeros((2, 2048), dtype=torch.int32, device=DEV)
+    with pytest.raises(qb.QsdpError):                                       # rows long enough, stride too small
+        qb.qsdp_dequantize_gathered(wide.view(-1)[:2048 + 1024].as_strided((2, 1024), (512, 1)), m, 2, 8192, 4096, 8,
+                                    1024, out)
     qb.qsdp_dequantize_gathered(c, m, 2, 8192, 4096, 8, 1024, out)          # the valid form of the same call
 
 

@@ -101,8 +101,8 @@ def test_recv_step_rejects_bad_arguments():
     gm = torch.zeros((2, 4), dtype=torch.float32, device=DEV)
     with pytest.raises(qb.QsdpError):
         qb.qsdp_recv_step(x, gc, gm, 2, 0.5, 1e-3, 8, 4, 1024, 0.0, 0, qb.QSDP_FLAG_GRAD_SHIFT)
-    with pytest.raises(qb.QsdpError):
-        qb.qsdp_recv_step(x, gc[:, :128], gm, 2, 0.5, 1e-3, 8, 8, 1024, 0.0, 0)     # slots closer than a slice
+    with pytest.raises(ValueError):                                                  # the binding's size check
+        qb.qsdp_recv_step(x, gc[:, :128], gm, 2, 0.5, 1e-3, 8, 8, 1024, 0.0, 0)     # rows shorter than a slice
     with pytest.raises(qb.QsdpError):
         qb.qsdp_recv_step(x, gc, gm, 2, float("nan"), 1e-3, 8, 4, 1024, 0.0, 0)
     qb.qsdp_recv_step(x, gc, gm, 2, 0.5, 1e-3, 8, 4, 1024, 0.0, 0)

@@ -87,3 +87,20 @@ def test_binding_declares_the_signature_of_every_export():
         nargs = 0 if decl in ("", "void") else decl.count(",") + 1
         assert len(fn.argtypes) == nargs, (name, len(fn.argtypes), nargs)
         assert fn.restype is not C_INT_DEFAULT or name in INT_RETURNING, name
+
+
+def test_binding_rejects_undersized_buffers_before_calling_the_library():
+    """The C ABI takes raw pointers; the binding is where buffer sizes can still be checked. CPU
+    tensors fail the device check first, so the size helpers are exercised directly."""
+    import torch
+    codes = torch.zeros(255, dtype=torch.int32)
+    meta = torch.zeros(2, dtype=torch.float32)
+    with pytest.raises(ValueError):
+        qb._packed_ok(codes, meta, 1024, 8, 1024)          # 256 words needed
+    qb._packed_ok(torch.zeros(256, dtype=torch.int32), meta, 1024, 8, 1024)
+    with pytest.raises(ValueError):
+        qb._packed_ok(torch.zeros(512, dtype=torch.int32), meta, 1025, 8, 1024)   # two buckets: 4 meta floats
+    with pytest.raises(ValueError):
+        qb._rows_ok(torch.zeros((3, 100), dtype=torch.int32), torch.zeros((3, 2)), 1024, 4, 1024)
+    qb._rows_ok(torch.zeros((3, 128), dtype=torch.int32), torch.zeros((3, 2)), 1024, 4, 1024)
+    qb._packed_ok(codes, meta, 1024, 9, 1024)                # invalid bits: left to the library
