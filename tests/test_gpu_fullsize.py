@@ -206,14 +206,22 @@ def test_config5_lattice_quantizer_full_vector(gpt1p3b, delta, wbits):
     check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, wbits, 4, delta, 3)
 
 
-@pytest.mark.parametrize("wbits,gbits,B", [(4, 2, 128), (8, 8, 4096), (6, 3, 512)])
+@pytest.mark.parametrize("wbits,gbits,B", [(4, 2, 128), (8, 8, 4096), (6, 3, 512), (5, 4, 1024), (7, 5, 2048), (1, 1, 256)])
 def test_config5_diagonal_full_vector(gpt1p3b, wbits, gbits, B):
     n, x0, g = gpt1p3b
     ids = sample_bucket_ids(n // B, 200, 7)
     x = x0.clone()
     xb, gb = gather_rows(x, ids, B), gather_rows(g, ids, B)
-    qb.qsdp_fused_step(x, g, 1e-3, wbits, gbits, B, 0.0, 8)
+    wc, wm = qb.alloc_packed(n, wbits, B, DEV)
+    qb.qsdp_fused_step(x, g, 1e-3, wbits, gbits, B, 0.0, 8, 0, wc, wm.reshape(-1))
     check_fused_buckets(xb, gb, gather_rows(x, ids, B), ids, B, 1e-3, wbits, gbits, 0.0, 8)
+    # the packed codes and meta of the sampled buckets (every stored width has its own wave kernel)
+    wpb = B * wbits // 32
+    crow, mrow = u32(gather_rows(wc, ids, wpb)), u32(gather_rows(wm.reshape(-1), ids, 2))
+    for r, j in enumerate(ids[:60]):
+        _, c, m, _ = ref.fused_step(xb[r], gb[r], 1e-3, wbits, gbits, B, 0.0, 8, index_offset=int(j) * B,
+                                    emit_codes=True)
+        assert np.array_equal(crow[r], c) and np.array_equal(mrow[r], u32(m).reshape(-1)), int(j)
 
 
 def test_config5_layerwise_dequantize_to_bf16(gpt1p3b):
