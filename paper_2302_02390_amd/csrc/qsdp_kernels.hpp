@@ -342,6 +342,47 @@ __device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, in
     unstage_codes<G, R, BITS>(stage, fetch_code_tile<G, R, BITS>(tile_in, lane, active_buckets), lane, c);
 }
 
+// The same two phases for a code width known only at run time (the peers' gradient codes of the
+// receive-side modes; wave-uniform `gb` in 1..8), so that those modes are not instantiated per
+// width. The tile (32*R*gb bytes) is staged as it is; lane l then cuts the 4*gb bits of its four
+// consecutive elements of a row out of the two staged words that hold them (the stage has a
+// spare word past the tile for the last lane's second read).
+template <int G, int R>
+__device__ __forceinline__ u4 fetch_code_tile_rt(const u4* tile_in, int lane, int active_buckets, int gb) {
+    const int pieces = 2 * R * gb;            // 16-byte pieces in the tile
+    const int bucket_bytes = G * R * gb / 2;  // 4*G*R codes of gb bits
+    u4 piece = {0u, 0u, 0u, 0u};
+    if (lane < pieces && lane * 16 < active_buckets * bucket_bytes) piece = __builtin_nontemporal_load(tile_in + lane);
+    return piece;
+}
+
+template <int G, int R>
+__device__ __forceinline__ void unstage_codes_rt(uint8_t* stage, u4 piece, int lane, int gb, float (&c)[R][4]) {
+    const int l = lane % G;
+    const int sub = lane / G;
+    if (lane < 2 * R * gb) reinterpret_cast<u4*>(stage)[lane] = piece;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(stage);
+    const uint32_t mask = (1u << gb) - 1u;
+    const uint32_t bit0 = (uint32_t)((sub * G * R + l) * 4 * gb);  // this lane's first code of row 0
+    const uint32_t row_bits = (uint32_t)(G * 4 * gb);             // wave-uniform
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t bit = bit0 + (uint32_t)r * row_bits;
+        const uint32_t w = bit >> 5;
+        // the 32 bits that start at `bit` (the 4*gb <= 32 bits of interest are its low part); a 64-bit
+        // shift measured 4 % faster here than v_alignbit_b32
+        const uint64_t two = (uint64_t)words[w] | ((uint64_t)words[w + 1] << 32);
+        const uint32_t q = (uint32_t)(two >> (bit & 31u));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[r][i] = (float)((q >> (i * gb)) & mask);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Combine per-wave (lo, hi) across the W waves of a workgroup that share a bucket. `slot` is a
 // [2][W] LDS array that no other reduction uses; callers alternate two slots between loop
 // iterations so that a fast wave's next write cannot overtake a slow wave's read.
@@ -361,21 +402,62 @@ __device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float
     }
 }
 
+// ghat-sum of the receive-side modes for the wave's tile: sum = ((d_0 + d_1) + d_2) + ..., d_k the
+// decoded slice of peer k. The tiles of up to kPeerGroup peers are in flight before the first is
+// unpacked. The peers' code width p.gbits is a run-time value here (compile-time unpacking of the
+// common widths next to the generic one, chosen by a wave-uniform branch, measured 15 % slower
+// than the generic path alone: three inlined copies of the loop cost registers).
+template <int G, int R>
+__device__ __forceinline__ void sum_peer_slices(const Params& p, uint8_t* stage, uint64_t tile_slot0,
+                                                uint64_t bucket, int lane, int active_buckets,
+                                                float (&sum)[R][4]) {
+    constexpr int kPeerGroup = 4;
+    const int gb = p.gbits;
+    const u4* gtile = reinterpret_cast<const u4*>(reinterpret_cast<const uint8_t*>(p.peer_codes) +
+                                                  (tile_slot0 >> 3) * (uint64_t)gb);
+    const uint64_t stride_u4 = p.peer_codes_stride_words >> 2;
+    for (int peer0 = 0; peer0 < p.npeers; peer0 += kPeerGroup) {
+        u4 piece[kPeerGroup];
+        float gbase[kPeerGroup], gscale[kPeerGroup];
+#pragma unroll
+        for (int k = 0; k < kPeerGroup; ++k) {
+            // past the last peer: re-read the last one (in bounds), its values are not used
+            const uint64_t peer = peer0 + k < p.npeers ? peer0 + k : p.npeers - 1;
+            piece[k] = fetch_code_tile_rt<G, R>(gtile + peer * stride_u4, lane, active_buckets, gb);
+            const float* pm = p.peer_meta + peer * p.peer_meta_stride_floats;
+            gbase[k] = pm[2 * bucket];
+            gscale[k] = pm[2 * bucket + 1];
+        }
+#pragma unroll
+        for (int k = 0; k < kPeerGroup; ++k) {
+            if (peer0 + k < p.npeers) {  // wave-uniform
+                float c[R][4];
+                unstage_codes_rt<G, R>(stage, piece[k], lane, gb, c);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float d = fmaf(c[r][i], gscale[k], gbase[k]);
+                        sum[r][i] = (peer0 + k == 0) ? d : sum[r][i] + d;
+                    }
+            }
+        }
+    }
+}
+
 // Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
 // be short). BITS is the width of the codes that are stored (0: FUSED / ADAMW without code
 // output). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
-template <int MODE, int G, int R, int BITS, int W, int GB = 0>
+template <int MODE, int G, int R, int BITS, int W>
 __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
-    static_assert(mode_is_recv(MODE) == (GB != 0), "GB = width of the peers' gradient codes (receive-side modes only)");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
     constexpr int B = T * W;
     constexpr int BPW = 64 / G;
     constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
-    constexpr int GBW = GB ? GB : 8;     // only used when GB != 0
     const int lane = threadIdx.x & 63;
     const int sub = lane / G;
     const int l = lane % G;
@@ -388,10 +470,11 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 
     // LDS staging tile of the packed codes (stored, or read from the peers): 32*R*bits bytes per
     // wave, up to 4 waves per block
-    constexpr int kStageBits = (BITS > GB) ? BITS : GB;
-    constexpr int kTileBytes = 32 * R * (kStageBits ? kStageBits : 8);
-    __shared__ u4 stage_all[kStageBits ? 4 * kTileBytes / 16 : 1];
-    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStageBits ? wave_in_block * kTileBytes : 0);
+    // (the peers' tiles are at most 8 bits wide and take one spare 16-byte piece, see unstage_codes_rt)
+    constexpr bool kStaged = BITS != 0 || mode_is_recv(MODE);
+    constexpr int kTileBytes = mode_is_recv(MODE) ? 32 * R * 8 + 16 : 32 * R * SB;
+    __shared__ u4 stage_all[kStaged ? 4 * kTileBytes / 16 : 1];
+    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
     __shared__ float level_table[MODE == MODE_LEVELS ? (1 << SB) : 1];
@@ -512,46 +595,15 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 continue;
             }
         } else if constexpr (mode_is_recv(MODE)) {
-            // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k; the tiles of
-            // up to kPeerGroup peers are in flight before the first is unpacked
+            // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k
             load_rows<G, R>(p.x + e0, l, m, partial, w);
             float mom[R][4], var[R][4];  // MODE_RECV_ADAMW only
             if constexpr (MODE == MODE_RECV_ADAMW) {
                 load_rows<G, R>(p.mom + e0, l, m, partial, mom);
                 load_rows<G, R>(p.var + e0, l, m, partial, var);
             }
-            constexpr int kPeerGroup = 4;
-            const u4* gtile = reinterpret_cast<const u4*>(reinterpret_cast<const uint8_t*>(p.peer_codes) +
-                                                          (tile_slot0 >> 3) * GBW);
-            const uint64_t stride_u4 = p.peer_codes_stride_words >> 2;
             float sum[R][4];
-            for (int peer0 = 0; peer0 < p.npeers; peer0 += kPeerGroup) {
-                u4 piece[kPeerGroup];
-                float gbase[kPeerGroup], gscale[kPeerGroup];
-#pragma unroll
-                for (int k = 0; k < kPeerGroup; ++k) {
-                    // past the last peer: re-read the last one (in bounds), its values are not used
-                    const uint64_t peer = peer0 + k < p.npeers ? peer0 + k : p.npeers - 1;
-                    piece[k] = fetch_code_tile<G, R, GBW>(gtile + peer * stride_u4, lane, active_buckets);
-                    const float* pm = p.peer_meta + peer * p.peer_meta_stride_floats;
-                    gbase[k] = pm[2 * bucket];
-                    gscale[k] = pm[2 * bucket + 1];
-                }
-#pragma unroll
-                for (int k = 0; k < kPeerGroup; ++k) {
-                    if (peer0 + k < p.npeers) {  // wave-uniform
-                        float c[R][4];
-                        unstage_codes<G, R, GBW>(stage, piece[k], lane, c);
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const float d = fmaf(c[r][i], gscale[k], gbase[k]);
-                                sum[r][i] = (peer0 + k == 0) ? d : sum[r][i] + d;
-                            }
-                    }
-                }
-            }
+            sum_peer_slices<G, R>(p, stage, tile_slot0, bucket, lane, active_buckets, sum);
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll

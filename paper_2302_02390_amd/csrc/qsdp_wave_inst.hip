@@ -37,47 +37,6 @@ hipError_t by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
     }
 }
 
-// Receive-side modes: GB = width of the peers' gradient codes, BITS = width of the weight codes
-// stored (or 0)
-template <int MODE, int GB, int BITS>
-hipError_t go_recv(const Params& p, unsigned grid, hipStream_t s) {
-    const unsigned block = QSDP_W == 1 ? 256u : 64u * QSDP_W;
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W, GB>), dim3(grid), dim3(block), 0, s, p,
-                       p.segs);
-    return hipGetLastError();
-}
-
-template <int MODE, int GB>
-hipError_t recv_by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
-    switch (bits) {
-        case 0: return go_recv<MODE, GB, 0>(p, grid, s);
-        case 1: return go_recv<MODE, GB, 1>(p, grid, s);
-        case 2: return go_recv<MODE, GB, 2>(p, grid, s);
-        case 3: return go_recv<MODE, GB, 3>(p, grid, s);
-        case 4: return go_recv<MODE, GB, 4>(p, grid, s);
-        case 5: return go_recv<MODE, GB, 5>(p, grid, s);
-        case 6: return go_recv<MODE, GB, 6>(p, grid, s);
-        case 7: return go_recv<MODE, GB, 7>(p, grid, s);
-        case 8: return go_recv<MODE, GB, 8>(p, grid, s);
-        default: return hipErrorInvalidValue;
-    }
-}
-
-template <int MODE>
-hipError_t recv(int bits, const Params& p, unsigned grid, hipStream_t s) {
-    switch (p.gbits) {
-        case 1: return recv_by_bits<MODE, 1>(bits, p, grid, s);
-        case 2: return recv_by_bits<MODE, 2>(bits, p, grid, s);
-        case 3: return recv_by_bits<MODE, 3>(bits, p, grid, s);
-        case 4: return recv_by_bits<MODE, 4>(bits, p, grid, s);
-        case 5: return recv_by_bits<MODE, 5>(bits, p, grid, s);
-        case 6: return recv_by_bits<MODE, 6>(bits, p, grid, s);
-        case 7: return recv_by_bits<MODE, 7>(bits, p, grid, s);
-        case 8: return recv_by_bits<MODE, 8>(bits, p, grid, s);
-        default: return hipErrorInvalidValue;
-    }
-}
-
 }  // namespace
 
 hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, unsigned grid,
@@ -93,8 +52,12 @@ hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, u
         case MODE_ADAMW:
             if (bits == 0) return go<MODE_ADAMW, 0>(p, grid, s);
             return by_bits<MODE_ADAMW>(bits, p, grid, s);
-        case MODE_RECV: return recv<MODE_RECV>(bits, p, grid, s);
-        case MODE_RECV_ADAMW: return recv<MODE_RECV_ADAMW>(bits, p, grid, s);
+        case MODE_RECV:  // the width of the peers' codes (p.gbits) is a run-time value in these two
+            if (bits == 0) return go<MODE_RECV, 0>(p, grid, s);
+            return by_bits<MODE_RECV>(bits, p, grid, s);
+        case MODE_RECV_ADAMW:
+            if (bits == 0) return go<MODE_RECV_ADAMW, 0>(p, grid, s);
+            return by_bits<MODE_RECV_ADAMW>(bits, p, grid, s);
         default: return hipErrorInvalidValue;
     }
 }
