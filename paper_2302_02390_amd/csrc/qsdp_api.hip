@@ -192,7 +192,7 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
     p.first_bucket = 0;
     int bpw = 1;
     WaveLauncher wl = wave_launcher(p.bucket, &bpw);
-    const bool peer_bits_ok = !mode_is_recv(mode) || (p.gbits != 0 && wave_bits_supported(p.gbits));
+    const bool peer_bits_ok = !mode_reads_peers(mode) || (p.gbits != 0 && wave_bits_supported(p.gbits));
     if (wl != nullptr && wave_bits_supported(stored_bits) && peer_bits_ok) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
@@ -439,6 +439,23 @@ int qsdp_dequantize_add(const uint32_t* codes, uint64_t codes_stride_bytes, cons
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (codes_stride_bytes & 3u) ||
         (meta_stride_bytes & 3u))
         return QSDP_EALIGN;
+    int unused_bpw = 0;
+    if (wave_launcher(bucket, &unused_bpw) != nullptr && (codes_stride_bytes & 15u) == 0) {
+        // a bucket size the wave kernels cover: 16-byte code fetches staged through LDS instead of
+        // per-lane word loads
+        Params p = {};
+        set_common(p, n, bucket, 0, 0, 0.0f);
+        p.x = out;
+        p.peer_codes = codes;
+        p.peer_meta = meta;
+        p.peer_codes_stride_words = codes_stride_bytes / 4;
+        p.peer_meta_stride_floats = meta_stride_bytes / 4;
+        p.npeers = npeers;
+        p.alpha = alpha;
+        p.gbits = bits;
+        p.wbits = bits;
+        return run(MODE_SUM, p, 0, static_cast<hipStream_t>(stream));
+    }
     DequantAddParams q = {};
     unsigned grid = 0;
     q.d = decoder_params(codes, meta, n, bits, bucket, false, out, &grid);

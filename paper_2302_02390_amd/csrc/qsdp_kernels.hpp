@@ -34,10 +34,12 @@ namespace qsdp {
 // MODE_RECV: the shard owner's step with P workers: the gradient is the scaled sum of the
 // decoded slices of all peers (no Q^g here), then the SGD step and Q^w as in MODE_FUSED.
 // MODE_RECV_ADAMW: the same with the AdamW update of MODE_ADAMW in place of the SGD step.
+// MODE_SUM: only the first half of MODE_RECV: out = alpha * (sum of the decoded peer slices).
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
-            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7 };
+            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7, MODE_SUM = 8 };
 
 constexpr bool mode_is_recv(int mode) { return mode == MODE_RECV || mode == MODE_RECV_ADAMW; }
+constexpr bool mode_reads_peers(int mode) { return mode_is_recv(mode) || mode == MODE_SUM; }
 constexpr bool mode_is_adamw(int mode) { return mode == MODE_ADAMW || mode == MODE_RECV_ADAMW; }
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
@@ -471,8 +473,8 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     // LDS staging tile of the packed codes (stored, or read from the peers): 32*R*bits bytes per
     // wave, up to 4 waves per block
     // (the peers' tiles are at most 8 bits wide and take one spare 16-byte piece, see unstage_codes_rt)
-    constexpr bool kStaged = BITS != 0 || mode_is_recv(MODE);
-    constexpr int kTileBytes = mode_is_recv(MODE) ? 32 * R * 8 + 16 : 32 * R * SB;
+    constexpr bool kStaged = BITS != 0 || mode_reads_peers(MODE);
+    constexpr int kTileBytes = mode_reads_peers(MODE) ? 32 * R * 8 + 16 : 32 * R * SB;
     __shared__ u4 stage_all[kStaged ? 4 * kTileBytes / 16 : 1];
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
@@ -491,7 +493,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
     constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE);
     const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
-    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
+    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS && MODE != MODE_SUM);
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
@@ -594,6 +596,15 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 }
                 continue;
             }
+        } else if constexpr (MODE == MODE_SUM) {
+            // out (passed in p.x) = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k
+            sum_peer_slices<G, R>(p, stage, tile_slot0, bucket, lane, active_buckets, w);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[r][i] = p.alpha * w[r][i];
+            if (active) store_rows<G, R>(p.x + e0, l, m, partial, w);
+            continue;
         } else if constexpr (mode_is_recv(MODE)) {
             // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k
             load_rows<G, R>(p.x + e0, l, m, partial, w);
