@@ -635,6 +635,63 @@ int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, c
     return QSDP_REF_OK;
 }
 
+/* Unbiased rounding onto non-uniform levels: the coin-flip quantizer of the appendix between the
+ * two levels that enclose z. With i the largest index such that q_i <= z and q_{i+1} the next
+ * level (so q_i <= z < q_{i+1}): code = i + [u < (z - q_i) / (q_{i+1} - q_i)]. z below the first
+ * level gives code 0, z at or above the last gives K-1: no pair of levels encloses those, so the
+ * quantizer is unbiased exactly on [q_0, q_{K-1}]. */
+static int stochastic_level(float z, float u, const float* levels, int K) {
+    if (!(z >= levels[0])) return 0;
+    int i = 0;
+    for (int k = 1; k < K; ++k)
+        if (levels[k] <= z) i = k;
+    if (i == K - 1) return K - 1;
+    float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */
+    float p = (z - levels[i]) / gap;
+    return i + (u < p ? 1 : 0);
+}
+
+int qsdp_ref_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                                        uint64_t seed, uint64_t index_offset, uint32_t* codes, float* meta) {
+    if (!v || !levels || !codes || !meta || !args_ok(n, bits, bucket) || !levels_ok(levels, bits))
+        return QSDP_REF_EINVAL;
+    if (index_offset % 8u != 0u) return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int wpb = bucket * bits / 32;
+    int K = 1 << bits;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float z[MAX_BUCKET];
+        uint8_t code[MAX_BUCKET];
+        normalize_bucket(v + s, m, z, &meta[2 * j], &meta[2 * j + 1]);
+        for (int i = 0; i < m; ++i) {
+            float u = qsdp_ref_grad_uniform(seed, index_offset + s + (uint64_t)i);
+            code[i] = (uint8_t)stochastic_level(z[i], u, levels, K);
+        }
+        pack_bucket(code, m, bits, bucket, codes + (uint64_t)j * (uint64_t)wpb);
+    }
+    return QSDP_REF_OK;
+}
+
+/* The same with the uniform of every element given by the caller (for exhaustive tests). */
+int qsdp_ref_quantize_levels_u(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                               const float* u, uint8_t* codes, float* meta) {
+    if (!v || !levels || !u || !codes || !meta || !args_ok(n, bits, bucket) || !levels_ok(levels, bits))
+        return QSDP_REF_EINVAL;
+    int64_t nb = (int64_t)num_buckets(n, bucket);
+    int K = 1 << bits;
+    for (int64_t j = 0; j < nb; ++j) {
+        uint64_t s = (uint64_t)j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, (uint64_t)j);
+        float z[MAX_BUCKET];
+        normalize_bucket(v + s, m, z, &meta[2 * j], &meta[2 * j + 1]);
+        for (int i = 0; i < m; ++i) codes[s + (uint64_t)i] = (uint8_t)stochastic_level(z[i], u[s + (uint64_t)i], levels, K);
+    }
+    return QSDP_REF_OK;
+}
+
 int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                                int bucket, const float* levels, int out_dtype, void* out) {
     if (!codes || !meta || !levels || !out || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;

@@ -157,6 +157,12 @@ int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, c
                              uint32_t* codes, float* meta);
 int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                                int bucket, const float* levels, int out_dtype, void* out);
+/* Unbiased (coin-flip) rounding onto the two levels that enclose the normalised value; uniforms
+ * from Philox stream 0 as for the gradient quantizer. codes of the _u form are unpacked (u8). */
+int qsdp_ref_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                                        uint64_t seed, uint64_t index_offset, uint32_t* codes, float* meta);
+int qsdp_ref_quantize_levels_u(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                               const float* u, uint8_t* codes, float* meta);
 int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
                         uint64_t max_batches, float* levels /* in: start, out: fitted */);
 

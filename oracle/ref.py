@@ -64,6 +64,8 @@ def lib():
         L.qsdp_ref_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp]
         L.qsdp_ref_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp]
         L.qsdp_ref_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp]
+        L.qsdp_ref_quantize_levels_stochastic.argtypes = [vp, u64, i32, i32, vp, u64, u64, vp, vp]
+        L.qsdp_ref_quantize_levels_u.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp]
         L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp]
         L.qsdp_ref_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64,
                                           vp, vp, vp]
@@ -302,6 +304,29 @@ def quantize_levels(v, bits, bucket, levels):
     meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
     _check(lib().qsdp_ref_quantize_levels(_p(v), n, bits, bucket, _p(levels), _p(codes), _p(meta)),
            "quantize_levels")
+    return codes, meta
+
+
+def quantize_levels_stochastic(v, bits, bucket, levels, seed, index_offset=0):
+    """Unbiased rounding onto the enclosing levels. Returns (packed codes, meta f32[nb,2] = {lo, hi-lo})."""
+    v = _f32(v); levels = _f32(levels)
+    n = v.size
+    codes = np.zeros(codes_bytes(n, bits, bucket) // 4, dtype=np.uint32)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    _check(lib().qsdp_ref_quantize_levels_stochastic(_p(v), n, bits, bucket, _p(levels), int(seed),
+                                                     int(index_offset), _p(codes), _p(meta)),
+           "quantize_levels_stochastic")
+    return codes, meta
+
+
+def quantize_levels_u(v, bits, bucket, levels, u):
+    """The same with explicit uniforms. Returns (codes u8[n], meta)."""
+    v = _f32(v); levels = _f32(levels); u = _f32(u)
+    n = v.size
+    codes = np.zeros(n, dtype=np.uint8)
+    meta = np.zeros((_nb(n, bucket), 2), dtype=np.float32)
+    _check(lib().qsdp_ref_quantize_levels_u(_p(v), n, bits, bucket, _p(levels), _p(u), _p(codes), _p(meta)),
+           "quantize_levels_u")
     return codes, meta
 
 

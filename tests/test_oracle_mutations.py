@@ -69,6 +69,12 @@ MUTANTS = [
      ["test_oracle_keep_master.py"]),
     ("keep_master_recv_copies_old_weights", "memcpy(x, ghat, (size_t)n * sizeof(float)); /* x <- y: the partition stays unquantized */",
      "(void)0;", ["test_oracle_keep_master.py"]),
+    ("level_coin_flip_inverted", "return i + (u < p ? 1 : 0);", "return i + (u < p ? 0 : 1);",
+     ["test_oracle_levels_stochastic.py"]),
+    ("level_coin_flip_uses_distance_to_upper", "float p = (z - levels[i]) / gap;", "float p = (levels[i + 1] - z) / gap;",
+     ["test_oracle_levels_stochastic.py"]),
+    ("level_upper_neighbour_skipped", "float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */",
+     "float gap = levels[K - 1] - levels[i];", ["test_oracle_levels_stochastic.py"]),
     ("recv_step_sign_flipped", "ghat[i] = fmaf(-lr, ghat[i], x[i]); /* y, in place */",
      "ghat[i] = fmaf(lr, ghat[i], x[i]); /* y, in place */", ["test_oracle_recv_step.py"]),
     ("recv_step_average_dropped", "npeers, n, gbits,\n                                     bucket, alpha, ghat);",
