@@ -282,6 +282,14 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
  *   qsdp_levels_uniform     host only: fills a HOST array with k/(2^bits-1), the usual start.
  *   qsdp_quantize_levels    code = index of the NEAREST level to z (ties and equal levels: the
  *                           lowest index); deterministic. Wire format as for the other codes.
+ *   qsdp_quantize_levels_stochastic  the unbiased counterpart for gradients (the coin-flip
+ *                           definition of the appendix applied between the two levels that
+ *                           enclose z): with i the largest index such that levels[i] <= z,
+ *                           code = i + [u < (z - levels[i]) / (levels[i+1] - levels[i])], u the
+ *                           rounding uniform of qsdp_quantize_grad (same seed / index_offset
+ *                           rules); z below the first level gives 0, at or above the last
+ *                           2^bits-1, so the mean of the decoded value equals the input exactly
+ *                           when the table starts at 0 and ends at 1.
  *   qsdp_dequantize_levels  out = fma(levels[code], hi-lo, lo), fp32 or bf16.
  *   qsdp_fit_levels         the level optimisation of Algorithm 1 in batched form, batch = one
  *                           bucket, visited in order (the first max_batches only, if > 0): the
@@ -298,6 +306,9 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
 int qsdp_levels_uniform(int bits, float* levels);
 int qsdp_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const float* levels,
                          uint32_t* codes, float* meta, void* stream);
+int qsdp_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bucket,
+                                    const float* levels, uint64_t seed, uint64_t index_offset,
+                                    uint32_t* codes, float* meta, void* stream);
 int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                            int bucket, const float* levels, qsdp_dtype out_dtype,
                            void* out, void* stream);

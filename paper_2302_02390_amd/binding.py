@@ -24,7 +24,8 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
            "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
            "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
-           "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented")
+           "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
+           "qsdp_quantize_levels_stochastic")
 
 _lib = None
 
@@ -98,6 +99,8 @@ def lib():
         L.qsdp_fused_step_codes_segmented.argtypes = [vp, vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64, u64,
                                                       C.c_uint32, vp, vp]
         L.qsdp_fused_step_codes_segmented.restype = i32
+        L.qsdp_quantize_levels_stochastic.argtypes = [vp, u64, i32, i32, vp, u64, u64, vp, vp, vp]
+        L.qsdp_quantize_levels_stochastic.restype = i32
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
@@ -274,6 +277,17 @@ def qsdp_quantize_levels(v, bits, bucket, levels, codes, meta):
     with torch.cuda.device(v.device):
         _check(lib().qsdp_quantize_levels(_ptr(v), v.numel(), bits, bucket, _ptr(levels), _ptr(codes), _ptr(meta),
                                           _stream(v)), "qsdp_quantize_levels")
+
+
+def qsdp_quantize_levels_stochastic(v, bits, bucket, levels, seed, index_offset, codes, meta):
+    _is(v, torch.float32); _is(levels, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if levels.numel() != (1 << bits):
+        raise ValueError("levels must hold 2^bits entries")
+    _packed_ok(codes, meta, v.numel(), bits, bucket)
+    with torch.cuda.device(v.device):
+        _check(lib().qsdp_quantize_levels_stochastic(_ptr(v), v.numel(), bits, bucket, _ptr(levels), seed,
+                                                     index_offset, _ptr(codes), _ptr(meta), _stream(v)),
+               "qsdp_quantize_levels_stochastic")
 
 
 def qsdp_dequantize_levels(codes, meta, n, bits, bucket, levels, out):

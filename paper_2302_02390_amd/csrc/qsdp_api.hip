@@ -395,6 +395,24 @@ int qsdp_quantize_levels(const float* v, uint64_t n, int bits, int bucket, const
     return run(MODE_LEVELS, p, bits, static_cast<hipStream_t>(stream));
 }
 
+int qsdp_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bucket, const float* levels,
+                                    uint64_t seed, uint64_t index_offset, uint32_t* codes, float* meta,
+                                    void* stream) {
+    if (!v || !levels || !codes || !meta || !shape_ok(n, bits, bucket) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(v) || !aligned16(codes) || !aligned16(meta) || (reinterpret_cast<uintptr_t>(levels) & 3u))
+        return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, n, bucket, seed, index_offset, 0.0f);
+    p.flags = FLAG_LEVELS_STOCHASTIC;
+    p.xin = v;
+    p.levels = levels;
+    p.codes = codes;
+    p.meta = meta;
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(MODE_LEVELS, p, bits, static_cast<hipStream_t>(stream));
+}
+
 int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
                            const float* levels, qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !levels || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;

@@ -214,6 +214,25 @@ __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     return c;
 }
 
+// Unbiased rounding of z onto the two of the K = 2^BITS ascending levels `lv` (in LDS) that
+// enclose it: with i the largest index such that lv[i] <= z, code = i + [h * 2^-16 < p],
+// p = (z - lv[i]) / (lv[i+1] - lv[i]); z below the first level gives 0, at or above the last K-1.
+// h is the 16-bit rounding uniform as a float (exact), so h < p * 2^16 is the same comparison.
+template <int BITS>
+__device__ __forceinline__ int stochastic_level(float z, float h, const float* lv) {
+    constexpr int K = 1 << BITS;
+    int cnt = 0;  // number of levels <= z among the first K-1 (branch-free search), then the last one
+#pragma unroll
+    for (int step = K / 2; step >= 1; step >>= 1)
+        if (lv[cnt + step - 1] <= z) cnt += step;
+    if (cnt == K - 1 && lv[K - 1] <= z) cnt = K;
+    if (cnt == 0) return 0;
+    if (cnt == K) return K - 1;
+    const int i = cnt - 1;
+    const float p = (z - lv[i]) / (lv[i + 1] - lv[i]);
+    return i + (h < p * 65536.0f ? 1 : 0);
+}
+
 // ---------------------------------------------------------------------------------------
 // Packing: 4 consecutive codes of a lane, 8 consecutive codes (a chunk) = BITS bytes
 // ---------------------------------------------------------------------------------------

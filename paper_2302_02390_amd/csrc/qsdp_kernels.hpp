@@ -102,7 +102,9 @@ __device__ __forceinline__ float step_value(const Params& p, float x, float ghat
 
 // Quantizer variants (same values as the QSDP_FLAG_* of the C header)
 // FLAG_KEEP_MASTER (step modes): x receives the updated value itself, the codes still Q^w of it
-enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u, FLAG_KEEP_MASTER = 8u };
+// FLAG_LEVELS_STOCHASTIC (internal, MODE_LEVELS): coin-flip rounding between the enclosing levels
+enum : uint32_t { FLAG_GRAD_SHIFT = 1u, FLAG_NO_SHIFT = 2u, FLAG_SYMMETRIC = 4u, FLAG_KEEP_MASTER = 8u,
+                  FLAG_LEVELS_STOCHASTIC = 0x100u };
 
 struct Shifts {
     float xi;    // weight shift
@@ -641,13 +643,27 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);  // scale = hi - lo, inv = 1/(hi - lo)
             base = grid.lo;
             scale = grid.scale;
+            if (p.flags & FLAG_LEVELS_STOCHASTIC) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+                for (int cp = 0; cp < R / 2; ++cp) {
+                    float h[8];
+                    grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float z = (w[r][i] - grid.lo) * grid.inv;
-                    w[r][i] = (float)nearest_level<SB>(z, level_table);
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = 2 * cp + (i >> 2);
+                        const float z = (w[r][i & 3] - grid.lo) * grid.inv;
+                        w[r][i & 3] = (float)stochastic_level<SB>(z, h[i], level_table);
+                    }
                 }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float z = (w[r][i] - grid.lo) * grid.inv;
+                        w[r][i] = (float)nearest_level<SB>(z, level_table);
+                    }
+            }
         } else if (lattice) {
             float lo, unused_hi;
             rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
@@ -866,8 +882,33 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 base = grid.lo;
                 scale = grid.scale;
                 const int K = 1 << p.wbits;
+                const bool stochastic = (p.flags & FLAG_LEVELS_STOCHASTIC) != 0;
                 for (int i = tid; i < m; i += 256) {
                     const float z = (val[i] - grid.lo) * grid.inv;
+                    if (stochastic) {
+                        // plain scan for the largest index whose level is <= z, then the coin flip
+                        const uint64_t e = (p.block0 << 3) + e0 + (uint64_t)i;
+                        uint32_t w[4];
+                        const uint64_t blk = e >> 3;
+                        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, p.key0, p.key1, w);
+                        const uint32_t j = (uint32_t)(e & 7u);
+                        const uint32_t word = w[j >> 1];
+                        const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
+                        int c = 0;
+                        if (z >= p.levels[0]) {
+                            int lower = 0;
+                            for (int k = 1; k < K; ++k)
+                                if (p.levels[k] <= z) lower = k;
+                            c = lower;
+                            if (lower < K - 1) {
+                                const float q0 = p.levels[lower];
+                                const float prob = (z - q0) / (p.levels[lower + 1] - q0);
+                                c = lower + (h < prob * 65536.0f ? 1 : 0);
+                            }
+                        }
+                        code[i] = (uint8_t)c;
+                        continue;
+                    }
                     // plain scan: nearest level, first index on ties (the table is in global memory)
                     int best = 0;
                     float best_d = fabsf(z - p.levels[0]);

@@ -78,3 +78,43 @@ def test_learned_levels_lower_the_error_on_a_gpt_block():
             errs.append(float(torch.linalg.vector_norm(out - data) / torch.linalg.vector_norm(data)))
         assert errs[1] < errs[0]
         assert torch.all(fit[1:] >= fit[:-1])
+
+
+@pytest.mark.parametrize("bucket", [32, 96, 128, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_quantize_levels_stochastic(bits, bucket):
+    """Unbiased rounding onto the enclosing levels: codes and meta bit-exact, for a uniform table, an
+    irregular one with a duplicate pair, and one that does not reach 0 and 1 (values outside clamp)."""
+    n = 5 * bucket + bucket // 2 + 3
+    _, g = synth(n, 950 + bits)
+    inner = _levels(bits, 40 + bits).copy()
+    inner[0], inner[-1] = 0.2, 0.9
+    inner = np.sort(inner)
+    for lv in (ref.levels_uniform(bits), _levels(bits, bits), inner):
+        lvd = torch.from_numpy(lv).to(DEV)
+        codes, meta = qb.alloc_packed(n, bits, bucket, DEV)
+        qb.qsdp_quantize_levels_stochastic(torch.from_numpy(g).to(DEV), bits, bucket, lvd, 31, 64, codes,
+                                           meta.reshape(-1))
+        wc, wm = ref.quantize_levels_stochastic(g, bits, bucket, lv, 31, index_offset=64)
+        assert np.array_equal(np_u32(meta), wm.view(np.uint32).reshape(-1))
+        assert np.array_equal(np_u32(codes), wc)
+
+
+def test_quantize_levels_stochastic_is_unbiased_on_the_gpu():
+    """Mean over 400 seeds of the decoded value (table from 0 to 1) against the input."""
+    bits, B, n = 3, 1024, 8 * 1024
+    _, g = synth(n, 77)
+    lv = _levels(bits, 5)
+    lvd, gd = torch.from_numpy(lv).to(DEV), torch.from_numpy(g).to(DEV)
+    codes, meta = qb.alloc_packed(n, bits, B, DEV)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    acc = torch.zeros(n, dtype=torch.float64, device=DEV)
+    S = 400
+    for seed in range(S):
+        qb.qsdp_quantize_levels_stochastic(gd, bits, B, lvd, seed, 0, codes, meta.reshape(-1))
+        qb.qsdp_dequantize_levels(codes, meta.reshape(-1), n, bits, B, lvd, out)
+        acc += out.double()
+    rng_b = meta[:, 1].double().repeat_interleave(B)
+    gap = float(np.max(np.diff(lv.astype(np.float64))))
+    err = (acc / S - gd.double()).abs()
+    assert bool(torch.all(err <= 5 * 0.5 * gap * rng_b / np.sqrt(S) + 1e-9))
