@@ -404,6 +404,13 @@ int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float*
                                     uint64_t total_buckets, float lr, int wbits, int gbits,
                                     int bucket, float delta, uint64_t seed, uint64_t index_offset,
                                     uint32_t flags, uint64_t* n_saturated, void* stream);
+/* The level fit of many tensors side by side (the paper fits every large layer on its own,
+ * Appendix C): tensor t of the table is fitted exactly as qsdp_fit_levels would fit it alone
+ * (at most max_batches of its buckets, if > 0), starting from and overwriting
+ * levels[t * 2^bits .. (t+1) * 2^bits); one workgroup per tensor, all in one launch. */
+int qsdp_fit_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg, int bits,
+                              int bucket, float lr, uint64_t max_batches, float* levels,
+                              void* stream);
 int qsdp_recv_step_segmented(float* x, const qsdp_segment* table, uint32_t nseg,
                              uint64_t total_buckets, const uint32_t* gcodes,
                              uint64_t gcodes_stride_bytes, const float* gmeta,

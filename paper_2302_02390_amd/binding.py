@@ -25,7 +25,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
            "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
            "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
-           "qsdp_quantize_levels_stochastic")
+           "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented")
 
 _lib = None
 
@@ -101,6 +101,8 @@ def lib():
         L.qsdp_fused_step_codes_segmented.restype = i32
         L.qsdp_quantize_levels_stochastic.argtypes = [vp, u64, i32, i32, vp, u64, u64, vp, vp, vp]
         L.qsdp_quantize_levels_stochastic.restype = i32
+        L.qsdp_fit_levels_segmented.argtypes = [vp, vp, C.c_uint32, i32, i32, f32, u64, vp, vp]
+        L.qsdp_fit_levels_segmented.restype = i32
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
@@ -610,3 +612,15 @@ def qsdp_fused_step_codes_segmented(wcodes, wmeta, g, segs, lr, wbits, gbits, de
                                                      segs.total_buckets, lr, wbits, gbits, segs.bucket, delta, seed,
                                                      index_offset, flags, _ptr(n_saturated), _stream(g)),
                "qsdp_fused_step_codes_segmented")
+
+
+def qsdp_fit_levels_segmented(v, segs, bits, lr, levels, max_batches=0):
+    """levels float32[nseg, 2^bits]: row t is the start table of tensor t and receives its fitted levels."""
+    _is(v, torch.float32); _is(levels, torch.float32)
+    if v.numel() < segs.n:
+        raise ValueError("v is smaller than the segments")
+    if levels.numel() != segs.nseg * (1 << bits):
+        raise ValueError("levels must hold nseg * 2^bits entries")
+    with torch.cuda.device(v.device):
+        _check(lib().qsdp_fit_levels_segmented(_ptr(v), _ptr(segs.device), segs.nseg, bits, segs.bucket, lr,
+                                               max_batches, _ptr(levels), _stream(v)), "qsdp_fit_levels_segmented")

@@ -109,16 +109,16 @@ hipError_t launch_dequant_seg(int bits, bool bf16, const DequantSegParams& q, un
     }
 }
 
-hipError_t launch_fit_levels(const FitParams& p, hipStream_t s) {
+hipError_t launch_fit_levels(const FitParams& p, unsigned grid, hipStream_t s) {
     switch (p.bits) {
-        case 1: hipLaunchKernelGGL(fit_levels_kernel<1>, dim3(1), dim3(256), 0, s, p); break;
-        case 2: hipLaunchKernelGGL(fit_levels_kernel<2>, dim3(1), dim3(256), 0, s, p); break;
-        case 3: hipLaunchKernelGGL(fit_levels_kernel<3>, dim3(1), dim3(256), 0, s, p); break;
-        case 4: hipLaunchKernelGGL(fit_levels_kernel<4>, dim3(1), dim3(256), 0, s, p); break;
-        case 5: hipLaunchKernelGGL(fit_levels_kernel<5>, dim3(1), dim3(256), 0, s, p); break;
-        case 6: hipLaunchKernelGGL(fit_levels_kernel<6>, dim3(1), dim3(256), 0, s, p); break;
-        case 7: hipLaunchKernelGGL(fit_levels_kernel<7>, dim3(1), dim3(256), 0, s, p); break;
-        case 8: hipLaunchKernelGGL(fit_levels_kernel<8>, dim3(1), dim3(256), 0, s, p); break;
+        case 1: hipLaunchKernelGGL(fit_levels_kernel<1>, dim3(grid), dim3(256), 0, s, p); break;
+        case 2: hipLaunchKernelGGL(fit_levels_kernel<2>, dim3(grid), dim3(256), 0, s, p); break;
+        case 3: hipLaunchKernelGGL(fit_levels_kernel<3>, dim3(grid), dim3(256), 0, s, p); break;
+        case 4: hipLaunchKernelGGL(fit_levels_kernel<4>, dim3(grid), dim3(256), 0, s, p); break;
+        case 5: hipLaunchKernelGGL(fit_levels_kernel<5>, dim3(grid), dim3(256), 0, s, p); break;
+        case 6: hipLaunchKernelGGL(fit_levels_kernel<6>, dim3(grid), dim3(256), 0, s, p); break;
+        case 7: hipLaunchKernelGGL(fit_levels_kernel<7>, dim3(grid), dim3(256), 0, s, p); break;
+        case 8: hipLaunchKernelGGL(fit_levels_kernel<8>, dim3(grid), dim3(256), 0, s, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -441,7 +441,25 @@ int qsdp_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr, 
     p.bucket = bucket;
     p.bits = bits;
     p.lr = lr;
-    if (launch_fit_levels(p, static_cast<hipStream_t>(stream)) != hipSuccess) return QSDP_ELAUNCH;
+    if (launch_fit_levels(p, 1u, static_cast<hipStream_t>(stream)) != hipSuccess) return QSDP_ELAUNCH;
+    return QSDP_OK;
+}
+
+int qsdp_fit_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg, int bits, int bucket,
+                              float lr, uint64_t max_batches, float* levels, void* stream) {
+    if (!v || !table || nseg == 0 || !levels || !shape_ok(1, bits, bucket) || !(lr > 0.0f && lr < 1.0f))
+        return QSDP_EINVAL;
+    if (!aligned16(v) || (reinterpret_cast<uintptr_t>(levels) & 3u) || (reinterpret_cast<uintptr_t>(table) & 7u))
+        return QSDP_EALIGN;
+    FitParams p = {};
+    p.v = v;
+    p.levels = levels;
+    p.num_batches = max_batches;
+    p.segs = reinterpret_cast<const Segment*>(table);
+    p.bucket = bucket;
+    p.bits = bits;
+    p.lr = lr;
+    if (launch_fit_levels(p, nseg, static_cast<hipStream_t>(stream)) != hipSuccess) return QSDP_ELAUNCH;
     return QSDP_OK;
 }
 

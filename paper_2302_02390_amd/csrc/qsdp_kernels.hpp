@@ -1305,9 +1305,10 @@ __global__ void __launch_bounds__(256) dequant_add_kernel(const DequantAddParams
 // ---------------------------------------------------------------------------------------
 struct FitParams {
     const float* v;
-    float* levels;  // in/out, 2^bits floats
+    float* levels;  // in/out, 2^bits floats (one table per tensor when segs is given)
     uint64_t n;
-    uint64_t num_batches;
+    uint64_t num_batches;  // with segs: the cap on the batches of every tensor (0 = none)
+    const Segment* segs;   // multi-tensor fit: workgroup t fits tensor t on its own table
     int bucket;
     int bits;
     float lr;
@@ -1329,7 +1330,19 @@ __global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
     const int copy = kCopies == 1 ? 0 : (tid >> 6);
     const int B = p.bucket;
     const bool prefetch = B <= 256 * kPre;
-    for (int k = tid; k < K; k += 256) lv[k] = p.levels[k];
+    // this workgroup's tensor: the whole vector, or tensor blockIdx.x of a multi-tensor fit
+    const float* v = p.v;
+    float* levels = p.levels;
+    uint64_t n = p.n, num_batches = p.num_batches;
+    if (p.segs != nullptr) {
+        const Segment seg = p.segs[blockIdx.x];
+        v += seg.offset;
+        levels += (uint64_t)blockIdx.x * K;
+        n = seg.n;
+        num_batches = (n + (uint64_t)B - 1) / (uint64_t)B;
+        if (p.num_batches > 0 && p.num_batches < num_batches) num_batches = p.num_batches;
+    }
+    for (int k = tid; k < K; k += 256) lv[k] = levels[k];
     const double one_minus = 1.0 - (double)p.lr;
     if (tid == 0) {
         // (1 - lr)^c by repeated multiplication, the order in which c single steps compound
@@ -1344,17 +1357,17 @@ __global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
     float nxt[kPre];
     auto fetch = [&](uint64_t j) {
         const uint64_t e0 = j * (uint64_t)B;
-        const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
+        const int m = (int)((n - e0 < (uint64_t)B) ? (n - e0) : (uint64_t)B);
 #pragma unroll
         for (int q = 0; q < kPre; ++q) {
             const int i = tid + 256 * q;
-            nxt[q] = i < m ? p.v[e0 + i] : 0.0f;
+            nxt[q] = i < m ? v[e0 + i] : 0.0f;
         }
     };
-    if (prefetch && p.num_batches > 0) fetch(0);
-    for (uint64_t j = 0; j < p.num_batches; ++j) {
+    if (prefetch && num_batches > 0) fetch(0);
+    for (uint64_t j = 0; j < num_batches; ++j) {
         const uint64_t e0 = j * (uint64_t)B;
-        const int m = (int)((p.n - e0 < (uint64_t)B) ? (p.n - e0) : (uint64_t)B);
+        const int m = (int)((n - e0 < (uint64_t)B) ? (n - e0) : (uint64_t)B);
         __syncthreads();  // previous batch's level update and LDS reads are complete (and keep_tab is written)
         float lo = __builtin_inff(), hi = -__builtin_inff();
         if (prefetch) {
@@ -1367,10 +1380,10 @@ __global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
                     hi = fmaxf(hi, nxt[q]);
                 }
             }
-            if (j + 1 < p.num_batches) fetch(j + 1);  // in flight while this batch is processed
+            if (j + 1 < num_batches) fetch(j + 1);  // in flight while this batch is processed
         } else {
             for (int i = tid; i < m; i += 256) {
-                const float x = p.v[e0 + i];
+                const float x = v[e0 + i];
                 val[i] = x;
                 lo = fminf(lo, x);
                 hi = fmaxf(hi, x);
@@ -1408,7 +1421,7 @@ __global__ void __launch_bounds__(256) fit_levels_kernel(const FitParams p) {
         }
     }
     __syncthreads();
-    for (int k = tid; k < K; k += 256) p.levels[k] = lv[k];
+    for (int k = tid; k < K; k += 256) levels[k] = lv[k];
 }
 
 }  // namespace qsdp

@@ -25,7 +25,7 @@ QSDP_DECLARE_WAVE(4096)
 
 hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s);
 hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, dim3 grid, hipStream_t s);
-hipError_t launch_fit_levels(const FitParams& p, hipStream_t s);
+hipError_t launch_fit_levels(const FitParams& p, unsigned grid, hipStream_t s);
 hipError_t launch_dequant_add(int bits, const DequantAddParams& p, unsigned grid, hipStream_t s);
 
 }  // namespace qsdp

@@ -118,3 +118,24 @@ def test_quantize_levels_stochastic_is_unbiased_on_the_gpu():
     gap = float(np.max(np.diff(lv.astype(np.float64))))
     err = (acc / S - gd.double()).abs()
     assert bool(torch.all(err <= 5 * 0.5 * gap * rng_b / np.sqrt(S) + 1e-9))
+
+
+@pytest.mark.parametrize("bits,bucket,max_batches", [(3, 1024, 0), (5, 128, 7), (2, 96, 0)])
+def test_fit_levels_segmented_equals_per_tensor_fits(bits, bucket, max_batches):
+    """Many tensors fitted side by side in one launch: every tensor's table equals the oracle's fit of
+    that tensor alone (bit for bit), each from its own start table."""
+    sizes = [768 * 8, 2304, 8, 3072 * 3, 16, 1024 * 5 + 8, 4096 * 2, 5000 + 3]
+    n = sum(sizes)
+    x, _ = synth(n, 515 + bits)
+    segs = qb.Segments(sizes, bucket, DEV)
+    K = 1 << bits
+    start = np.stack([np.sort(np.clip(ref.levels_uniform(bits) + 0.01 * np.sin(np.arange(K) + t), 0, 1)).astype(np.float32)
+                      for t in range(len(sizes))])
+    lv = torch.from_numpy(start.copy()).to(DEV)
+    qb.qsdp_fit_levels_segmented(torch.from_numpy(x).to(DEV), segs, bits, 0.02, lv, max_batches)
+    got = lv.cpu().numpy()
+    off = 0
+    for t, s in enumerate(sizes):
+        want = ref.fit_levels(x[off:off + s], bits, bucket, 0.02, start[t], max_batches)
+        assert bits_equal(got[t], want), t
+        off += s
