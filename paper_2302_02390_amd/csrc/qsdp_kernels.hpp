@@ -450,8 +450,8 @@ __device__ __forceinline__ void sum_peer_slices(const Params& p, uint8_t* stage,
 }
 
 // Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
-// be short). BITS is the width of the codes that are stored (0: FUSED / ADAMW without code
-// output). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
+// be short). BITS is the width of the codes that are stored (0: a step without code output, or
+// MODE_SUM). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
 template <int MODE, int G, int R, int BITS, int W>
@@ -473,8 +473,8 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const uint64_t nunits = (p.num_buckets + BPW - 1) / BPW;
 
     // LDS staging tile of the packed codes (stored, or read from the peers): 32*R*bits bytes per
-    // wave, up to 4 waves per block
-    // (the peers' tiles are at most 8 bits wide and take one spare 16-byte piece, see unstage_codes_rt)
+    // wave, up to 4 waves per block (the peers' tiles are at most 8 bits wide and take one spare
+    // 16-byte piece, see unstage_codes_rt)
     constexpr bool kStaged = BITS != 0 || mode_reads_peers(MODE);
     constexpr int kTileBytes = mode_reads_peers(MODE) ? 32 * R * 8 + 16 : 32 * R * SB;
     __shared__ u4 stage_all[kStaged ? 4 * kTileBytes / 16 : 1];
