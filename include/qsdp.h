@@ -240,6 +240,20 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
                        uint64_t* n_saturated, void* stream);
 
 /*
+ * qsdp_fused_step_ex with the seed advanced from device memory, for callers that capture the
+ * step in a HIP graph: kernel arguments are frozen at capture, so a replayed step would draw the
+ * same random numbers again; here the seed in force is seed + *seed_dev (mod 2^64), read when the
+ * kernel starts, and other work in the same graph (any kernel that increments *seed_dev) moves it
+ * on between replays. seed_dev: device uint64, 8-byte aligned. Equal to qsdp_fused_step_ex called
+ * with that sum.
+ */
+int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr,
+                          int wbits, int gbits, int bucket, float delta,
+                          uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
+                          uint32_t flags, uint32_t* wcodes, float* wmeta,
+                          uint64_t* n_saturated, void* stream);
+
+/*
  * The quantized step with AdamW (the optimizer of the paper's experiments, Appendix A: betas
  * 0.9 / 0.95, eps 1e-8) between the two quantizers in place of the plain SGD update, one pass
  * over HBM: read x, g, m, v; write x, m, v (28 bytes per parameter). Per bucket

@@ -25,7 +25,8 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
            "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
            "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
-           "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented")
+           "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented",
+           "qsdp_fused_step_dseed")
 
 _lib = None
 
@@ -103,6 +104,9 @@ def lib():
         L.qsdp_quantize_levels_stochastic.restype = i32
         L.qsdp_fit_levels_segmented.argtypes = [vp, vp, C.c_uint32, i32, i32, f32, u64, vp, vp]
         L.qsdp_fit_levels_segmented.restype = i32
+        L.qsdp_fused_step_dseed.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, vp, u64, C.c_uint32, vp, vp, vp,
+                                            vp]
+        L.qsdp_fused_step_dseed.restype = i32
         L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
                                      vp, vp, vp, vp]
         L.qsdp_recv_step.restype = i32
@@ -624,3 +628,20 @@ def qsdp_fit_levels_segmented(v, segs, bits, lr, levels, max_batches=0):
     with torch.cuda.device(v.device):
         _check(lib().qsdp_fit_levels_segmented(_ptr(v), _ptr(segs.device), segs.nseg, bits, segs.bucket, lr,
                                                max_batches, _ptr(levels), _stream(v)), "qsdp_fit_levels_segmented")
+
+
+def qsdp_fused_step_dseed(x, g, lr, wbits, gbits, bucket, delta, seed, seed_dev, index_offset=0, flags=0, wcodes=None,
+                          wmeta=None, n_saturated=None):
+    """qsdp_fused_step_ex with the seed in force = seed + seed_dev[0] (an int64 GPU tensor read by the
+    kernel), so that a step captured in a graph can be replayed with an advancing seed."""
+    _is(x, torch.float32); _is(g, torch.float32); _is(seed_dev, torch.int64)
+    if g.numel() != x.numel():
+        raise ValueError("x and g differ in size")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_dseed(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
+                                           _ptr(seed_dev), index_offset, flags, _ptr(wcodes), _ptr(wmeta),
+                                           _ptr(n_saturated), _stream(x)), "qsdp_fused_step_dseed")

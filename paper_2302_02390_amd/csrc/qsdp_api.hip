@@ -510,9 +510,10 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
                               n_saturated, stream);
 }
 
-int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
-                       float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
-                       float* wmeta, uint64_t* n_saturated, void* stream) {
+static int fused_step_common(const uint64_t* seed_dev, float* x, const float* g, uint64_t n, float lr, int wbits,
+                             int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                             uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (seed_dev && (reinterpret_cast<uintptr_t>(seed_dev) & 7u)) return QSDP_EALIGN;
     if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
         (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
@@ -531,7 +532,23 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
+    p.seed_dev = reinterpret_cast<const unsigned long long*>(seed_dev);
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                       float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
+                       float* wmeta, uint64_t* n_saturated, void* stream) {
+    return fused_step_common(nullptr, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+                             wmeta, n_saturated, stream);
+}
+
+int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                          float delta, uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
+                          uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (!seed_dev) return QSDP_EINVAL;
+    return fused_step_common(seed_dev, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+                             wmeta, n_saturated, stream);
 }
 
 static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g, const AdamScalars& adam, uint64_t n,

@@ -83,7 +83,25 @@ struct Params {
     float delta, inv_delta;  // lattice mode when delta > 0
     int delta_pow2;
     uint32_t key0, key1;
+    // optional device-resident seed increment (8-byte aligned): the Philox key is taken from
+    // seed + *seed_dev, read when the kernel starts, so that a captured launch can be replayed
+    // with a seed that other work in the graph advances
+    const unsigned long long* seed_dev;
 };
+
+struct PhiloxKey {
+    uint32_t k0, k1;
+};
+
+__device__ __forceinline__ PhiloxKey launch_key(const Params& p) {
+    PhiloxKey k = {p.key0, p.key1};
+    if (p.seed_dev != nullptr) {
+        const unsigned long long s = (((unsigned long long)p.key1 << 32) | p.key0) + *p.seed_dev;
+        k.k0 = (uint32_t)s;
+        k.k1 = (uint32_t)(s >> 32);
+    }
+    return k;
+}
 
 // The value that gets weight-quantized: x - lr * ghat, or the AdamW update (binary32, in the
 // order m <- fma(b1, m, (1-b1) g); v <- fma(b2, v, ((1-b2) g) g); u = (m/c1) / (sqrt(v/c2) + eps);
@@ -111,11 +129,11 @@ struct Shifts {
     float xi_g;  // gradient shift (FLAG_GRAD_SHIFT)
 };
 
-__device__ __forceinline__ Shifts draw_shifts(const Params& p, bool weights) {
+__device__ __forceinline__ Shifts draw_shifts(const Params& p, PhiloxKey key, bool weights) {
     Shifts s = {0.0f, 0.0f};
     if (!(p.flags & FLAG_NO_SHIFT)) {
-        if (weights) s.xi = stream_shift(1u, p.key0, p.key1);
-        if (p.flags & FLAG_GRAD_SHIFT) s.xi_g = stream_shift(2u, p.key0, p.key1);
+        if (weights) s.xi = stream_shift(1u, key.k0, key.k1);
+        if (p.flags & FLAG_GRAD_SHIFT) s.xi_g = stream_shift(2u, key.k0, key.k1);
     }
     return s;
 }
@@ -495,7 +513,8 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
     constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE);
     const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
-    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS && MODE != MODE_SUM);
+    const PhiloxKey key = launch_key(p);
+    const Shifts shifts = draw_shifts(p, key, MODE != MODE_GRAD && MODE != MODE_LEVELS && MODE != MODE_SUM);
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
@@ -569,7 +588,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
                 for (int cp = 0; cp < R / 2; ++cp) {
                     float h[8];
-                    grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
+                    grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int r = 2 * cp + (i >> 2);
@@ -647,7 +666,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
                 for (int cp = 0; cp < R / 2; ++cp) {
                     float h[8];
-                    grad_uniforms_rows<G>(block_e0, cp, l, p.key0, p.key1, h);
+                    grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int r = 2 * cp + (i >> 2);
@@ -765,7 +784,8 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
     const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
     const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
     const bool keep_master = (p.flags & FLAG_KEEP_MASTER) != 0;
-    const Shifts shifts = draw_shifts(p, MODE != MODE_GRAD && MODE != MODE_LEVELS);
+    const PhiloxKey key = launch_key(p);
+    const Shifts shifts = draw_shifts(p, key, MODE != MODE_GRAD && MODE != MODE_LEVELS);
     const float xi = shifts.xi;
     if (tid == 0) sat_block = 0;
 
@@ -803,7 +823,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     const uint64_t e = (p.block0 << 3) + e0 + (uint64_t)i;
                     uint32_t w[4];
                     const uint64_t blk = e >> 3;
-                    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, p.key0, p.key1, w);
+                    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, key.k0, key.k1, w);
                     const uint32_t j = (uint32_t)(e & 7u);
                     const uint32_t word = w[j >> 1];
                     const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
@@ -890,7 +910,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                         const uint64_t e = (p.block0 << 3) + e0 + (uint64_t)i;
                         uint32_t w[4];
                         const uint64_t blk = e >> 3;
-                        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, p.key0, p.key1, w);
+                        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, key.k0, key.k1, w);
                         const uint32_t j = (uint32_t)(e & 7u);
                         const uint32_t word = w[j >> 1];
                         const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));

@@ -52,3 +52,42 @@ def test_captured_steps_replay_identically():
         tmp = x0.clone()
         qb.qsdp_fused_step(tmp, g, 1e-3, 8, 4, B, 0.0, 99)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("B,flags", [(1024, 0), (96, qb.QSDP_FLAG_GRAD_SHIFT)])
+def test_replayed_graph_advances_its_seed_from_device_memory(B, flags):
+    """One captured iteration = [step counter += 1, fused step seeded from the counter]. Every replay
+    must equal the eager step with the seed the counter holds at that replay (kernel arguments are
+    frozen at capture, the counter is not)."""
+    n = 300 * 1024 + 77
+    xh, gh = synth(n, 1600 + B)
+    g = torch.from_numpy(gh).to(DEV)
+    x = torch.from_numpy(xh).to(DEV)
+    counter = torch.zeros(1, dtype=torch.int64, device=DEV)
+    codes, meta = qb.alloc_packed(n, 8, B, DEV)
+    meta = meta.reshape(-1)
+
+    def iteration():
+        counter.add_(1)
+        qb.qsdp_fused_step_dseed(x, g, 1e-3, 8, 4, B, 0.0, 1000, counter, 0, flags, codes, meta)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()                          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    # restart from known state
+    x.copy_(torch.from_numpy(xh).to(DEV))
+    counter.zero_()
+    x_eager = torch.from_numpy(xh).to(DEV)
+    ec, em = qb.alloc_packed(n, 8, B, DEV)
+    for replay in range(1, 6):
+        graph.replay()
+        qb.qsdp_fused_step_ex(x_eager, g, 1e-3, 8, 4, B, 0.0, 1000 + replay, 0, flags, ec, em.reshape(-1))
+        torch.cuda.synchronize()
+        assert int(counter) == replay
+        assert torch.equal(x, x_eager) and torch.equal(codes, ec) and torch.equal(meta, em.reshape(-1)), replay
