@@ -425,6 +425,22 @@ int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float*
 int qsdp_fit_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg, int bits,
                               int bucket, float lr, uint64_t max_batches, float* levels,
                               void* stream);
+/* Learned levels with ONE TABLE PER TENSOR (Section 5.2 fits the levels of every layer, and of its
+ * weights and gradients, separately; Appendix C leaves small layers on the uniform table): `levels`
+ * holds nseg tables of 2^bits floats back to back, tensor t's at levels + t * 2^bits, the layout
+ * qsdp_fit_levels_segmented writes. Equal, tensor by tensor, to qsdp_quantize_levels (stochastic =
+ * 0) or qsdp_quantize_levels_stochastic (stochastic = 1, uniforms from index_offset + the position
+ * in the flat buffer) and to qsdp_dequantize_levels with that tensor's table. */
+int qsdp_quantize_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg,
+                                   uint64_t total_buckets, int bits, int bucket,
+                                   const float* levels, int stochastic, uint64_t seed,
+                                   uint64_t index_offset, uint32_t* codes, float* meta,
+                                   void* stream);
+int qsdp_dequantize_levels_segmented(const uint32_t* codes, const float* meta,
+                                     const qsdp_segment* table, uint32_t nseg,
+                                     uint64_t total_buckets, int bits, int bucket,
+                                     const float* levels, qsdp_dtype out_dtype, void* out,
+                                     void* stream);
 int qsdp_recv_step_segmented(float* x, const qsdp_segment* table, uint32_t nseg,
                              uint64_t total_buckets, const uint32_t* gcodes,
                              uint64_t gcodes_stride_bytes, const float* gmeta,

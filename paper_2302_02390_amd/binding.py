@@ -26,7 +26,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
            "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
            "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented",
-           "qsdp_fused_step_dseed")
+           "qsdp_fused_step_dseed", "qsdp_quantize_levels_segmented", "qsdp_dequantize_levels_segmented")
 
 _lib = None
 
@@ -104,6 +104,10 @@ def lib():
         L.qsdp_quantize_levels_stochastic.restype = i32
         L.qsdp_fit_levels_segmented.argtypes = [vp, vp, C.c_uint32, i32, i32, f32, u64, vp, vp]
         L.qsdp_fit_levels_segmented.restype = i32
+        L.qsdp_quantize_levels_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, vp, i32, u64, u64, vp, vp, vp]
+        L.qsdp_quantize_levels_segmented.restype = i32
+        L.qsdp_dequantize_levels_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, vp, i32, vp, vp]
+        L.qsdp_dequantize_levels_segmented.restype = i32
         L.qsdp_fused_step_dseed.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, vp, u64, C.c_uint32, vp, vp, vp,
                                             vp]
         L.qsdp_fused_step_dseed.restype = i32
@@ -645,3 +649,38 @@ def qsdp_fused_step_dseed(x, g, lr, wbits, gbits, bucket, delta, seed, seed_dev,
         _check(lib().qsdp_fused_step_dseed(_ptr(x), _ptr(g), x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                            _ptr(seed_dev), index_offset, flags, _ptr(wcodes), _ptr(wmeta),
                                            _ptr(n_saturated), _stream(x)), "qsdp_fused_step_dseed")
+
+
+def qsdp_quantize_levels_segmented(v, segs, bits, levels, codes, meta, stochastic=False, seed=0, index_offset=0):
+    """levels float32[nseg, 2^bits]: row t is the level table of tensor t."""
+    _is(v, torch.float32); _is(levels, torch.float32); _is(codes, torch.int32); _is(meta, torch.float32)
+    if v.numel() < segs.n:
+        raise ValueError("v is smaller than the segments")
+    if levels.numel() != segs.nseg * (1 << bits):
+        raise ValueError("levels must hold nseg * 2^bits entries")
+    segs.check_packed(codes, meta, bits)
+    with torch.cuda.device(v.device):
+        _check(lib().qsdp_quantize_levels_segmented(_ptr(v), _ptr(segs.device), segs.nseg, segs.total_buckets, bits,
+                                                    segs.bucket, _ptr(levels), int(bool(stochastic)), seed,
+                                                    index_offset, _ptr(codes), _ptr(meta), _stream(v)),
+               "qsdp_quantize_levels_segmented")
+
+
+def qsdp_dequantize_levels_segmented(codes, meta, segs, bits, levels, out):
+    _is(codes, torch.int32); _is(meta, torch.float32); _is(levels, torch.float32)
+    if out.dtype == torch.float32:
+        dt = QSDP_F32
+    elif out.dtype == torch.bfloat16:
+        dt = QSDP_BF16
+    else:
+        raise TypeError("out must be float32 or bfloat16")
+    _is(out, out.dtype)
+    if out.numel() < segs.n:
+        raise ValueError("out is smaller than the segments")
+    if levels.numel() != segs.nseg * (1 << bits):
+        raise ValueError("levels must hold nseg * 2^bits entries")
+    segs.check_packed(codes, meta, bits)
+    with torch.cuda.device(out.device):
+        _check(lib().qsdp_dequantize_levels_segmented(_ptr(codes), _ptr(meta), _ptr(segs.device), segs.nseg,
+                                                      segs.total_buckets, bits, segs.bucket, _ptr(levels), dt,
+                                                      _ptr(out), _stream(out)), "qsdp_dequantize_levels_segmented")

@@ -79,18 +79,21 @@ hipError_t launch_dequant_add(int bits, const DequantAddParams& p, unsigned grid
 }
 
 namespace {
-template <int BITS, bool BF16>
+template <int BITS, bool BF16, bool LUT>
 void dequant_seg_launch(int bk, const DequantSegParams& q, unsigned grid, hipStream_t s) {
-    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_TILE_UNIFORM>), dim3(grid), dim3(256), 0, s, q, q.segs);
-    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_SHIFT>), dim3(grid), dim3(256), 0, s, q, q.segs);
-    else hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_DIVIDE>), dim3(grid), dim3(256), 0, s, q, q.segs);
+    if (bk == BK_TILE_UNIFORM) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_TILE_UNIFORM, LUT>), dim3(grid), dim3(256), 0, s, q, q.segs);
+    else if (bk == BK_SHIFT) hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_SHIFT, LUT>), dim3(grid), dim3(256), 0, s, q, q.segs);
+    else hipLaunchKernelGGL((dequant_seg_kernel<BITS, BF16, BK_DIVIDE, LUT>), dim3(grid), dim3(256), 0, s, q, q.segs);
 }
 
 template <int BITS>
 hipError_t dequant_seg_go(bool bf16, const DequantSegParams& q, unsigned grid, hipStream_t s) {
     const int bk = bucket_indexing(q.d, bf16);
-    if (bf16) dequant_seg_launch<BITS, true>(bk, q, grid, s);
-    else dequant_seg_launch<BITS, false>(bk, q, grid, s);
+    const bool lut = q.d.levels != nullptr;  // one table per tensor
+    if (bf16 && lut) dequant_seg_launch<BITS, true, true>(bk, q, grid, s);
+    else if (bf16) dequant_seg_launch<BITS, true, false>(bk, q, grid, s);
+    else if (lut) dequant_seg_launch<BITS, false, true>(bk, q, grid, s);
+    else dequant_seg_launch<BITS, false, false>(bk, q, grid, s);
     return hipGetLastError();
 }
 }  // namespace
@@ -198,7 +201,8 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
         if (wl(mode, stored_bits, p, capped_grid(blocks), s) != hipSuccess) return QSDP_ELAUNCH;
     } else {
-        if (launch_block(mode, p, capped_grid(nb), s) != hipSuccess) return QSDP_ELAUNCH;
+        if (launch_block(mode == MODE_LEVELS_COIN ? MODE_LEVELS : mode, p, capped_grid(nb), s) != hipSuccess)
+            return QSDP_ELAUNCH;
     }
     return QSDP_OK;
 }
@@ -410,7 +414,7 @@ int qsdp_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bu
     p.meta = meta;
     p.gbits = bits;
     p.wbits = bits;
-    return run(MODE_LEVELS, p, bits, static_cast<hipStream_t>(stream));
+    return run(MODE_LEVELS_COIN, p, bits, static_cast<hipStream_t>(stream));
 }
 
 int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
@@ -737,9 +741,35 @@ int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* tabl
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
-int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qsdp_segment* table,
-                              uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
-                              qsdp_dtype out_dtype, void* out, void* stream) {
+int qsdp_quantize_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg,
+                                   uint64_t total_buckets, int bits, int bucket, const float* levels,
+                                   int stochastic, uint64_t seed, uint64_t index_offset, uint32_t* codes,
+                                   float* meta, void* stream) {
+    if (!v || !levels || !codes || !meta || !table || nseg == 0 || total_buckets < nseg || !shape_ok(1, bits, bucket))
+        return QSDP_EINVAL;
+    if ((stochastic != 0 && stochastic != 1) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(v) || !aligned16(codes) || !aligned16(meta) || (reinterpret_cast<uintptr_t>(table) & 7u) ||
+        (reinterpret_cast<uintptr_t>(levels) & 3u))
+        return QSDP_EALIGN;
+    Params p = {};
+    set_common(p, 0, bucket, seed, index_offset, 0.0f);
+    p.segs = reinterpret_cast<const Segment*>(table);
+    p.nseg = nseg;
+    p.num_buckets = total_buckets;
+    p.flags = stochastic ? FLAG_LEVELS_STOCHASTIC : 0u;
+    p.xin = v;
+    p.levels = levels;
+    p.levels_per_tensor = 1u;
+    p.codes = codes;
+    p.meta = meta;
+    p.gbits = bits;
+    p.wbits = bits;
+    return run(stochastic ? MODE_LEVELS_COIN : MODE_LEVELS, p, bits, static_cast<hipStream_t>(stream));
+}
+
+static int dequantize_segmented_common(const float* levels, const uint32_t* codes, const float* meta,
+                                       const qsdp_segment* table, uint32_t nseg, uint64_t total_buckets, int bits,
+                                       int bucket, qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !table || !out || nseg == 0 || total_buckets < nseg || !shape_ok(1, bits, bucket))
         return QSDP_EINVAL;
     if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
@@ -750,11 +780,28 @@ int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qs
     DequantSegParams q = {};
     q.d = decoder_params(codes, meta, total_buckets * (uint64_t)bucket, bits, bucket, out_dtype == QSDP_BF16, out,
                          &grid);
+    q.d.levels = levels;
     q.segs = reinterpret_cast<const Segment*>(table);
     q.nseg = nseg;
     if (launch_dequant_seg(bits, out_dtype == QSDP_BF16, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
+}
+
+int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qsdp_segment* table,
+                              uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
+                              qsdp_dtype out_dtype, void* out, void* stream) {
+    return dequantize_segmented_common(nullptr, codes, meta, table, nseg, total_buckets, bits, bucket, out_dtype, out,
+                                       stream);
+}
+
+int qsdp_dequantize_levels_segmented(const uint32_t* codes, const float* meta, const qsdp_segment* table,
+                                     uint32_t nseg, uint64_t total_buckets, int bits, int bucket,
+                                     const float* levels, qsdp_dtype out_dtype, void* out, void* stream) {
+    if (!levels) return QSDP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(levels) & 3u) return QSDP_EALIGN;
+    return dequantize_segmented_common(levels, codes, meta, table, nseg, total_buckets, bits, bucket, out_dtype, out,
+                                       stream);
 }
 
 static int dequantize_gathered_common(const float* levels, const uint32_t* codes, uint64_t codes_stride_bytes,

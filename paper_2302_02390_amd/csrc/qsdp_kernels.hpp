@@ -35,8 +35,14 @@ namespace qsdp {
 // decoded slices of all peers (no Q^g here), then the SGD step and Q^w as in MODE_FUSED.
 // MODE_RECV_ADAMW: the same with the AdamW update of MODE_ADAMW in place of the SGD step.
 // MODE_SUM: only the first half of MODE_RECV: out = alpha * (sum of the decoded peer slices).
+// MODE_LEVELS_COIN: MODE_LEVELS with the unbiased coin flip between the two enclosing levels
+// instead of the nearest level (wave kernels only: a kernel of its own so that the nearest-level
+// encoder does not carry the registers of the rounding uniforms; the block kernel takes
+// MODE_LEVELS with FLAG_LEVELS_STOCHASTIC).
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
-            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7, MODE_SUM = 8 };
+            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7, MODE_SUM = 8, MODE_LEVELS_COIN = 9 };
+
+constexpr bool mode_is_levels(int mode) { return mode == MODE_LEVELS || mode == MODE_LEVELS_COIN; }
 
 constexpr bool mode_is_recv(int mode) { return mode == MODE_RECV || mode == MODE_RECV_ADAMW; }
 constexpr bool mode_reads_peers(int mode) { return mode_is_recv(mode) || mode == MODE_SUM; }
@@ -55,7 +61,8 @@ struct Params {
     const float* g;      // GRAD, FUSED: gradient
     float* x;            // FUSED: in/out weights
     const float* xin;    // WEIGHT, LEVELS: values to quantize
-    const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]
+    const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]; segmented calls with
+                         // levels_per_tensor: one such table per tensor, back to back
     float* mom;          // ADAMW: first moment, in/out
     float* var;          // ADAMW: second moment, in/out
     float beta1, beta2, omb1, omb2, eps, weight_decay, bias1, bias2;  // ADAMW
@@ -76,6 +83,7 @@ struct Params {
     uint64_t num_buckets;   // buckets this launch handles
     uint64_t block0;        // index_offset / 8
     uint32_t nseg;
+    uint32_t levels_per_tensor;  // LEVELS with segs: table of tensor t at levels + t * 2^wbits
     uint32_t flags;  // FLAG_* variants
     int bucket;
     int gbits, wbits;
@@ -144,7 +152,7 @@ __device__ __forceinline__ Shifts draw_shifts(const Params& p, PhiloxKey key, bo
 // argument so that the uniform search compiles to scalar loads; through the vector memory path
 // every probe would cost a round trip behind the streaming traffic.
 __device__ __forceinline__ Segment find_segment(const Segment* __restrict__ segs, uint32_t nseg, uint64_t gb0,
-                                                uint64_t gb) {
+                                                uint64_t gb, uint32_t* index = nullptr) {
     uint32_t lo = 0, hi = nseg;  // segs[lo].first_bucket <= gb0 < segs[hi].first_bucket
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
@@ -158,6 +166,7 @@ __device__ __forceinline__ Segment find_segment(const Segment* __restrict__ segs
         seg = segs[idx];
         next_first = idx + 1 < nseg ? segs[idx + 1].first_bucket : ~0ull;
     }
+    if (index != nullptr) *index = idx;
     return seg;
 }
 
@@ -166,14 +175,16 @@ __device__ __forceinline__ Segment find_segment(const Segment* __restrict__ segs
 struct BucketRef {
     uint64_t e0;
     uint32_t m;
+    uint32_t tensor;  // index in the segment table (0 for a single tensor)
 };
 
 __device__ __forceinline__ BucketRef locate_bucket(const Params& p, const Segment* __restrict__ segs, uint64_t gb0,
                                                    uint64_t gb, uint32_t B) {
     BucketRef ref;
     uint64_t left;
+    ref.tensor = 0;
     if (segs != nullptr) {
-        const Segment seg = find_segment(segs, p.nseg, gb0, gb);
+        const Segment seg = find_segment(segs, p.nseg, gb0, gb, &ref.tensor);
         const uint64_t local = (gb - seg.first_bucket) * B;
         ref.e0 = seg.offset + local;
         left = seg.n - local;
@@ -499,10 +510,18 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
-    __shared__ float level_table[MODE == MODE_LEVELS ? (1 << SB) : 1];
-    if constexpr (MODE == MODE_LEVELS) {
-        for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_table[k] = p.levels[k];
-        __syncthreads();
+    // MODE_LEVELS: the level table in LDS. One table for the whole call is loaded once per
+    // workgroup; with one table per tensor every wave keeps the table of the tensor it works on
+    // in a slot of its own and reloads it when its buckets move on to another tensor.
+    __shared__ float level_tables[mode_is_levels(MODE) ? 4 * (1 << SB) : 1];
+    const bool levels_per_tensor = mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr;
+    const float* level_table = level_tables + (levels_per_tensor ? wave_in_block * (1u << SB) : 0u);
+    uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
+    if constexpr (mode_is_levels(MODE)) {
+        if (!levels_per_tensor) {
+            for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_tables[k] = p.levels[k];
+            __syncthreads();
+        }
     }
 
     const float Lg = (float)((1 << p.gbits) - 1);
@@ -514,7 +533,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE);
     const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
     const PhiloxKey key = launch_key(p);
-    const Shifts shifts = draw_shifts(p, key, MODE != MODE_GRAD && MODE != MODE_LEVELS && MODE != MODE_SUM);
+    const Shifts shifts = draw_shifts(p, key, MODE != MODE_GRAD && !mode_is_levels(MODE) && MODE != MODE_SUM);
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
@@ -655,34 +674,60 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
         if (kWritesX && keep_master && active) store_rows<G, R>(p.x + e0, l, m, partial, w);
 
         // weight quantization of w
-        if constexpr (MODE == MODE_LEVELS) {
+        if constexpr (mode_is_levels(MODE)) {
             float lo, hi;
             rows_minmax<G, R>(w, l, m, partial, lo, hi);
             block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
             const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);  // scale = hi - lo, inv = 1/(hi - lo)
             base = grid.lo;
             scale = grid.scale;
-            if (p.flags & FLAG_LEVELS_STOCHASTIC) {
-#pragma unroll
-                for (int cp = 0; cp < R / 2; ++cp) {
-                    float h[8];
-                    grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int r = 2 * cp + (i >> 2);
-                        const float z = (w[r][i & 3] - grid.lo) * grid.inv;
-                        w[r][i & 3] = (float)stochastic_level<SB>(z, h[i], level_table);
+            // One pass per distinct tensor among the wave's buckets (one pass, unless the buckets
+            // straddle tensors): every lane computes, the lanes of the pass's tensor replace their
+            // values by the codes (a lane belongs to exactly one pass; what it computes in the others,
+            // from values or from codes, is dropped). All lanes stay converged (the uniforms are
+            // exchanged between lanes).
+            uint64_t pending = ~0ull;
+            do {
+                bool mine = true;
+                if (levels_per_tensor) {
+                    const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)ref.tensor, __builtin_ctzll(pending));
+                    mine = ref.tensor == cur;
+                    if (cur != loaded_tensor) {
+                        float* slot = level_tables + wave_in_block * (1u << SB);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slot are done
+                        __builtin_amdgcn_wave_barrier();
+                        for (int k = lane; k < (1 << SB); k += 64) slot[k] = p.levels[(uint64_t)cur * (1u << SB) + k];
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        loaded_tensor = cur;
                     }
                 }
-            } else {
+                if constexpr (MODE == MODE_LEVELS_COIN) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+                    for (int cp = 0; cp < R / 2; ++cp) {
+                        float h[8];
+                        grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float z = (w[r][i] - grid.lo) * grid.inv;
-                        w[r][i] = (float)nearest_level<SB>(z, level_table);
+                        for (int i = 0; i < 8; ++i) {
+                            const int r = 2 * cp + (i >> 2);
+                            const float z = (w[r][i & 3] - grid.lo) * grid.inv;
+                            const float c = (float)stochastic_level<SB>(z, h[i], level_table);
+                            w[r][i & 3] = mine ? c : w[r][i & 3];
+                        }
                     }
-            }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float z = (w[r][i] - grid.lo) * grid.inv;
+                            const float c = (float)nearest_level<SB>(z, level_table);
+                            w[r][i] = mine ? c : w[r][i];
+                        }
+                }
+                pending &= ~__builtin_amdgcn_ballot_w64(mine);
+            } while (pending != 0);
         } else if (lattice) {
             float lo, unused_hi;
             rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
@@ -903,6 +948,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 scale = grid.scale;
                 const int K = 1 << p.wbits;
                 const bool stochastic = (p.flags & FLAG_LEVELS_STOCHASTIC) != 0;
+                const float* levels = p.levels + (p.levels_per_tensor != 0 ? (uint64_t)ref.tensor * K : 0);
                 for (int i = tid; i < m; i += 256) {
                     const float z = (val[i] - grid.lo) * grid.inv;
                     if (stochastic) {
@@ -915,14 +961,14 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                         const uint32_t word = w[j >> 1];
                         const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
                         int c = 0;
-                        if (z >= p.levels[0]) {
+                        if (z >= levels[0]) {
                             int lower = 0;
                             for (int k = 1; k < K; ++k)
-                                if (p.levels[k] <= z) lower = k;
+                                if (levels[k] <= z) lower = k;
                             c = lower;
                             if (lower < K - 1) {
-                                const float q0 = p.levels[lower];
-                                const float prob = (z - q0) / (p.levels[lower + 1] - q0);
+                                const float q0 = levels[lower];
+                                const float prob = (z - q0) / (levels[lower + 1] - q0);
                                 c = lower + (h < prob * 65536.0f ? 1 : 0);
                             }
                         }
@@ -931,9 +977,9 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     }
                     // plain scan: nearest level, first index on ties (the table is in global memory)
                     int best = 0;
-                    float best_d = fabsf(z - p.levels[0]);
+                    float best_d = fabsf(z - levels[0]);
                     for (int k = 1; k < K; ++k) {
-                        const float d = fabsf(z - p.levels[k]);
+                        const float d = fabsf(z - levels[k]);
                         if (d < best_d) {
                             best_d = d;
                             best = k;
@@ -1165,7 +1211,10 @@ __global__ void __launch_bounds__(256) dequant_kernel(const DequantParams p) {
 // first slot is found by a wave-uniform search (scalar loads, see find_segment). A tile that
 // lies inside that tensor's elements (the common case) is decoded without per-lane control
 // flow; a tile that reaches a tensor's padding or the next tensor goes lane by lane, each lane
-// walking on from the tile's tensor to its own.
+// walking on from the tile's tensor to its own. LUT: learned levels, one table of 2^BITS floats
+// per tensor at d.levels (tensor t's at d.levels + t * 2^BITS); a wave keeps the table of its
+// tile's tensor in an LDS slot of its own and reads the tables through global memory on the
+// lane-by-lane path.
 // ---------------------------------------------------------------------------------------
 struct DequantSegParams {
     DequantParams d;  // d.n: slots (total buckets * bucket); d.out: the flat output
@@ -1173,10 +1222,13 @@ struct DequantSegParams {
     uint32_t nseg;
 };
 
-template <int BITS, bool BF16, int BK>
+template <int BITS, bool BF16, int BK, bool LUT>
 __global__ void __launch_bounds__(256) dequant_seg_kernel(const DequantSegParams q,
                                                           const Segment* __restrict__ segs) {
     const DequantParams& p = q.d;
+    constexpr int K = 1 << BITS;
+    __shared__ float lut_all[LUT ? 4 * K : 1];
+    uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
     constexpr int E = BF16 ? 8 : 4;
     constexpr int U = kDequantRows;
     constexpr uint64_t T = (uint64_t)U * 64 * E;
@@ -1190,10 +1242,21 @@ __global__ void __launch_bounds__(256) dequant_seg_kernel(const DequantSegParams
          tile += nwaves) {
         const uint64_t s0 = tile * T;
         const uint64_t bucket0 = (uint32_t)(s0 >> 5) / p.bucket32;  // wave-uniform
-        const Segment seg0 = find_segment(segs, q.nseg, bucket0, bucket0);
+        uint32_t tensor0;
+        const Segment seg0 = find_segment(segs, q.nseg, bucket0, bucket0, &tensor0);
         const uint64_t e0 = seg0.offset + (s0 - seg0.first_bucket * B);  // element of slot s0
         const uint64_t end0 = seg0.offset + seg0.n;
         if (e0 + T <= end0) {
+            float* lut = lut_all + (LUT ? wave_in_block * K : 0);
+            if (LUT && tensor0 != loaded_tensor) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slot are done
+                __builtin_amdgcn_wave_barrier();
+                for (int k = lane; k < K; k += 64) lut[k] = p.levels[(uint64_t)tensor0 * K + k];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                loaded_tensor = tensor0;
+            }
             uint64_t bits[U];
             float base[U], scale[U];
 #pragma unroll
@@ -1206,20 +1269,21 @@ __global__ void __launch_bounds__(256) dequant_seg_kernel(const DequantSegParams
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                decode_store<BITS, BF16, false>(p, e0 + (uint64_t)(u * 64 * E + lane * E), bits[u], base[u], scale[u],
-                                                true, nullptr, end0);
+                decode_store<BITS, BF16, LUT>(p, e0 + (uint64_t)(u * 64 * E + lane * E), bits[u], base[u], scale[u],
+                                              true, lut, end0);
         } else {
             for (int u = 0; u < U; ++u) {
                 const uint64_t s = s0 + (uint64_t)(u * 64 * E + lane * E);
                 if (s < p.n) {
                     const uint64_t bucket = bucket_of<BK>(s, p);
-                    const Segment seg = find_segment(segs, q.nseg, bucket0, bucket);
+                    uint32_t tensor;
+                    const Segment seg = find_segment(segs, q.nseg, bucket0, bucket, &tensor);
                     const uint64_t e = seg.offset + (s - seg.first_bucket * B);
                     const uint64_t end = seg.offset + seg.n;
                     if (e < end) {
                         const uint64_t bits = load_bits<E * BITS>(p.codes, s * BITS, last_word);
-                        decode_store<BITS, BF16, false>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
-                                                        e + E <= end, nullptr, end);
+                        decode_store<BITS, BF16, LUT>(p, e, bits, p.meta[2 * bucket], p.meta[2 * bucket + 1],
+                                                      e + E <= end, LUT ? p.levels + (uint64_t)tensor * K : nullptr, end);
                     }
                 }
             }

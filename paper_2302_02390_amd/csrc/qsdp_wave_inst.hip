@@ -49,6 +49,7 @@ hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, u
             return by_bits<MODE_FUSED>(bits, p, grid, s);
         case MODE_FUSED_CODES: return by_bits<MODE_FUSED_CODES>(bits, p, grid, s);
         case MODE_LEVELS: return by_bits<MODE_LEVELS>(bits, p, grid, s);
+        case MODE_LEVELS_COIN: return by_bits<MODE_LEVELS_COIN>(bits, p, grid, s);
         case MODE_ADAMW:
             if (bits == 0) return go<MODE_ADAMW, 0>(p, grid, s);
             return by_bits<MODE_ADAMW>(bits, p, grid, s);

@@ -139,3 +139,73 @@ def test_fit_levels_segmented_equals_per_tensor_fits(bits, bucket, max_batches):
         want = ref.fit_levels(x[off:off + s], bits, bucket, 0.02, start[t], max_batches)
         assert bits_equal(got[t], want), t
         off += s
+
+
+@pytest.mark.parametrize("stochastic", [False, True])
+@pytest.mark.parametrize("bits,bucket", [(1, 128), (2, 96), (3, 1024), (4, 128), (5, 512), (6, 4096), (7, 256),
+                                         (8, 2048), (4, 1024), (8, 32)])
+def test_levels_per_tensor_segmented(bits, bucket, stochastic):
+    """Every tensor of a multi-tensor buffer with a level table of its own (small tensors, so the
+    buckets one wave works on straddle several tensors): codes and meta equal the oracle's
+    single-tensor encoding with that tensor's table, and so do the decoded values."""
+    sizes = [768, 2304, 768 * 40, 8, 3072, 16, 1024 * 3 + 8, 128, 128, 256, 50257 * 8, 4096 * 2, 24, 5000 + 3]
+    n = sum(sizes)
+    x, _ = synth(n, 620 + bits)
+    segs = qb.Segments(sizes, bucket, DEV)
+    tables = np.stack([ref.levels_uniform(bits) if t % 4 == 3 else _levels(bits, 100 * bits + t)
+                       for t in range(len(sizes))])
+    lvd = torch.from_numpy(tables).to(DEV)
+    xd = torch.from_numpy(x).to(DEV)
+    codes, meta = segs.alloc_packed(bits)
+    qb.qsdp_quantize_levels_segmented(xd, segs, bits, lvd, codes, meta.reshape(-1), stochastic, seed=9,
+                                      index_offset=128)
+    want_c, want_m, want_f32, want_bf16 = [], [], [], []
+    off = 0
+    for t, s in enumerate(sizes):
+        if stochastic:
+            c, m = ref.quantize_levels_stochastic(x[off:off + s], bits, bucket, tables[t], 9, index_offset=128 + off)
+        else:
+            c, m = ref.quantize_levels(x[off:off + s], bits, bucket, tables[t])
+        want_c.append(c); want_m.append(m)
+        want_f32.append(ref.dequantize_levels(c, m, s, bits, bucket, tables[t]))
+        want_bf16.append(ref.dequantize_levels(c, m, s, bits, bucket, tables[t], ref.BF16))
+        off += s
+    assert np.array_equal(np_u32(meta), np.concatenate(want_m).view(np.uint32).reshape(-1))
+    assert np.array_equal(np_u32(codes), np.concatenate(want_c))
+    out = torch.full((n,), -7.0, dtype=torch.float32, device=DEV)
+    qb.qsdp_dequantize_levels_segmented(codes, meta.reshape(-1), segs, bits, lvd, out)
+    assert bits_equal(np_f32(out), np.concatenate(want_f32))
+    outh = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    qb.qsdp_dequantize_levels_segmented(codes, meta.reshape(-1), segs, bits, lvd, outh)
+    assert np.array_equal(outh.view(torch.int16).cpu().numpy().view(np.uint16), np.concatenate(want_bf16))
+
+
+def test_levels_per_tensor_gpt125m_layers_equal_per_tensor_calls():
+    """The 125M model as per-layer tensors (d = 768: most tensors end in a short bucket), 5-bit
+    tables fitted per tensor on the GPU, encode + decode in one launch each against per-tensor calls
+    (themselves checked against the oracle above)."""
+    shape, B, bits = wl.GPT_125M, 1024, 5
+    sizes = [s for _, s in wl.model_tensors(shape)]
+    n = sum(sizes)
+    x = wl.weights(n, 1240, DEV)
+    segs = qb.Segments(sizes, B, DEV)
+    lv = torch.from_numpy(np.tile(ref.levels_uniform(bits), (len(sizes), 1))).to(DEV)
+    qb.qsdp_fit_levels_segmented(x, segs, bits, 0.01, lv, 64)
+    codes, meta = segs.alloc_packed(bits)
+    qb.qsdp_quantize_levels_segmented(x, segs, bits, lv, codes, meta.reshape(-1))
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    qb.qsdp_dequantize_levels_segmented(codes, meta.reshape(-1), segs, bits, lv, out)
+    words = B * bits // 32
+    off = fb = 0
+    for t, s in enumerate(sizes):
+        nb = -(-s // B)
+        c1, m1 = qb.alloc_packed(s, bits, B, DEV)
+        xs = x[off:off + s].clone()
+        qb.qsdp_quantize_levels(xs, bits, B, lv[t].clone(), c1, m1.reshape(-1))
+        assert torch.equal(codes[fb * words:(fb + nb) * words], c1), t
+        assert torch.equal(meta.reshape(-1)[2 * fb:2 * (fb + nb)], m1.reshape(-1)), t
+        o1 = torch.empty(s, dtype=torch.bfloat16, device=DEV)
+        qb.qsdp_dequantize_levels(c1, m1.reshape(-1), s, bits, B, lv[t].clone(), o1)
+        assert torch.equal(out[off:off + s], o1), t
+        off += s
+        fb += nb
