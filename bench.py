@@ -384,6 +384,15 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"fused_step_codes_W{wbits}G{gbits}_shared_shift_gradients",
         lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i, 0, None,
                                            qb.QSDP_FLAG_GRAD_SHIFT), 4 + 2 * (wbits / 8.0 + meta_b))
+    # gradients handed over in 16 bits (widened exactly on load): 2 bytes of gradient traffic per parameter
+    for name, dt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
+        g16 = g.to(dt)
+        run(f"quantize_grad_b{gbits}_{name}_gradient",
+            lambda i: qb.qsdp_quantize_grad_g16(g16, gbits, bucket, i, 0, gc, gm), 2 + gbits / 8.0 + meta_b)
+        xh = x.clone()
+        run(f"fused_step_W{wbits}G{gbits}_{name}_gradient",
+            lambda i: qb.qsdp_fused_step_g16(xh, g16, 1e-3, wbits, gbits, bucket, 0.0, i), 10.0)
+        del g16, xh
     # AdamW between the quantizers (moments in fp32): read x, g, m, v; write x, m, v
     mom = torch.zeros(n, dtype=torch.float32, device=dev)
     var = torch.zeros(n, dtype=torch.float32, device=dev)

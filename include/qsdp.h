@@ -61,7 +61,9 @@ enum {
     QSDP_ELAUNCH = -3  /* the HIP runtime refused the launch */
 };
 
-typedef enum { QSDP_F32 = 0, QSDP_BF16 = 1 } qsdp_dtype;
+/* QSDP_F16 (IEEE binary16) is an INPUT format of the *_g16 entry points only; the decoders write
+ * QSDP_F32 or QSDP_BF16. */
+typedef enum { QSDP_F32 = 0, QSDP_BF16 = 1, QSDP_F16 = 2 } qsdp_dtype;
 
 /* Version of the arithmetic/wire specification implemented (2: 16-bit uniforms, 8 per
  * Philox block). */
@@ -238,6 +240,25 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
                        uint64_t seed, uint64_t index_offset, uint32_t flags,
                        uint32_t* wcodes, float* wmeta,
                        uint64_t* n_saturated, void* stream);
+
+/*
+ * Gradients that arrive in a 16-bit format: the paper's system receives half-precision
+ * gradients and converts them to full precision before quantizing (Section 6, experimental
+ * setup). Here the kernels widen each value to binary32 on load, which is exact for both
+ * formats, so the result equals the fp32 entry point called on the converted gradient, without
+ * the conversion pass and with 2 bytes of gradient traffic per parameter instead of 4.
+ *   g        in  device uint16[n] bit patterns of g_dtype, 16-byte aligned
+ *   g_dtype      QSDP_F16 (IEEE binary16, the paper's) or QSDP_BF16; anything else: QSDP_EINVAL
+ * Everything else as in qsdp_quantize_grad_ex / qsdp_fused_step_ex.
+ */
+int qsdp_quantize_grad_g16(const void* g, qsdp_dtype g_dtype, uint64_t n, int bits, int bucket,
+                           uint64_t seed, uint64_t index_offset, uint32_t flags,
+                           uint32_t* codes, float* meta, void* stream);
+int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr,
+                        int wbits, int gbits, int bucket, float delta,
+                        uint64_t seed, uint64_t index_offset, uint32_t flags,
+                        uint32_t* wcodes, float* wmeta,
+                        uint64_t* n_saturated, void* stream);
 
 /*
  * qsdp_fused_step_ex with the seed advanced from device memory, for callers that capture the

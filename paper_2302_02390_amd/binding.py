@@ -26,7 +26,8 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
            "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
            "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented",
-           "qsdp_fused_step_dseed", "qsdp_quantize_levels_segmented", "qsdp_dequantize_levels_segmented")
+           "qsdp_fused_step_dseed", "qsdp_quantize_levels_segmented", "qsdp_dequantize_levels_segmented",
+           "qsdp_quantize_grad_g16", "qsdp_fused_step_g16")
 
 _lib = None
 
@@ -108,6 +109,11 @@ def lib():
         L.qsdp_quantize_levels_segmented.restype = i32
         L.qsdp_dequantize_levels_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, vp, i32, vp, vp]
         L.qsdp_dequantize_levels_segmented.restype = i32
+        L.qsdp_quantize_grad_g16.argtypes = [vp, i32, u64, i32, i32, u64, u64, C.c_uint32, vp, vp, vp]
+        L.qsdp_quantize_grad_g16.restype = i32
+        L.qsdp_fused_step_g16.argtypes = [vp, vp, i32, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp, vp,
+                                          vp]
+        L.qsdp_fused_step_g16.restype = i32
         L.qsdp_fused_step_dseed.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, vp, u64, C.c_uint32, vp, vp, vp,
                                             vp]
         L.qsdp_fused_step_dseed.restype = i32
@@ -684,3 +690,36 @@ def qsdp_dequantize_levels_segmented(codes, meta, segs, bits, levels, out):
         _check(lib().qsdp_dequantize_levels_segmented(_ptr(codes), _ptr(meta), _ptr(segs.device), segs.nseg,
                                                       segs.total_buckets, bits, segs.bucket, _ptr(levels), dt,
                                                       _ptr(out), _stream(out)), "qsdp_dequantize_levels_segmented")
+
+
+
+_G16 = {torch.bfloat16: 1, torch.float16: 2}
+
+
+def qsdp_quantize_grad_g16(g, bits, bucket, seed, index_offset, codes, meta, flags=0):
+    """qsdp_quantize_grad_ex on a float16 or bfloat16 gradient (widened exactly to float32 inside the kernel)."""
+    if g.dtype not in _G16:
+        raise TypeError("g must be float16 or bfloat16")
+    _is(g, g.dtype); _is(codes, torch.int32); _is(meta, torch.float32)
+    _packed_ok(codes, meta, g.numel(), bits, bucket)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_quantize_grad_g16(_ptr(g), _G16[g.dtype], g.numel(), bits, bucket, seed, index_offset, flags,
+                                            _ptr(codes), _ptr(meta), _stream(g)), "qsdp_quantize_grad_g16")
+
+
+def qsdp_fused_step_g16(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, flags=0, wcodes=None, wmeta=None,
+                        n_saturated=None):
+    """qsdp_fused_step_ex with a float16 or bfloat16 gradient (widened exactly to float32 inside the kernel)."""
+    if g.dtype not in _G16:
+        raise TypeError("g must be float16 or bfloat16")
+    _is(x, torch.float32); _is(g, g.dtype)
+    if g.numel() != x.numel():
+        raise ValueError("x and g differ in size")
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_g16(_ptr(x), _ptr(g), _G16[g.dtype], x.numel(), lr, wbits, gbits, bucket, delta,
+                                         seed, index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
+                                         _stream(x)), "qsdp_fused_step_g16")

@@ -300,20 +300,36 @@ int qsdp_quantize_grad(const float* g, uint64_t n, int bits, int bucket, uint64_
     return qsdp_quantize_grad_ex(g, n, bits, bucket, seed, index_offset, 0u, codes, meta, stream);
 }
 
-int qsdp_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
-                          uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta, void* stream) {
+static int quantize_grad_common(uint32_t g_half, const void* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                                uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta, void* stream) {
     if (!g || !codes || !meta || !shape_ok(n, bits, bucket) || (index_offset & 7u) || (flags & ~QSDP_FLAG_ALL))
         return QSDP_EINVAL;
     if (!aligned16(g) || !aligned16(codes) || !aligned16(meta)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, 0.0f);
     p.flags = flags;
-    p.g = g;
+    p.g = static_cast<const float*>(g);
+    p.g_half = g_half;
     p.codes = codes;
     p.meta = meta;
     p.gbits = bits;
     p.wbits = bits;
     return run(MODE_GRAD, p, bits, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_quantize_grad_ex(const float* g, uint64_t n, int bits, int bucket, uint64_t seed,
+                          uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta, void* stream) {
+    return quantize_grad_common(0u, g, n, bits, bucket, seed, index_offset, flags, codes, meta, stream);
+}
+
+// 1 / 2 for a 2-byte gradient format of the C header, 0 for anything else
+static uint32_t half_format(qsdp_dtype t) { return t == QSDP_BF16 ? 1u : t == QSDP_F16 ? 2u : 0u; }
+
+int qsdp_quantize_grad_g16(const void* g, qsdp_dtype g_dtype, uint64_t n, int bits, int bucket, uint64_t seed,
+                           uint64_t index_offset, uint32_t flags, uint32_t* codes, float* meta, void* stream) {
+    if (half_format(g_dtype) == 0u) return QSDP_EINVAL;
+    return quantize_grad_common(half_format(g_dtype), g, n, bits, bucket, seed, index_offset, flags, codes, meta,
+                                stream);
 }
 
 int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket, float delta,
@@ -514,7 +530,7 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
                               n_saturated, stream);
 }
 
-static int fused_step_common(const uint64_t* seed_dev, float* x, const float* g, uint64_t n, float lr, int wbits,
+static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, float* x, const void* g, uint64_t n, float lr, int wbits,
                              int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                              uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (seed_dev && (reinterpret_cast<uintptr_t>(seed_dev) & 7u)) return QSDP_EALIGN;
@@ -529,7 +545,7 @@ static int fused_step_common(const uint64_t* seed_dev, float* x, const float* g,
     set_common(p, n, bucket, seed, index_offset, delta);
     p.flags = flags;
     p.x = x;
-    p.g = g;
+    p.g = static_cast<const float*>(g);
     p.codes = wcodes;
     p.meta = wmeta;
     p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
@@ -537,13 +553,14 @@ static int fused_step_common(const uint64_t* seed_dev, float* x, const float* g,
     p.wbits = wbits;
     p.lr = lr;
     p.seed_dev = reinterpret_cast<const unsigned long long*>(seed_dev);
+    p.g_half = g_half;
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                        float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, uint64_t* n_saturated, void* stream) {
-    return fused_step_common(nullptr, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -551,7 +568,15 @@ int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr, int wb
                           float delta, uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!seed_dev) return QSDP_EINVAL;
-    return fused_step_common(seed_dev, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(seed_dev, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+                             wmeta, n_saturated, stream);
+}
+
+int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr, int wbits, int gbits,
+                        int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
+                        uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
+    if (half_format(g_dtype) == 0u) return QSDP_EINVAL;
+    return fused_step_common(nullptr, half_format(g_dtype), x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 

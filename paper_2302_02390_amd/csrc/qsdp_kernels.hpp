@@ -58,7 +58,7 @@ struct Segment {
 
 struct Params {
     // tensors
-    const float* g;      // GRAD, FUSED: gradient
+    const float* g;      // GRAD, FUSED: gradient (2-byte values when g_half != 0)
     float* x;            // FUSED: in/out weights
     const float* xin;    // WEIGHT, LEVELS: values to quantize
     const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]; segmented calls with
@@ -83,6 +83,7 @@ struct Params {
     uint64_t num_buckets;   // buckets this launch handles
     uint64_t block0;        // index_offset / 8
     uint32_t nseg;
+    uint32_t g_half;  // 0: binary32 gradient; 1: bf16, 2: binary16, widened to binary32 (exactly) on load
     uint32_t levels_per_tensor;  // LEVELS with segs: table of tensor t at levels + t * 2^wbits
     uint32_t flags;  // FLAG_* variants
     int bucket;
@@ -217,6 +218,38 @@ __device__ __forceinline__ void load_rows(const float* base, int l, int m, bool 
             for (int i = 0; i < 4; ++i) {
                 const int idx = (r * G + l) * 4 + i;
                 v[r][i] = idx < m ? base[idx] : 0.0f;
+            }
+    }
+}
+
+// A 2-byte floating-point value widened to binary32 (exact in both formats): bf16 is the upper
+// half of the binary32 pattern, binary16 goes through the hardware conversion.
+template <bool BF16>
+__device__ __forceinline__ float widen16(uint32_t h) {
+    if (BF16) return __builtin_bit_cast(float, h << 16);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+
+// The same tile read from 2-byte values, 8 bytes per lane and row.
+template <int G, int R, bool BF16>
+__device__ __forceinline__ void load_rows_half(const uint16_t* base, int l, int m, bool partial, float (&v)[R][4]) {
+    if (!partial) {
+        const u2* p = reinterpret_cast<const u2*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const u2 a = __builtin_nontemporal_load(p + r * G);
+            v[r][0] = widen16<BF16>(a[0] & 0xFFFFu);
+            v[r][1] = widen16<BF16>(a[0] >> 16);
+            v[r][2] = widen16<BF16>(a[1] & 0xFFFFu);
+            v[r][3] = widen16<BF16>(a[1] >> 16);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                v[r][i] = idx < m ? widen16<BF16>(base[idx]) : 0.0f;
             }
     }
 }
@@ -567,7 +600,12 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
             float mom[R][4], var[R][4];  // MODE_ADAMW only
-            load_rows<G, R>(p.g + e0, l, m, partial, gv);
+            if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 1)
+                load_rows_half<G, R, true>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
+            else if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 2)
+                load_rows_half<G, R, false>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
+            else
+                load_rows<G, R>(p.g + e0, l, m, partial, gv);
             if (MODE == MODE_FUSED || MODE == MODE_ADAMW) load_rows<G, R>(p.x + e0, l, m, partial, w);
             if constexpr (MODE == MODE_ADAMW) {
                 load_rows<G, R>(p.mom + e0, l, m, partial, mom);
@@ -852,7 +890,9 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
         if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
             float lo = __builtin_inff(), hi = -__builtin_inff();
             for (int i = tid; i < m; i += 256) {
-                const float v = p.g[e0 + i];
+                const uint16_t* g16 = reinterpret_cast<const uint16_t*>(p.g);
+                const float v = p.g_half == 1 ? widen16<true>(g16[e0 + i])
+                                : p.g_half == 2 ? widen16<false>(g16[e0 + i]) : p.g[e0 + i];
                 val[i] = v;
                 lo = fminf(lo, v);
                 hi = fmaxf(hi, v);

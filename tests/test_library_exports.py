@@ -58,6 +58,13 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.qsdp_fused_step(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ok, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step(ok, ok, 10, float("inf"), 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step(ok, odd, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EALIGN
+    # 16-bit gradient entry points: only the two 2-byte formats are inputs; the decoders never write binary16
+    assert L.qsdp_quantize_grad_g16(ok, 0, 10, 8, 1024, 0, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad_g16(ok, 3, 10, 8, 1024, 0, 0, 0, ok, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_quantize_grad_g16(odd, 2, 10, 8, 1024, 0, 0, 0, ok, ok, None) == qb.QSDP_EALIGN
+    assert L.qsdp_fused_step_g16(ok, ok, 0, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_fused_step_g16(ok, ok, 1, 10, 1e-3, 8, 4, 1024, 0.0, 0, 4, 0, None, None, None, None) == qb.QSDP_EINVAL
+    assert L.qsdp_dequantize_segmented(ok, ok, ok, 1, 1, 8, 1024, 2, ok, None) == qb.QSDP_EINVAL
     assert qb.status_string(qb.QSDP_EALIGN).startswith("pointer")
 
 
