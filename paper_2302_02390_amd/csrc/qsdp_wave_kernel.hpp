@@ -1,0 +1,645 @@
+// Wave kernels: a bucket is owned by an aligned group of G lanes of one wave (or by the W waves
+// of a workgroup) and its values never leave registers. Layout and launch shape: see the
+// overview in qsdp_kernels.hpp.
+#pragma once
+
+#include "qsdp_params.hpp"
+
+namespace qsdp {
+
+// ---------------------------------------------------------------------------------------
+// Wave kernels
+// ---------------------------------------------------------------------------------------
+// Lane l's rows of a tile of 4*G*R elements at `base`. `m` = how many of the tile's elements
+// exist; `partial` (wave-uniform) selects the guarded element-wise path for a short bucket.
+template <int G, int R>
+__device__ __forceinline__ void load_rows(const float* base, int l, int m, bool partial, float (&v)[R][4]) {
+    if (!partial) {
+        const f4* p = reinterpret_cast<const f4*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const f4 a = __builtin_nontemporal_load(p + r * G);
+            v[r][0] = a[0]; v[r][1] = a[1]; v[r][2] = a[2]; v[r][3] = a[3];
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                v[r][i] = idx < m ? base[idx] : 0.0f;
+            }
+    }
+}
+
+// A 2-byte floating-point value widened to binary32 (exact in both formats): bf16 is the upper
+// half of the binary32 pattern, binary16 goes through the hardware conversion.
+template <bool BF16>
+__device__ __forceinline__ float widen16(uint32_t h) {
+    if (BF16) return __builtin_bit_cast(float, h << 16);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+
+// The same tile read from 2-byte values, 8 bytes per lane and row.
+template <int G, int R, bool BF16>
+__device__ __forceinline__ void load_rows_half(const uint16_t* base, int l, int m, bool partial, float (&v)[R][4]) {
+    if (!partial) {
+        const u2* p = reinterpret_cast<const u2*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const u2 a = __builtin_nontemporal_load(p + r * G);
+            v[r][0] = widen16<BF16>(a[0] & 0xFFFFu);
+            v[r][1] = widen16<BF16>(a[0] >> 16);
+            v[r][2] = widen16<BF16>(a[1] & 0xFFFFu);
+            v[r][3] = widen16<BF16>(a[1] >> 16);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                v[r][i] = idx < m ? widen16<BF16>(base[idx]) : 0.0f;
+            }
+    }
+}
+
+template <int G, int R>
+__device__ __forceinline__ void store_rows(float* base, int l, int m, bool partial, const float (&v)[R][4]) {
+    if (!partial) {
+        f4* p = reinterpret_cast<f4*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const f4 a = {v[r][0], v[r][1], v[r][2], v[r][3]};
+            __builtin_nontemporal_store(a, p + r * G);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                if (idx < m) base[idx] = v[r][i];
+            }
+    }
+}
+
+// min and max over the bucket (the group's G lanes); slots at or past m do not take part
+template <int G, int R>
+__device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m, bool partial, float& lo,
+                                            float& hi) {
+    if (!partial) {
+        lo = v[0][0];
+        hi = v[0][0];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo = fminf(lo, v[r][i]);
+                hi = fmaxf(hi, v[r][i]);
+            }
+    } else {
+        lo = __builtin_inff();
+        hi = -__builtin_inff();
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool valid = (r * G + l) * 4 + i < m;
+                lo = valid ? fminf(lo, v[r][i]) : lo;
+                hi = valid ? fmaxf(hi, v[r][i]) : hi;
+            }
+    }
+    lo = group_min<G>(lo);
+    hi = group_max<G>(hi);
+}
+
+// Slots at or past m (a short bucket) carry code 0. Only called on the guarded path.
+template <int G, int R, typename CodeT>
+__device__ __forceinline__ void zero_slots_past_end(CodeT (&c)[R][4], int l, int m) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((r * G + l) * 4 + i >= m) c[r][i] = CodeT(0);
+}
+
+// Pack the codes of all rows and stage them in LDS in wire order, then write the wave's code
+// tile (its 64/G buckets are consecutive, so the tile is 32*R*BITS contiguous bytes) with
+// 16-byte stores, one contiguous run per instruction. c[r][i] are the codes of this lane's
+// elements; `stage` is this wave's LDS tile; `tile_out` the tile's place in the code buffer;
+// buckets at or past `active_buckets` of the wave's 64/G are not written.
+template <int G, int R, int BITS, typename CodeT>
+__device__ __forceinline__ void store_codes(uint8_t* stage, u4* tile_out, int lane, int active_buckets,
+                                            const CodeT (&c)[R][4]) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;  // 16-byte pieces in the tile
+    const int l = lane % G;
+    const int sub = lane / G;
+    const int odd = l & 1;
+#pragma unroll
+    for (int cp = 0; cp < R / 2; ++cp) {
+        const uint32_t q0 = pack4<BITS>(c[2 * cp]);      // this lane's 4 codes of row 2cp
+        const uint32_t q1 = pack4<BITS>(c[2 * cp + 1]);  // ... of row 2cp+1
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(odd ? q0 : q1), 0xB1, 0xF,
+                                                                    0xF, false);
+        // even lane: chunk of row 2cp = own q0 (low half) | partner's q0; odd lane: chunk of
+        // row 2cp+1 = partner's q1 (low half) | own q1
+        const uint64_t chunk = odd ? ((uint64_t)recv | ((uint64_t)q1 << (4 * BITS)))
+                                   : ((uint64_t)q0 | ((uint64_t)recv << (4 * BITS)));
+        const int chunk_index = ((2 * cp + odd) * G + (l - odd)) >> 1;
+        store_chunk<BITS>(stage + sub * kBucketBytes + chunk_index * BITS, chunk);
+    }
+    // LDS traffic of one wave is processed in order; keep the compiler from reordering it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const u4* staged = reinterpret_cast<const u4*>(stage);
+#pragma unroll
+    for (int k0 = 0; k0 < kPieces; k0 += 64) {
+        const int k = k0 + lane;
+        if (k < kPieces && (k * 16) / kBucketBytes < active_buckets)
+            __builtin_nontemporal_store(staged[k], tile_out + k);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The reverse of store_codes, in two phases so that several tiles can be in flight: fetch the
+// wave's code tile with 16-byte loads (one piece per lane: 2*R*BITS <= 64 pieces), then stage
+// it in LDS and give every lane the codes of its own elements (as floats). The even lane reads
+// the chunk of row 2cp (its own 4 codes, then its partner's), the odd lane that of row 2cp+1
+// (its partner's 4 codes, then its own); one DPP quad permute hands each lane the half it lacks.
+template <int G, int R, int BITS>
+__device__ __forceinline__ u4 fetch_code_tile(const u4* tile_in, int lane, int active_buckets) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;
+    static_assert(kPieces <= 64, "one 16-byte piece per lane");
+    u4 piece = {0u, 0u, 0u, 0u};
+    if (lane < kPieces && (lane * 16) / kBucketBytes < active_buckets) piece = __builtin_nontemporal_load(tile_in + lane);
+    return piece;
+}
+
+template <int G, int R, int BITS>
+__device__ __forceinline__ void unstage_codes(uint8_t* stage, u4 piece, int lane, float (&c)[R][4]) {
+    constexpr int kBucketBytes = 4 * G * R * BITS / 8;
+    constexpr int kPieces = 2 * R * BITS;
+    constexpr uint32_t kHalfMask = (BITS == 8) ? 0xFFFFFFFFu : ((1u << (4 * BITS)) - 1u);
+    const int l = lane % G;
+    const int sub = lane / G;
+    const int odd = l & 1;
+    if (lane < kPieces) reinterpret_cast<u4*>(stage)[lane] = piece;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int cp = 0; cp < R / 2; ++cp) {
+        const int chunk_index = ((2 * cp + odd) * G + (l - odd)) >> 1;
+        const uint64_t chunk = load_chunk<BITS>(stage + sub * kBucketBytes + chunk_index * BITS);
+        const uint32_t lo4 = (uint32_t)chunk & kHalfMask;
+        const uint32_t hi4 = (uint32_t)(chunk >> (4 * BITS)) & kHalfMask;
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(odd ? lo4 : hi4), 0xB1, 0xF, 0xF,
+                                                                    false);
+        const uint32_t q0 = odd ? recv : lo4;  // this lane's 4 codes of row 2cp
+        const uint32_t q1 = odd ? hi4 : recv;  // ... of row 2cp+1
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            c[2 * cp][i] = (float)((q0 >> (i * BITS)) & ((1u << BITS) - 1u));
+            c[2 * cp + 1][i] = (float)((q1 >> (i * BITS)) & ((1u << BITS) - 1u));
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int G, int R, int BITS>
+__device__ __forceinline__ void load_codes(uint8_t* stage, const u4* tile_in, int lane, int active_buckets,
+                                           float (&c)[R][4]) {
+    unstage_codes<G, R, BITS>(stage, fetch_code_tile<G, R, BITS>(tile_in, lane, active_buckets), lane, c);
+}
+
+// The same two phases for a code width known only at run time (the peers' gradient codes of the
+// receive-side modes; wave-uniform `gb` in 1..8), so that those modes are not instantiated per
+// width. The tile (32*R*gb bytes) is staged as it is; lane l then cuts the 4*gb bits of its four
+// consecutive elements of a row out of the two staged words that hold them (the stage has a
+// spare word past the tile for the last lane's second read).
+template <int G, int R>
+__device__ __forceinline__ u4 fetch_code_tile_rt(const u4* tile_in, int lane, int active_buckets, int gb) {
+    const int pieces = 2 * R * gb;            // 16-byte pieces in the tile
+    const int bucket_bytes = G * R * gb / 2;  // 4*G*R codes of gb bits
+    u4 piece = {0u, 0u, 0u, 0u};
+    if (lane < pieces && lane * 16 < active_buckets * bucket_bytes) piece = __builtin_nontemporal_load(tile_in + lane);
+    return piece;
+}
+
+template <int G, int R>
+__device__ __forceinline__ void unstage_codes_rt(uint8_t* stage, u4 piece, int lane, int gb, float (&c)[R][4]) {
+    const int l = lane % G;
+    const int sub = lane / G;
+    if (lane < 2 * R * gb) reinterpret_cast<u4*>(stage)[lane] = piece;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(stage);
+    const uint32_t mask = (1u << gb) - 1u;
+    const uint32_t bit0 = (uint32_t)((sub * G * R + l) * 4 * gb);  // this lane's first code of row 0
+    const uint32_t row_bits = (uint32_t)(G * 4 * gb);             // wave-uniform
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t bit = bit0 + (uint32_t)r * row_bits;
+        const uint32_t w = bit >> 5;
+        // the 32 bits that start at `bit` (the 4*gb <= 32 bits of interest are its low part); a 64-bit
+        // shift measured 4 % faster here than v_alignbit_b32
+        const uint64_t two = (uint64_t)words[w] | ((uint64_t)words[w + 1] << 32);
+        const uint32_t q = (uint32_t)(two >> (bit & 31u));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[r][i] = (float)((q >> (i * gb)) & mask);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Combine per-wave (lo, hi) across the W waves of a workgroup that share a bucket. `slot` is a
+// [2][W] LDS array that no other reduction uses; callers alternate two slots between loop
+// iterations so that a fast wave's next write cannot overtake a slow wave's read.
+template <int W>
+__device__ __forceinline__ void block_combine_minmax(float& lo, float& hi, float* slot, uint32_t wave) {
+    if (W > 1) {
+        if ((threadIdx.x & 63) == 0) {
+            slot[wave] = lo;
+            slot[W + wave] = hi;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            lo = fminf(lo, slot[i]);
+            hi = fmaxf(hi, slot[W + i]);
+        }
+    }
+}
+
+// ghat-sum of the receive-side modes for the wave's tile: sum = ((d_0 + d_1) + d_2) + ..., d_k the
+// decoded slice of peer k. The tiles of up to kPeerGroup peers are in flight before the first is
+// unpacked. The peers' code width p.gbits is a run-time value here (compile-time unpacking of the
+// common widths next to the generic one, chosen by a wave-uniform branch, measured 15 % slower
+// than the generic path alone: three inlined copies of the loop cost registers).
+template <int G, int R>
+__device__ __forceinline__ void sum_peer_slices(const Params& p, uint8_t* stage, uint64_t tile_slot0,
+                                                uint64_t bucket, int lane, int active_buckets,
+                                                float (&sum)[R][4]) {
+    constexpr int kPeerGroup = 4;
+    const int gb = p.gbits;
+    const u4* gtile = reinterpret_cast<const u4*>(reinterpret_cast<const uint8_t*>(p.peer_codes) +
+                                                  (tile_slot0 >> 3) * (uint64_t)gb);
+    const uint64_t stride_u4 = p.peer_codes_stride_words >> 2;
+    for (int peer0 = 0; peer0 < p.npeers; peer0 += kPeerGroup) {
+        u4 piece[kPeerGroup];
+        float gbase[kPeerGroup], gscale[kPeerGroup];
+#pragma unroll
+        for (int k = 0; k < kPeerGroup; ++k) {
+            // past the last peer: re-read the last one (in bounds), its values are not used
+            const uint64_t peer = peer0 + k < p.npeers ? peer0 + k : p.npeers - 1;
+            piece[k] = fetch_code_tile_rt<G, R>(gtile + peer * stride_u4, lane, active_buckets, gb);
+            const float* pm = p.peer_meta + peer * p.peer_meta_stride_floats;
+            gbase[k] = pm[2 * bucket];
+            gscale[k] = pm[2 * bucket + 1];
+        }
+#pragma unroll
+        for (int k = 0; k < kPeerGroup; ++k) {
+            if (peer0 + k < p.npeers) {  // wave-uniform
+                float c[R][4];
+                unstage_codes_rt<G, R>(stage, piece[k], lane, gb, c);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float d = fmaf(c[r][i], gscale[k], gbase[k]);
+                        sum[r][i] = (peer0 + k == 0) ? d : sum[r][i] + d;
+                    }
+            }
+        }
+    }
+}
+
+// Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
+// be short). BITS is the width of the codes that are stored (0: a step without code output, or
+// MODE_SUM). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
+// per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
+// wave-uniform branches).
+template <int MODE, int G, int R, int BITS, int W>
+__global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
+    static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
+    static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
+    constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
+    constexpr int B = T * W;
+    constexpr int BPW = 64 / G;
+    constexpr int SB = BITS ? BITS : 8;  // only used when BITS != 0
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / G;
+    const int l = lane % G;
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t waves_per_block = blockDim.x >> 6;
+    // W == 1: a wave strides over groups of BPW buckets; W > 1: a workgroup strides over buckets
+    const uint64_t unit0 = W == 1 ? (uint64_t)blockIdx.x * waves_per_block + wave_in_block : blockIdx.x;
+    const uint64_t unit_stride = W == 1 ? (uint64_t)gridDim.x * waves_per_block : gridDim.x;
+    const uint64_t nunits = (p.num_buckets + BPW - 1) / BPW;
+
+    // LDS staging tile of the packed codes (stored, or read from the peers): 32*R*bits bytes per
+    // wave, up to 4 waves per block (the peers' tiles are at most 8 bits wide and take one spare
+    // 16-byte piece, see unstage_codes_rt)
+    constexpr bool kStaged = BITS != 0 || mode_reads_peers(MODE);
+    constexpr int kTileBytes = mode_reads_peers(MODE) ? 32 * R * 8 + 16 : 32 * R * SB;
+    __shared__ u4 stage_all[kStaged ? 4 * kTileBytes / 16 : 1];
+    uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
+    __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
+    uint32_t parity = 0;
+    // MODE_LEVELS: the level table in LDS. One table for the whole call is loaded once per
+    // workgroup; with one table per tensor every wave keeps the table of the tensor it works on
+    // in a slot of its own and reloads it when its buckets move on to another tensor.
+    __shared__ float level_tables[mode_is_levels(MODE) ? 4 * (1 << SB) : 1];
+    const bool levels_per_tensor = mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr;
+    const float* level_table = level_tables + (levels_per_tensor ? wave_in_block * (1u << SB) : 0u);
+    uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
+    if constexpr (mode_is_levels(MODE)) {
+        if (!levels_per_tensor) {
+            for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_tables[k] = p.levels[k];
+            __syncthreads();
+        }
+    }
+
+    const float Lg = (float)((1 << p.gbits) - 1);
+    const float Lw = (float)((1 << p.wbits) - 1);
+    const Divider div = {p.delta, p.inv_delta, p.delta_pow2 != 0};
+    const bool lattice = p.delta > 0.0f;
+    const bool symmetric = (p.flags & FLAG_SYMMETRIC) != 0;
+    const bool grad_shift = (p.flags & FLAG_GRAD_SHIFT) != 0;
+    constexpr bool kWritesX = MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE);
+    const bool keep_master = kWritesX && (p.flags & FLAG_KEEP_MASTER) != 0;
+    const PhiloxKey key = launch_key(p);
+    const Shifts shifts = draw_shifts(p, key, MODE != MODE_GRAD && !mode_is_levels(MODE) && MODE != MODE_SUM);
+    const float xi = shifts.xi;
+    uint32_t saturated = 0;
+
+    for (uint64_t q = unit0; q < nunits; q += unit_stride, parity ^= 1u) {
+        const uint64_t rel = q * BPW + sub;          // bucket within this launch
+        const bool active = rel < p.num_buckets;
+        const uint64_t left = p.num_buckets - q * BPW;
+        const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
+        const uint64_t bucket0 = p.first_bucket + q * BPW;  // wave-uniform
+        const uint64_t bucket = active ? p.first_bucket + rel : bucket0;
+        const BucketRef ref = locate_bucket(p, segs, bucket0, bucket, B);
+        // this wave's tile of the bucket: all of it, or the wave's 1/W
+        const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
+        const uint64_t e0 = ref.e0 + part0;
+        const int m = ref.m > part0 ? (int)(ref.m - part0 < (uint32_t)T ? ref.m - part0 : (uint32_t)T) : 0;
+        const bool partial = __builtin_amdgcn_ballot_w64(m < T) != 0;
+        // Philox block of the tile's first element; the tile's place in the code buffer (the
+        // code stream is indexed by bucket number, every bucket padded to B slots)
+        const uint64_t block_e0 = p.block0 + (e0 >> 3);
+        const uint64_t tile_slot0 = (W == 1 ? (p.first_bucket + q * BPW) * (uint64_t)B
+                                            : bucket * (uint64_t)B + part0);
+        u4* tile_out = reinterpret_cast<u4*>(reinterpret_cast<uint8_t*>(p.codes) + (tile_slot0 >> 3) * SB);
+        float* red_g = red_all + (W > 1 ? parity * 4 * W : 0);
+        float* red_w = red_g + (W > 1 ? 2 * W : 0);
+        const bool writes_meta = active && l == 0 && (W == 1 || wave_in_block == 0);
+
+        float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
+        float base = 0.0f, scale = 0.0f;
+
+        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
+            float gv[R][4];
+            uint32_t gcode[R][4];  // MODE_GRAD only
+            float mom[R][4], var[R][4];  // MODE_ADAMW only
+            if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 1)
+                load_rows_half<G, R, true>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
+            else if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 2)
+                load_rows_half<G, R, false>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
+            else
+                load_rows<G, R>(p.g + e0, l, m, partial, gv);
+            if (MODE == MODE_FUSED || MODE == MODE_ADAMW) load_rows<G, R>(p.x + e0, l, m, partial, w);
+            if constexpr (MODE == MODE_ADAMW) {
+                load_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                load_rows<G, R>(p.var + e0, l, m, partial, var);
+            }
+            if constexpr (MODE == MODE_FUSED_CODES) {
+                // x = decode(codes, meta) in registers
+                load_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
+                const float xbase = p.meta[2 * bucket];
+                const float xscale = p.meta[2 * bucket + 1];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], xscale, xbase);
+            }
+            float lo, hi;
+            rows_minmax<G, R>(gv, l, m, partial, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_g, wave_in_block);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lg, symmetric);
+            // base of the decoded gradient: lo, or lo + xi_g * scale for the shared-shift variant
+            const float gbase = grad_shift ? fmaf(shifts.xi_g, grid.scale, grid.lo) : grid.lo;
+            if (grad_shift) {
+                // random-shift quantizer on the gradient: nothing is drawn per element
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float code = weight_code_minmax(gv[r][i], grid, Lg, shifts.xi_g);
+                        if constexpr (MODE == MODE_GRAD) {
+                            gcode[r][i] = (uint32_t)code;
+                        } else {
+                            const float ghat = fmaf(code, grid.scale, gbase);
+                            w[r][i] = step_value<MODE>(p, w[r][i], ghat, mom[r][i], var[r][i]);
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int cp = 0; cp < R / 2; ++cp) {
+                    float h[8];
+                    grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int r = 2 * cp + (i >> 2);
+                        if constexpr (MODE == MODE_GRAD) {
+                            gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
+                        } else {
+                            const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
+                            const float ghat = fmaf(code, grid.scale, grid.lo);
+                            w[r][i & 3] = step_value<MODE>(p, w[r][i & 3], ghat, mom[r][i & 3], var[r][i & 3]);
+                        }
+                    }
+                }
+            }
+            if constexpr (MODE == MODE_ADAMW) {
+                if (active) {
+                    store_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                    store_rows<G, R>(p.var + e0, l, m, partial, var);
+                }
+            }
+            if constexpr (MODE == MODE_GRAD) {
+                if (partial) zero_slots_past_end<G, R>(gcode, l, m);
+                store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
+                if (writes_meta) {
+                    p.meta[2 * bucket] = gbase;
+                    p.meta[2 * bucket + 1] = grid.scale;
+                }
+                continue;
+            }
+        } else if constexpr (MODE == MODE_SUM) {
+            // out (passed in p.x) = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k
+            sum_peer_slices<G, R>(p, stage, tile_slot0, bucket, lane, active_buckets, w);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[r][i] = p.alpha * w[r][i];
+            if (active) store_rows<G, R>(p.x + e0, l, m, partial, w);
+            continue;
+        } else if constexpr (mode_is_recv(MODE)) {
+            // ghat = alpha * (((d_0 + d_1) + d_2) + ...), d_k = decoded slice of peer k
+            load_rows<G, R>(p.x + e0, l, m, partial, w);
+            float mom[R][4], var[R][4];  // MODE_RECV_ADAMW only
+            if constexpr (MODE == MODE_RECV_ADAMW) {
+                load_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                load_rows<G, R>(p.var + e0, l, m, partial, var);
+            }
+            float sum[R][4];
+            sum_peer_slices<G, R>(p, stage, tile_slot0, bucket, lane, active_buckets, sum);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    w[r][i] = step_value<MODE>(p, w[r][i], p.alpha * sum[r][i], mom[r][i], var[r][i]);
+            if constexpr (MODE == MODE_RECV_ADAMW) {
+                if (active) {
+                    store_rows<G, R>(p.mom + e0, l, m, partial, mom);
+                    store_rows<G, R>(p.var + e0, l, m, partial, var);
+                }
+            }
+        } else {
+            load_rows<G, R>(p.xin + e0, l, m, partial, w);
+        }
+
+        // the full-precision partition keeps the updated value itself (stored before w turns into codes)
+        if (kWritesX && keep_master && active) store_rows<G, R>(p.x + e0, l, m, partial, w);
+
+        // weight quantization of w
+        if constexpr (mode_is_levels(MODE)) {
+            float lo, hi;
+            rows_minmax<G, R>(w, l, m, partial, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);  // scale = hi - lo, inv = 1/(hi - lo)
+            base = grid.lo;
+            scale = grid.scale;
+            // One pass per distinct tensor among the wave's buckets (one pass, unless the buckets
+            // straddle tensors): every lane computes, the lanes of the pass's tensor replace their
+            // values by the codes (a lane belongs to exactly one pass; what it computes in the others,
+            // from values or from codes, is dropped). All lanes stay converged (the uniforms are
+            // exchanged between lanes).
+            uint64_t pending = ~0ull;
+            do {
+                bool mine = true;
+                if (levels_per_tensor) {
+                    const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)ref.tensor, __builtin_ctzll(pending));
+                    mine = ref.tensor == cur;
+                    if (cur != loaded_tensor) {
+                        float* slot = level_tables + wave_in_block * (1u << SB);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slot are done
+                        __builtin_amdgcn_wave_barrier();
+                        for (int k = lane; k < (1 << SB); k += 64) slot[k] = p.levels[(uint64_t)cur * (1u << SB) + k];
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        loaded_tensor = cur;
+                    }
+                }
+                if constexpr (MODE == MODE_LEVELS_COIN) {
+#pragma unroll
+                    for (int cp = 0; cp < R / 2; ++cp) {
+                        float h[8];
+                        grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const int r = 2 * cp + (i >> 2);
+                            const float z = (w[r][i & 3] - grid.lo) * grid.inv;
+                            const float c = (float)stochastic_level<SB>(z, h[i], level_table);
+                            w[r][i & 3] = mine ? c : w[r][i & 3];
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float z = (w[r][i] - grid.lo) * grid.inv;
+                            const float c = (float)nearest_level<SB>(z, level_table);
+                            w[r][i] = mine ? c : w[r][i];
+                        }
+                }
+                pending &= ~__builtin_amdgcn_ballot_w64(mine);
+            } while (pending != 0);
+        } else if (lattice) {
+            float lo, unused_hi;
+            rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
+            block_combine_minmax<W>(lo, unused_hi, red_w, wave_in_block);
+            lo = lo + 0.0f;
+            const float k0 = rintf(div_delta(lo, div) - xi);
+            base = (k0 + xi) * p.delta;
+            scale = p.delta;
+            uint32_t sat_here = 0;
+            if (!partial) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[r][i] = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_here);
+            } else {  // short bucket: slots past the end neither count as saturated nor carry a code
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        uint32_t sat_one = 0;
+                        const float c = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_one);
+                        const bool valid = (r * G + l) * 4 + i < m;
+                        w[r][i] = valid ? c : 0.0f;
+                        sat_here += valid ? sat_one : 0u;
+                    }
+            }
+            if (active) saturated += sat_here;
+        } else {
+            float lo, hi;
+            rows_minmax<G, R>(w, l, m, partial, lo, hi);
+            block_combine_minmax<W>(lo, hi, red_w, wave_in_block);
+            const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw, symmetric);
+            base = fmaf(xi, grid.scale, grid.lo);
+            scale = grid.scale;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
+        }
+        if (partial && BITS != 0) zero_slots_past_end<G, R>(w, l, m);
+
+        if (BITS != 0) {
+            store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
+            if (writes_meta) {
+                p.meta[2 * bucket] = base;
+                p.meta[2 * bucket + 1] = scale;
+            }
+        }
+        if (active && !keep_master) {
+            if (kWritesX) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], scale, base);
+                store_rows<G, R>(p.x + e0, l, m, partial, w);
+            }
+        }
+    }
+
+    if (MODE != MODE_GRAD && p.n_saturated != nullptr) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) saturated += __shfl_down(saturated, off, 64);
+        if (lane == 0 && saturated != 0) atomicAdd(p.n_saturated, (unsigned long long)saturated);
+    }
+}
+
+}  // namespace qsdp
