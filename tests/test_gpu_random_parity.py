@@ -1,7 +1,8 @@
 """Randomised GPU parity against the oracle: seeded random cases over every family of entry
 points (sizes, bucket sizes with and without a wave kernel, code widths, explicit grids that are
 not powers of two, variant flags, seeds, offsets; Gaussian, heavy-tailed, huge and tiny, sparse and
-nearly constant data). A longer run of the same generator (144,000 cases) found no mismatch."""
+nearly constant data; 16-bit gradients; per-tensor level tables). Longer runs of the same generator
+(144,000 cases, and 101,000 more after the last two families were added) found no mismatch."""
 import numpy as np
 import pytest
 import torch
@@ -59,7 +60,7 @@ def one_case(rng):
     keep = KEEP if rng.random() < 0.3 else 0
     x, g = data(rng, n, int(rng.integers(0, 5))), data(rng, n, int(rng.integers(0, 5)))
     xd, gd = torch.from_numpy(x).to(DEV), torch.from_numpy(g).to(DEV)
-    which = int(rng.integers(0, 7))
+    which = int(rng.integers(0, 9))
     tag = (which, n, B, wbits, gbits, delta, seed, off, flags, keep)
     sat = torch.zeros(1, dtype=torch.int64, device=DEV)
     if which == 0:
@@ -122,6 +123,51 @@ def one_case(rng):
                                                        B, delta, seed, off, flags | keep, True)
         assert eq(np_f32(xd), wx) and eq(np_f32(md), wmo) and eq(np_f32(vd), wvo), tag
         assert eq(np_u32(c), wc) and eq(np_u32(m), wm), tag
+    elif which == 7:
+        # gradient handed over in 16 bits: the oracle sees the values widened by torch on the CPU
+        dt = torch.float16 if rng.random() < 0.5 else torch.bfloat16
+        g16 = torch.from_numpy(g).to(dt)
+        wide = g16.float().numpy()
+        if not np.all(np.isfinite(wide)):
+            return
+        if rng.random() < 0.5:
+            c, m = qb.alloc_packed(n, gbits, B, DEV)
+            qb.qsdp_quantize_grad_g16(g16.to(DEV), gbits, B, seed, off, c, m.reshape(-1), flags)
+            wc, wm = ref.quantize_grad(wide, gbits, B, seed, off, flags)
+            assert eq(np_u32(c), wc) and eq(np_u32(m), wm), tag
+        else:
+            c, m = qb.alloc_packed(n, wbits, B, DEV)
+            qb.qsdp_fused_step_g16(xd, g16.to(DEV), 1e-3, wbits, gbits, B, delta, seed, off, flags | keep, c,
+                                   m.reshape(-1), sat)
+            wx, wc, wm, ws = ref.fused_step(x, wide, 1e-3, wbits, gbits, B, delta, seed, off, True, flags | keep)
+            assert eq(np_f32(xd), wx) and eq(np_u32(c), wc) and eq(np_u32(m), wm) and int(sat) == ws, tag
+    elif which == 8:
+        # several tensors in one buffer, each with a level table of its own
+        nseg = int(rng.integers(1, 7))
+        sizes = [int(rng.integers(1, 6 * B // 8 + 2)) * 8 for _ in range(nseg - 1)] + [int(rng.integers(1, 5 * B))]
+        total = sum(sizes)
+        v = data(rng, total, int(rng.integers(0, 3)))
+        segs = qb.Segments(sizes, B, DEV)
+        tables = np.sort(rng.random((nseg, 1 << wbits)), axis=1).astype(np.float32)
+        tables[::2, 0], tables[::2, -1] = 0.0, 1.0
+        lvd = torch.from_numpy(tables).to(DEV)
+        stochastic = rng.random() < 0.5
+        c, m = segs.alloc_packed(wbits)
+        qb.qsdp_quantize_levels_segmented(torch.from_numpy(v).to(DEV), segs, wbits, lvd, c, m.reshape(-1), stochastic,
+                                          seed, off)
+        wcs, wms, outs, o0 = [], [], [], 0
+        for t, sz in enumerate(sizes):
+            if stochastic:
+                wc, wm = ref.quantize_levels_stochastic(v[o0:o0 + sz], wbits, B, tables[t], seed, off + o0)
+            else:
+                wc, wm = ref.quantize_levels(v[o0:o0 + sz], wbits, B, tables[t])
+            wcs.append(wc); wms.append(wm.reshape(-1))
+            outs.append(ref.dequantize_levels(wc, wm, sz, wbits, B, tables[t]))
+            o0 += sz
+        assert eq(np_u32(c), np.concatenate(wcs)) and eq(np_u32(m), np.concatenate(wms)), tag + (sizes,)
+        o = torch.empty(total, dtype=torch.float32, device=DEV)
+        qb.qsdp_dequantize_levels_segmented(c, m.reshape(-1), segs, wbits, lvd, o)
+        assert eq(np_f32(o), np.concatenate(outs)), tag + (sizes,)
     else:
         lv = np.sort(rng.random(1 << wbits)).astype(np.float32)
         if rng.random() < 0.5:
