@@ -114,7 +114,10 @@ def main():
         return 0
 
     if a.levels_report:
-        print(json.dumps(levels_report(torch, qb, x, g, n, a.workload, bucket, dev)))
+        rep = levels_report(torch, qb, x, g, n, a.workload, bucket, dev)
+        if a.workload != "1m":
+            rep["per_layer_W5G4"] = levels_per_layer(torch, qb, wl, x, g, shape, bucket, dev)
+        print(json.dumps(rep))
         return 0
 
     if a.segmented:
@@ -264,6 +267,36 @@ def levels_report(torch, qb, x, g, n, workload, bucket, dev):
             del codes, meta
     return {"metric": "relative L2 compression error, uniform vs fitted levels", "workload": workload, "n": n,
             "bucket": bucket, "data": "synthetic", "levels": rows}
+
+
+def levels_per_layer(torch, qb, wl, x, g, shape, bucket, dev):
+    """The learned-level pipeline the way Section 5.2 / Appendix C run it: every layer tensor of the model has a
+    table of its own, fitted on that tensor (tensors of at most 1e5 elements keep the uniform table); W5 for the
+    weights, G4 with the unbiased coin flip for the gradients; fit, encode and decode are one launch each over
+    all tensors."""
+    sizes = [size for _, size in wl.model_tensors(shape)]
+    n = sum(sizes)
+    segs = qb.Segments(sizes, bucket, dev)
+    small = torch.tensor([s <= 100000 for s in sizes], device=dev)
+    out = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    res = {"tensors": len(sizes), "tensors_with_fitted_table": int((~small).sum()), "fit_batches_per_tensor": 1024}
+    for name, v, bits, coin in (("weights_W5", x, 5, False), ("gradients_G4", g, 4, True)):
+        uniform = qb.levels_uniform(bits, dev)
+        tables = uniform.repeat(len(sizes), 1).contiguous()
+        fit_ms, _ = time_call(lambda i: qb.qsdp_fit_levels_segmented(v, segs, bits, 0.01, tables, 1024), 1, torch)
+        tables[small] = uniform
+        codes, meta = segs.alloc_packed(bits)
+        meta = meta.reshape(-1)
+        enc_ms, _ = time_call(lambda i: qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, i, 0),
+                              5, torch)
+        dec_ms, _ = time_call(lambda i: qb.qsdp_dequantize_levels_segmented(codes, meta, segs, bits, tables, out), 5,
+                              torch)
+        res[name] = {"fit_ms": round(fit_ms, 3), "encode_ms": round(enc_ms, 4), "decode_bf16_ms": round(dec_ms, 4),
+                     "encode_GB/s": round((4 + bits / 8 + 8 / bucket) * n / enc_ms / 1e6, 1),
+                     "decode_GB/s": round((2 + bits / 8 + 8 / bucket) * n / dec_ms / 1e6, 1),
+                     "rounding": "coin flip between the enclosing levels" if coin else "nearest level"}
+        del codes, meta
+    return res
 
 
 def sweep(torch, qb, wl, x, g, n, workload, dev):
