@@ -149,3 +149,31 @@ def test_segmented_codec_on_the_1p3b_layer_list(gpt1p3b):
             assert np.array_equal(u32(codes[j * wpb:(j + 1) * wpb].cpu().numpy()), wc), (t, lb)
             assert np.array_equal(u32(meta[j].cpu().numpy()), u32(wm_).reshape(-1)), (t, lb)
             assert bits_equal(out[lo:hi].cpu().numpy(), ref.dequantize(wc, wm_, hi - lo, 8, B)), (t, lb)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_16bit_gradient_steps_on_the_full_vector(gpt1p3b, dtype):
+    """Two fused steps (W8 G4, seed = step index) and the 4-bit gradient encoding with the gradient handed over
+    in 16 bits; the oracle gets the sampled buckets widened by torch on the CPU."""
+    n, x0, g = gpt1p3b
+    ids = sample_bucket_ids(n // B, 150, 24)
+    g16 = g.to(dtype)
+    gh = g16.view(torch.int16)
+    wide = torch.from_numpy(gather_rows(gh, ids, B)).view(dtype).float().numpy()
+    x = x0.clone()
+    for step in range(2):
+        xb = gather_rows(x, ids, B)
+        qb.qsdp_fused_step_g16(x, g16, 1e-3, 8, 4, B, 0.0, step)
+        xa = gather_rows(x, ids, B)
+        for r, j in enumerate(ids):
+            want, _, _, _ = ref.fused_step(xb[r], wide[r], 1e-3, 8, 4, B, 0.0, step, index_offset=int(j) * B)
+            assert bits_equal(xa[r], want), (step, int(j))
+    del x
+    gc, gm = qb.alloc_packed(n, 4, B, DEV)
+    qb.qsdp_quantize_grad_g16(g16, 4, B, 5, 0, gc, gm.reshape(-1))
+    cs, ms = u32(gather_rows(gc, ids, B * 4 // 32)), u32(gather_rows(gm.reshape(-1), ids, 2))
+    for r, j in enumerate(ids):
+        want_c, want_m = ref.quantize_grad(wide[r], 4, B, 5, index_offset=int(j) * B)
+        assert np.array_equal(cs[r], want_c) and np.array_equal(ms[r], u32(want_m).reshape(-1)), int(j)
+    del g16, gc, gm
+    torch.cuda.empty_cache()
