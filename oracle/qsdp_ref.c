@@ -276,6 +276,41 @@ uint16_t qsdp_ref_f32_to_bf16(float v) {
     return (uint16_t)(bitsv >> 16);
 }
 
+/* binary32 -> IEEE binary16, round to nearest even: subnormal results kept, values beyond the
+ * largest finite half (65504 + half an ulp) become infinity. The half-precision format of the
+ * paper's mixed-precision setting (Section 6, experimental setup). */
+uint16_t qsdp_ref_f32_to_f16(float v) {
+    uint32_t b;
+    memcpy(&b, &v, sizeof b);
+    uint32_t sign = (b >> 16) & 0x8000u;
+    uint32_t mag = b & 0x7FFFFFFFu;
+    if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u); /* NaN */
+    if (mag == 0x7F800000u) return (uint16_t)(sign | 0x7C00u);
+    int e = (int)(mag >> 23);
+    if (e == 0) return (uint16_t)sign;            /* below 2^-126: far under half the smallest half subnormal */
+    uint32_t m = (mag & 0x7FFFFFu) | 0x800000u;   /* |v| = m * 2^(e-150), m has 24 bits */
+    int he = e - 127 + 15;                        /* biased half exponent if the result is normal */
+    int drop = he >= 1 ? 13 : 13 + (1 - he);      /* low bits of m that do not fit (subnormals lose more) */
+    if (drop > 24) return (uint16_t)sign;         /* |v| < 2^-25: rounds to zero */
+    uint32_t q = m >> drop;
+    uint32_t rem = m & ((1u << drop) - 1u);
+    uint32_t half = 1u << (drop - 1);
+    if (rem > half || (rem == half && (q & 1u))) q += 1u;
+    /* normal: q carries the implicit one in bit 10, so adding it to (he-1)<<10 also lets a
+     * rounding carry move into the exponent; subnormal: q is the result (0x400 = smallest normal) */
+    uint32_t h = he >= 1 ? ((uint32_t)(he - 1) << 10) + q : q;
+    if (h >= 0x7C00u) h = 0x7C00u;
+    return (uint16_t)(sign | h);
+}
+
+static uint16_t to_half_format(float v, int out_dtype) {
+    return out_dtype == QSDP_REF_F16 ? qsdp_ref_f32_to_f16(v) : qsdp_ref_f32_to_bf16(v);
+}
+
+static int out_dtype_ok(int out_dtype) {
+    return out_dtype == QSDP_REF_F32 || out_dtype == QSDP_REF_BF16 || out_dtype == QSDP_REF_F16;
+}
+
 static int bucket_len(uint64_t n, int bucket, uint64_t j) {
     uint64_t start = j * (uint64_t)bucket;
     uint64_t rest = n - start;
@@ -411,7 +446,7 @@ int qsdp_ref_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket
 int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                         int bucket, int out_dtype, void* out) {
     if (!codes || !meta || !out || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
-    if (out_dtype != QSDP_REF_F32 && out_dtype != QSDP_REF_BF16) return QSDP_REF_EINVAL;
+    if (!out_dtype_ok(out_dtype)) return QSDP_REF_EINVAL;
     int64_t nb = (int64_t)num_buckets(n, bucket);
     int wpb = bucket * bits / 32;
 #pragma omp parallel for schedule(static) num_threads(g_threads)
@@ -425,7 +460,7 @@ int qsdp_ref_dequantize(const uint32_t* codes, const float* meta, uint64_t n, in
         if (out_dtype == QSDP_REF_F32) {
             for (int i = 0; i < m; ++i) ((float*)out)[s + (uint64_t)i] = val[i];
         } else {
-            for (int i = 0; i < m; ++i) ((uint16_t*)out)[s + (uint64_t)i] = qsdp_ref_f32_to_bf16(val[i]);
+            for (int i = 0; i < m; ++i) ((uint16_t*)out)[s + (uint64_t)i] = to_half_format(val[i], out_dtype);
         }
     }
     return QSDP_REF_OK;
@@ -695,7 +730,7 @@ int qsdp_ref_quantize_levels_u(const float* v, uint64_t n, int bits, int bucket,
 int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits,
                                int bucket, const float* levels, int out_dtype, void* out) {
     if (!codes || !meta || !levels || !out || !args_ok(n, bits, bucket)) return QSDP_REF_EINVAL;
-    if (out_dtype != QSDP_REF_F32 && out_dtype != QSDP_REF_BF16) return QSDP_REF_EINVAL;
+    if (!out_dtype_ok(out_dtype)) return QSDP_REF_EINVAL;
     int64_t nb = (int64_t)num_buckets(n, bucket);
     int wpb = bucket * bits / 32;
 #pragma omp parallel for schedule(static) num_threads(g_threads)
@@ -707,7 +742,7 @@ int qsdp_ref_dequantize_levels(const uint32_t* codes, const float* meta, uint64_
         for (int i = 0; i < m; ++i) {
             float val = fmaf(levels[code[i]], meta[2 * j + 1], meta[2 * j]);
             if (out_dtype == QSDP_REF_F32) ((float*)out)[s + (uint64_t)i] = val;
-            else ((uint16_t*)out)[s + (uint64_t)i] = qsdp_ref_f32_to_bf16(val);
+            else ((uint16_t*)out)[s + (uint64_t)i] = to_half_format(val, out_dtype);
         }
     }
     return QSDP_REF_OK;

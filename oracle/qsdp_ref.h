@@ -37,7 +37,7 @@ extern "C" {
 #endif
 
 enum { QSDP_REF_OK = 0, QSDP_REF_EINVAL = -1 };
-enum { QSDP_REF_F32 = 0, QSDP_REF_BF16 = 1 };
+enum { QSDP_REF_F32 = 0, QSDP_REF_BF16 = 1, QSDP_REF_F16 = 2 };
 
 /* Quantizer variants the paper names as admissible (flags of the *_ex routines):
  *  GRAD_SHIFT  gradients are quantized by random shift too (the appendix observes that the
@@ -91,6 +91,8 @@ int qsdp_ref_quantize_weight_xi_ex(const float* x, uint64_t n, int bits, int buc
 void qsdp_ref_pack(const uint8_t* codes, uint64_t n, int bits, int bucket, uint32_t* words);
 void qsdp_ref_unpack(const uint32_t* words, uint64_t n, int bits, int bucket, uint8_t* codes);
 uint16_t qsdp_ref_f32_to_bf16(float v);
+/* binary32 -> IEEE binary16, round to nearest even, subnormals kept, overflow to infinity. */
+uint16_t qsdp_ref_f32_to_f16(float v);
 
 /* --- the four operations, same meaning as the library's entry points, on host
  * pointers, synchronous --- */

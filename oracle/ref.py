@@ -12,7 +12,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 FLAG_GRAD_SHIFT, FLAG_NO_SHIFT, FLAG_SYMMETRIC, FLAG_KEEP_MASTER = 1, 2, 4, 8
 
 _lib = None
@@ -54,6 +54,8 @@ def lib():
         L.qsdp_ref_unpack.restype = None
         L.qsdp_ref_f32_to_bf16.argtypes = [f32]
         L.qsdp_ref_f32_to_bf16.restype = C.c_uint16
+        L.qsdp_ref_f32_to_f16.argtypes = [f32]
+        L.qsdp_ref_f32_to_f16.restype = C.c_uint16
         L.qsdp_ref_quantize_grad.argtypes = [vp, u64, i32, i32, u64, u64, vp, vp]
         L.qsdp_ref_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp]
         L.qsdp_ref_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp]
@@ -172,6 +174,10 @@ def f32_to_bf16(v):
     return int(lib().qsdp_ref_f32_to_bf16(float(v)))
 
 
+def f32_to_f16(v):
+    return int(lib().qsdp_ref_f32_to_f16(float(v)))
+
+
 def quantize_grad(g, bits, bucket, seed, index_offset=0, flags=0):
     """Returns (packed codes u32[...], meta f32[nb,2])."""
     g = _f32(g)
@@ -196,7 +202,7 @@ def quantize_weight(x, bits, bucket, delta, seed, flags=0):
 
 
 def dequantize(codes, meta, n, bits, bucket, out_dtype=F32):
-    """Returns f32[n], or the bf16 bit patterns as u16[n]."""
+    """Returns f32[n], or the bf16 / binary16 bit patterns as u16[n]."""
     codes = np.ascontiguousarray(codes, dtype=np.uint32).reshape(-1)
     meta = np.ascontiguousarray(meta, dtype=np.float32).reshape(-1)
     assert codes.size * 4 == codes_bytes(n, bits, bucket)

@@ -67,6 +67,41 @@ def test_bf16_rounding_against_torch_exhaustively():
         assert np.array_equal(got, want)
 
 
+def test_f16_rounding_against_numpy_and_torch_on_every_half_boundary():
+    """Every finite non-negative binary16 value h, the midpoint to its successor (a tie), and the float32
+    neighbours of that midpoint, both signs; plus the overflow boundary, tiny values and a random sweep."""
+    h = np.arange(0x7C00, dtype=np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    nxt = np.append(lo[1:], 65536.0)                      # the value after 65504 would be 65536
+    mid = ((lo + nxt) / 2).astype(np.float32)             # exact in float32 (12 significant bits)
+    cases = np.concatenate([lo.astype(np.float32), mid, np.nextafter(mid, np.float32(0)),
+                            np.nextafter(mid, np.float32(np.inf)),
+                            np.float32([1e-10, 2.0 ** -25, 2.0 ** -24, 3e-8, 65519.9, 65520.0, 70000.0, 3e38])])
+    rng = np.random.default_rng(5)
+    cases = np.concatenate([cases, (rng.standard_normal(20000) * 10.0 ** rng.integers(-9, 6, 20000)).astype(np.float32)])
+    cases = np.concatenate([cases, -cases])
+    with np.errstate(over="ignore"):
+        want = cases.astype(np.float16).view(np.uint16)
+    got = np.array([ref.f32_to_f16(v) for v in cases], dtype=np.uint16)
+    assert np.array_equal(got, want)
+    want_t = torch.from_numpy(cases).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want_t)
+
+
+def test_dequantize_f16_output():
+    rng = np.random.default_rng(2)
+    x = (rng.normal(size=1000) * 0.02).astype(np.float32)
+    x[:4] = [6e-8, -3e-6, 1e-5, 0.0]                      # binary16 subnormals among the decoded values
+    c, m, _ = ref.quantize_weight(x, 8, 128, 0.0, 3)
+    f = ref.dequantize(c, m, x.size, 8, 128, ref.F32)
+    h = ref.dequantize(c, m, x.size, 8, 128, ref.F16)
+    assert np.array_equal(h, f.astype(np.float16).view(np.uint16))
+    lv = np.sort(rng.random(16)).astype(np.float32)
+    cl, ml = ref.quantize_levels(x, 4, 128, lv)
+    hl = ref.dequantize_levels(cl, ml, x.size, 4, 128, lv, ref.F16)
+    assert np.array_equal(hl, ref.dequantize_levels(cl, ml, x.size, 4, 128, lv).astype(np.float16).view(np.uint16))
+
+
 def test_dequantize_bf16_output():
     rng = np.random.default_rng(1)
     x = (rng.normal(size=1000) * 0.02).astype(np.float32)

@@ -31,6 +31,13 @@ MUTANTS = [
     ("pack_bits_reversed", "words[p / 32] |= (uint32_t)1u << (p % 32);", "words[p / 32] |= (uint32_t)1u << (31 - p % 32);",
      ["test_oracle_codec.py"]),
     ("bf16_truncates", "bitsv += 0x7FFFu + ((bitsv >> 16) & 1u);", "", ["test_oracle_codec.py"]),
+    ("f16_ties_round_up", "if (rem > half || (rem == half && (q & 1u))) q += 1u;", "if (rem >= half) q += 1u;",
+     ["test_oracle_codec.py"]),
+    ("f16_subnormals_flushed", "int drop = he >= 1 ? 13 : 13 + (1 - he);", "if (he < 1) return (uint16_t)sign;\n    int drop = 13;",
+     ["test_oracle_codec.py"]),
+    ("f16_overflow_saturates", "if (h >= 0x7C00u) h = 0x7C00u;", "if (h >= 0x7C00u) h = 0x7BFFu;", ["test_oracle_codec.py"]),
+    ("f16_output_written_as_bf16", "return out_dtype == QSDP_REF_F16 ? qsdp_ref_f32_to_f16(v) : qsdp_ref_f32_to_bf16(v);",
+     "return qsdp_ref_f32_to_bf16(v);", ["test_oracle_codec.py"]),
     ("decode_not_fused", "out[i] = fmaf((float)code[i], scale, base);", "out[i] = (float)code[i] * scale + base;",
      ["test_oracle_codec.py"]),
     ("peer_sum_keeps_last_only", "sum[i] = (p == 0) ? val[i] : sum[i] + val[i];", "sum[i] = val[i];",
