@@ -410,6 +410,10 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"dequantize_b{gbits}_bf16", lambda i: qb.qsdp_dequantize(gc, gm, n, gbits, bucket, out16),
         2 + gbits / 8.0 + meta_b)
     del out16
+    outh = torch.empty(n, dtype=torch.float16, device=dev)
+    run(f"dequantize_b{wbits}_f16", lambda i: qb.qsdp_dequantize(wc, wm, n, wbits, bucket, outh),
+        2 + wbits / 8.0 + meta_b)
+    del outh
     # the fused step with x resident as codes (wc, wm hold Q^w(x) from the call above)
     run(f"fused_step_codes_W{wbits}G{gbits}",
         lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i),

@@ -61,8 +61,8 @@ enum {
     QSDP_ELAUNCH = -3  /* the HIP runtime refused the launch */
 };
 
-/* QSDP_F16 (IEEE binary16) is an INPUT format of the *_g16 entry points only; the decoders write
- * QSDP_F32 or QSDP_BF16. */
+/* Formats of decoded output (all three) and of 16-bit gradient input (QSDP_BF16, QSDP_F16).
+ * QSDP_F16 is IEEE binary16, the half precision of the paper's mixed-precision setting. */
 typedef enum { QSDP_F32 = 0, QSDP_BF16 = 1, QSDP_F16 = 2 } qsdp_dtype;
 
 /* Version of the arithmetic/wire specification implemented (2: 16-bit uniforms, 8 per
@@ -110,8 +110,10 @@ int qsdp_quantize_weight(const float* x, uint64_t n, int bits, int bucket,
  * Decoding (the inverse map of Section 4.1: lattice coordinate back to a value, shift
  * included; what a worker does with a gathered quantized layer in Algorithm 2):
  * out[i] = fma(code_i, scale_j, base_j),
- * stored as float (QSDP_F32) or rounded to nearest-even bfloat16 (QSDP_BF16). Serves both
- * quantizers. Elements past n are not written.
+ * stored as float (QSDP_F32) or rounded to nearest-even bfloat16 (QSDP_BF16) or IEEE binary16
+ * (QSDP_F16: subnormal results kept, magnitudes beyond 65504 + half an ulp become infinity); the
+ * same three formats hold for every decoding entry point below. Serves both quantizers. Elements
+ * past n are not written.
  *   out  out  device float[n] or uint16[n]
  */
 int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits,

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqsdp.so")
 
 QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
-QSDP_F32, QSDP_BF16 = 0, 1
+QSDP_F32, QSDP_BF16, QSDP_F16 = 0, 1, 2
 QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC, QSDP_FLAG_KEEP_MASTER = 1, 2, 4, 8
 
 EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
@@ -165,6 +165,14 @@ def _is(t, dtype):
         raise TypeError(f"expected a contiguous {dtype} tensor on the GPU")
 
 
+def _out_dtype(out):
+    """The decoders' output formats: float32, bfloat16 or float16 (IEEE binary16)."""
+    dt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16, torch.float16: QSDP_F16}.get(out.dtype)
+    if dt is None:
+        raise TypeError("out must be float32, bfloat16 or float16")
+    return dt
+
+
 def _is_rows(t, dtype):
     """A 2-D tensor whose rows are contiguous (the rows themselves may be strided apart)."""
     if not (t.is_cuda and t.dtype == dtype and t.dim() == 2 and (t.shape[1] == 1 or t.stride(1) == 1)):
@@ -262,12 +270,7 @@ def qsdp_quantize_weight(x, bits, bucket, delta, seed, codes, meta, n_saturated=
 
 def qsdp_dequantize(codes, meta, n, bits, bucket, out):
     _is(codes, torch.int32); _is(meta, torch.float32)
-    if out.dtype == torch.float32:
-        dt = QSDP_F32
-    elif out.dtype == torch.bfloat16:
-        dt = QSDP_BF16
-    else:
-        raise TypeError("out must be float32 or bfloat16")
+    dt = _out_dtype(out)
     _is(out, out.dtype)
     if out.numel() < n:
         raise ValueError("out is too small")
@@ -310,9 +313,7 @@ def qsdp_dequantize_levels(codes, meta, n, bits, bucket, levels, out):
     _is(codes, torch.int32); _is(meta, torch.float32); _is(levels, torch.float32)
     if levels.numel() != (1 << bits):
         raise ValueError("levels must hold 2^bits entries")
-    dt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16}.get(out.dtype)
-    if dt is None:
-        raise TypeError("out must be float32 or bfloat16")
+    dt = _out_dtype(out)
     _is(out, out.dtype)
     if out.numel() < n:
         raise ValueError("out is too small")
@@ -472,12 +473,7 @@ def qsdp_fused_step_segmented(x, g, segs, lr, wbits, gbits, delta, seed, index_o
 
 def qsdp_dequantize_segmented(codes, meta, segs, bits, out):
     _is(codes, torch.int32); _is(meta, torch.float32)
-    if out.dtype == torch.float32:
-        dt = QSDP_F32
-    elif out.dtype == torch.bfloat16:
-        dt = QSDP_BF16
-    else:
-        raise TypeError("out must be float32 or bfloat16")
+    dt = _out_dtype(out)
     _is(out, out.dtype)
     if out.numel() < segs.n:
         raise ValueError("out is smaller than the segments")
@@ -494,12 +490,7 @@ def qsdp_dequantize_gathered(codes, meta, npeers, n, shard, bits, bucket, out, l
     (row p = peer p's slot; rows may be views into one receive buffer); out float32/bfloat16[n].
     levels: the table the slots were encoded with by qsdp_quantize_levels, or None for uniform codes."""
     _is_rows(codes, torch.int32); _is_rows(meta, torch.float32)
-    if out.dtype == torch.float32:
-        dt = QSDP_F32
-    elif out.dtype == torch.bfloat16:
-        dt = QSDP_BF16
-    else:
-        raise TypeError("out must be float32 or bfloat16")
+    dt = _out_dtype(out)
     _is(out, out.dtype)
     if codes.shape[0] != npeers or meta.shape[0] != npeers:
         raise ValueError("codes and meta must be [npeers, ...]")
@@ -674,12 +665,7 @@ def qsdp_quantize_levels_segmented(v, segs, bits, levels, codes, meta, stochasti
 
 def qsdp_dequantize_levels_segmented(codes, meta, segs, bits, levels, out):
     _is(codes, torch.int32); _is(meta, torch.float32); _is(levels, torch.float32)
-    if out.dtype == torch.float32:
-        dt = QSDP_F32
-    elif out.dtype == torch.bfloat16:
-        dt = QSDP_BF16
-    else:
-        raise TypeError("out must be float32 or bfloat16")
+    dt = _out_dtype(out)
     _is(out, out.dtype)
     if out.numel() < segs.n:
         raise ValueError("out is smaller than the segments")

@@ -382,12 +382,13 @@ static DequantParams decoder_params(const uint32_t* codes, const float* meta, ui
 int qsdp_dequantize(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
                     qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
-    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16 && out_dtype != QSDP_F16) return QSDP_EINVAL;
     if (n >= (1ull << 37)) return QSDP_EINVAL;  // the decoder indexes buckets with 32-bit arithmetic
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out)) return QSDP_EALIGN;
     unsigned grid = 0;
-    const DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype == QSDP_BF16, out, &grid);
-    if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+    DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype != QSDP_F32, out, &grid);
+    p.out_f16 = out_dtype == QSDP_F16 ? 1u : 0u;
+    if (launch_dequant(bits, out_dtype != QSDP_F32, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
 }
@@ -436,14 +437,15 @@ int qsdp_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bu
 int qsdp_dequantize_levels(const uint32_t* codes, const float* meta, uint64_t n, int bits, int bucket,
                            const float* levels, qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !levels || !out || !shape_ok(n, bits, bucket)) return QSDP_EINVAL;
-    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16 && out_dtype != QSDP_F16) return QSDP_EINVAL;
     if (n >= (1ull << 37)) return QSDP_EINVAL;
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (reinterpret_cast<uintptr_t>(levels) & 3u))
         return QSDP_EALIGN;
     unsigned grid = 0;
-    DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype == QSDP_BF16, out, &grid);
+    DequantParams p = decoder_params(codes, meta, n, bits, bucket, out_dtype != QSDP_F32, out, &grid);
     p.levels = levels;
-    if (launch_dequant(bits, out_dtype == QSDP_BF16, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+    p.out_f16 = out_dtype == QSDP_F16 ? 1u : 0u;
+    if (launch_dequant(bits, out_dtype != QSDP_F32, p, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
 }
@@ -797,18 +799,19 @@ static int dequantize_segmented_common(const float* levels, const uint32_t* code
                                        int bucket, qsdp_dtype out_dtype, void* out, void* stream) {
     if (!codes || !meta || !table || !out || nseg == 0 || total_buckets < nseg || !shape_ok(1, bits, bucket))
         return QSDP_EINVAL;
-    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16 && out_dtype != QSDP_F16) return QSDP_EINVAL;
     if (total_buckets >= (1ull << 37) / (uint64_t)bucket) return QSDP_EINVAL;  // 32-bit bucket indexing
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(out) || (reinterpret_cast<uintptr_t>(table) & 7u))
         return QSDP_EALIGN;
     unsigned grid = 0;
     DequantSegParams q = {};
-    q.d = decoder_params(codes, meta, total_buckets * (uint64_t)bucket, bits, bucket, out_dtype == QSDP_BF16, out,
+    q.d = decoder_params(codes, meta, total_buckets * (uint64_t)bucket, bits, bucket, out_dtype != QSDP_F32, out,
                          &grid);
+    q.d.out_f16 = out_dtype == QSDP_F16 ? 1u : 0u;
     q.d.levels = levels;
     q.segs = reinterpret_cast<const Segment*>(table);
     q.nseg = nseg;
-    if (launch_dequant_seg(bits, out_dtype == QSDP_BF16, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
+    if (launch_dequant_seg(bits, out_dtype != QSDP_F32, q, grid, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;
 }
@@ -834,7 +837,7 @@ static int dequantize_gathered_common(const float* levels, const uint32_t* codes
                                       uint64_t shard, int bits, int bucket, qsdp_dtype out_dtype, void* out,
                                       void* stream) {
     if (!codes || !meta || !out || !shape_ok(n, bits, bucket) || npeers < 1 || npeers > 65535) return QSDP_EINVAL;
-    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16) return QSDP_EINVAL;
+    if (out_dtype != QSDP_F32 && out_dtype != QSDP_BF16 && out_dtype != QSDP_F16) return QSDP_EINVAL;
     if (shard == 0 || shard % (uint64_t)bucket != 0 || ceil_div(n, shard) != (uint64_t)npeers) return QSDP_EINVAL;
     if (shard >= (1ull << 37)) return QSDP_EINVAL;
     if ((codes_stride_bytes & 15u) || (meta_stride_bytes & 15u)) return QSDP_EALIGN;
@@ -843,7 +846,7 @@ static int dequantize_gathered_common(const float* levels, const uint32_t* codes
     if (npeers > 1 && (codes_stride_bytes < qsdp_codes_bytes(shard, bits, bucket) ||
                        meta_stride_bytes < qsdp_meta_bytes(shard, bucket)))
         return QSDP_EINVAL;
-    const bool bf16 = out_dtype == QSDP_BF16;
+    const bool bf16 = out_dtype != QSDP_F32;  // a 2-byte output format
     unsigned grid = 0, grid_last = 0;
     DequantParams p = decoder_params(codes, meta, first, bits, bucket, bf16, out, &grid);
     const DequantParams last = decoder_params(codes, meta, n - (uint64_t)(npeers - 1) * shard, bits, bucket, bf16, out,
@@ -854,6 +857,7 @@ static int dequantize_gathered_common(const float* levels, const uint32_t* codes
     p.codes_stride_words = codes_stride_bytes / 4;
     p.meta_stride_floats = meta_stride_bytes / 4;
     p.levels = levels;
+    p.out_f16 = out_dtype == QSDP_F16 ? 1u : 0u;
     if (launch_dequant(bits, bf16, p, dim3(grid, (unsigned)npeers), static_cast<hipStream_t>(stream)) != hipSuccess)
         return QSDP_ELAUNCH;
     return QSDP_OK;

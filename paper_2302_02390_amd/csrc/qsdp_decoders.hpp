@@ -17,6 +17,7 @@ struct DequantParams {
     const float* meta;
     const float* levels;  // learned-level table (2^bits floats) or nullptr
     void* out;
+    uint32_t out_f16;  // 2-byte output: IEEE binary16 instead of bf16
     uint64_t n;
     uint64_t nwords;  // 32-bit words in the code buffer
     uint64_t ntiles;  // wave tiles of U*64*E elements
@@ -76,7 +77,8 @@ __device__ __forceinline__ uint64_t bucket_of(uint64_t e, const DequantParams& p
 }
 
 // `lut` = the level table in LDS (learned levels: the code indexes it), or nullptr (uniform
-// levels: the code is the level).
+// levels: the code is the level). BF16 selects the 2-byte output path (8 elements per 16-byte
+// store): bf16, or binary16 when p.out_f16 is set (a wave-uniform choice of the conversion).
 template <int BITS, bool BF16, bool LUT>
 __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e, uint64_t bits, float base,
                                              float scale, bool whole, const float* lut, uint64_t limit) {
@@ -87,11 +89,12 @@ __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e,
         const uint32_t c = (uint32_t)(bits >> (i * BITS)) & ((1u << BITS) - 1u);
         o[i] = fmaf(LUT ? lut[c] : (float)c, scale, base);
     }
+    const bool f16 = BF16 && p.out_f16 != 0;
     if (whole) {
         if (BF16) {
             u4 w;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) w[i] = bf16_bits(o[2 * i]) | (bf16_bits(o[2 * i + 1]) << 16);
+            for (int i = 0; i < 4; ++i) w[i] = half_bits(o[2 * i], f16) | (half_bits(o[2 * i + 1], f16) << 16);
             __builtin_nontemporal_store(w, reinterpret_cast<u4*>(static_cast<uint16_t*>(p.out) + e));
         } else {
             const f4 a = {o[0], o[1], o[2], o[3]};
@@ -100,7 +103,7 @@ __device__ __forceinline__ void decode_store(const DequantParams& p, uint64_t e,
     } else {
         for (int i = 0; i < E; ++i) {
             if (e + i < limit) {
-                if (BF16) static_cast<uint16_t*>(p.out)[e + i] = (uint16_t)bf16_bits(o[i]);
+                if (BF16) static_cast<uint16_t*>(p.out)[e + i] = (uint16_t)half_bits(o[i], f16);
                 else static_cast<float*>(p.out)[e + i] = o[i];
             }
         }

@@ -299,4 +299,13 @@ __device__ __forceinline__ uint32_t bf16_bits(float v) {
     return b >> 16;
 }
 
+// binary32 -> IEEE binary16 bits: the hardware conversion (round to nearest even, subnormal
+// results kept, overflow to infinity)
+__device__ __forceinline__ uint32_t f16_bits(float v) {
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v);
+}
+
+// the 2-byte output formats of the decoders
+__device__ __forceinline__ uint32_t half_bits(float v, bool f16) { return f16 ? f16_bits(v) : bf16_bits(v); }
+
 }  // namespace qsdp

@@ -53,7 +53,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.qsdp_quantize_weight(ok, 10, 8, 1024, -1.0, 0, ok, ok, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_quantize_weight(ok, 10, 8, 1024, float("nan"), 0, ok, ok, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_quantize_weight(ok, 10, 8, 1024, 0.0, 0, odd, ok, None, None) == qb.QSDP_EALIGN
-    assert L.qsdp_dequantize(ok, ok, 10, 8, 1024, 2, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_dequantize(ok, ok, 10, 8, 1024, 3, ok, None) == qb.QSDP_EINVAL
     assert L.qsdp_dequantize(ok, ok, 10, 8, 1024, 1, odd, None) == qb.QSDP_EALIGN
     assert L.qsdp_fused_step(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ok, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step(ok, ok, 10, float("inf"), 8, 4, 1024, 0.0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
@@ -64,7 +64,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.qsdp_quantize_grad_g16(odd, 2, 10, 8, 1024, 0, 0, 0, ok, ok, None) == qb.QSDP_EALIGN
     assert L.qsdp_fused_step_g16(ok, ok, 0, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step_g16(ok, ok, 1, 10, 1e-3, 8, 4, 1024, 0.0, 0, 4, 0, None, None, None, None) == qb.QSDP_EINVAL
-    assert L.qsdp_dequantize_segmented(ok, ok, ok, 1, 1, 8, 1024, 2, ok, None) == qb.QSDP_EINVAL
+    assert L.qsdp_dequantize_segmented(ok, ok, ok, 1, 1, 8, 1024, 3, ok, None) == qb.QSDP_EINVAL
     assert qb.status_string(qb.QSDP_EALIGN).startswith("pointer")
 
 
