@@ -80,6 +80,10 @@ def one_case(rng):
         qb.qsdp_dequantize(c, m.reshape(-1), n, wbits, B, o16)
         assert np.array_equal(o16.view(torch.int16).cpu().numpy().view(np.uint16),
                               ref.dequantize(wc, wm, n, wbits, B, ref.BF16)), tag
+        oh = torch.empty(n, dtype=torch.float16, device=DEV)
+        qb.qsdp_dequantize(c, m.reshape(-1), n, wbits, B, oh)
+        assert np.array_equal(oh.view(torch.int16).cpu().numpy().view(np.uint16),
+                              ref.dequantize(wc, wm, n, wbits, B, ref.F16)), tag
     elif which == 2:
         c, m = qb.alloc_packed(n, wbits, B, DEV)
         qb.qsdp_fused_step_ex(xd, gd, 1e-3, wbits, gbits, B, delta, seed, off, flags | keep, c, m.reshape(-1), sat)
