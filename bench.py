@@ -437,6 +437,12 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"fused_adamw_step_W{wbits}G{gbits}",
         lambda i: qb.qsdp_fused_adamw_step(xa, g, mom, var, 2e-4, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** (i + 1),
                                            1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i), 28.0)
+    # the same with the weights resident as codes: read codes, g, m, v; write codes, m, v
+    qb.qsdp_quantize_weight(x, wbits, bucket, 0.0, 5, wc, wm)
+    run(f"fused_adamw_step_codes_W{wbits}G{gbits}",
+        lambda i: qb.qsdp_fused_adamw_step_codes(wc, wm, g, mom, var, 2e-4, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** (i + 1),
+                                                 1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i),
+        20 + 2 * (wbits / 8.0 + meta_b))
     del mom, var, xa
     # decode-and-sum of 8 peers' gradient slices on one GPU's 1/8 shard (the receive side of the
     # quantized gradient exchange): the 8 slices are 8 quantizations of the shard with different seeds

@@ -312,6 +312,20 @@ int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64
                           uint64_t* n_saturated, void* stream);
 
 /*
+ * qsdp_fused_adamw_step on code-resident weights: x_t is decoded from (wcodes, wmeta) in
+ * registers as in qsdp_fused_step_codes, the AdamW update uses the fp32 moments m, v (read and
+ * written), and the codes and meta of x_{t+1} = Q^w(y) overwrite the inputs. Bit-identical to
+ * qsdp_dequantize followed by qsdp_fused_adamw_step with code output. flags: the quantizer
+ * variants only (there is no fp32 copy of x to keep).
+ */
+int qsdp_fused_adamw_step_codes(uint32_t* wcodes, float* wmeta, const float* g, float* m, float* v,
+                                uint64_t n, float lr, float beta1, float beta2, float eps,
+                                float weight_decay, float bias1, float bias2,
+                                int wbits, int gbits, int bucket, float delta,
+                                uint64_t seed, uint64_t index_offset, uint32_t flags,
+                                uint64_t* n_saturated, void* stream);
+
+/*
  * Learned (non-uniform) quantization levels: Section 5.2, Algorithm 1, Appendix C.
  * A level table is 2^bits floats in bucket-normalised coordinates z = (v-lo)/(hi-lo) in
  * [0,1], ascending (DEVICE memory, 4-byte aligned; the library does not validate its contents;

@@ -27,7 +27,7 @@ EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_sta
            "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
            "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented",
            "qsdp_fused_step_dseed", "qsdp_quantize_levels_segmented", "qsdp_dequantize_levels_segmented",
-           "qsdp_quantize_grad_g16", "qsdp_fused_step_g16")
+           "qsdp_quantize_grad_g16", "qsdp_fused_step_g16", "qsdp_fused_adamw_step_codes")
 
 _lib = None
 
@@ -114,6 +114,9 @@ def lib():
         L.qsdp_fused_step_g16.argtypes = [vp, vp, i32, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp, vp,
                                           vp]
         L.qsdp_fused_step_g16.restype = i32
+        L.qsdp_fused_adamw_step_codes.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, f32, f32, i32, i32, i32,
+                                                  f32, u64, u64, C.c_uint32, vp, vp]
+        L.qsdp_fused_adamw_step_codes.restype = i32
         L.qsdp_fused_step_dseed.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, vp, u64, C.c_uint32, vp, vp, vp,
                                             vp]
         L.qsdp_fused_step_dseed.restype = i32
@@ -709,3 +712,21 @@ def qsdp_fused_step_g16(x, g, lr, wbits, gbits, bucket, delta, seed, index_offse
         _check(lib().qsdp_fused_step_g16(_ptr(x), _ptr(g), _G16[g.dtype], x.numel(), lr, wbits, gbits, bucket, delta,
                                          seed, index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(n_saturated),
                                          _stream(x)), "qsdp_fused_step_g16")
+
+
+def qsdp_fused_adamw_step_codes(wcodes, wmeta, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits,
+                                bucket, delta, seed, index_offset=0, flags=0, n_saturated=None):
+    """The AdamW step on weights held as packed codes + meta (updated in place); m, v float32, updated in place."""
+    _is(wcodes, torch.int32); _is(wmeta, torch.float32); _is(g, torch.float32); _is(m, torch.float32)
+    _is(v, torch.float32)
+    n = g.numel()
+    if m.numel() != n or v.numel() != n:
+        raise ValueError("g, m and v differ in size")
+    if n_saturated is not None:
+        _is(n_saturated, torch.int64)
+    _packed_ok(wcodes, wmeta, n, wbits, bucket)
+    with torch.cuda.device(g.device):
+        _check(lib().qsdp_fused_adamw_step_codes(_ptr(wcodes), _ptr(wmeta), _ptr(g), _ptr(m), _ptr(v), n, lr, beta1,
+                                                 beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket, delta,
+                                                 seed, index_offset, flags, _ptr(n_saturated), _stream(g)),
+               "qsdp_fused_adamw_step_codes")

@@ -18,6 +18,7 @@ hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s)
         case MODE_FUSED_CODES: hipLaunchKernelGGL(block_kernel<MODE_FUSED_CODES>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_LEVELS: hipLaunchKernelGGL(block_kernel<MODE_LEVELS>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
+        case MODE_ADAMW_CODES: hipLaunchKernelGGL(block_kernel<MODE_ADAMW_CODES>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_RECV: hipLaunchKernelGGL(block_kernel<MODE_RECV>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         case MODE_RECV_ADAMW: hipLaunchKernelGGL(block_kernel<MODE_RECV_ADAMW>, dim3(grid), dim3(256), 0, s, p, p.segs); break;
         default: return hipErrorInvalidValue;
@@ -636,7 +637,7 @@ int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v
                               wmeta, n_saturated, stream);
 }
 
-static int fused_step_codes_common(const SegmentTable* segs, uint32_t* wcodes, float* wmeta, const float* g,
+static int fused_step_codes_common(const AdamScalars* adam, const SegmentTable* segs, uint32_t* wcodes, float* wmeta, const float* g,
                                    uint64_t n, float lr, int wbits, int gbits, int bucket, float delta,
                                    uint64_t seed, uint64_t index_offset, uint32_t flags, uint64_t* n_saturated,
                                    void* stream) {
@@ -648,7 +649,9 @@ static int fused_step_codes_common(const SegmentTable* segs, uint32_t* wcodes, f
         (flags & ~QSDP_FLAG_ALL))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (adam && !adam_ok(*adam)) return QSDP_EINVAL;
     if (!aligned16(wcodes) || !aligned16(wmeta) || !aligned16(g)) return QSDP_EALIGN;
+    if (adam && (!aligned16(adam->m) || !aligned16(adam->v))) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, segs ? 0 : n, bucket, seed, index_offset, delta);
@@ -661,13 +664,14 @@ static int fused_step_codes_common(const SegmentTable* segs, uint32_t* wcodes, f
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    return run(MODE_FUSED_CODES, p, wbits, static_cast<hipStream_t>(stream));
+    if (adam) set_adam(p, *adam);
+    return run(adam ? MODE_ADAMW_CODES : MODE_FUSED_CODES, p, wbits, static_cast<hipStream_t>(stream));
 }
 
 int qsdp_fused_step_codes(uint32_t* wcodes, float* wmeta, const float* g, uint64_t n, float lr, int wbits,
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                           uint32_t flags, uint64_t* n_saturated, void* stream) {
-    return fused_step_codes_common(nullptr, wcodes, wmeta, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset,
+    return fused_step_codes_common(nullptr, nullptr, wcodes, wmeta, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset,
                                    flags, n_saturated, stream);
 }
 
@@ -676,8 +680,17 @@ int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float*
                                     int bucket, float delta, uint64_t seed, uint64_t index_offset,
                                     uint32_t flags, uint64_t* n_saturated, void* stream) {
     const SegmentTable segs = {table, nseg, total_buckets};
-    return fused_step_codes_common(&segs, wcodes, wmeta, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset,
+    return fused_step_codes_common(nullptr, &segs, wcodes, wmeta, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset,
                                    flags, n_saturated, stream);
+}
+
+int qsdp_fused_adamw_step_codes(uint32_t* wcodes, float* wmeta, const float* g, float* m, float* v, uint64_t n,
+                                float lr, float beta1, float beta2, float eps, float weight_decay, float bias1,
+                                float bias2, int wbits, int gbits, int bucket, float delta, uint64_t seed,
+                                uint64_t index_offset, uint32_t flags, uint64_t* n_saturated, void* stream) {
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    return fused_step_codes_common(&adam, nullptr, wcodes, wmeta, g, n, lr, wbits, gbits, bucket, delta, seed,
+                                   index_offset, flags, n_saturated, stream);
 }
 
 uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table) {

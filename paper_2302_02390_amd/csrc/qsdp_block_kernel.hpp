@@ -53,13 +53,13 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
         float base = 0.0f, scale = 0.0f;
         int bits = (MODE == MODE_GRAD) ? p.gbits : p.wbits;
 
-        // MODE_FUSED_CODES: the old iterate is decoded from the bucket's codes and meta
+        // code-resident weights: the old iterate is decoded from the bucket's codes and meta
         const int wpb_in = B * p.wbits / 32;
-        const uint32_t* old_words = (MODE == MODE_FUSED_CODES) ? p.codes + bucket * (uint64_t)wpb_in : nullptr;
-        const float old_base = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket] : 0.0f;
-        const float old_scale = (MODE == MODE_FUSED_CODES) ? p.meta[2 * bucket + 1] : 0.0f;
+        const uint32_t* old_words = mode_codes_resident(MODE) ? p.codes + bucket * (uint64_t)wpb_in : nullptr;
+        const float old_base = mode_codes_resident(MODE) ? p.meta[2 * bucket] : 0.0f;
+        const float old_scale = mode_codes_resident(MODE) ? p.meta[2 * bucket + 1] : 0.0f;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
+        if (mode_local_gradient(MODE)) {
             float lo = __builtin_inff(), hi = -__builtin_inff();
             for (int i = tid; i < m; i += 256) {
                 const uint16_t* g16 = reinterpret_cast<const uint16_t*>(p.g);
@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                 } else {
                     const float ghat = fmaf(c, grid.scale, gbase);
                     float xold;
-                    if (MODE == MODE_FUSED_CODES) {
+                    if (mode_codes_resident(MODE)) {
                         const int bit = i * p.wbits;
                         uint64_t two = old_words[bit >> 5];
                         if ((bit >> 5) + 1 < wpb_in) two |= (uint64_t)old_words[(bit >> 5) + 1] << 32;
@@ -101,12 +101,12 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                         xold = p.x[e0 + i];
                     }
                     float mom = 0.0f, var = 0.0f;
-                    if (MODE == MODE_ADAMW) {
+                    if (mode_local_adamw(MODE)) {
                         mom = p.mom[e0 + i];
                         var = p.var[e0 + i];
                     }
                     val[i] = step_value<MODE>(p, xold, ghat, mom, var);
-                    if (MODE == MODE_ADAMW) {
+                    if (mode_local_adamw(MODE)) {
                         p.mom[e0 + i] = mom;
                         p.var[e0 + i] = var;
                     }

@@ -20,19 +20,33 @@ constexpr int kMaxBucket = 8192;
 // MODE_RECV: the shard owner's step with P workers: the gradient is the scaled sum of the
 // decoded slices of all peers (no Q^g here), then the SGD step and Q^w as in MODE_FUSED.
 // MODE_RECV_ADAMW: the same with the AdamW update of MODE_ADAMW in place of the SGD step.
+// MODE_ADAMW_CODES: MODE_ADAMW on code-resident weights (x_t decoded from codes + meta as in
+// MODE_FUSED_CODES, the moments in fp32).
 // MODE_SUM: only the first half of MODE_RECV: out = alpha * (sum of the decoded peer slices).
 // MODE_LEVELS_COIN: MODE_LEVELS with the unbiased coin flip between the two enclosing levels
 // instead of the nearest level (wave kernels only: a kernel of its own so that the nearest-level
 // encoder does not carry the registers of the rounding uniforms; the block kernel takes
 // MODE_LEVELS with FLAG_LEVELS_STOCHASTIC).
 enum Mode { MODE_GRAD = 0, MODE_WEIGHT = 1, MODE_FUSED = 2, MODE_FUSED_CODES = 3, MODE_LEVELS = 4,
-            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7, MODE_SUM = 8, MODE_LEVELS_COIN = 9 };
+            MODE_ADAMW = 5, MODE_RECV = 6, MODE_RECV_ADAMW = 7, MODE_SUM = 8, MODE_LEVELS_COIN = 9,
+            MODE_ADAMW_CODES = 10 };
 
 constexpr bool mode_is_levels(int mode) { return mode == MODE_LEVELS || mode == MODE_LEVELS_COIN; }
 
 constexpr bool mode_is_recv(int mode) { return mode == MODE_RECV || mode == MODE_RECV_ADAMW; }
 constexpr bool mode_reads_peers(int mode) { return mode_is_recv(mode) || mode == MODE_SUM; }
-constexpr bool mode_is_adamw(int mode) { return mode == MODE_ADAMW || mode == MODE_RECV_ADAMW; }
+constexpr bool mode_is_adamw(int mode) {
+    return mode == MODE_ADAMW || mode == MODE_RECV_ADAMW || mode == MODE_ADAMW_CODES;
+}
+// the weights live as packed codes + meta (decoded in registers, overwritten by the new codes)
+constexpr bool mode_codes_resident(int mode) { return mode == MODE_FUSED_CODES || mode == MODE_ADAMW_CODES; }
+// the gradient is a local fp32 (or 16-bit) vector that goes through Q^g inside the kernel
+constexpr bool mode_local_gradient(int mode) {
+    return mode == MODE_GRAD || mode == MODE_FUSED || mode == MODE_FUSED_CODES || mode == MODE_ADAMW ||
+           mode == MODE_ADAMW_CODES;
+}
+// the AdamW moments are read and written next to a local gradient
+constexpr bool mode_local_adamw(int mode) { return mode == MODE_ADAMW || mode == MODE_ADAMW_CODES; }
 
 // One tensor of a multi-tensor ("segmented") call: `n` elements at element offset `offset` of
 // the flat buffers; its buckets are numbered first_bucket .. first_bucket + ceil(n/B) - 1.

@@ -53,6 +53,7 @@ hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, u
         case MODE_ADAMW:
             if (bits == 0) return go<MODE_ADAMW, 0>(p, grid, s);
             return by_bits<MODE_ADAMW>(bits, p, grid, s);
+        case MODE_ADAMW_CODES: return by_bits<MODE_ADAMW_CODES>(bits, p, grid, s);
         case MODE_RECV:  // the width of the peers' codes (p.gbits) is a run-time value in these two
             if (bits == 0) return go<MODE_RECV, 0>(p, grid, s);
             return by_bits<MODE_RECV>(bits, p, grid, s);

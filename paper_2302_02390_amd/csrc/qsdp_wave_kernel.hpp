@@ -406,10 +406,10 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
         float base = 0.0f, scale = 0.0f;
 
-        if (MODE == MODE_GRAD || MODE == MODE_FUSED || MODE == MODE_FUSED_CODES || MODE == MODE_ADAMW) {
+        if (mode_local_gradient(MODE)) {
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
-            float mom[R][4], var[R][4];  // MODE_ADAMW only
+            float mom[R][4], var[R][4];  // AdamW modes only
             if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 1)
                 load_rows_half<G, R, true>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
             else if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 2)
@@ -417,11 +417,11 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             else
                 load_rows<G, R>(p.g + e0, l, m, partial, gv);
             if (MODE == MODE_FUSED || MODE == MODE_ADAMW) load_rows<G, R>(p.x + e0, l, m, partial, w);
-            if constexpr (MODE == MODE_ADAMW) {
+            if constexpr (mode_local_adamw(MODE)) {
                 load_rows<G, R>(p.mom + e0, l, m, partial, mom);
                 load_rows<G, R>(p.var + e0, l, m, partial, var);
             }
-            if constexpr (MODE == MODE_FUSED_CODES) {
+            if constexpr (mode_codes_resident(MODE)) {
                 // x = decode(codes, meta) in registers
                 load_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
                 const float xbase = p.meta[2 * bucket];
@@ -469,7 +469,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                     }
                 }
             }
-            if constexpr (MODE == MODE_ADAMW) {
+            if constexpr (mode_local_adamw(MODE)) {
                 if (active) {
                     store_rows<G, R>(p.mom + e0, l, m, partial, mom);
                     store_rows<G, R>(p.var + e0, l, m, partial, var);

@@ -80,3 +80,43 @@ def test_adamw_argument_errors():
         with pytest.raises(qb.QsdpError) as e:
             qb.qsdp_fused_adamw_step(z, z.clone(), z.clone(), z.clone(), **a)
         assert e.value.status == qb.QSDP_EINVAL
+
+
+@pytest.mark.parametrize("bucket", [32, 96, 128, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("wbits,gbits,delta,flags", [(8, 4, 0.0, 0), (6, 3, 0.0, 0), (5, 7, 0.0, 1), (8, 4, 2.0**-10, 0),
+                                                     (4, 2, 0.0, 4), (1, 8, 0.0, 2)])
+def test_adamw_steps_on_code_resident_weights(wbits, gbits, delta, flags, bucket):
+    """Three AdamW steps with the weights held only as codes + meta: every step equals the oracle's decode
+    followed by its AdamW step with code output (codes, meta, moments, saturation count bit for bit)."""
+    n = 6 * bucket + bucket // 2 + 7
+    x, g = synth(n, 1150 + wbits + gbits)
+    hc, hm_, _ = ref.quantize_weight(x, wbits, bucket, delta, 77)
+    codes = torch.from_numpy(hc.view(np.int32)).to(DEV)
+    meta = torch.from_numpy(hm_.reshape(-1)).to(DEV)
+    md = torch.zeros(n, dtype=torch.float32, device=DEV)
+    vd = torch.zeros(n, dtype=torch.float32, device=DEV)
+    hmom, hvar = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for t in range(1, 4):
+        gt = (g * np.float32(1 + 0.1 * t)).astype(np.float32)
+        bc1, bc2 = 1 - 0.9**t, 1 - 0.95**t
+        sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+        qb.qsdp_fused_adamw_step_codes(codes, meta, torch.from_numpy(gt).to(DEV), md, vd, bias1=bc1, bias2=bc2,
+                                       wbits=wbits, gbits=gbits, bucket=bucket, delta=delta, seed=t, index_offset=16,
+                                       flags=flags, n_saturated=sat, **HYPER)
+        xt = ref.dequantize(hc, hm_, n, wbits, bucket)
+        _, hmom, hvar, hc, hm_, ws = ref.fused_adamw_step(xt, gt, hmom, hvar, bias1=bc1, bias2=bc2, wbits=wbits,
+                                                          gbits=gbits, bucket=bucket, delta=delta, seed=t,
+                                                          index_offset=16, flags=flags, emit_codes=True, **HYPER)
+        assert np.array_equal(np_u32(codes), hc) and np.array_equal(np_u32(meta), hm_.view(np.uint32).reshape(-1)), t
+        assert bits_equal(np_f32(md), hmom) and bits_equal(np_f32(vd), hvar), t
+        assert int(sat) == ws
+
+
+def test_code_resident_adamw_rejects_keep_master():
+    n, B = 2048, 1024
+    codes, meta = qb.alloc_packed(n, 8, B, DEV)
+    z = torch.zeros(n, dtype=torch.float32, device=DEV)
+    with pytest.raises(qb.QsdpError):
+        qb.qsdp_fused_adamw_step_codes(codes, meta.reshape(-1), z, z.clone(), z.clone(), bias1=0.1, bias2=0.05,
+                                       wbits=8, gbits=4, bucket=B, delta=0.0, seed=0,
+                                       flags=qb.QSDP_FLAG_KEEP_MASTER, **HYPER)

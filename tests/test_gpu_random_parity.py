@@ -120,6 +120,19 @@ def one_case(rng):
     elif which == 5:
         mo, vo = np.abs(data(rng, n, 1)), np.abs(data(rng, n, 1)) ** 2
         md, vd = torch.from_numpy(mo).to(DEV), torch.from_numpy(vo).to(DEV)
+        if rng.random() < 0.4:
+            # weights resident as codes: decode + AdamW step with code output, composed from the oracle's routines
+            wc0, wm0, _ = ref.quantize_weight(x, wbits, B, delta, seed ^ 9)
+            c = torch.from_numpy(wc0.view(np.int32)).to(DEV)
+            m = torch.from_numpy(wm0.reshape(-1)).to(DEV)
+            qb.qsdp_fused_adamw_step_codes(c, m, gd, md, vd, 2e-4, 0.9, 0.95, 1e-8, 0.1, 0.3, 0.2, wbits, gbits, B, delta,
+                                           seed, off, flags, sat)
+            _, wmo, wvo, wc, wm, ws = ref.fused_adamw_step(ref.dequantize(wc0, wm0, n, wbits, B), g, mo, vo, 2e-4, 0.9,
+                                                           0.95, 1e-8, 0.1, 0.3, 0.2, wbits, gbits, B, delta, seed, off,
+                                                           flags, True)
+            assert eq(np_f32(md), wmo) and eq(np_f32(vd), wvo) and int(sat) == ws, tag
+            assert eq(np_u32(c), wc) and eq(np_u32(m), wm), tag
+            return
         c, m = qb.alloc_packed(n, wbits, B, DEV)
         qb.qsdp_fused_adamw_step(xd, gd, md, vd, 2e-4, 0.9, 0.95, 1e-8, 0.1, 0.3, 0.2, wbits, gbits, B, delta, seed, off,
                                  flags | keep, c, m.reshape(-1))
