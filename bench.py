@@ -25,7 +25,7 @@ BYTES_PER_PARAM = 12.0
 # HBM bytes per fused-step launch on the 1.3B workload from rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by the same counters on a plain copy kernel); see
 # profiles/fused_step_gpt1p3b.md.
-MEASURED_TRAFFIC_BYTES = 15788794336
+MEASURED_TRAFFIC_BYTES = 15788811000
 
 
 def parse():
