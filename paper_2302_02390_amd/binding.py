@@ -6,6 +6,7 @@ order of the C entry points. There is no fallback: if the library is not built, 
 the symbols raises.
 """
 import ctypes as C
+import functools
 import os
 
 import torch
@@ -17,17 +18,72 @@ QSDP_OK, QSDP_EINVAL, QSDP_EALIGN, QSDP_ELAUNCH = 0, -1, -2, -3
 QSDP_F32, QSDP_BF16, QSDP_F16 = 0, 1, 2
 QSDP_FLAG_GRAD_SHIFT, QSDP_FLAG_NO_SHIFT, QSDP_FLAG_SYMMETRIC, QSDP_FLAG_KEEP_MASTER = 1, 2, 4, 8
 
-EXPORTS = ("qsdp_spec_version", "qsdp_codes_bytes", "qsdp_meta_bytes", "qsdp_status_string",
-           "qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
-           "qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex",
-           "qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels",
-           "qsdp_fused_adamw_step", "qsdp_dequantize_add", "qsdp_fused_step_codes", "qsdp_segments_build", "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-           "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered", "qsdp_recv_step",
-           "qsdp_recv_adamw_step", "qsdp_dequantize_levels_gathered", "qsdp_recv_step_segmented",
-           "qsdp_recv_adamw_step_segmented", "qsdp_fused_adamw_step_segmented", "qsdp_fused_step_codes_segmented",
-           "qsdp_quantize_levels_stochastic", "qsdp_fit_levels_segmented",
-           "qsdp_fused_step_dseed", "qsdp_quantize_levels_segmented", "qsdp_dequantize_levels_segmented",
-           "qsdp_quantize_grad_g16", "qsdp_fused_step_g16", "qsdp_fused_adamw_step_codes")
+# Signature of every export of include/qsdp.h: name -> (result, arguments). vp: pointer (device memory unless the
+# header says host), the last vp of an entry point that launches work is the stream.
+_u64, _u32, _i32, _f32, _vp = C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_void_p
+_SIGNATURES = {
+    "qsdp_spec_version": (_u32, []),
+    "qsdp_codes_bytes": (C.c_size_t, [_u64, _i32, _i32]),
+    "qsdp_meta_bytes": (C.c_size_t, [_u64, _i32]),
+    "qsdp_status_string": (C.c_char_p, [_i32]),
+    "qsdp_quantize_grad": (_i32, [_vp, _u64, _i32, _i32, _u64, _u64, _vp, _vp, _vp]),
+    "qsdp_quantize_grad_ex": (_i32, [_vp, _u64, _i32, _i32, _u64, _u64, _u32, _vp, _vp, _vp]),
+    "qsdp_quantize_grad_g16": (_i32, [_vp, _i32, _u64, _i32, _i32, _u64, _u64, _u32, _vp, _vp, _vp]),
+    "qsdp_quantize_weight": (_i32, [_vp, _u64, _i32, _i32, _f32, _u64, _vp, _vp, _vp, _vp]),
+    "qsdp_quantize_weight_ex": (_i32, [_vp, _u64, _i32, _i32, _f32, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_dequantize": (_i32, [_vp, _vp, _u64, _i32, _i32, _i32, _vp, _vp]),
+    "qsdp_fused_step": (_i32, [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_ex": (_i32,
+        [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_g16": (_i32,
+        [_vp, _vp, _i32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_dseed": (_i32,
+        [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_codes": (_i32, [_vp, _vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp]),
+    "qsdp_fused_adamw_step": (_i32,
+        [_vp, _vp, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32, _u64,
+         _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_adamw_step_codes": (_i32,
+        [_vp, _vp, _vp, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32,
+         _u64, _u64, _u32, _vp, _vp]),
+    "qsdp_dequantize_add": (_i32, [_vp, _u64, _vp, _u64, _i32, _u64, _i32, _i32, _f32, _vp, _vp]),
+    "qsdp_dequantize_gathered": (_i32, [_vp, _u64, _vp, _u64, _i32, _u64, _u64, _i32, _i32, _i32, _vp, _vp]),
+    "qsdp_recv_step": (_i32,
+        [_vp, _vp, _u64, _vp, _u64, _i32, _u64, _f32, _f32, _i32, _i32, _i32, _f32, _u64, _u32, _vp, _vp,
+         _vp, _vp]),
+    "qsdp_recv_adamw_step": (_i32,
+        [_vp, _vp, _vp, _vp, _u64, _vp, _u64, _i32, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _f32,
+         _i32, _i32, _i32, _f32, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_levels_uniform": (_i32, [_i32, _vp]),
+    "qsdp_quantize_levels": (_i32, [_vp, _u64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "qsdp_quantize_levels_stochastic": (_i32, [_vp, _u64, _i32, _i32, _vp, _u64, _u64, _vp, _vp, _vp]),
+    "qsdp_dequantize_levels": (_i32, [_vp, _vp, _u64, _i32, _i32, _vp, _i32, _vp, _vp]),
+    "qsdp_dequantize_levels_gathered": (_i32,
+        [_vp, _u64, _vp, _u64, _i32, _u64, _u64, _i32, _i32, _vp, _i32, _vp, _vp]),
+    "qsdp_fit_levels": (_i32, [_vp, _u64, _i32, _i32, _f32, _u64, _vp, _vp]),
+    "qsdp_segments_build": (_u64, [_vp, _u32, _i32, _vp]),
+    "qsdp_quantize_grad_segmented": (_i32, [_vp, _vp, _u32, _u64, _i32, _i32, _u64, _u64, _vp, _vp, _vp]),
+    "qsdp_quantize_weight_segmented": (_i32, [_vp, _vp, _u32, _u64, _i32, _i32, _f32, _u64, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_segmented": (_i32,
+        [_vp, _vp, _vp, _u32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _vp, _vp, _vp, _vp]),
+    "qsdp_dequantize_segmented": (_i32, [_vp, _vp, _vp, _u32, _u64, _i32, _i32, _i32, _vp, _vp]),
+    "qsdp_fused_adamw_step_segmented": (_i32,
+        [_vp, _vp, _vp, _vp, _vp, _u32, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32,
+         _f32, _u64, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_codes_segmented": (_i32,
+        [_vp, _vp, _vp, _vp, _u32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp]),
+    "qsdp_recv_step_segmented": (_i32,
+        [_vp, _vp, _u32, _u64, _vp, _u64, _vp, _u64, _i32, _f32, _f32, _i32, _i32, _i32, _f32, _u64, _u32,
+         _vp, _vp, _vp, _vp]),
+    "qsdp_recv_adamw_step_segmented": (_i32,
+        [_vp, _vp, _vp, _vp, _u32, _u64, _vp, _u64, _vp, _u64, _i32, _f32, _f32, _f32, _f32, _f32, _f32,
+         _f32, _f32, _i32, _i32, _i32, _f32, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fit_levels_segmented": (_i32, [_vp, _vp, _u32, _i32, _i32, _f32, _u64, _vp, _vp]),
+    "qsdp_quantize_levels_segmented": (_i32,
+        [_vp, _vp, _u32, _u64, _i32, _i32, _vp, _i32, _u64, _u64, _vp, _vp, _vp]),
+    "qsdp_dequantize_levels_segmented": (_i32, [_vp, _vp, _vp, _u32, _u64, _i32, _i32, _vp, _i32, _vp, _vp]),
+}
+EXPORTS = tuple(_SIGNATURES)
 
 _lib = None
 
@@ -45,91 +101,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2302_02390_amd.build`")
         L = C.CDLL(LIB_PATH)
-        u64, i32, f32, vp = C.c_uint64, C.c_int, C.c_float, C.c_void_p
-        L.qsdp_spec_version.argtypes = []
-        L.qsdp_spec_version.restype = C.c_uint32
-        L.qsdp_codes_bytes.argtypes = [u64, i32, i32]
-        L.qsdp_codes_bytes.restype = C.c_size_t
-        L.qsdp_meta_bytes.argtypes = [u64, i32]
-        L.qsdp_meta_bytes.restype = C.c_size_t
-        L.qsdp_status_string.argtypes = [i32]
-        L.qsdp_status_string.restype = C.c_char_p
-        L.qsdp_quantize_grad.argtypes = [vp, u64, i32, i32, u64, u64, vp, vp, vp]
-        L.qsdp_quantize_weight.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp, vp, vp]
-        L.qsdp_dequantize.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
-        L.qsdp_fused_step.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, vp, vp, vp, vp]
-        u32 = C.c_uint32
-        L.qsdp_quantize_grad_ex.argtypes = [vp, u64, i32, i32, u64, u64, u32, vp, vp, vp]
-        L.qsdp_quantize_weight_ex.argtypes = [vp, u64, i32, i32, f32, u64, u32, vp, vp, vp, vp]
-        L.qsdp_fused_step_ex.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, u32, vp, vp, vp, vp]
-        for name in ("qsdp_quantize_grad_ex", "qsdp_quantize_weight_ex", "qsdp_fused_step_ex"):
-            getattr(L, name).restype = i32
-        L.qsdp_levels_uniform.argtypes = [i32, vp]
-        L.qsdp_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp]
-        L.qsdp_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp, vp]
-        L.qsdp_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp, vp]
-        for name in ("qsdp_levels_uniform", "qsdp_quantize_levels", "qsdp_dequantize_levels", "qsdp_fit_levels"):
-            getattr(L, name).restype = i32
-        L.qsdp_fused_adamw_step.argtypes = [vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, f32, f32, i32, i32, i32,
-                                            f32, u64, u64, u32, vp, vp, vp, vp]
-        L.qsdp_fused_adamw_step.restype = i32
-        L.qsdp_dequantize_add.argtypes = [vp, u64, vp, u64, i32, u64, i32, i32, f32, vp, vp]
-        L.qsdp_dequantize_add.restype = i32
-        L.qsdp_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp]
-        L.qsdp_fused_step_codes.restype = i32
-        L.qsdp_segments_build.argtypes = [vp, C.c_uint32, i32, vp]
-        L.qsdp_segments_build.restype = u64
-        L.qsdp_quantize_grad_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, u64, u64, vp, vp, vp]
-        L.qsdp_quantize_weight_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, f32, u64, vp, vp,
-                                                     vp, vp]
-        L.qsdp_fused_step_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64,
-                                                u64, vp, vp, vp, vp]
-        L.qsdp_dequantize_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, i32, vp, vp]
-        L.qsdp_dequantize_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, i32, vp, vp]
-        L.qsdp_dequantize_levels_gathered.argtypes = [vp, u64, vp, u64, i32, u64, u64, i32, i32, vp, i32, vp, vp]
-        L.qsdp_dequantize_levels_gathered.restype = i32
-        L.qsdp_recv_step_segmented.argtypes = [vp, vp, C.c_uint32, u64, vp, u64, vp, u64, i32, f32, f32, i32, i32, i32,
-                                               f32, u64, C.c_uint32, vp, vp, vp, vp]
-        L.qsdp_recv_step_segmented.restype = i32
-        L.qsdp_recv_adamw_step_segmented.argtypes = [vp, vp, vp, vp, C.c_uint32, u64, vp, u64, vp, u64, i32, f32, f32,
-                                                     f32, f32, f32, f32, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
-                                                     vp, vp, vp, vp]
-        L.qsdp_recv_adamw_step_segmented.restype = i32
-        L.qsdp_fused_adamw_step_segmented.argtypes = [vp, vp, vp, vp, vp, C.c_uint32, u64, f32, f32, f32, f32, f32, f32,
-                                                      f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp, vp, vp]
-        L.qsdp_fused_adamw_step_segmented.restype = i32
-        L.qsdp_fused_step_codes_segmented.argtypes = [vp, vp, vp, vp, C.c_uint32, u64, f32, i32, i32, i32, f32, u64, u64,
-                                                      C.c_uint32, vp, vp]
-        L.qsdp_fused_step_codes_segmented.restype = i32
-        L.qsdp_quantize_levels_stochastic.argtypes = [vp, u64, i32, i32, vp, u64, u64, vp, vp, vp]
-        L.qsdp_quantize_levels_stochastic.restype = i32
-        L.qsdp_fit_levels_segmented.argtypes = [vp, vp, C.c_uint32, i32, i32, f32, u64, vp, vp]
-        L.qsdp_fit_levels_segmented.restype = i32
-        L.qsdp_quantize_levels_segmented.argtypes = [vp, vp, C.c_uint32, u64, i32, i32, vp, i32, u64, u64, vp, vp, vp]
-        L.qsdp_quantize_levels_segmented.restype = i32
-        L.qsdp_dequantize_levels_segmented.argtypes = [vp, vp, vp, C.c_uint32, u64, i32, i32, vp, i32, vp, vp]
-        L.qsdp_dequantize_levels_segmented.restype = i32
-        L.qsdp_quantize_grad_g16.argtypes = [vp, i32, u64, i32, i32, u64, u64, C.c_uint32, vp, vp, vp]
-        L.qsdp_quantize_grad_g16.restype = i32
-        L.qsdp_fused_step_g16.argtypes = [vp, vp, i32, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp, vp, vp,
-                                          vp]
-        L.qsdp_fused_step_g16.restype = i32
-        L.qsdp_fused_adamw_step_codes.argtypes = [vp, vp, vp, vp, vp, u64, f32, f32, f32, f32, f32, f32, f32, i32, i32, i32,
-                                                  f32, u64, u64, C.c_uint32, vp, vp]
-        L.qsdp_fused_adamw_step_codes.restype = i32
-        L.qsdp_fused_step_dseed.argtypes = [vp, vp, u64, f32, i32, i32, i32, f32, u64, vp, u64, C.c_uint32, vp, vp, vp,
-                                            vp]
-        L.qsdp_fused_step_dseed.restype = i32
-        L.qsdp_recv_step.argtypes = [vp, vp, u64, vp, u64, i32, u64, f32, f32, i32, i32, i32, f32, u64, C.c_uint32,
-                                     vp, vp, vp, vp]
-        L.qsdp_recv_step.restype = i32
-        L.qsdp_recv_adamw_step.argtypes = [vp, vp, vp, vp, u64, vp, u64, i32, u64, f32, f32, f32, f32, f32, f32, f32,
-                                           f32, i32, i32, i32, f32, u64, C.c_uint32, vp, vp, vp, vp]
-        L.qsdp_recv_adamw_step.restype = i32
-        for name in ("qsdp_quantize_grad", "qsdp_quantize_weight", "qsdp_dequantize", "qsdp_fused_step",
-                     "qsdp_quantize_grad_segmented", "qsdp_quantize_weight_segmented",
-                     "qsdp_fused_step_segmented", "qsdp_dequantize_segmented", "qsdp_dequantize_gathered"):
-            getattr(L, name).restype = i32
+        for name, (restype, argtypes) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = restype
+            fn.argtypes = argtypes
         _lib = L
     return _lib
 
@@ -730,3 +705,28 @@ def qsdp_fused_adamw_step_codes(wcodes, wmeta, g, m, v, lr, beta1, beta2, eps, w
                                                  beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket, delta,
                                                  seed, index_offset, flags, _ptr(n_saturated), _stream(g)),
                "qsdp_fused_adamw_step_codes")
+
+
+def _one_device(fn):
+    """Every tensor argument of an entry point (and a segment table) must live on the same device: the
+    kernel runs on the device of the first one and would fault on memory of another."""
+    @functools.wraps(fn)
+    def checked(*args, **kwargs):
+        device = None
+        for a in list(args) + list(kwargs.values()):
+            for t in (a if isinstance(a, (tuple, list)) else (a,)):
+                if isinstance(t, Segments):
+                    t = t.device
+                if isinstance(t, torch.Tensor):
+                    if device is None:
+                        device = t.device
+                    elif t.device != device:
+                        raise ValueError(f"{fn.__name__}: tensors on {device} and on {t.device}")
+        return fn(*args, **kwargs)
+    return checked
+
+
+for _name, _fn in list(globals().items()):
+    if _name.startswith("qsdp_") and callable(_fn):
+        globals()[_name] = _one_device(_fn)
+del _name, _fn

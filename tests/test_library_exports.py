@@ -91,9 +91,18 @@ def test_binding_declares_the_signature_of_every_export():
         fn = getattr(L, name)
         assert fn.argtypes is not None, name
         decl = re.search(r"\b" + name + r"\s*\(([^)]*)\)", text).group(1).strip()
-        nargs = 0 if decl in ("", "void") else decl.count(",") + 1
-        assert len(fn.argtypes) == nargs, (name, len(fn.argtypes), nargs)
+        params = [] if decl in ("", "void") else [" ".join(p_.split()) for p_ in decl.split(",")]
+        assert len(fn.argtypes) == len(params), (name, len(fn.argtypes), len(params))
         assert fn.restype is not C_INT_DEFAULT or name in INT_RETURNING, name
+        # ... and each argument's type must be the header's: a pointer, or the scalar of that width
+        for k, (param, ctype) in enumerate(zip(params, fn.argtypes)):
+            if "*" in param:
+                want = ctypes.c_void_p
+            else:
+                base = param.rsplit(" ", 1)[0].replace("const ", "")
+                want = {"uint64_t": ctypes.c_uint64, "uint32_t": ctypes.c_uint32, "int": ctypes.c_int,
+                        "float": ctypes.c_float, "qsdp_dtype": ctypes.c_int}[base]
+            assert ctype is want, (name, k, param, ctype)
 
 
 def test_binding_rejects_undersized_buffers_before_calling_the_library():
@@ -111,3 +120,17 @@ def test_binding_rejects_undersized_buffers_before_calling_the_library():
         qb._rows_ok(torch.zeros((3, 100), dtype=torch.int32), torch.zeros((3, 2)), 1024, 4, 1024)
     qb._rows_ok(torch.zeros((3, 128), dtype=torch.int32), torch.zeros((3, 2)), 1024, 4, 1024)
     qb._packed_ok(codes, meta, 1024, 9, 1024)                # invalid bits: left to the library
+
+
+def test_binding_rejects_tensors_on_different_devices():
+    """A kernel runs on the device of its first tensor; memory of another device would fault there, so the
+    binding refuses the call (shown with the `meta` device standing in for a second GPU)."""
+    import torch
+    x = torch.zeros(1024)
+    g = torch.zeros(1024, device="meta")
+    with pytest.raises(ValueError, match="tensors on"):
+        qb.qsdp_fused_step(x, g, 1e-3, 8, 4, 1024, 0.0, 0)
+    with pytest.raises(ValueError, match="tensors on"):
+        qb.qsdp_dequantize(torch.zeros(256, dtype=torch.int32), torch.zeros(2), 1024, 8, 1024, out=g)
+    with pytest.raises(TypeError):                             # same device, but not a GPU tensor
+        qb.qsdp_fused_step(x, torch.zeros(1024), 1e-3, 8, 4, 1024, 0.0, 0)
