@@ -193,7 +193,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES if (a.workload == "gpt-1.3b" and not a.emit_codes) else None,
+            "traffic": MEASURED_TRAFFIC_BYTES if (a.workload == "gpt-1.3b" and not (a.emit_codes or a.per_layer or a.segmented)
+                                                 and (wbits, gbits, bucket, delta) == (8, 4, 1024, 0.0)) else None,
             "kernel": "wave_kernel<FUSED> (qsdp_fused_step)",
             "algorithmic_bytes_per_launch": alg_bytes,
             "kernel_ms_mean": round(ev_mean, 4),
