@@ -14,7 +14,7 @@ namespace qsdp {
 // exist; `partial` (wave-uniform) selects the guarded element-wise path for a short bucket.
 template <int G, int R>
 __device__ __forceinline__ void load_rows(const float* base, int l, int m, bool partial, float (&v)[R][4]) {
-    if (!partial) {
+    if (__builtin_expect(!partial, 1)) {
         const f4* p = reinterpret_cast<const f4*>(base) + l;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -43,7 +43,7 @@ __device__ __forceinline__ float widen16(uint32_t h) {
 // The same tile read from 2-byte values, 8 bytes per lane and row.
 template <int G, int R, bool BF16>
 __device__ __forceinline__ void load_rows_half(const uint16_t* base, int l, int m, bool partial, float (&v)[R][4]) {
-    if (!partial) {
+    if (__builtin_expect(!partial, 1)) {
         const u2* p = reinterpret_cast<const u2*>(base) + l;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -66,7 +66,7 @@ __device__ __forceinline__ void load_rows_half(const uint16_t* base, int l, int 
 
 template <int G, int R>
 __device__ __forceinline__ void store_rows(float* base, int l, int m, bool partial, const float (&v)[R][4]) {
-    if (!partial) {
+    if (__builtin_expect(!partial, 1)) {
         f4* p = reinterpret_cast<f4*>(base) + l;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -88,7 +88,7 @@ __device__ __forceinline__ void store_rows(float* base, int l, int m, bool parti
 template <int G, int R>
 __device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m, bool partial, float& lo,
                                             float& hi) {
-    if (!partial) {
+    if (__builtin_expect(!partial, 1)) {
         lo = v[0][0];
         hi = v[0][0];
 #pragma unroll
@@ -476,7 +476,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 }
             }
             if constexpr (MODE == MODE_GRAD) {
-                if (partial) zero_slots_past_end<G, R>(gcode, l, m);
+                if (__builtin_expect(partial, 0)) zero_slots_past_end<G, R>(gcode, l, m);
                 store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, gcode);
                 if (writes_meta) {
                     p.meta[2 * bucket] = gbase;
@@ -585,7 +585,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             base = (k0 + xi) * p.delta;
             scale = p.delta;
             uint32_t sat_here = 0;
-            if (!partial) {
+            if (__builtin_expect(!partial, 1)) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
