@@ -214,6 +214,31 @@ __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     return c;
 }
 
+// The same search without control flow per element: `first[k]` = the lowest index whose level
+// equals lv[k] (fill_first_equal), looked up instead of walked to. The encoder's 16 independent
+// searches of a lane then interleave freely; with the loop above each of them is a basic block.
+template <int BITS>
+__device__ __forceinline__ int nearest_level(float z, const float* lv, const int* first) {
+    constexpr int K = 1 << BITS;
+    int j = 0;
+#pragma unroll
+    for (int step = K / 2; step >= 1; step >>= 1)
+        if (lv[j + step - 1] < z) j += step;
+    const int lo_idx = j > 0 ? j - 1 : 0;
+    const float d_lo = fabsf(z - lv[lo_idx]);
+    const float d_hi = fabsf(z - lv[j]);
+    return first[d_hi < d_lo ? j : lo_idx];
+}
+
+// first[k] for k = k0, k0 + stride, ... < K (lv complete and visible to the caller's threads)
+__device__ __forceinline__ void fill_first_equal(const float* lv, int* first, int K, int k0, int stride) {
+    for (int k = k0; k < K; k += stride) {
+        int j = k;
+        while (j > 0 && lv[j - 1] == lv[j]) --j;
+        first[k] = j;
+    }
+}
+
 // Unbiased rounding of z onto the two of the K = 2^BITS ascending levels `lv` (in LDS) that
 // enclose it: with i the largest index such that lv[i] <= z, code = i + [h * 2^-16 < p],
 // p = (z - lv[i]) / (lv[i+1] - lv[i]); z below the first level gives 0, at or above the last K-1.

@@ -357,13 +357,19 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     // workgroup; with one table per tensor every wave keeps the table of the tensor it works on
     // in a slot of its own and reloads it when its buckets move on to another tensor.
     __shared__ float level_tables[mode_is_levels(MODE) ? 4 * (1 << SB) : 1];
+    __shared__ int level_firsts[MODE == MODE_LEVELS ? 4 * (1 << SB) : 1];  // see fill_first_equal
     const bool levels_per_tensor = mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr;
     const float* level_table = level_tables + (levels_per_tensor ? wave_in_block * (1u << SB) : 0u);
+    const int* level_first = level_firsts + (levels_per_tensor && MODE == MODE_LEVELS ? wave_in_block * (1u << SB) : 0u);
     uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
     if constexpr (mode_is_levels(MODE)) {
         if (!levels_per_tensor) {
             for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_tables[k] = p.levels[k];
             __syncthreads();
+            if constexpr (MODE == MODE_LEVELS) {
+                fill_first_equal(level_tables, level_firsts, 1 << SB, threadIdx.x, blockDim.x);
+                __syncthreads();
+            }
         }
     }
 
@@ -548,6 +554,12 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        if constexpr (MODE == MODE_LEVELS) {
+                            fill_first_equal(slot, level_firsts + wave_in_block * (1u << SB), 1 << SB, lane, 64);
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                            __builtin_amdgcn_wave_barrier();
+                            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        }
                         loaded_tensor = cur;
                     }
                 }
@@ -570,7 +582,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const float z = (w[r][i] - grid.lo) * grid.inv;
-                            const float c = (float)nearest_level<SB>(z, level_table);
+                            const float c = (float)nearest_level<SB>(z, level_table, level_first);
                             w[r][i] = mine ? c : w[r][i];
                         }
                 }
