@@ -252,9 +252,11 @@ def levels_report(torch, qb, x, g, n, workload, bucket, dev):
             fit_ms, _ = time_call(lambda i: qb.qsdp_fit_levels(v, bits, bucket, 0.01, fitted, fit_buckets), 1, torch)
             row = {"tensor": name, "bits": bits, "fit_ms": round(fit_ms, 3), "fit_batches": fit_buckets}
             for label, table in (("uniform", uniform), ("fitted", fitted)):
-                enc_ms, _ = time_call(lambda i: qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta), 3, torch)
-                dec_ms, _ = time_call(lambda i: qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out), 3,
-                                      torch)
+                qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta)          # untimed first calls
+                qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out)
+                _, enc_ms = time_call(lambda i: qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta), 9, torch)
+                _, dec_ms = time_call(lambda i: qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out), 9,
+                                      torch)  # medians
                 err = float(torch.linalg.vector_norm((out - v).double())) / vnorm
                 # the quantity the fit minimises: rms error in bucket-normalised coordinates (full buckets only)
                 nbf = n // bucket
@@ -288,10 +290,12 @@ def levels_per_layer(torch, qb, wl, x, g, shape, bucket, dev):
         tables[small] = uniform
         codes, meta = segs.alloc_packed(bits)
         meta = meta.reshape(-1)
-        enc_ms, _ = time_call(lambda i: qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, i, 0),
-                              5, torch)
-        dec_ms, _ = time_call(lambda i: qb.qsdp_dequantize_levels_segmented(codes, meta, segs, bits, tables, out), 5,
-                              torch)
+        qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, 0, 0)      # untimed first calls
+        qb.qsdp_dequantize_levels_segmented(codes, meta, segs, bits, tables, out)
+        _, enc_ms = time_call(lambda i: qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, i, 0),
+                              9, torch)
+        _, dec_ms = time_call(lambda i: qb.qsdp_dequantize_levels_segmented(codes, meta, segs, bits, tables, out), 9,
+                              torch)  # medians
         res[name] = {"fit_ms": round(fit_ms, 3), "encode_ms": round(enc_ms, 4), "decode_bf16_ms": round(dec_ms, 4),
                      "encode_GB/s": round((4 + bits / 8 + 8 / bucket) * n / enc_ms / 1e6, 1),
                      "decode_GB/s": round((2 + bits / 8 + 8 / bucket) * n / dec_ms / 1e6, 1),
