@@ -29,6 +29,9 @@ def _units():
     for b, (g, r, w) in WAVE_SHAPES.items():
         units.append((f"qsdp_wave_{b}.o", "qsdp_wave_inst.hip",
                       [f"-DQSDP_G={g}", f"-DQSDP_R={r}", f"-DQSDP_W={w}", f"-DQSDP_B={b}"]))
+    # the weight quantizer alone also as two waves per 1024-bucket (its faster shape; the other modes are not)
+    units.append(("qsdp_wave_1024w2.o", "qsdp_wave_inst.hip",
+                  ["-DQSDP_G=64", "-DQSDP_R=2", "-DQSDP_W=2", "-DQSDP_B=1024", "-DQSDP_WEIGHT_ONLY=1024w2"]))
     return units
 
 

@@ -21,6 +21,7 @@ QSDP_DECLARE_WAVE(512)
 QSDP_DECLARE_WAVE(1024)
 QSDP_DECLARE_WAVE(2048)
 QSDP_DECLARE_WAVE(4096)
+QSDP_DECLARE_WAVE(1024w2)  // weight quantizer only: two waves per 1024-bucket
 #undef QSDP_DECLARE_WAVE
 
 hipError_t launch_block(int mode, const Params& p, unsigned grid, hipStream_t s);

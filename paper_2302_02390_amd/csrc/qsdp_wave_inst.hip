@@ -1,6 +1,7 @@
 // Instantiations of the wave kernels for one bucket shape; compiled with
 // -DQSDP_G=<lanes per bucket> -DQSDP_R=<rows of 4*G elements per wave> -DQSDP_W=<waves per
-// bucket> -DQSDP_B=<4*G*R*W>.
+// bucket> -DQSDP_B=<4*G*R*W>. With -DQSDP_WEIGHT_ONLY=<name suffix> only the weight quantizer is
+// instantiated, as launch_wave_<suffix> (a second shape for a bucket size that has one already).
 #include "qsdp_launch.hpp"
 
 #if !defined(QSDP_G) || !defined(QSDP_R) || !defined(QSDP_W) || !defined(QSDP_B)
@@ -39,6 +40,12 @@ hipError_t by_bits(int bits, const Params& p, unsigned grid, hipStream_t s) {
 
 }  // namespace
 
+#ifdef QSDP_WEIGHT_ONLY
+hipError_t QSDP_CAT(launch_wave_, QSDP_WEIGHT_ONLY)(int mode, int bits, const Params& p, unsigned grid,
+                                                    hipStream_t s) {
+    return mode == MODE_WEIGHT ? by_bits<MODE_WEIGHT>(bits, p, grid, s) : hipErrorInvalidValue;
+}
+#else
 hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, unsigned grid,
                                           hipStream_t s) {
     switch (mode) {
@@ -64,5 +71,6 @@ hipError_t QSDP_CAT(launch_wave_, QSDP_B)(int mode, int bits, const Params& p, u
         default: return hipErrorInvalidValue;
     }
 }
+#endif
 
 }  // namespace qsdp
