@@ -17,7 +17,9 @@
 //   * block kernel: one 256-thread workgroup per bucket, staged in LDS; any bucket size, any
 //     bits. Used for the bucket sizes the wave kernels are not instantiated for (several times
 //     slower: the values make a round trip through LDS and the codes are packed bit by bit).
-// Decoders, the decode-and-sum kernel and the level-fitting kernel follow at the end.
+// The modes and parameters are in qsdp_params.hpp, the two encoder families in qsdp_wave_kernel.hpp and
+// qsdp_block_kernel.hpp, the decoders and the element-wise decode-and-sum in qsdp_decoders.hpp, the
+// level fit in qsdp_fit_kernel.hpp.
 #pragma once
 
 #include "qsdp_params.hpp"

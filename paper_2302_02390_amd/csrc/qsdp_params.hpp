@@ -10,6 +10,13 @@ namespace qsdp {
 // Largest bucket any kernel accepts (the block kernel and the level fit stage one bucket in LDS).
 constexpr int kMaxBucket = 8192;
 
+// What one launch of an encoder kernel does:
+// MODE_GRAD: Q^g of a gradient vector: coin-flip (or shared-shift) rounding onto the bucket's
+// min-max grid, packed codes + meta out (Section 3.2, the appendix definition).
+// MODE_WEIGHT: Q^w of a weight vector: random-shift rounding onto the bucket's min-max grid or onto
+// the explicit lattice delta, packed codes + meta out (Definition 1).
+// MODE_FUSED: x <- Q^w(x - lr * Q^g(g)) in one pass, x updated in place, codes + meta of the new x
+// optionally emitted (the iteration of Sections 3.3 / 4.1).
 // MODE_FUSED_CODES: the fused step with the weights resident as packed codes + meta (the
 // iterate always lies on its bucket grids, so codes + meta hold it exactly): decode, step,
 // re-quantize, write codes + meta back in place; no fp32 copy of x is read or written.
