@@ -2,7 +2,8 @@
 points (sizes, bucket sizes with and without a wave kernel, code widths, explicit grids that are
 not powers of two, variant flags, seeds, offsets; Gaussian, heavy-tailed, huge and tiny, sparse and
 nearly constant data; 16-bit gradients; per-tensor level tables). Longer runs of the same generator
-(144,000 cases, and 101,000 more after the last two families were added) found no mismatch."""
+(144,000 cases, 101,000 more after the last two families were added, 148,000 more with binary16 decoding and the
+code-resident AdamW step) found no mismatch."""
 import numpy as np
 import pytest
 import torch
