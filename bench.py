@@ -520,10 +520,18 @@ def cpu_baseline(x_head, g_head, lr, wbits, gbits, bucket, delta, bytes_per_para
     ref.fused_step(xs, gs, lr, wbits, gbits, bucket, delta, 0)
     dt = time.perf_counter() - t0
     ref.set_threads(1)
+    # the same oracle on one thread, on a sixteenth of that sample (about as long)
+    m1 = max(bucket, m // 16 // bucket * bucket)
+    t0 = time.perf_counter()
+    ref.fused_step(xs[:m1], gs[:m1], lr, wbits, gbits, bucket, delta, 0)
+    dt1 = time.perf_counter() - t0
     return {"value": round(bytes_per_param * m / dt / 1e9, 3), "unit": "GB/s", "cores": threads,
             "kind": "oracle", "params_per_s": round(m / dt, 1), "seconds": round(dt, 3),
             "sample": f"first {m} elements of the same x and g, one fused step (seed 0), "
-                      f"bucket-parallel oracle on {threads} threads"}
+                      f"bucket-parallel oracle on {threads} threads",
+            "single_thread": {"value": round(bytes_per_param * m1 / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                              "params_per_s": round(m1 / dt1, 1), "seconds": round(dt1, 3),
+                              "sample": f"first {m1} elements"}}
 
 
 if __name__ == "__main__":
