@@ -434,6 +434,12 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
         xh = x.clone()
         run(f"fused_step_W{wbits}G{gbits}_{name}_gradient",
             lambda i: qb.qsdp_fused_step_g16(xh, g16, 1e-3, wbits, gbits, bucket, 0.0, i), 10.0)
+        if name == "bf16":
+            # ... and the new weights written once more as bf16 for the next forward pass
+            x16 = torch.empty(n, dtype=dt, device=dev)
+            run(f"fused_step_mp_W{wbits}G{gbits}_bf16_gradient_bf16_weights_out",
+                lambda i: qb.qsdp_fused_step_mp(xh, g16, 1e-3, wbits, gbits, bucket, 0.0, i, x16=x16), 12.0)
+            del x16
         del g16, xh
     # AdamW between the quantizers (moments in fp32): read x, g, m, v; write x, m, v
     mom = torch.zeros(n, dtype=torch.float32, device=dev)

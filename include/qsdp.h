@@ -263,6 +263,23 @@ int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n,
                         uint64_t* n_saturated, void* stream);
 
 /*
+ * The fused step in a mixed-precision training loop: the gradient may arrive in 16 bits (as in
+ * the *_g16 calls; g_dtype QSDP_F32, QSDP_F16 or QSDP_BF16 says what g points to), and the new
+ * quantized weights Q^w(y), which x receives in fp32 (unless QSDP_FLAG_KEEP_MASTER keeps y
+ * there), can be written once more in 16 bits for the next forward pass:
+ *   x16        out, nullable  device uint16[n], 16-byte aligned: decode(Q^w(y)) rounded to x16_dtype
+ *                             (nearest even), i.e. what qsdp_dequantize gives for the emitted codes
+ *   x16_dtype                 QSDP_BF16 or QSDP_F16 (ignored when x16 is NULL)
+ * 2 more bytes written per parameter instead of a separate conversion or decoding pass.
+ * Everything else as in qsdp_fused_step_ex.
+ */
+int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr,
+                       int wbits, int gbits, int bucket, float delta,
+                       uint64_t seed, uint64_t index_offset, uint32_t flags,
+                       uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
+                       uint64_t* n_saturated, void* stream);
+
+/*
  * qsdp_fused_step_ex with the seed advanced from device memory, for callers that capture the
  * step in a HIP graph: kernel arguments are frozen at capture, so a replayed step would draw the
  * same random numbers again; here the seed in force is seed + *seed_dev (mod 2^64), read when the

@@ -37,6 +37,8 @@ _SIGNATURES = {
         [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _vp]),
     "qsdp_fused_step_g16": (_i32,
         [_vp, _vp, _i32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_mp": (_i32,
+        [_vp, _vp, _i32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _i32, _vp, _vp]),
     "qsdp_fused_step_dseed": (_i32,
         [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
     "qsdp_fused_step_codes": (_i32, [_vp, _vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp]),
@@ -705,6 +707,33 @@ def qsdp_fused_adamw_step_codes(wcodes, wmeta, g, m, v, lr, beta1, beta2, eps, w
                                                  beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket, delta,
                                                  seed, index_offset, flags, _ptr(n_saturated), _stream(g)),
                "qsdp_fused_adamw_step_codes")
+
+
+def qsdp_fused_step_mp(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, flags=0, wcodes=None, wmeta=None,
+                       x16=None, n_saturated=None):
+    """The fused step with a float32 / float16 / bfloat16 gradient and, optionally, the new quantized weights
+    written once more as float16 / bfloat16 into x16."""
+    gdt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16, torch.float16: QSDP_F16}.get(g.dtype)
+    if gdt is None:
+        raise TypeError("g must be float32, float16 or bfloat16")
+    _is(x, torch.float32); _is(g, g.dtype)
+    if g.numel() != x.numel():
+        raise ValueError("x and g differ in size")
+    xdt = QSDP_BF16
+    if x16 is not None:
+        if x16.dtype not in _G16:
+            raise TypeError("x16 must be float16 or bfloat16")
+        _is(x16, x16.dtype)
+        _need(x16, x.numel(), "x16")
+        xdt = _G16[x16.dtype]
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    _packed_ok(wcodes, wmeta, x.numel(), wbits, bucket)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_mp(_ptr(x), _ptr(g), gdt, x.numel(), lr, wbits, gbits, bucket, delta, seed,
+                                        index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
+                                        _ptr(n_saturated), _stream(x)), "qsdp_fused_step_mp")
 
 
 def _one_device(fn):

@@ -540,7 +540,8 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
                               n_saturated, stream);
 }
 
-static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, float* x, const void* g, uint64_t n, float lr, int wbits,
+static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, void* x16, uint32_t x16_f16, float* x, const void* g,
+                             uint64_t n, float lr, int wbits,
                              int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                              uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (seed_dev && (reinterpret_cast<uintptr_t>(seed_dev) & 7u)) return QSDP_EALIGN;
@@ -549,12 +550,14 @@ static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, float* x
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta)) return QSDP_EALIGN;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) || !aligned16(x16)) return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
     set_common(p, n, bucket, seed, index_offset, delta);
     p.flags = flags;
     p.x = x;
+    p.x16 = x16;
+    p.x16_f16 = x16_f16;
     p.g = static_cast<const float*>(g);
     p.codes = wcodes;
     p.meta = wmeta;
@@ -570,7 +573,7 @@ static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, float* x
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                        float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, uint64_t* n_saturated, void* stream) {
-    return fused_step_common(nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(nullptr, 0u, nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -578,7 +581,7 @@ int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr, int wb
                           float delta, uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!seed_dev) return QSDP_EINVAL;
-    return fused_step_common(seed_dev, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(seed_dev, 0u, nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -586,8 +589,17 @@ int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n,
                         int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
                         uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    return fused_step_common(nullptr, half_format(g_dtype), x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(nullptr, half_format(g_dtype), nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
+}
+
+int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr, int wbits, int gbits,
+                       int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
+                       float* wmeta, void* x16, qsdp_dtype x16_dtype, uint64_t* n_saturated, void* stream) {
+    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
+    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
+    return fused_step_common(nullptr, half_format(g_dtype), x16, x16_dtype == QSDP_F16 ? 1u : 0u, x, g, n, lr, wbits,
+                             gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta, n_saturated, stream);
 }
 
 static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g, const AdamScalars& adam, uint64_t n,

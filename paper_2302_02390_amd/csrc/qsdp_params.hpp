@@ -67,6 +67,7 @@ struct Params {
     // tensors
     const float* g;      // GRAD, FUSED: gradient (2-byte values when g_half != 0)
     float* x;            // FUSED: in/out weights
+    void* x16;           // FUSED, optional: the new quantized weights once more as bf16 / binary16 values
     const float* xin;    // WEIGHT, LEVELS: values to quantize
     const float* levels; // LEVELS: 2^wbits ascending levels in [0, 1]; segmented calls with
                          // levels_per_tensor: one such table per tensor, back to back
@@ -90,6 +91,7 @@ struct Params {
     uint64_t num_buckets;   // buckets this launch handles
     uint64_t block0;        // index_offset / 8
     uint32_t nseg;
+    uint32_t x16_f16;  // x16 holds IEEE binary16 instead of bf16
     uint32_t g_half;  // 0: binary32 gradient; 1: bf16, 2: binary16, widened to binary32 (exactly) on load
     uint32_t levels_per_tensor;  // LEVELS with segs: table of tensor t at levels + t * 2^wbits
     uint32_t flags;  // FLAG_* variants

@@ -84,6 +84,29 @@ __device__ __forceinline__ void store_rows(float* base, int l, int m, bool parti
     }
 }
 
+// The tile rounded to a 2-byte format (bf16, or binary16 when f16), 8 bytes per lane and row.
+template <int G, int R>
+__device__ __forceinline__ void store_rows_half(uint16_t* base, int l, int m, bool partial, bool f16,
+                                                const float (&v)[R][4]) {
+    if (__builtin_expect(!partial, 1)) {
+        u2* p = reinterpret_cast<u2*>(base) + l;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const u2 a = {half_bits(v[r][0], f16) | (half_bits(v[r][1], f16) << 16),
+                          half_bits(v[r][2], f16) | (half_bits(v[r][3], f16) << 16)};
+            __builtin_nontemporal_store(a, p + r * G);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = (r * G + l) * 4 + i;
+                if (idx < m) base[idx] = (uint16_t)half_bits(v[r][i], f16);
+            }
+    }
+}
+
 // min and max over the bucket (the group's G lanes); slots at or past m do not take part
 template <int G, int R>
 __device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m, bool partial, float& lo,
@@ -636,14 +659,16 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 p.meta[2 * bucket + 1] = scale;
             }
         }
-        if (active && !keep_master) {
-            if (kWritesX) {
+        // the decoded new weights: into x (unless x keeps the unquantized value) and, on request, once
+        // more in 16 bits (what a forward pass in reduced precision reads)
+        const bool want16 = MODE == MODE_FUSED && p.x16 != nullptr;
+        if (active && kWritesX && (!keep_master || want16)) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], scale, base);
-                store_rows<G, R>(p.x + e0, l, m, partial, w);
-            }
+                for (int i = 0; i < 4; ++i) w[r][i] = fmaf(w[r][i], scale, base);
+            if (!keep_master) store_rows<G, R>(p.x + e0, l, m, partial, w);
+            if (want16) store_rows_half<G, R>(static_cast<uint16_t*>(p.x16) + e0, l, m, partial, p.x16_f16 != 0, w);
         }
     }
 

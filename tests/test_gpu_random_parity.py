@@ -155,9 +155,18 @@ def one_case(rng):
             assert eq(np_u32(c), wc) and eq(np_u32(m), wm), tag
         else:
             c, m = qb.alloc_packed(n, wbits, B, DEV)
-            qb.qsdp_fused_step_g16(xd, g16.to(DEV), 1e-3, wbits, gbits, B, delta, seed, off, flags | keep, c,
-                                   m.reshape(-1), sat)
             wx, wc, wm, ws = ref.fused_step(x, wide, 1e-3, wbits, gbits, B, delta, seed, off, True, flags | keep)
+            if rng.random() < 0.5:
+                qb.qsdp_fused_step_g16(xd, g16.to(DEV), 1e-3, wbits, gbits, B, delta, seed, off, flags | keep, c,
+                                       m.reshape(-1), sat)
+            else:
+                # ... with the new quantized weights once more in 16 bits
+                xdt = torch.float16 if rng.random() < 0.5 else torch.bfloat16
+                x16 = torch.empty(n, dtype=xdt, device=DEV)
+                qb.qsdp_fused_step_mp(xd, g16.to(DEV), 1e-3, wbits, gbits, B, delta, seed, off, flags | keep, c,
+                                      m.reshape(-1), x16, sat)
+                assert np.array_equal(x16.view(torch.int16).cpu().numpy().view(np.uint16),
+                                      ref.dequantize(wc, wm, n, wbits, B, ref.F16 if xdt == torch.float16 else ref.BF16)), tag
             assert eq(np_f32(xd), wx) and eq(np_u32(c), wc) and eq(np_u32(m), wm) and int(sat) == ws, tag
     elif which == 8:
         # several tensors in one buffer, each with a level table of its own
