@@ -472,6 +472,14 @@ int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float*
                                     uint64_t total_buckets, float lr, int wbits, int gbits,
                                     int bucket, float delta, uint64_t seed, uint64_t index_offset,
                                     uint32_t flags, uint64_t* n_saturated, void* stream);
+/* qsdp_fused_step_mp for many tensors in one launch (flags as in qsdp_fused_step_ex; x16, like x and g,
+ * is indexed by the position in the flat buffer). */
+int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype,
+                                 const qsdp_segment* table, uint32_t nseg, uint64_t total_buckets,
+                                 float lr, int wbits, int gbits, int bucket, float delta,
+                                 uint64_t seed, uint64_t index_offset, uint32_t flags,
+                                 uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
+                                 uint64_t* n_saturated, void* stream);
 /* The level fit of many tensors side by side (the paper fits every large layer on its own,
  * Appendix C): tensor t of the table is fitted exactly as qsdp_fit_levels would fit it alone
  * (at most max_batches of its buckets, if > 0), starting from and overwriting

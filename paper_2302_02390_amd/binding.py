@@ -68,6 +68,9 @@ _SIGNATURES = {
     "qsdp_quantize_weight_segmented": (_i32, [_vp, _vp, _u32, _u64, _i32, _i32, _f32, _u64, _vp, _vp, _vp, _vp]),
     "qsdp_fused_step_segmented": (_i32,
         [_vp, _vp, _vp, _u32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_segmented_mp": (_i32,
+        [_vp, _vp, _i32, _vp, _u32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _i32,
+         _vp, _vp]),
     "qsdp_dequantize_segmented": (_i32, [_vp, _vp, _vp, _u32, _u64, _i32, _i32, _i32, _vp, _vp]),
     "qsdp_fused_adamw_step_segmented": (_i32,
         [_vp, _vp, _vp, _vp, _vp, _u32, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32,
@@ -734,6 +737,32 @@ def qsdp_fused_step_mp(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset
         _check(lib().qsdp_fused_step_mp(_ptr(x), _ptr(g), gdt, x.numel(), lr, wbits, gbits, bucket, delta, seed,
                                         index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
                                         _ptr(n_saturated), _stream(x)), "qsdp_fused_step_mp")
+
+
+def qsdp_fused_step_segmented_mp(x, g, segs, lr, wbits, gbits, delta, seed, index_offset=0, flags=0, wcodes=None,
+                                 wmeta=None, x16=None, n_saturated=None):
+    """qsdp_fused_step_mp over the tensors of a segment table, one launch."""
+    gdt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16, torch.float16: QSDP_F16}.get(g.dtype)
+    if gdt is None:
+        raise TypeError("g must be float32, float16 or bfloat16")
+    _is(x, torch.float32); _is(g, g.dtype)
+    _need(x, segs.n, "x"); _need(g, segs.n, "g")
+    xdt = QSDP_BF16
+    if x16 is not None:
+        if x16.dtype not in _G16:
+            raise TypeError("x16 must be float16 or bfloat16")
+        _is(x16, x16.dtype)
+        _need(x16, segs.n, "x16")
+        xdt = _G16[x16.dtype]
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    segs.check_packed(wcodes, wmeta, wbits)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_step_segmented_mp(_ptr(x), _ptr(g), gdt, _ptr(segs.device), segs.nseg,
+                                                  segs.total_buckets, lr, wbits, gbits, segs.bucket, delta, seed,
+                                                  index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
+                                                  _ptr(n_saturated), _stream(x)), "qsdp_fused_step_segmented_mp")
 
 
 def _one_device(fn):

@@ -540,24 +540,39 @@ int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, i
                               n_saturated, stream);
 }
 
-static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, void* x16, uint32_t x16_f16, float* x, const void* g,
-                             uint64_t n, float lr, int wbits,
+// The optional parts of a fused step: a multi-tensor table, a device-resident seed increment, the
+// gradient's format (0: fp32, 1: bf16, 2: binary16) and a 16-bit copy of the new weights.
+struct FusedStepOptions {
+    const SegmentTable* segs;
+    const uint64_t* seed_dev;
+    uint32_t g_half;
+    void* x16;
+    uint32_t x16_f16;
+};
+
+static int fused_step_common(const FusedStepOptions& opt, float* x, const void* g, uint64_t n, float lr, int wbits,
                              int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                              uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
-    if (seed_dev && (reinterpret_cast<uintptr_t>(seed_dev) & 7u)) return QSDP_EALIGN;
+    if (opt.segs) {
+        const int rc = segments_ok(*opt.segs, bucket, &n);
+        if (rc != QSDP_OK) return rc;
+    }
+    if (opt.seed_dev && (reinterpret_cast<uintptr_t>(opt.seed_dev) & 7u)) return QSDP_EALIGN;
     if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
         (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) || !aligned16(x16)) return QSDP_EALIGN;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) || !aligned16(opt.x16))
+        return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
-    set_common(p, n, bucket, seed, index_offset, delta);
+    set_common(p, opt.segs ? 0 : n, bucket, seed, index_offset, delta);
+    if (opt.segs) set_segments(p, *opt.segs);
     p.flags = flags;
     p.x = x;
-    p.x16 = x16;
-    p.x16_f16 = x16_f16;
+    p.x16 = opt.x16;
+    p.x16_f16 = opt.x16_f16;
     p.g = static_cast<const float*>(g);
     p.codes = wcodes;
     p.meta = wmeta;
@@ -565,15 +580,15 @@ static int fused_step_common(const uint64_t* seed_dev, uint32_t g_half, void* x1
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    p.seed_dev = reinterpret_cast<const unsigned long long*>(seed_dev);
-    p.g_half = g_half;
+    p.seed_dev = reinterpret_cast<const unsigned long long*>(opt.seed_dev);
+    p.g_half = opt.g_half;
     return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
 }
 
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                        float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, uint64_t* n_saturated, void* stream) {
-    return fused_step_common(nullptr, 0u, nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    return fused_step_common(FusedStepOptions{}, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -581,7 +596,9 @@ int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr, int wb
                           float delta, uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!seed_dev) return QSDP_EINVAL;
-    return fused_step_common(seed_dev, 0u, nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    FusedStepOptions opt = {};
+    opt.seed_dev = seed_dev;
+    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -589,7 +606,9 @@ int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n,
                         int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
                         uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    return fused_step_common(nullptr, half_format(g_dtype), nullptr, 0u, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    FusedStepOptions opt = {};
+    opt.g_half = half_format(g_dtype);
+    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                              wmeta, n_saturated, stream);
 }
 
@@ -598,8 +617,29 @@ int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, 
                        float* wmeta, void* x16, qsdp_dtype x16_dtype, uint64_t* n_saturated, void* stream) {
     if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
     if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
-    return fused_step_common(nullptr, half_format(g_dtype), x16, x16_dtype == QSDP_F16 ? 1u : 0u, x, g, n, lr, wbits,
-                             gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta, n_saturated, stream);
+    FusedStepOptions opt = {};
+    opt.g_half = half_format(g_dtype);
+    opt.x16 = x16;
+    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
+    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta,
+                             n_saturated, stream);
+}
+
+int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype, const qsdp_segment* table,
+                                 uint32_t nseg, uint64_t total_buckets, float lr, int wbits, int gbits,
+                                 int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
+                                 uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
+                                 uint64_t* n_saturated, void* stream) {
+    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
+    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
+    const SegmentTable segs = {table, nseg, total_buckets};
+    FusedStepOptions opt = {};
+    opt.segs = &segs;
+    opt.g_half = half_format(g_dtype);
+    opt.x16 = x16;
+    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
+    return fused_step_common(opt, x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta,
+                             n_saturated, stream);
 }
 
 static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g, const AdamScalars& adam, uint64_t n,
@@ -775,29 +815,11 @@ int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* tabl
                               uint64_t total_buckets, float lr, int wbits, int gbits, int bucket,
                               float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes,
                               float* wmeta, uint64_t* n_saturated, void* stream) {
-    if (!x || !g || !table || nseg == 0 || total_buckets < nseg || !shape_ok(1, wbits, bucket) ||
-        !shape_ok(1, gbits, bucket))
-        return QSDP_EINVAL;
-    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
-    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) ||
-        (reinterpret_cast<uintptr_t>(table) & 7u))
-        return QSDP_EALIGN;
-    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
-    Params p = {};
-    set_common(p, 0, bucket, seed, index_offset, delta);
-    p.segs = reinterpret_cast<const Segment*>(table);
-    p.nseg = nseg;
-    p.num_buckets = total_buckets;
-    p.x = x;
-    p.g = g;
-    p.codes = wcodes;
-    p.meta = wmeta;
-    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
-    p.gbits = gbits;
-    p.wbits = wbits;
-    p.lr = lr;
-    return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+    const SegmentTable segs = {table, nseg, total_buckets};
+    FusedStepOptions opt = {};
+    opt.segs = &segs;
+    return fused_step_common(opt, x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, 0u, wcodes, wmeta,
+                             n_saturated, stream);
 }
 
 int qsdp_quantize_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg,

@@ -68,3 +68,33 @@ def test_mixed_precision_step_argument_errors():
     assert L.qsdp_fused_step_mp(p(x), p(g), 0, n, 1e-3, 8, 4, B, 0.0, 0, 0, 0, None, None, p(x16[1:]), 1, None, None) == qb.QSDP_EALIGN
     with pytest.raises(ValueError):
         qb.qsdp_fused_step_mp(x, g, 1e-3, 8, 4, B, 0.0, 0, x16=x16[:100])
+
+
+@pytest.mark.parametrize("gdtype,xdtype", [(torch.float16, torch.float16), (torch.bfloat16, torch.bfloat16),
+                                           (torch.float32, torch.bfloat16)])
+@pytest.mark.parametrize("B,wbits,gbits,flags", [(1024, 8, 4, 0), (128, 5, 4, qb.QSDP_FLAG_KEEP_MASTER), (96, 6, 3, 0)])
+def test_segmented_mixed_precision_step(gdtype, xdtype, B, wbits, gbits, flags):
+    """Per-layer tensors in one launch: every tensor equals the oracle's single-tensor step on the widened
+    gradient (index_offset + the tensor's position), its 16-bit copy the oracle's decode of the emitted codes."""
+    sizes = [768, 2304, 768 * 12, 8, 3072, 16, 1024 * 3 + 8, 4096 * 2, 24, 5000 + 3]
+    n = sum(sizes)
+    x, g = synth(n, 1350 + B)
+    gt = torch.from_numpy(g).to(gdtype)
+    wide = gt.float().numpy()
+    segs = qb.Segments(sizes, B, DEV)
+    xd = torch.from_numpy(x).to(DEV)
+    x16 = torch.empty(n, dtype=xdtype, device=DEV)
+    codes, meta = segs.alloc_packed(wbits)
+    sat = torch.zeros(1, dtype=torch.int64, device=DEV)
+    qb.qsdp_fused_step_segmented_mp(xd, gt.to(DEV), segs, 1e-3, wbits, gbits, 0.0, 4, 64, flags, codes,
+                                    meta.reshape(-1), x16, sat)
+    wx, wc, wm, w16, off = [], [], [], [], 0
+    for s in sizes:
+        a, c, m, _ = ref.fused_step(x[off:off + s], wide[off:off + s], 1e-3, wbits, gbits, B, 0.0, 4,
+                                    index_offset=64 + off, emit_codes=True, flags=flags)
+        wx.append(a); wc.append(c); wm.append(m.reshape(-1))
+        w16.append(ref.dequantize(c, m, s, wbits, B, REF_DT[xdtype]))
+        off += s
+    assert bits_equal(np_f32(xd), np.concatenate(wx))
+    assert np.array_equal(np_u32(codes), np.concatenate(wc)) and np.array_equal(np_u32(meta), np.concatenate(wm).view(np.uint32))
+    assert np.array_equal(_h(x16), np.concatenate(w16))
