@@ -448,6 +448,13 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"fused_adamw_step_W{wbits}G{gbits}",
         lambda i: qb.qsdp_fused_adamw_step(xa, g, mom, var, 2e-4, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** (i + 1),
                                            1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i), 28.0)
+    # ... as a mixed-precision training step: bf16 gradient in (2 B), bf16 copy of the new weights out (2 B)
+    g16 = g.to(torch.bfloat16)
+    x16 = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    run(f"fused_adamw_step_mp_W{wbits}G{gbits}_bf16_gradient_bf16_weights_out",
+        lambda i: qb.qsdp_fused_adamw_step_mp(xa, g16, mom, var, 2e-4, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** (i + 1),
+                                              1 - 0.95 ** (i + 1), wbits, gbits, bucket, 0.0, i, x16=x16), 28.0)
+    del g16, x16
     # the same with the weights resident as codes: read codes, g, m, v; write codes, m, v
     qb.qsdp_quantize_weight(x, wbits, bucket, 0.0, 5, wc, wm)
     run(f"fused_adamw_step_codes_W{wbits}G{gbits}",

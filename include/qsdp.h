@@ -279,6 +279,16 @@ int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, 
                        uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
                        uint64_t* n_saturated, void* stream);
 
+/* qsdp_fused_adamw_step in the same mixed-precision form (gradient format g_dtype, optional 16-bit
+ * copy x16 of the new quantized weights): the training step of the paper's experiments on one worker. */
+int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float* m, float* v,
+                             uint64_t n, float lr, float beta1, float beta2, float eps,
+                             float weight_decay, float bias1, float bias2,
+                             int wbits, int gbits, int bucket, float delta,
+                             uint64_t seed, uint64_t index_offset, uint32_t flags,
+                             uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
+                             uint64_t* n_saturated, void* stream);
+
 /*
  * qsdp_fused_step_ex with the seed advanced from device memory, for callers that capture the
  * step in a HIP graph: kernel arguments are frozen at capture, so a replayed step would draw the

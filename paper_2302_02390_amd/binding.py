@@ -45,6 +45,9 @@ _SIGNATURES = {
     "qsdp_fused_adamw_step": (_i32,
         [_vp, _vp, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32, _u64,
          _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_adamw_step_mp": (_i32,
+        [_vp, _vp, _i32, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32, _u64,
+         _u64, _u32, _vp, _vp, _vp, _i32, _vp, _vp]),
     "qsdp_fused_adamw_step_codes": (_i32,
         [_vp, _vp, _vp, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32,
          _u64, _u64, _u32, _vp, _vp]),
@@ -763,6 +766,35 @@ def qsdp_fused_step_segmented_mp(x, g, segs, lr, wbits, gbits, delta, seed, inde
                                                   segs.total_buckets, lr, wbits, gbits, segs.bucket, delta, seed,
                                                   index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
                                                   _ptr(n_saturated), _stream(x)), "qsdp_fused_step_segmented_mp")
+
+
+def qsdp_fused_adamw_step_mp(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket, delta,
+                             seed, index_offset=0, flags=0, wcodes=None, wmeta=None, x16=None, n_saturated=None):
+    """qsdp_fused_adamw_step with a float32 / float16 / bfloat16 gradient and an optional float16 / bfloat16
+    copy x16 of the new quantized weights."""
+    gdt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16, torch.float16: QSDP_F16}.get(g.dtype)
+    if gdt is None:
+        raise TypeError("g must be float32, float16 or bfloat16")
+    _is(x, torch.float32); _is(g, g.dtype); _is(m, torch.float32); _is(v, torch.float32)
+    n = x.numel()
+    if g.numel() != n or m.numel() != n or v.numel() != n:
+        raise ValueError("x, g, m and v differ in size")
+    xdt = QSDP_BF16
+    if x16 is not None:
+        if x16.dtype not in _G16:
+            raise TypeError("x16 must be float16 or bfloat16")
+        _is(x16, x16.dtype)
+        _need(x16, n, "x16")
+        xdt = _G16[x16.dtype]
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    _packed_ok(wcodes, wmeta, n, wbits, bucket)
+    with torch.cuda.device(x.device):
+        _check(lib().qsdp_fused_adamw_step_mp(_ptr(x), _ptr(g), gdt, _ptr(m), _ptr(v), n, lr, beta1, beta2, eps,
+                                              weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed,
+                                              index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
+                                              _ptr(n_saturated), _stream(x)), "qsdp_fused_adamw_step_mp")
 
 
 def _one_device(fn):

@@ -642,10 +642,11 @@ int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype, co
                              n_saturated, stream);
 }
 
-static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g, const AdamScalars& adam, uint64_t n,
+static int fused_adamw_common(const FusedStepOptions& opt, float* x, const void* g, const AdamScalars& adam, uint64_t n,
                               float lr, int wbits, int gbits, int bucket, float delta, uint64_t seed,
                               uint64_t index_offset, uint32_t flags, uint32_t* wcodes, float* wmeta,
                               uint64_t* n_saturated, void* stream) {
+    const SegmentTable* segs = opt.segs;
     if (segs) {
         const int rc = segments_ok(*segs, bucket, &n);
         if (rc != QSDP_OK) return rc;
@@ -656,7 +657,7 @@ static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
     if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
     if (!aligned16(x) || !aligned16(g) || !aligned16(adam.m) || !aligned16(adam.v) || !aligned16(wcodes) ||
-        !aligned16(wmeta))
+        !aligned16(wmeta) || !aligned16(opt.x16))
         return QSDP_EALIGN;
     if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
     Params p = {};
@@ -664,7 +665,10 @@ static int fused_adamw_common(const SegmentTable* segs, float* x, const float* g
     if (segs) set_segments(p, *segs);
     p.flags = flags;
     p.x = x;
-    p.g = g;
+    p.x16 = opt.x16;
+    p.x16_f16 = opt.x16_f16;
+    p.g = static_cast<const float*>(g);
+    p.g_half = opt.g_half;
     p.codes = wcodes;
     p.meta = wmeta;
     p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
@@ -680,8 +684,24 @@ int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
-    return fused_adamw_common(nullptr, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags,
+    return fused_adamw_common(FusedStepOptions{}, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags,
                               wcodes, wmeta, n_saturated, stream);
+}
+
+int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float* m, float* v, uint64_t n, float lr,
+                             float beta1, float beta2, float eps, float weight_decay, float bias1, float bias2,
+                             int wbits, int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                             uint32_t flags, uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
+                             uint64_t* n_saturated, void* stream) {
+    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
+    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
+    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
+    FusedStepOptions opt = {};
+    opt.g_half = half_format(g_dtype);
+    opt.x16 = x16;
+    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
+    return fused_adamw_common(opt, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+                              wmeta, n_saturated, stream);
 }
 
 int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v, const qsdp_segment* table,
@@ -692,7 +712,9 @@ int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v
                                     void* stream) {
     const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
     const SegmentTable segs = {table, nseg, total_buckets};
-    return fused_adamw_common(&segs, x, g, adam, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
+    FusedStepOptions opt = {};
+    opt.segs = &segs;
+    return fused_adamw_common(opt, x, g, adam, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
                               wmeta, n_saturated, stream);
 }
 

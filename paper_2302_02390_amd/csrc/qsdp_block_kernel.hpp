@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     code[i] = (uint8_t)(uint32_t)c;
                     if (MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE))
                         p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
-                    if (MODE == MODE_FUSED && p.x16 != nullptr)
+                    if ((MODE == MODE_FUSED || MODE == MODE_ADAMW) && p.x16 != nullptr)
                         static_cast<uint16_t*>(p.x16)[e0 + i] = (uint16_t)half_bits(fmaf(c, scale, base), p.x16_f16 != 0);
                 }
                 if (sat_here) atomicAdd(&sat_block, sat_here);
@@ -222,7 +222,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     code[i] = (uint8_t)(uint32_t)c;
                     if (MODE == MODE_FUSED || MODE == MODE_ADAMW || mode_is_recv(MODE))
                         p.x[e0 + i] = keep_master ? val[i] : fmaf(c, scale, base);
-                    if (MODE == MODE_FUSED && p.x16 != nullptr)
+                    if ((MODE == MODE_FUSED || MODE == MODE_ADAMW) && p.x16 != nullptr)
                         static_cast<uint16_t*>(p.x16)[e0 + i] = (uint16_t)half_bits(fmaf(c, scale, base), p.x16_f16 != 0);
                 }
             }

@@ -52,6 +52,8 @@ constexpr bool mode_local_gradient(int mode) {
     return mode == MODE_GRAD || mode == MODE_FUSED || mode == MODE_FUSED_CODES || mode == MODE_ADAMW ||
            mode == MODE_ADAMW_CODES;
 }
+// modes that take the gradient in 16 bits and can write a 16-bit copy of the new weights
+constexpr bool mode_mixed_precision(int mode) { return mode == MODE_GRAD || mode == MODE_FUSED || mode == MODE_ADAMW; }
 // the AdamW moments are read and written next to a local gradient
 constexpr bool mode_local_adamw(int mode) { return mode == MODE_ADAMW || mode == MODE_ADAMW_CODES; }
 

@@ -439,9 +439,9 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             float gv[R][4];
             uint32_t gcode[R][4];  // MODE_GRAD only
             float mom[R][4], var[R][4];  // AdamW modes only
-            if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 1)
+            if (mode_mixed_precision(MODE) && p.g_half == 1)
                 load_rows_half<G, R, true>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
-            else if ((MODE == MODE_GRAD || MODE == MODE_FUSED) && p.g_half == 2)
+            else if (mode_mixed_precision(MODE) && p.g_half == 2)
                 load_rows_half<G, R, false>(reinterpret_cast<const uint16_t*>(p.g) + e0, l, m, partial, gv);
             else
                 load_rows<G, R>(p.g + e0, l, m, partial, gv);
@@ -661,7 +661,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
         }
         // the decoded new weights: into x (unless x keeps the unquantized value) and, on request, once
         // more in 16 bits (what a forward pass in reduced precision reads)
-        const bool want16 = MODE == MODE_FUSED && p.x16 != nullptr;
+        const bool want16 = (MODE == MODE_FUSED || MODE == MODE_ADAMW) && p.x16 != nullptr;
         if (active && kWritesX && (!keep_master || want16)) {
 #pragma unroll
             for (int r = 0; r < R; ++r)

@@ -98,3 +98,34 @@ def test_segmented_mixed_precision_step(gdtype, xdtype, B, wbits, gbits, flags):
     assert bits_equal(np_f32(xd), np.concatenate(wx))
     assert np.array_equal(np_u32(codes), np.concatenate(wc)) and np.array_equal(np_u32(meta), np.concatenate(wm).view(np.uint32))
     assert np.array_equal(_h(x16), np.concatenate(w16))
+
+
+@pytest.mark.parametrize("gdtype,xdtype", [(torch.float16, torch.float16), (torch.bfloat16, torch.bfloat16),
+                                           (torch.float32, torch.float16)])
+@pytest.mark.parametrize("B,wbits,gbits,flags", [(1024, 8, 4, 0), (4096, 5, 4, qb.QSDP_FLAG_KEEP_MASTER), (96, 6, 3, 0),
+                                                 (128, 8, 2, qb.QSDP_FLAG_GRAD_SHIFT)])
+def test_adamw_step_in_mixed_precision(gdtype, xdtype, B, wbits, gbits, flags):
+    """Two AdamW steps with the gradient in 16 bits and the 16-bit copy of the new weights: moments, weights,
+    codes as the oracle's AdamW step on the widened gradient, the copy as its decode of the emitted codes."""
+    n = 9 * B + B // 2 + 5
+    x, g = synth(n, 1400 + B)
+    hyper = dict(lr=2e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    xd = torch.from_numpy(x).to(DEV)
+    md = torch.zeros(n, device=DEV)
+    vd = torch.zeros(n, device=DEV)
+    hx, hm, hv = x, np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for t in (1, 2):
+        gt = torch.from_numpy((g * np.float32(1 + 0.3 * t)).astype(np.float32)).to(gdtype)
+        wide = gt.float().numpy()
+        c1, c2 = 1 - 0.9 ** t, 1 - 0.95 ** t
+        codes, meta = qb.alloc_packed(n, wbits, B, DEV)
+        x16 = torch.empty(n, dtype=xdtype, device=DEV)
+        qb.qsdp_fused_adamw_step_mp(xd, gt.to(DEV), md, vd, bias1=c1, bias2=c2, wbits=wbits, gbits=gbits, bucket=B,
+                                    delta=0.0, seed=t, index_offset=8, flags=flags, wcodes=codes,
+                                    wmeta=meta.reshape(-1), x16=x16, **hyper)
+        hx, hm, hv, wc, wm, _ = ref.fused_adamw_step(hx, wide, hm, hv, bias1=c1, bias2=c2, wbits=wbits, gbits=gbits,
+                                                     bucket=B, delta=0.0, seed=t, index_offset=8, flags=flags,
+                                                     emit_codes=True, **hyper)
+        assert bits_equal(np_f32(xd), hx) and bits_equal(np_f32(md), hm) and bits_equal(np_f32(vd), hv), t
+        assert np.array_equal(np_u32(codes), wc) and np.array_equal(np_u32(meta), wm.view(np.uint32).reshape(-1)), t
+        assert np.array_equal(_h(x16), ref.dequantize(wc, wm, n, wbits, B, REF_DT[xdtype])), t
