@@ -784,6 +784,47 @@ int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float 
     return QSDP_REF_OK;
 }
 
+/* Algorithm 1 exactly as Section 5.2 prints it: after the bucket-wise normalisation the values
+ * are visited one by one, in storage order; each value picks the level closest to it in the
+ * table AS IT STANDS at that moment, and that one level takes one gradient step of rate lr
+ * towards the value, q <- q - lr*(q - v), before the next value is looked at. No batching: the
+ * batch size of Appendix C does not enter. The table is carried in binary64 (the step is a
+ * convex combination, so a level never leaves its cell and the table stays ascending) and
+ * rounded to binary32 once, at the end. qsdp_ref_fit_levels above is the parallel reading of
+ * the same algorithm that the GPU library implements; the tests measure one against the other. */
+int qsdp_ref_fit_levels_sequential(const float* v, uint64_t n, int bits, int bucket, float lr,
+                                   uint64_t max_batches, float* levels) {
+    if (!v || !levels || !args_ok(n, bits, bucket) || !levels_ok(levels, bits)) return QSDP_REF_EINVAL;
+    if (!(lr > 0.0f && lr < 1.0f)) return QSDP_REF_EINVAL;
+    uint64_t nb = num_buckets(n, bucket);
+    if (max_batches > 0 && max_batches < nb) nb = max_batches;
+    int K = 1 << bits;
+    double q[256];
+    for (int k = 0; k < K; ++k) q[k] = (double)levels[k];
+    for (uint64_t j = 0; j < nb; ++j) {
+        uint64_t s = j * (uint64_t)bucket;
+        int m = bucket_len(n, bucket, j);
+        float z[MAX_BUCKET];
+        float lo, range;
+        normalize_bucket(v + s, m, z, &lo, &range);
+        for (int i = 0; i < m; ++i) {
+            double zi = (double)z[i];
+            int best = 0; /* find_closest against the current table, first index on ties */
+            double best_d = fabs(zi - q[0]);
+            for (int k = 1; k < K; ++k) {
+                double d = fabs(zi - q[k]);
+                if (d < best_d) {
+                    best_d = d;
+                    best = k;
+                }
+            }
+            q[best] = q[best] - (double)lr * (q[best] - zi);
+        }
+    }
+    for (int k = 0; k < K; ++k) levels[k] = (float)q[k];
+    return QSDP_REF_OK;
+}
+
 /* ------------------------------------------------------------------------- */
 /* AdamW inside the quantized iteration (Appendix A names the optimizer)       */
 /* ------------------------------------------------------------------------- */

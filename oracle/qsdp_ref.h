@@ -167,6 +167,10 @@ int qsdp_ref_quantize_levels_u(const float* v, uint64_t n, int bits, int bucket,
                                const float* u, uint8_t* codes, float* meta);
 int qsdp_ref_fit_levels(const float* v, uint64_t n, int bits, int bucket, float lr,
                         uint64_t max_batches, float* levels /* in: start, out: fitted */);
+/* Algorithm 1 as printed: one value at a time against the current table, one step of the chosen
+ * level per value (no batches; `max_batches` only bounds how many buckets of values are visited). */
+int qsdp_ref_fit_levels_sequential(const float* v, uint64_t n, int bits, int bucket, float lr,
+                                   uint64_t max_batches, float* levels /* in: start, out: fitted */);
 
 /* The step on weights held as codes: decode (wcodes, wmeta), take the fused step, write the
  * codes and meta of the result back. By definition the composition of the two routines. */

@@ -66,6 +66,7 @@ def lib():
         L.qsdp_ref_quantize_levels.argtypes = [vp, u64, i32, i32, vp, vp, vp]
         L.qsdp_ref_dequantize_levels.argtypes = [vp, vp, u64, i32, i32, vp, i32, vp]
         L.qsdp_ref_fit_levels.argtypes = [vp, u64, i32, i32, f32, u64, vp]
+        L.qsdp_ref_fit_levels_sequential.argtypes = [vp, u64, i32, i32, f32, u64, vp]
         L.qsdp_ref_quantize_levels_stochastic.argtypes = [vp, u64, i32, i32, vp, u64, u64, vp, vp]
         L.qsdp_ref_quantize_levels_u.argtypes = [vp, u64, i32, i32, vp, vp, vp, vp]
         L.qsdp_ref_fused_step_codes.argtypes = [vp, vp, vp, u64, f32, i32, i32, i32, f32, u64, u64, C.c_uint32, vp]
@@ -241,6 +242,24 @@ def fused_step(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, emit
     return x, wcodes, wmeta, int(sat[0])
 
 
+def fused_step_inplace(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, wcodes=None, wmeta=None,
+                       flags=0):
+    """The fused step on caller-owned arrays, for vectors too large to copy: x (float32, C-contiguous) is
+    updated in place; wcodes (uint32) and wmeta (float32), when given, receive the packed codes and the
+    meta of the new x. Returns n_saturated."""
+    for a, t in ((x, np.float32), (g, np.float32), (wcodes, np.uint32), (wmeta, np.float32)):
+        assert a is None or (a.dtype == t and a.flags.c_contiguous)
+    n = x.size
+    assert g.size == n and x.flags.writeable
+    if wcodes is not None:
+        assert wcodes.size * 4 == codes_bytes(n, wbits, bucket) and wmeta.size == 2 * _nb(n, bucket)
+    sat = np.zeros(1, dtype=np.uint64)
+    _check(lib().qsdp_ref_fused_step_ex(_p(x), _p(g), n, float(lr), wbits, gbits, bucket, float(delta), int(seed),
+                                        int(index_offset), flags, _p(wcodes), _p(wmeta), _p(sat)),
+           "fused_step_inplace")
+    return int(sat[0])
+
+
 def fused_step_codes(wcodes, wmeta, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, flags=0):
     """Returns (new wcodes, new wmeta, n_saturated); inputs are not modified."""
     g = _f32(g)
@@ -352,6 +371,16 @@ def fit_levels(v, bits, bucket, lr, levels, max_batches=0):
     lv = _f32(levels).copy()
     _check(lib().qsdp_ref_fit_levels(_p(v), v.size, bits, bucket, float(lr), int(max_batches), _p(lv)),
            "fit_levels")
+    return lv
+
+
+def fit_levels_sequential(v, bits, bucket, lr, levels, max_batches=0):
+    """Algorithm 1 as printed (one value at a time against the current table). Returns the fitted levels;
+    `levels` is the start and is not modified."""
+    v = _f32(v)
+    lv = _f32(levels).copy()
+    _check(lib().qsdp_ref_fit_levels_sequential(_p(v), v.size, bits, bucket, float(lr), int(max_batches), _p(lv)),
+           "fit_levels_sequential")
     return lv
 
 

@@ -1,5 +1,7 @@
 """Helpers for the GPU parity tests: run the library through its binding, the oracle on the
 host copy of the same inputs, and compare."""
+import os
+
 import numpy as np
 import torch
 
@@ -115,3 +117,42 @@ def gather_rows(t, ids, row_len):
     view = t[: nfull * row_len].view(nfull, row_len)
     idx = torch.from_numpy(ids).to(t.device)
     return view.index_select(0, idx).cpu().numpy()
+
+
+# ---------------------------------------------------------------------------------------
+# Whole-vector checks at full size: the bucket-parallel oracle recomputes every element on
+# pinned host copies of the inputs, and the two results are compared bit for bit on the
+# device, chunk by chunk.
+# ---------------------------------------------------------------------------------------
+ORACLE_THREADS = min(16, os.cpu_count() or 1)
+
+
+def pinned_copy(t):
+    """A page-locked host copy of tensor t, as (torch tensor, numpy view of the same memory)."""
+    h = torch.empty(t.numel(), dtype=t.dtype, pin_memory=True)
+    h.copy_(t.reshape(-1))
+    return h, h.numpy()
+
+
+def pinned_empty(numel, dtype):
+    h = torch.empty(numel, dtype=dtype, pin_memory=True)
+    return h, h.numpy()
+
+
+def _as_ints(t):
+    return t.view({1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[t.element_size()])
+
+
+def first_mismatch(dev, host, chunk=1 << 27):
+    """Index of the first element whose bit pattern differs between device tensor `dev` and host
+    tensor (or numpy array) `host` of the same length and element size, or -1 when all are equal."""
+    if isinstance(host, np.ndarray):
+        host = torch.from_numpy(host)
+    d, h = _as_ints(dev.reshape(-1)), _as_ints(host.reshape(-1))
+    assert d.numel() == h.numel() and d.dtype == h.dtype, (d.shape, h.shape, d.dtype, h.dtype)
+    for s in range(0, d.numel(), chunk):
+        a = d[s:s + chunk]
+        b = h[s:s + chunk].to(dev.device)
+        if not torch.equal(a, b):
+            return s + int((a != b).nonzero()[0])
+    return -1

@@ -1,13 +1,13 @@
 """GPU parity of the multi-tensor (segmented) entry points: one launch over many tensors must
 give, tensor by tensor, what the oracle gives for that tensor alone (bucketing restarts at each
-tensor; the rounding uniforms follow the position in the flat buffer)."""
+tensor; the rounding uniforms follow the position in the flat buffer). The GPT-350M layer list as
+a whole model is in test_gpu_fullsize.py."""
 import numpy as np
 import pytest
 import torch
 
 from oracle import ref
 from paper_2302_02390_amd import binding as qb
-from paper_2302_02390_amd import workloads as wl
 from gpu_util import DEV, bits_equal, np_f32, np_u32, synth
 
 pytestmark = pytest.mark.gpu
@@ -68,34 +68,6 @@ def test_segmented_matches_per_tensor_oracle(B, wbits, gbits, delta):
     assert torch.equal(x1, x2)
 
 
-def test_segmented_gpt350m_layers_equal_per_tensor_calls():
-    """The 350M model as per-layer tensors, W8 G4, bucket 1024: one segmented launch equals the
-    per-tensor launches (themselves checked against the oracle elsewhere), bit for bit."""
-    shape, B = wl.GPT_350M, 1024
-    sizes = [s for _, s in wl.model_tensors(shape)]
-    n = sum(sizes)
-    x = wl.weights(n, 1238, DEV)
-    g = wl.grads_student_t3(n, 1239, DEV)
-    segs = qb.Segments(sizes, B, DEV)
-    x_seg = x.clone()
-    qb.qsdp_fused_step_segmented(x_seg, g, segs, 1e-3, 8, 4, 0.0, 3)
-    x_per = x.clone()
-    off = 0
-    for s in sizes:
-        qb.qsdp_fused_step(x_per[off:off + s], g[off:off + s], 1e-3, 8, 4, B, 0.0, 3, off)
-        off += s
-    assert torch.equal(x_seg, x_per)
-    # and a few tensors against the oracle directly
-    off = 0
-    for t, s in enumerate(sizes):
-        if t in (2, 3, 5, 290) or s == shape.d:
-            if t % 7 == 0 or t in (2, 3, 5, 290):
-                want, _, _, _ = ref.fused_step(x[off:off + s].cpu().numpy(), g[off:off + s].cpu().numpy(), 1e-3,
-                                               8, 4, B, 0.0, 3, index_offset=off)
-                assert bits_equal(x_seg[off:off + s].cpu().numpy(), want)
-        off += s
-
-
 def test_segments_build_rejects_bad_sizes():
     with pytest.raises(qb.QsdpError):
         qb.Segments([1024, 0, 8], 1024, DEV)
@@ -135,26 +107,6 @@ def test_dequantize_segmented_matches_per_tensor_oracle(B, bits, dtype):
         assert bits_equal(got[:n].numpy(), want)
     else:
         assert np.array_equal(got[:n].view(torch.int16).numpy().view(np.uint16), want)
-
-
-def test_dequantize_segmented_gpt350m_equals_per_tensor_calls():
-    shape, B = wl.GPT_350M, 1024
-    sizes = [s for _, s in wl.model_tensors(shape)]
-    n = sum(sizes)
-    x = wl.weights(n, 1240, DEV)
-    segs = qb.Segments(sizes, B, DEV)
-    codes, meta = segs.alloc_packed(8)
-    qb.qsdp_quantize_weight_segmented(x, segs, 8, 0.0, 5, codes, meta.reshape(-1))
-    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
-    qb.qsdp_dequantize_segmented(codes, meta.reshape(-1), segs, 8, out)
-    per = torch.empty_like(out)
-    host = segs.host
-    wpb = B * 8 // 32
-    for off, s, fb in host.tolist():
-        nb = -(-s // B)
-        qb.qsdp_dequantize(codes[fb * wpb:(fb + nb) * wpb], meta[fb:fb + nb].clone().reshape(-1), s, 8, B,
-                           per[off:off + s])
-    assert torch.equal(out.view(torch.int16), per.view(torch.int16))
 
 
 @pytest.mark.parametrize("B,wbits,gbits,delta,flags", [(1024, 8, 4, 0.0, 0), (128, 5, 2, 0.0, qb.QSDP_FLAG_KEEP_MASTER),

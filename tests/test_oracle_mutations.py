@@ -55,6 +55,12 @@ MUTANTS = [
      "levels[k] = (float)(q + (1.0 - keep[count[k]]) * (q - mean));", ["test_oracle_levels.py"]),
     ("level_update_single_step", "levels[k] = (float)(q - (1.0 - keep[count[k]]) * (q - mean));",
      "levels[k] = (float)(q - (1.0 - keep[1]) * (q - mean));", ["test_oracle_levels.py"]),
+    ("sequential_fit_moves_away", "q[best] = q[best] - (double)lr * (q[best] - zi);",
+     "q[best] = q[best] + (double)lr * (q[best] - zi);", ["test_oracle_levels.py"]),
+    ("sequential_fit_searches_the_start_table", "double d = fabs(zi - q[k]);", "double d = fabs(zi - (double)levels[k]);",
+     ["test_oracle_levels.py"]),
+    ("sequential_fit_jumps_onto_the_value", "q[best] = q[best] - (double)lr * (q[best] - zi);", "q[best] = zi;",
+     ["test_oracle_levels.py"]),
     ("level_decode_ignores_table", "float val = fmaf(levels[code[i]], meta[2 * j + 1], meta[2 * j]);",
      "float val = fmaf((float)code[i], meta[2 * j + 1], meta[2 * j]);", ["test_oracle_levels.py"]),
     ("adamw_second_moment_not_squared", "float vi = fmaf(beta2, *var, (omb2 * ghat) * ghat);",
