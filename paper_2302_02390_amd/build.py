@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqsdp.so")
+BENCH_LIB = os.path.join(HERE, "libqsdp_bench.so")  # streaming kernels for bench.py, not part of the codec
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -56,7 +57,19 @@ def build(jobs=None, verbose=False):
         raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
     if verbose:
         print(LIB)
+    build_bench_support(verbose)
     return LIB
+
+
+def build_bench_support(verbose=False):
+    """libqsdp_bench.so: the plain streaming kernels bench.py times beside the codec (csrc/qsdp_bench_stream.hip)."""
+    cmd = [HIPCC] + FLAGS + ["-shared", os.path.join(CSRC, "qsdp_bench_stream.hip"), "-o", BENCH_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"{' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(BENCH_LIB)
+    return BENCH_LIB
 
 
 def build_client(verbose=False):
