@@ -51,9 +51,8 @@ void qsdp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32
 }
 
 /* Gradient stream (stream id 0): one Philox block serves the 8 elements with
- * the same e/8; element e takes 16 bits: word (e%8)/2, low half first.
- * u = h * 2^-16 is exact in binary32 and lies in [0,1). */
-float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e) {
+ * the same e/8; element e takes the 16 bits h of word (e%8)/2, low half first. */
+uint32_t qsdp_ref_grad_uniform16(uint64_t seed, uint64_t e) {
     uint64_t block = e / 8u;
     uint32_t ctr[4] = {(uint32_t)block, (uint32_t)(block >> 32), 0u, 0u};
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
@@ -61,8 +60,12 @@ float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e) {
     qsdp_ref_philox4x32_10(ctr, key, out);
     unsigned j = (unsigned)(e % 8u);
     uint32_t w = out[j / 2u];
-    uint32_t h = (j % 2u) ? (w >> 16) : (w & 0xFFFFu);
-    return (float)h * 0x1p-16f;
+    return (j % 2u) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+/* The same as a real number: u = h * 2^-16 is exact in binary32 and lies in [0,1). */
+float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e) {
+    return (float)qsdp_ref_grad_uniform16(seed, e) * 0x1p-16f;
 }
 
 /* Weight stream (stream id 1): one draw per call, whatever the shard.
@@ -114,7 +117,8 @@ size_t qsdp_ref_meta_bytes(uint64_t n, int bucket) {
 /* Min-max statistics of a bucket (Section 5.1: each bucket is scaled by its
  * own min and max). Signed zeros are canonicalised to +0 so that the stored
  * meta-data has one bit pattern. A bucket whose range is zero, not finite, or
- * so small that L/range overflows is treated as constant: scale = inv = 0. */
+ * so small that 2^16 * L/range overflows (the coin flip works in units of 2^-16
+ * of a cell) is treated as constant: scale = inv = 0. */
 static void bucket_stats(const float* v, int m, float Lf, int symmetric, float* lo_out,
                          float* hi_out, float* scale_out, float* inv_out) {
     float lo = v[0], hi = v[0];
@@ -133,7 +137,7 @@ static void bucket_stats(const float* v, int m, float Lf, int symmetric, float* 
     float scale = 0.0f, inv = 0.0f;
     if (range > 0.0f && isfinite(range)) {
         float inv_try = Lf / range;
-        if (isfinite(inv_try)) {
+        if (isfinite(inv_try * 65536.0f)) {
             scale = range / Lf;
             inv = inv_try;
         }
@@ -141,21 +145,33 @@ static void bucket_stats(const float* v, int m, float Lf, int symmetric, float* 
     *lo_out = lo; *hi_out = hi; *scale_out = scale; *inv_out = inv;
 }
 
-/* Coin-flip quantizer in bucket coordinates t = (g - lo)/scale in [0, L]:
- * floor(t) with probability 1 - frac(t), floor(t)+1 with probability frac(t),
- * decided by u < frac(t) for u uniform in [0,1). */
+/* Coin-flip quantizer in bucket coordinates t = (g - lo)/scale in [0, L]: floor(t) with
+ * probability 1 - frac(t), floor(t)+1 with probability frac(t). The coin is a 16-bit uniform
+ * integer h, so the decision is taken in integers: the position is expressed in units of 2^-16
+ * of a cell and rounded to the nearest unit (one fused multiply-add, then truncation),
+ *     ti = min(floor(fma(g - lo, inv * 2^16, 1/2)), L * 2^16),
+ * and the code is floor((ti + h) / 2^16): that is floor(t) + 1 for exactly (ti mod 2^16) of the
+ * 2^16 values of h, the largest ones. The rounding of frac(t) to 16 bits is to nearest, so what it
+ * adds to E[Q(g)] - g has no preferred sign (at most scale * 2^-17 either way). u[i] in [0,1)
+ * carries h as h * 2^-16. */
+static uint32_t grid_position16(float d, float inv16, uint32_t top16) {
+    float t16 = fmaf(d, inv16, 0.5f);
+    if (!(t16 >= 0.0f)) return 0u; /* cannot happen for finite input: d >= 0, inv16 >= 0 */
+    if (t16 >= (float)top16) return top16;
+    return (uint32_t)t16;
+}
+
 static void grad_bucket(const float* g, const float* u, int m, int bits, int symmetric,
                         uint8_t* code, float* base_out, float* scale_out) {
     float Lf = (float)((1 << bits) - 1);
     float lo, hi, scale, inv;
     bucket_stats(g, m, Lf, symmetric, &lo, &hi, &scale, &inv);
+    uint32_t top16 = (uint32_t)((1 << bits) - 1) << 16;
+    float inv16 = inv * 65536.0f;
     for (int i = 0; i < m; ++i) {
-        float t = (g[i] - lo) * inv;
-        t = fminf(fmaxf(t, 0.0f), Lf);
-        float f = floorf(t);
-        float frac = t - f;
-        int c = (int)f + (u[i] < frac ? 1 : 0);
-        code[i] = (uint8_t)c;
+        uint32_t h = (uint32_t)(u[i] * 65536.0f);
+        uint32_t ti = grid_position16(g[i] - lo, inv16, top16);
+        code[i] = (uint8_t)((ti + h) >> 16);
     }
     *base_out = lo;
     *scale_out = scale;
@@ -627,7 +643,7 @@ static void normalize_bucket(const float* v, int m, float* z, float* lo_out, flo
     float inv = 0.0f;
     if (range > 0.0f && isfinite(range)) {
         float t = 1.0f / range;
-        if (isfinite(t)) inv = t; else range = 0.0f;
+        if (isfinite(t * 65536.0f)) inv = t; else range = 0.0f; /* the rule of bucket_stats */
     } else {
         range = 0.0f;
     }
@@ -672,8 +688,10 @@ int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, c
 
 /* Unbiased rounding onto non-uniform levels: the coin-flip quantizer of the appendix between the
  * two levels that enclose z. With i the largest index such that q_i <= z and q_{i+1} the next
- * level (so q_i <= z < q_{i+1}): code = i + [u < (z - q_i) / (q_{i+1} - q_i)]. z below the first
- * level gives code 0, z at or above the last gives K-1: no pair of levels encloses those, so the
+ * level (so q_i <= z < q_{i+1}) and p = (z - q_i) / (q_{i+1} - q_i): code = i + [1 - 2^-17 - u < p],
+ * i.e. with u = h * 2^-16 the level above is taken for the round(p * 2^16) largest values of h
+ * (p is rounded to 16 bits to nearest and large h rounds up, as in the uniform coin flip). z below the first level
+ * gives code 0, z at or above the last gives K-1: no pair of levels encloses those, so the
  * quantizer is unbiased exactly on [q_0, q_{K-1}]. */
 static int stochastic_level(float z, float u, const float* levels, int K) {
     if (!(z >= levels[0])) return 0;
@@ -683,7 +701,8 @@ static int stochastic_level(float z, float u, const float* levels, int K) {
     if (i == K - 1) return K - 1;
     float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */
     float p = (z - levels[i]) / gap;
-    return i + (u < p ? 1 : 0);
+    /* 2^16 - (h + 1/2) < p * 2^16: up for the round(p * 2^16) largest values of h (both sides exact) */
+    return i + ((1.0f - 0x1p-17f) - u < p ? 1 : 0);
 }
 
 int qsdp_ref_quantize_levels_stochastic(const float* v, uint64_t n, int bits, int bucket, const float* levels,

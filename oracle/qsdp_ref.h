@@ -68,6 +68,7 @@ void qsdp_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32
 /* The uniform u in [0,1) that decides the rounding of the gradient element whose
  * GLOBAL index is e, and the shift xi in [-1/2,1/2) of a weight quantization. */
 float qsdp_ref_grad_uniform(uint64_t seed, uint64_t e);
+uint32_t qsdp_ref_grad_uniform16(uint64_t seed, uint64_t e); /* the same as the integer h = u * 2^16 */
 float qsdp_ref_weight_shift(uint64_t seed);
 float qsdp_ref_grad_shift(uint64_t seed);
 

@@ -1,5 +1,5 @@
-"""Writes tests/golden/spec_v2_vectors.txt: known-answer vectors of arithmetic specification
-version 2, computed by the CPU oracle ONLY (never by the GPU path) on inputs given by integer
+"""Writes tests/golden/spec_v3_vectors.txt: known-answer vectors of arithmetic specification
+version 3, computed by the CPU oracle ONLY (never by the GPU path) on inputs given by integer
 formulas, so that an accidental change of the specification (rounding order, RNG mapping, wire
 format) shows up as a diff. Not a pin of the oracle against the paper: those are the
 test_oracle_*.py files.
@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 from oracle import ref  # noqa: E402
 
-OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "spec_v2_vectors.txt")
+OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "spec_v3_vectors.txt")
 
 
 def inputs(n):
@@ -41,7 +41,7 @@ def head(a, k=4):
 def vectors():
     n, B = 3 * 1024 + 100, 1024
     x, g = inputs(n)
-    lines = [f"spec_version 2", f"n {n} bucket {B}", f"x {digest(x)} {head(x)}", f"g {digest(g)} {head(g)}"]
+    lines = ["spec_version 3", f"n {n} bucket {B}", f"x {digest(x)} {head(x)}", f"g {digest(g)} {head(g)}"]
     c, m = ref.quantize_grad(g, 4, B, 5, index_offset=8192)
     lines.append(f"quantize_grad b4 seed5 off8192 codes {digest(c)} {head(c)} meta {digest(m)} {head(m)}")
     c, m, s = ref.quantize_weight(x, 8, B, 0.0, 5)

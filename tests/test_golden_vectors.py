@@ -1,4 +1,4 @@
-"""Known-answer vectors of specification version 2 (tests/golden/spec_v2_vectors.txt, written by
+"""Known-answer vectors of specification version 3 (tests/golden/spec_v3_vectors.txt, written by
 tests/golden/make_golden.py from the oracle alone): the oracle must still reproduce them (CPU),
 and the GPU path must produce the same digests (GPU)."""
 import hashlib
@@ -15,7 +15,7 @@ _spec.loader.exec_module(make_golden)
 
 
 def stored():
-    return open(os.path.join(HERE, "golden", "spec_v2_vectors.txt")).read().splitlines()
+    return open(os.path.join(HERE, "golden", "spec_v3_vectors.txt")).read().splitlines()
 
 
 def test_oracle_reproduces_the_stored_vectors():
@@ -35,7 +35,7 @@ def test_gpu_path_reproduces_the_stored_vectors():
     def dg(t):
         return hashlib.sha256(t.cpu().numpy().tobytes()).hexdigest()
 
-    assert qb.spec_version() == 2
+    assert qb.spec_version() == 3
     c, m = qb.alloc_packed(n, 4, B, dev)
     qb.qsdp_quantize_grad(gd, 4, B, 5, 8192, c, m.reshape(-1))
     ln = lines["quantize_grad b4"]

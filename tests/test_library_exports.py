@@ -37,7 +37,7 @@ def test_size_helpers_match_the_wire_format_and_the_oracle():
         assert qb.meta_bytes(n, bucket) == nb * 8 == ref.meta_bytes(n, bucket)
     assert qb.codes_bytes(0, 8, 1024) == 0 and qb.codes_bytes(10, 9, 1024) == 0
     assert qb.codes_bytes(10, 8, 100) == 0 and qb.meta_bytes(10, 8200) == 0
-    assert qb.spec_version() == 2
+    assert qb.spec_version() == 3
 
 
 def test_argument_errors_are_reported_before_any_launch():

@@ -2,7 +2,8 @@
 
 The expectations below come from the paper's statements, not from the oracle:
   * P(round up) = fractional position (coin-flip definition): exhaustive enumeration
-    of all 2^16 values of the uniform;
+    of all 2^16 values of the uniform; the fraction is rounded to 16 bits to nearest, so
+    the rounding adds no bias of a preferred sign;
   * unbiasedness and the variance delta^2 {x/delta}(1-{x/delta}) (coin-flip lemma);
   * codes in [0, 2^b-1]; values already on the grid are reproduced exactly.
 """
@@ -38,12 +39,30 @@ def test_coin_flip_probabilities_exhaustive(bits):
     frac = t - fl
     ups = (codes - fl[None, :].astype(np.int64))
     assert ups.min() >= 0 and ups.max() <= 1
-    # number of u = h/65536 with u < frac is exactly frac*65536 for these dyadic fractions
+    # the number of 16-bit uniforms that round up is exactly frac*65536 for these dyadic fractions
     assert np.array_equal(ups.sum(axis=0), (frac * 65536).astype(np.int64))
-    # and "up" happens exactly for the smallest uniforms
+    # and "up" happens exactly for the largest uniforms: floor((ti + h) / 2^16), ti = t * 2^16
     for i in range(B):
         k = int(frac[i] * 65536)
-        assert ups[:k, i].all() and not ups[k:, i].any()
+        assert ups[H - k:, i].all() and not ups[:H - k, i].any()
+
+
+def test_fraction_is_rounded_to_16_bits_to_nearest_not_downward():
+    """One-bit grid on [0, 1] (so t = g exactly): g = k * 2^-18 has the fraction k/4 units of 2^-16.
+    Rounded to nearest (halves up) that is floor(k/4 + 1/2) uniforms out of 2^16 that round up;
+    truncation would give floor(k/4) and a quantizer whose mean always falls short of g."""
+    B, H = 32, 65536
+    ks = np.array([1, 2, 3, 5, 6, 7, 9, 4 * 65536 - 3, 4 * 65536 - 2, 4 * 65536 - 1])
+    g = np.zeros(B, np.float32)
+    g[1] = 1.0
+    g[2:2 + ks.size] = (ks * 2.0 ** -18).astype(np.float32)
+    codes, meta = ref.quantize_grad_u(np.tile(g, H), 1, B, np.repeat(np.arange(H, dtype=np.float32) / 65536.0, B))
+    assert np.all(meta[:, 0] == 0.0) and np.all(meta[:, 1] == 1.0)
+    ups = codes.reshape(H, B)[:, 2:2 + ks.size].astype(np.int64).sum(axis=0)
+    assert np.array_equal(ups, (ks + 2) // 4)
+    # the mean over all uniforms is within half a unit of 2^-16 of g, on either side
+    err = ups / 65536.0 - ks * 2.0 ** -18
+    assert np.all(np.abs(err) <= 2.0 ** -17) and (err > 0).any() and (err < 0).any()
 
 
 @pytest.mark.parametrize("bits", [1, 2])
@@ -62,7 +81,7 @@ def test_coin_flip_probabilities_generic_values(bits):
     near_integer = np.minimum(frac, 1 - frac) < 1e-5
     ok = ~near_integer
     assert ups[:, ok].min() >= 0 and ups[:, ok].max() <= 1
-    want = np.ceil(frac * 65536)
+    want = np.floor(frac * 65536 + 0.5)
     assert np.all(np.abs(ups.sum(axis=0) - want)[ok] <= 1)
     assert codes.min() >= 0 and codes.max() <= L
 
@@ -142,9 +161,11 @@ def test_constant_bucket_short_tail_and_zero_signs():
     g2 = np.concatenate([np.linspace(-1, 1, B, dtype=np.float32), np.array([5, 6, 7], np.float32)])
     codes, meta = ref.quantize_grad_u(g2, 2, B, np.zeros(g2.size, np.float32))
     assert meta[1, 0] == 5 and meta[1, 1] == np.float32(2) / np.float32(3)
-    assert codes[B:].tolist() == [0, 2, 3]  # t = 0, 1.5, 3; u = 0 < 0.5 rounds 1.5 up
+    assert codes[B:].tolist() == [0, 1, 3]  # t = 0, 1.5, 3; h = 0: floor(1.5 + 0) = 1
     codes, _ = ref.quantize_grad_u(g2, 2, B, np.full(g2.size, 0.5, np.float32))
-    assert codes[B:].tolist() == [0, 1, 3]  # u = 0.5 is not < 0.5: 1.5 rounds down
+    assert codes[B:].tolist() == [0, 2, 3]  # h = 2^15: floor(1.5 + 0.5) = 2; below that 1.5 rounds down
+    codes, _ = ref.quantize_grad_u(g2, 2, B, np.full(g2.size, 0.5 - 2.0 ** -16, np.float32))
+    assert codes[B:].tolist() == [0, 1, 3]
 
 
 def test_shard_invariance():

@@ -16,8 +16,10 @@ def _table(bits, seed):
 
 
 def test_exhaustive_over_all_uniforms_gives_the_exact_up_count():
-    """For one value between two levels, the number of the 2^16 uniforms that round up equals
-    ceil(p * 2^16), p = (z - q_i) / (q_{i+1} - q_i) in binary32 (brute force over every u)."""
+    """For one value between two levels, the uniforms h * 2^-16 that round up are the largest ones, those
+    with 2^16 - (h + 1/2) < p * 2^16: round(p * 2^16) of them, p = (z - q_i) / (q_{i+1} - q_i) in binary32
+    (brute force over every h; the comparison is evaluated here in exact rational arithmetic)."""
+    from fractions import Fraction
     q = np.array([0.0, 0.125, 0.5, 1.0], dtype=np.float32)
     B = 32
     u_all = (np.arange(1 << 16, dtype=np.float32) * np.float32(2.0 ** -16))
@@ -34,7 +36,8 @@ def test_exhaustive_over_all_uniforms_gives_the_exact_up_count():
             codes_up += int(np.sum(c[2:] == i + 1))
             assert set(np.unique(c[2:])) <= {i, i + 1}
         # elements 0 and 1 of every bucket are the range markers: their two uniforms are not counted
-        want = sum(1 for h in range(1 << 16) if (h % B) >= 2 and np.float32(h * 2.0 ** -16) < p)
+        want = sum(1 for h in range(1 << 16)
+                   if (h % B) >= 2 and 65536 - (h + Fraction(1, 2)) < Fraction(float(p)) * 65536)
         assert codes_up == want, (z, codes_up, want)
         total = (1 << 16) - 2 * ((1 << 16) // B)
         assert abs(codes_up / total - float(p)) < 2e-4

@@ -12,10 +12,15 @@ SRC = os.path.join(ROOT, "oracle", "qsdp_ref.c")
 
 # (name, text to replace, replacement, pin files expected to notice)
 MUTANTS = [
-    ("coin_flip_swapped", "(u[i] < frac ? 1 : 0)", "(u[i] >= frac ? 1 : 0)", ["test_oracle_grad.py"]),
+    ("coin_flip_rounds_up_for_small_uniforms", "code[i] = (uint8_t)((ti + h) >> 16);",
+     "code[i] = (uint8_t)((ti + 65535u - h) >> 16);", ["test_oracle_grad.py"]),
+    ("coin_flip_ignores_the_uniform", "code[i] = (uint8_t)((ti + h) >> 16);", "code[i] = (uint8_t)((ti + 32768u) >> 16);",
+     ["test_oracle_grad.py"]),
+    ("fraction_truncated_to_16_bits", "float t16 = fmaf(d, inv16, 0.5f);", "float t16 = d * inv16;", ["test_oracle_grad.py"]),
+    ("position_clamp_one_cell_short", "uint32_t top16 = (uint32_t)((1 << bits) - 1) << 16;",
+     "uint32_t top16 = (uint32_t)((1 << bits) - 2) << 16;", ["test_oracle_grad.py"]),
     ("levels_off_by_one", "float Lf = (float)((1 << bits) - 1);\n    float lo, hi, scale, inv;\n    bucket_stats(g,",
      "float Lf = (float)(1 << bits);\n    float lo, hi, scale, inv;\n    bucket_stats(g,", ["test_oracle_grad.py"]),
-    ("floor_became_round", "float f = floorf(t);", "float f = rintf(t);", ["test_oracle_grad.py"]),
     ("uniform_high_half_first", "(j % 2u) ? (w >> 16) : (w & 0xFFFFu)", "(j % 2u) ? (w & 0xFFFFu) : (w >> 16)",
      ["test_oracle_rng.py"]),
     ("philox_multipliers_swapped", "(uint64_t)0xD2511F53u * (uint64_t)c0", "(uint64_t)0xCD9E8D57u * (uint64_t)c0",
@@ -82,8 +87,10 @@ MUTANTS = [
      ["test_oracle_keep_master.py"]),
     ("keep_master_recv_copies_old_weights", "memcpy(x, ghat, (size_t)n * sizeof(float)); /* x <- y: the partition stays unquantized */",
      "(void)0;", ["test_oracle_keep_master.py"]),
-    ("level_coin_flip_inverted", "return i + (u < p ? 1 : 0);", "return i + (u < p ? 0 : 1);",
+    ("level_coin_flip_inverted", "return i + ((1.0f - 0x1p-17f) - u < p ? 1 : 0);", "return i + ((1.0f - 0x1p-17f) - u < p ? 0 : 1);",
      ["test_oracle_levels_stochastic.py"]),
+    ("level_coin_flip_rounds_up_for_small_uniforms", "return i + ((1.0f - 0x1p-17f) - u < p ? 1 : 0);",
+     "return i + (u + 0x1p-17f < p ? 1 : 0);", ["test_oracle_levels_stochastic.py"]),
     ("level_coin_flip_uses_distance_to_upper", "float p = (z - levels[i]) / gap;", "float p = (levels[i + 1] - z) / gap;",
      ["test_oracle_levels_stochastic.py"]),
     ("level_upper_neighbour_skipped", "float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */",
