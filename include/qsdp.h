@@ -27,7 +27,7 @@
  * (seed low 32 bits, seed high 32 bits), counter = (c low, c high, stream, 0).
  *   stream 0, gradient rounding: the element with GLOBAL index e = index_offset + i uses
  *     block c = e/8 and the 16-bit half (e%8) of its four words (word (e%8)/2, low half
- *     first): u = h * 2^-16 in [0,1). index_offset must be a multiple of 8. Quantizing a
+ *     first): an integer h in [0, 2^16). index_offset must be a multiple of 8. Quantizing a
  *     bucket-aligned shard with its global offset gives the bytes the whole vector gives.
  *   stream 1, weight shift: c = 0, xi = (word0 >> 8) * 2^-24 - 1/2 in [-1/2, 1/2); one
  *     draw per call whatever the shard (Definition 1 shifts the whole vector by one scalar).
@@ -65,8 +65,8 @@ enum {
  * QSDP_F16 is IEEE binary16, the half precision of the paper's mixed-precision setting. */
 typedef enum { QSDP_F32 = 0, QSDP_BF16 = 1, QSDP_F16 = 2 } qsdp_dtype;
 
-/* Version of the arithmetic/wire specification implemented (2: 16-bit uniforms, 8 per
- * Philox block). */
+/* Version of the arithmetic/wire specification implemented (3: 16-bit uniforms, 8 per Philox
+ * block; coin flips decided in integers with the fraction rounded to 16 bits to nearest). */
 uint32_t qsdp_spec_version(void);
 
 /* Bytes of the packed codes / of the meta-data for n elements: nb*bucket*bits/8 and
@@ -79,9 +79,11 @@ const char* qsdp_status_string(int status);
 
 /*
  * Q^g: bucketed unbiased stochastic quantization (coin-flip definition; Section 5.1).
- * Per bucket: lo = min, hi = max, scale = (hi-lo)/L, L = 2^bits-1; t = (g-lo)*(L/(hi-lo));
- * code = floor(t) + [u < frac(t)]; meta = {lo, scale}. A constant bucket gets scale 0 and
- * codes 0.
+ * Per bucket: lo = min, hi = max, scale = (hi-lo)/L, L = 2^bits-1; the position t = (g-lo)*(L/(hi-lo))
+ * is taken in units of 2^-16 of a cell, rounded to nearest: ti = min(floor(fma(g-lo, 2^16*L/(hi-lo), 1/2)),
+ * L*2^16); code = floor((ti + h)/2^16), i.e. floor(t)+1 for (ti mod 2^16) of the 2^16 values of h,
+ * floor(t) otherwise; meta = {lo, scale}. A constant bucket (or one whose range is so small that
+ * 2^16*L/(hi-lo) overflows) gets scale 0 and codes 0.
  *   g      in   device float[n]
  *   codes  out  device uint32[qsdp_codes_bytes/4]
  *   meta   out  device float[2*nb]
@@ -363,9 +365,10 @@ int qsdp_fused_adamw_step_codes(uint32_t* wcodes, float* wmeta, const float* g, 
  *   qsdp_quantize_levels_stochastic  the unbiased counterpart for gradients (the coin-flip
  *                           definition of the appendix applied between the two levels that
  *                           enclose z): with i the largest index such that levels[i] <= z,
- *                           code = i + [u < (z - levels[i]) / (levels[i+1] - levels[i])], u the
- *                           rounding uniform of qsdp_quantize_grad (same seed / index_offset
- *                           rules); z below the first level gives 0, at or above the last
+ *                           code = i + [2^16 - (h + 1/2) < p * 2^16], p = (z - levels[i]) /
+ *                           (levels[i+1] - levels[i]), h the 16-bit rounding uniform of
+ *                           qsdp_quantize_grad (same seed / index_offset rules): up for the
+ *                           round(p * 2^16) largest values of h; z below the first level gives 0, at or above the last
  *                           2^bits-1, so the mean of the decoded value equals the input exactly
  *                           when the table starts at 0 and ends at 1.
  *   qsdp_dequantize_levels  out = fma(levels[code], hi-lo, lo), fp32 or bf16.

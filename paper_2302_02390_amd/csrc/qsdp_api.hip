@@ -281,7 +281,7 @@ static_assert(sizeof(qsdp_segment) == sizeof(Segment), "segment layout");
 
 extern "C" {
 
-uint32_t qsdp_spec_version(void) { return 2u; }
+uint32_t qsdp_spec_version(void) { return 3u; }
 
 size_t qsdp_codes_bytes(uint64_t n, int bits, int bucket) {
     if (!shape_ok(n, bits, bucket)) return 0;

@@ -83,8 +83,8 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                     philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, key.k0, key.k1, w);
                     const uint32_t j = (uint32_t)(e & 7u);
                     const uint32_t word = w[j >> 1];
-                    const float h = (float)((j & 1u) ? (word >> 16) : (word & 0xFFFFu));
-                    c = grad_code(val[i], grid, Lg, h);
+                    const uint32_t h = (j & 1u) ? (word >> 16) : (word & 0xFFFFu);
+                    c = grad_code(val[i], grid, (uint32_t)Lg << 16, h);
                 }
                 if (MODE == MODE_GRAD) {
                     code[i] = (uint8_t)(uint32_t)c;
@@ -181,7 +181,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                             if (lower < K - 1) {
                                 const float q0 = levels[lower];
                                 const float prob = (z - q0) / (levels[lower + 1] - q0);
-                                c = lower + (h < prob * 65536.0f ? 1 : 0);
+                                c = lower + ((65535.5f - h) < prob * 65536.0f ? 1 : 0);
                             }
                         }
                         code[i] = (uint8_t)c;

@@ -3,8 +3,10 @@
 // Arithmetic contract (binary32, round to nearest even, no contraction; this file is
 // compiled with -ffp-contract=off, fused multiply-adds are written as fmaf):
 //   bucket grid   lo = min + 0.0f, hi = max + 0.0f, range = hi - lo,
-//                 scale = range / L, inv = L / range (0, 0 for a degenerate bucket)
-//   Q^g           t = clamp((g - lo) * inv, 0, L); code = floor(t) + [u < t - floor(t)]
+//                 scale = range / L, inv = L / range (0, 0 for a degenerate bucket: range 0, not
+//                 finite, or inv * 2^16 not finite)
+//   Q^g           ti = min(trunc(fma(g - lo, inv * 2^16, 1/2)), L * 2^16); code = (ti + h) >> 16, h the
+//                 element's 16-bit uniform
 //   Q^w (min-max) k = clamp(rint((x - lo) * inv - xi), 0, L); base = fma(xi, scale, lo)
 //   Q^w (lattice) k = rint(x / delta - xi); code = min(k - k0, L); base = (k0 + xi) * delta
 //   decode        fma(code, scale, base)
@@ -40,28 +42,30 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// Rounding uniforms of a row pair, as the 16-bit integers h (u = h * 2^-16) converted to float
-// (exact). Lane l holds elements (r*G + l)*4 .. +3 of rows r = 2c and 2c+1. A Philox block (8
-// elements) spans the lane pair (l even, l+1) of one row: the even lane computes the block of
-// row 2c, the odd lane that of row 2c+1, and the pair swaps the halves the other needs.
-// h[0..3] serve row 2c, h[4..7] row 2c+1. bucket_block = index of the bucket's first block.
+// Rounding uniforms of a row pair: the 16-bit integers h of the lane's eight elements, still packed
+// two to a word (low half first). Lane l holds elements (r*G + l)*4 .. +3 of rows r = 2c and 2c+1.
+// A Philox block (8 elements) spans the lane pair (l even, l+1) of one row: the even lane computes
+// the block of row 2c, the odd lane that of row 2c+1, and the pair swaps the halves the other needs.
+// w[0..1] serve row 2c, w[2..3] row 2c+1. bucket_block = index of the bucket's first block.
 template <int G>
 __device__ __forceinline__ void grad_uniforms_rows(uint64_t bucket_block, int c, int l, uint32_t k0,
-                                                   uint32_t k1, float (&h)[8]) {
+                                                   uint32_t k1, uint32_t (&h)[4]) {
     const int odd = l & 1;
     const uint64_t block = bucket_block + (uint64_t)(((2 * c + odd) * G + (l - odd)) >> 1);
     uint32_t w[4];
     philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
     const uint32_t send0 = odd ? w[0] : w[2];
     const uint32_t send1 = odd ? w[1] : w[3];
-    const uint32_t recv0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send0, 0xB1, 0xF, 0xF, false);
-    const uint32_t recv1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send1, 0xB1, 0xF, 0xF, false);
-    const uint32_t a0 = odd ? recv0 : w[0], a1 = odd ? recv1 : w[1];  // row 2c
-    const uint32_t b0 = odd ? w[2] : recv0, b1 = odd ? w[3] : recv1;  // row 2c+1
-    h[0] = (float)(a0 & 0xFFFFu); h[1] = (float)(a0 >> 16);
-    h[2] = (float)(a1 & 0xFFFFu); h[3] = (float)(a1 >> 16);
-    h[4] = (float)(b0 & 0xFFFFu); h[5] = (float)(b0 >> 16);
-    h[6] = (float)(b1 & 0xFFFFu); h[7] = (float)(b1 >> 16);
+    // every lane has a partner, so the destination's previous value never shows
+    const uint32_t recv0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)send0, 0xB1, 0xF, 0xF, true);
+    const uint32_t recv1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)send1, 0xB1, 0xF, 0xF, true);
+    h[0] = odd ? recv0 : w[0]; h[1] = odd ? recv1 : w[1];  // row 2c
+    h[2] = odd ? w[2] : recv0; h[3] = odd ? w[3] : recv1;  // row 2c+1
+}
+
+// The 16-bit uniform of element i (0..7) of a row pair out of the packed words above.
+__device__ __forceinline__ uint32_t uniform16(const uint32_t (&h)[4], int i) {
+    return (i & 1) ? (h[i >> 1] >> 16) : (h[i >> 1] & 0xFFFFu);
 }
 
 // A shift xi in [-1/2, 1/2): counter 0 of stream 1 (weights) or 2 (shared-shift gradients).
@@ -134,7 +138,7 @@ __device__ __forceinline__ MinMaxGrid make_minmax_grid(float lo, float hi, float
     const float range = hi - lo;
     const float inv = Lf / range;
     const float scale = range / Lf;
-    const bool ok = (range > 0.0f) && (range < __builtin_inff()) && (inv < __builtin_inff());
+    const bool ok = (range > 0.0f) && (range < __builtin_inff()) && (inv * 65536.0f < __builtin_inff());
     MinMaxGrid g;
     g.lo = lo;
     g.scale = ok ? scale : 0.0f;
@@ -153,28 +157,24 @@ __device__ __forceinline__ float div_delta(float v, const Divider& d) {
     return d.pow2 ? v * d.inv_delta : v / d.delta;
 }
 
-// Coin-flip code of one gradient element: floor(t) + [u < frac(t)], t clamped to [0, L]
-// (t >= 0 always; the upper clamp catches (hi - lo) * inv rounding above L). v_med3 is the
-// clamp and v_fract is t - floor(t), exactly, for finite t >= 0. h = u * 2^16.
-__device__ __forceinline__ float grad_position(float g, const MinMaxGrid& grid, float Lf) {
-    const float t = (g - grid.lo) * grid.inv;
-    return __builtin_amdgcn_fmed3f(t, 0.0f, Lf);
+// Coin-flip code of one gradient element, decided in integers: the position in the bucket's grid
+// in units of 2^-16 of a cell, ti = min(trunc(fma(g - lo, inv * 2^16, 1/2)), L * 2^16) (the
+// conversion saturates, so a non-finite input cannot fault), plus the 16-bit uniform h; the code is
+// the sum's bits 16 and up: floor(t) + 1 for exactly (ti mod 2^16) of the 2^16 values of h.
+__device__ __forceinline__ uint32_t grad_sum16(float g, const MinMaxGrid& grid, uint32_t top16, uint32_t h) {
+    const float t16 = fmaf(g - grid.lo, grid.inv * 65536.0f, 0.5f);
+    const uint32_t ti = (uint32_t)t16;
+    return (ti < top16 ? ti : top16) + h;
 }
 
-// ... as a float (for decoding in registers)
-__device__ __forceinline__ float grad_code(float g, const MinMaxGrid& grid, float Lf, float h) {
-    const float t = grad_position(g, grid, Lf);
-    const float frac = __builtin_amdgcn_fractf(t);
-    const float u = h * 0x1p-16f;
-    return floorf(t) + ((u < frac) ? 1.0f : 0.0f);
+// ... as a float (for decoding in registers): byte 2 of the sum (the code is at most 255)
+__device__ __forceinline__ float grad_code(float g, const MinMaxGrid& grid, uint32_t top16, uint32_t h) {
+    return (float)((grad_sum16(g, grid, top16, h) >> 16) & 0xFFu);
 }
 
-// ... as an integer (for packing): truncation is floor for t >= 0
-__device__ __forceinline__ uint32_t grad_code_int(float g, const MinMaxGrid& grid, float Lf, float h) {
-    const float t = grad_position(g, grid, Lf);
-    const float frac = __builtin_amdgcn_fractf(t);
-    const float u = h * 0x1p-16f;
-    return (uint32_t)t + ((u < frac) ? 1u : 0u);
+// ... as an integer (for packing)
+__device__ __forceinline__ uint32_t grad_code_int(float g, const MinMaxGrid& grid, uint32_t top16, uint32_t h) {
+    return (grad_sum16(g, grid, top16, h) >> 16) & 0xFFu;
 }
 
 __device__ __forceinline__ float weight_code_minmax(float x, const MinMaxGrid& grid, float Lf,
@@ -240,9 +240,9 @@ __device__ __forceinline__ void fill_first_equal(const float* lv, int* first, in
 }
 
 // Unbiased rounding of z onto the two of the K = 2^BITS ascending levels `lv` (in LDS) that
-// enclose it: with i the largest index such that lv[i] <= z, code = i + [h * 2^-16 < p],
-// p = (z - lv[i]) / (lv[i+1] - lv[i]); z below the first level gives 0, at or above the last K-1.
-// h is the 16-bit rounding uniform as a float (exact), so h < p * 2^16 is the same comparison.
+// enclose it: with i the largest index such that lv[i] <= z and p = (z - lv[i]) / (lv[i+1] - lv[i]),
+// code = i + [2^16 - (h + 1/2) < p * 2^16]: up for the round(p * 2^16) largest of the 2^16 values of
+// the uniform h (given as a float, exact). z below the first level gives 0, at or above the last K-1.
 template <int BITS>
 __device__ __forceinline__ int stochastic_level(float z, float h, const float* lv) {
     constexpr int K = 1 << BITS;
@@ -255,7 +255,7 @@ __device__ __forceinline__ int stochastic_level(float z, float h, const float* l
     if (cnt == K) return K - 1;
     const int i = cnt - 1;
     const float p = (z - lv[i]) / (lv[i + 1] - lv[i]);
-    return i + (h < p * 65536.0f ? 1 : 0);
+    return i + ((65535.5f - h) < p * 65536.0f ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------

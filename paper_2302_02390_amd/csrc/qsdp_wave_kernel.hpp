@@ -397,6 +397,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     }
 
     const float Lg = (float)((1 << p.gbits) - 1);
+    const uint32_t top16_g = (uint32_t)((1 << p.gbits) - 1) << 16;  // L in units of 2^-16 of a cell
     const float Lw = (float)((1 << p.wbits) - 1);
     const Divider div = {p.delta, p.inv_delta, p.delta_pow2 != 0};
     const bool lattice = p.delta > 0.0f;
@@ -483,15 +484,15 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             } else {
 #pragma unroll
                 for (int cp = 0; cp < R / 2; ++cp) {
-                    float h[8];
+                    uint32_t h[4];
                     grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int r = 2 * cp + (i >> 2);
                         if constexpr (MODE == MODE_GRAD) {
-                            gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, Lg, h[i]);
+                            gcode[r][i & 3] = grad_code_int(gv[r][i & 3], grid, top16_g, uniform16(h, i));
                         } else {
-                            const float code = grad_code(gv[r][i & 3], grid, Lg, h[i]);
+                            const float code = grad_code(gv[r][i & 3], grid, top16_g, uniform16(h, i));
                             const float ghat = fmaf(code, grid.scale, grid.lo);
                             w[r][i & 3] = step_value<MODE>(p, w[r][i & 3], ghat, mom[r][i & 3], var[r][i & 3]);
                         }
@@ -589,13 +590,13 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                 if constexpr (MODE == MODE_LEVELS_COIN) {
 #pragma unroll
                     for (int cp = 0; cp < R / 2; ++cp) {
-                        float h[8];
+                        uint32_t h[4];
                         grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
 #pragma unroll
                         for (int i = 0; i < 8; ++i) {
                             const int r = 2 * cp + (i >> 2);
                             const float z = (w[r][i & 3] - grid.lo) * grid.inv;
-                            const float c = (float)stochastic_level<SB>(z, h[i], level_table);
+                            const float c = (float)stochastic_level<SB>(z, (float)uniform16(h, i), level_table);
                             w[r][i & 3] = mine ? c : w[r][i & 3];
                         }
                     }
