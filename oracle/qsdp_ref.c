@@ -688,7 +688,8 @@ int qsdp_ref_quantize_levels(const float* v, uint64_t n, int bits, int bucket, c
 
 /* Unbiased rounding onto non-uniform levels: the coin-flip quantizer of the appendix between the
  * two levels that enclose z. With i the largest index such that q_i <= z and q_{i+1} the next
- * level (so q_i <= z < q_{i+1}) and p = (z - q_i) / (q_{i+1} - q_i): code = i + [1 - 2^-17 - u < p],
+ * level (so q_i <= z < q_{i+1}) and p = (z - q_i) * (1 / (q_{i+1} - q_i)), the reciprocal of the gap
+ * rounded to binary32 first: code = i + [1 - 2^-17 - u < p],
  * i.e. with u = h * 2^-16 the level above is taken for the round(p * 2^16) largest values of h
  * (p is rounded to 16 bits to nearest and large h rounds up, as in the uniform coin flip). z below the first level
  * gives code 0, z at or above the last gives K-1: no pair of levels encloses those, so the
@@ -700,7 +701,8 @@ static int stochastic_level(float z, float u, const float* levels, int K) {
         if (levels[k] <= z) i = k;
     if (i == K - 1) return K - 1;
     float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */
-    float p = (z - levels[i]) / gap;
+    float r = 1.0f / gap;                  /* a property of the table: one division per level, not per value */
+    float p = (z - levels[i]) * r;
     /* 2^16 - (h + 1/2) < p * 2^16: up for the round(p * 2^16) largest values of h (both sides exact) */
     return i + ((1.0f - 0x1p-17f) - u < p ? 1 : 0);
 }

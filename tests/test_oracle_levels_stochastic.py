@@ -17,7 +17,7 @@ def _table(bits, seed):
 
 def test_exhaustive_over_all_uniforms_gives_the_exact_up_count():
     """For one value between two levels, the uniforms h * 2^-16 that round up are the largest ones, those
-    with 2^16 - (h + 1/2) < p * 2^16: round(p * 2^16) of them, p = (z - q_i) / (q_{i+1} - q_i) in binary32
+    with 2^16 - (h + 1/2) < p * 2^16: round(p * 2^16) of them, p = (z - q_i) * (1 / (q_{i+1} - q_i)) in binary32
     (brute force over every h; the comparison is evaluated here in exact rational arithmetic)."""
     from fractions import Fraction
     q = np.array([0.0, 0.125, 0.5, 1.0], dtype=np.float32)
@@ -25,7 +25,7 @@ def test_exhaustive_over_all_uniforms_gives_the_exact_up_count():
     u_all = (np.arange(1 << 16, dtype=np.float32) * np.float32(2.0 ** -16))
     for z, i in ((0.2, 1), (0.124, 0), (0.51, 2), (0.999, 2), (0.125, 1)):
         zf = np.float32(z)
-        p = np.float32((zf - q[i]) / (q[i + 1] - q[i]))
+        p = np.float32(zf - q[i]) * (np.float32(1.0) / np.float32(q[i + 1] - q[i]))   # binary32: gap, reciprocal, product
         # every one of the 2^16 uniforms once: buckets of B elements, one uniform per element
         codes_up = 0
         for start in range(0, 1 << 16, B):

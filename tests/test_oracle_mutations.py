@@ -91,7 +91,7 @@ MUTANTS = [
      ["test_oracle_levels_stochastic.py"]),
     ("level_coin_flip_rounds_up_for_small_uniforms", "return i + ((1.0f - 0x1p-17f) - u < p ? 1 : 0);",
      "return i + (u + 0x1p-17f < p ? 1 : 0);", ["test_oracle_levels_stochastic.py"]),
-    ("level_coin_flip_uses_distance_to_upper", "float p = (z - levels[i]) / gap;", "float p = (levels[i + 1] - z) / gap;",
+    ("level_coin_flip_uses_distance_to_upper", "float p = (z - levels[i]) * r;", "float p = (levels[i + 1] - z) * r;",
      ["test_oracle_levels_stochastic.py"]),
     ("level_upper_neighbour_skipped", "float gap = levels[i + 1] - levels[i]; /* > 0 by the choice of i */",
      "float gap = levels[K - 1] - levels[i];", ["test_oracle_levels_stochastic.py"]),
