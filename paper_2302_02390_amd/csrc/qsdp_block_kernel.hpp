@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(256) block_kernel(const Params p, const Segmen
                             c = lower;
                             if (lower < K - 1) {
                                 const float q0 = levels[lower];
-                                const float prob = (z - q0) / (levels[lower + 1] - q0);
+                                const float prob = (z - q0) * (1.0f / (levels[lower + 1] - q0));
                                 c = lower + ((65535.5f - h) < prob * 65536.0f ? 1 : 0);
                             }
                         }

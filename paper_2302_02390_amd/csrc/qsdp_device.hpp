@@ -195,9 +195,70 @@ __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, 
     return c;
 }
 
-// Nearest of the K = 2^BITS ascending levels `lv` (in LDS) to z; ties and equal levels resolve
-// to the lowest index. Branch-free lower bound over the power-of-two table, then the closer of
-// the two neighbours.
+// ---------------------------------------------------------------------------------------
+// Learned levels: K = 2^BITS ascending levels `lv` in LDS. Both encoders count the levels below z
+// with a branch-free binary search whose first two pivots are wave-uniform and held in scalar
+// registers (only the later steps read LDS), then fetch everything else they need about the
+// landing place with ONE more LDS read from a table built once per workgroup (or per wave, where
+// every tensor has its own levels).
+// ---------------------------------------------------------------------------------------
+struct LevelPivots {
+    float mid, lower, upper, last;  // lv[K/2-1], lv[K/4-1], lv[3K/4-1], lv[K-1]
+};
+
+// All lanes read the same addresses, so the values are wave-uniform and can live in SGPRs.
+template <int BITS>
+__device__ __forceinline__ LevelPivots load_level_pivots(const float* lv) {
+    constexpr int K = 1 << BITS;
+    auto uniform = [](float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); };
+    LevelPivots pv;
+    pv.mid = uniform(lv[K / 2 - 1]);
+    pv.lower = uniform(lv[BITS >= 2 ? K / 4 - 1 : 0]);
+    pv.upper = uniform(lv[BITS >= 2 ? 3 * K / 4 - 1 : 0]);
+    pv.last = uniform(lv[K - 1]);
+    return pv;
+}
+
+// How many of the first K-1 levels are < z (LE: <= z): a lower (upper) bound over the power-of-two table.
+template <int BITS, bool LE>
+__device__ __forceinline__ int count_levels_below(float z, const float* lv, const LevelPivots& pv) {
+    constexpr int K = 1 << BITS;
+    auto below = [](float q, float zz) { return LE ? q <= zz : q < zz; };
+    int j = below(pv.mid, z) ? K / 2 : 0;
+    if (BITS >= 2) j += below(j ? pv.upper : pv.lower, z) ? K / 4 : 0;
+#pragma unroll
+    for (int step = K / 8; step >= 1; step >>= 1)
+        if (below(lv[j + step - 1], z)) j += step;
+    return j;
+}
+
+// What the nearest-level encoder needs at landing place j (lv[j-1] < z <= lv[j]): the two candidate
+// levels and the code of the lower one, which is the lowest index whose level equals it (ties and
+// equal levels resolve to the lowest index). first_lo is an int kept in a float's bits.
+struct LevelNear {
+    float lo, hi, first_lo, unused;
+};
+
+// Entries k = k0, k0 + stride, ... < K of that table (lv complete and visible to the caller's threads).
+__device__ __forceinline__ void fill_level_near(const float* lv, LevelNear* near, int K, int k0, int stride) {
+    for (int k = k0; k < K; k += stride) {
+        int f = k > 0 ? k - 1 : 0;
+        const float lo = lv[f];
+        while (f > 0 && lv[f - 1] == lo) --f;
+        LevelNear e = {lo, lv[k], __int_as_float(f), 0.0f};
+        near[k] = e;
+    }
+}
+
+// Nearest of the levels to z; ties and equal levels resolve to the lowest index.
+template <int BITS>
+__device__ __forceinline__ int nearest_level(float z, const float* lv, const LevelNear* near, const LevelPivots& pv) {
+    const int j = count_levels_below<BITS, false>(z, lv, pv);  // j in [0, K-1]
+    const LevelNear e = near[j];
+    return fabsf(z - e.hi) < fabsf(z - e.lo) ? j : __float_as_int(e.first_lo);
+}
+
+// The same by the plain definition over a table in LDS (block kernel: one value per thread at a time).
 template <int BITS>
 __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     constexpr int K = 1 << BITS;
@@ -205,7 +266,6 @@ __device__ __forceinline__ int nearest_level(float z, const float* lv) {
 #pragma unroll
     for (int step = K / 2; step >= 1; step >>= 1)
         if (lv[j + step - 1] < z) j += step;
-    // levels[j-1] < z <= levels[j] (with j in [0, K-1]; if all of the first K-1 are < z, j = K-1)
     const int lo_idx = j > 0 ? j - 1 : 0;
     const float d_lo = fabsf(z - lv[lo_idx]);
     const float d_hi = fabsf(z - lv[j]);
@@ -214,47 +274,32 @@ __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     return c;
 }
 
-// The same search without control flow per element: `first[k]` = the lowest index whose level
-// equals lv[k] (fill_first_equal), looked up instead of walked to. The encoder's 16 independent
-// searches of a lane then interleave freely; with the loop above each of them is a basic block.
-template <int BITS>
-__device__ __forceinline__ int nearest_level(float z, const float* lv, const int* first) {
-    constexpr int K = 1 << BITS;
-    int j = 0;
-#pragma unroll
-    for (int step = K / 2; step >= 1; step >>= 1)
-        if (lv[j + step - 1] < z) j += step;
-    const int lo_idx = j > 0 ? j - 1 : 0;
-    const float d_lo = fabsf(z - lv[lo_idx]);
-    const float d_hi = fabsf(z - lv[j]);
-    return first[d_hi < d_lo ? j : lo_idx];
-}
+// What the coin-flip encoder needs at level i: the level and the reciprocal of the gap to the next
+// one (0 for the last level: nothing to round up to).
+struct LevelCoin {
+    float q, rgap;
+};
 
-// first[k] for k = k0, k0 + stride, ... < K (lv complete and visible to the caller's threads)
-__device__ __forceinline__ void fill_first_equal(const float* lv, int* first, int K, int k0, int stride) {
+__device__ __forceinline__ void fill_level_coin(const float* lv, LevelCoin* coin, int K, int k0, int stride) {
     for (int k = k0; k < K; k += stride) {
-        int j = k;
-        while (j > 0 && lv[j - 1] == lv[j]) --j;
-        first[k] = j;
+        LevelCoin e = {lv[k], k + 1 < K ? 1.0f / (lv[k + 1] - lv[k]) : 0.0f};
+        coin[k] = e;
     }
 }
 
-// Unbiased rounding of z onto the two of the K = 2^BITS ascending levels `lv` (in LDS) that
-// enclose it: with i the largest index such that lv[i] <= z and p = (z - lv[i]) / (lv[i+1] - lv[i]),
-// code = i + [2^16 - (h + 1/2) < p * 2^16]: up for the round(p * 2^16) largest of the 2^16 values of
-// the uniform h (given as a float, exact). z below the first level gives 0, at or above the last K-1.
+// Unbiased rounding of z onto the two levels that enclose it: with i the largest index such that
+// lv[i] <= z and p = (z - lv[i]) * (1 / (lv[i+1] - lv[i])), code = i + [2^16 - (h + 1/2) < p * 2^16]: up
+// for the round(p * 2^16) largest of the 2^16 values of the uniform h (given as a float, exact). z
+// below the first level gives 0 (p < 0 there), at or above the last K-1 (its reciprocal gap is 0).
 template <int BITS>
-__device__ __forceinline__ int stochastic_level(float z, float h, const float* lv) {
+__device__ __forceinline__ int stochastic_level(float z, float h, const float* lv, const LevelCoin* coin,
+                                                const LevelPivots& pv) {
     constexpr int K = 1 << BITS;
-    int cnt = 0;  // number of levels <= z among the first K-1 (branch-free search), then the last one
-#pragma unroll
-    for (int step = K / 2; step >= 1; step >>= 1)
-        if (lv[cnt + step - 1] <= z) cnt += step;
-    if (cnt == K - 1 && lv[K - 1] <= z) cnt = K;
-    if (cnt == 0) return 0;
-    if (cnt == K) return K - 1;
-    const int i = cnt - 1;
-    const float p = (z - lv[i]) / (lv[i + 1] - lv[i]);
+    int cnt = count_levels_below<BITS, true>(z, lv, pv);  // levels <= z among the first K-1 ...
+    cnt += (cnt == K - 1 && pv.last <= z) ? 1 : 0;        // ... and the last one
+    const int i = cnt > 0 ? cnt - 1 : 0;
+    const LevelCoin e = coin[i];
+    const float p = (z - e.q) * e.rgap;
     return i + ((65535.5f - h) < p * 65536.0f ? 1 : 0);
 }
 

@@ -376,23 +376,30 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
-    // MODE_LEVELS: the level table in LDS. One table for the whole call is loaded once per
-    // workgroup; with one table per tensor every wave keeps the table of the tensor it works on
-    // in a slot of its own and reloads it when its buckets move on to another tensor.
-    __shared__ float level_tables[mode_is_levels(MODE) ? 4 * (1 << SB) : 1];
-    __shared__ int level_firsts[MODE == MODE_LEVELS ? 4 * (1 << SB) : 1];  // see fill_first_equal
+    // Learned levels: the level table in LDS, next to it the per-level table its encoder reads at the
+    // end of the search (see LevelNear / LevelCoin), and the search's first pivots in scalar registers.
+    // One table for the whole call is loaded once per workgroup; with one table per tensor every wave
+    // keeps the table of the tensor it works on in a slot of its own and reloads it when its buckets
+    // move on to another tensor.
+    constexpr int kLevels = 1 << SB;
+    __shared__ float level_tables[mode_is_levels(MODE) ? 4 * kLevels : 1];
+    __shared__ LevelNear level_nears[MODE == MODE_LEVELS ? 4 * kLevels : 1];
+    __shared__ LevelCoin level_coins[MODE == MODE_LEVELS_COIN ? 4 * kLevels : 1];
     const bool levels_per_tensor = mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr;
-    const float* level_table = level_tables + (levels_per_tensor ? wave_in_block * (1u << SB) : 0u);
-    const int* level_first = level_firsts + (levels_per_tensor && MODE == MODE_LEVELS ? wave_in_block * (1u << SB) : 0u);
+    const uint32_t level_slot = levels_per_tensor ? wave_in_block * (uint32_t)kLevels : 0u;
+    float* level_table = level_tables + level_slot;
+    LevelNear* level_near = level_nears + (MODE == MODE_LEVELS ? level_slot : 0u);
+    LevelCoin* level_coin = level_coins + (MODE == MODE_LEVELS_COIN ? level_slot : 0u);
+    LevelPivots pivots = {0.0f, 0.0f, 0.0f, 0.0f};
     uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
     if constexpr (mode_is_levels(MODE)) {
         if (!levels_per_tensor) {
-            for (int k = threadIdx.x; k < (1 << SB); k += blockDim.x) level_tables[k] = p.levels[k];
+            for (int k = threadIdx.x; k < kLevels; k += blockDim.x) level_tables[k] = p.levels[k];
             __syncthreads();
-            if constexpr (MODE == MODE_LEVELS) {
-                fill_first_equal(level_tables, level_firsts, 1 << SB, threadIdx.x, blockDim.x);
-                __syncthreads();
-            }
+            if constexpr (MODE == MODE_LEVELS) fill_level_near(level_tables, level_nears, kLevels, threadIdx.x, blockDim.x);
+            else fill_level_coin(level_tables, level_coins, kLevels, threadIdx.x, blockDim.x);
+            __syncthreads();
+            pivots = load_level_pivots<SB>(level_tables);
         }
     }
 
@@ -571,19 +578,18 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                     const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)ref.tensor, __builtin_ctzll(pending));
                     mine = ref.tensor == cur;
                     if (cur != loaded_tensor) {
-                        float* slot = level_tables + wave_in_block * (1u << SB);
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slot are done
                         __builtin_amdgcn_wave_barrier();
-                        for (int k = lane; k < (1 << SB); k += 64) slot[k] = p.levels[(uint64_t)cur * (1u << SB) + k];
+                        for (int k = lane; k < kLevels; k += 64) level_table[k] = p.levels[(uint64_t)cur * kLevels + k];
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        if constexpr (MODE == MODE_LEVELS) {
-                            fill_first_equal(slot, level_firsts + wave_in_block * (1u << SB), 1 << SB, lane, 64);
-                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                            __builtin_amdgcn_wave_barrier();
-                            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        }
+                        if constexpr (MODE == MODE_LEVELS) fill_level_near(level_table, level_near, kLevels, lane, 64);
+                        else fill_level_coin(level_table, level_coin, kLevels, lane, 64);
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        pivots = load_level_pivots<SB>(level_table);
                         loaded_tensor = cur;
                     }
                 }
@@ -596,7 +602,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
                         for (int i = 0; i < 8; ++i) {
                             const int r = 2 * cp + (i >> 2);
                             const float z = (w[r][i & 3] - grid.lo) * grid.inv;
-                            const float c = (float)stochastic_level<SB>(z, (float)uniform16(h, i), level_table);
+                            const float c = (float)stochastic_level<SB>(z, (float)uniform16(h, i), level_table, level_coin, pivots);
                             w[r][i & 3] = mine ? c : w[r][i & 3];
                         }
                     }
@@ -606,7 +612,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const float z = (w[r][i] - grid.lo) * grid.inv;
-                            const float c = (float)nearest_level<SB>(z, level_table, level_first);
+                            const float c = (float)nearest_level<SB>(z, level_table, level_near, pivots);
                             w[r][i] = mine ? c : w[r][i];
                         }
                 }
