@@ -145,15 +145,15 @@ hipError_t launch_dequant(int bits, bool bf16, const DequantParams& p, dim3 grid
 namespace {
 
 constexpr unsigned kMaxGrid = 1u << 20;
+constexpr unsigned kLevelsGrid = 1u << 15;
 
 // Workgroups to launch for `blocks` units of work: all of them up to kMaxGrid, the kernels stride
 // beyond that. QSDP_DEBUG_MAXGRID (the library's one debug switch) lowers the cap so that the
 // striding paths can be exercised on small inputs.
-unsigned capped_grid(uint64_t blocks) {
-    unsigned cap = kMaxGrid;
+unsigned capped_grid(uint64_t blocks, unsigned cap = kMaxGrid) {
     if (const char* e = std::getenv("QSDP_DEBUG_MAXGRID")) {
         const long v = std::atol(e);
-        if (v >= 1 && v < (long)kMaxGrid) cap = (unsigned)v;
+        if (v >= 1 && v < (long)cap) cap = (unsigned)v;
     }
     return (unsigned)(blocks < cap ? blocks : cap);
 }
@@ -207,7 +207,10 @@ int run(int mode, Params p, int stored_bits, hipStream_t s) {
     if (wl != nullptr && wave_bits_supported(stored_bits) && peer_bits_ok) {
         // 4 waves per workgroup, each on bpw buckets; or one workgroup per bucket
         const uint64_t blocks = bpw > 0 ? ceil_div(ceil_div(nb, (uint64_t)bpw), 4) : nb;
-        if (wl(mode, stored_bits, p, capped_grid(blocks), s) != hipSuccess) return QSDP_ELAUNCH;
+        // The learned-level encoders set up lookup tables per workgroup: their workgroups stay resident
+        // and stride over the buckets (measured best around 128 workgroups per compute unit).
+        const unsigned cap = mode_is_levels(mode) ? kLevelsGrid : kMaxGrid;
+        if (wl(mode, stored_bits, p, capped_grid(blocks, cap), s) != hipSuccess) return QSDP_ELAUNCH;
     } else {
         if (launch_block(mode == MODE_LEVELS_COIN ? MODE_LEVELS : mode, p, capped_grid(nb), s) != hipSuccess)
             return QSDP_ELAUNCH;

@@ -196,12 +196,55 @@ __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Learned levels: K = 2^BITS ascending levels `lv` in LDS. Both encoders count the levels below z
-// with a branch-free binary search whose first two pivots are wave-uniform and held in scalar
-// registers (only the later steps read LDS), then fetch everything else they need about the
-// landing place with ONE more LDS read from a table built once per workgroup (or per wave, where
-// every tensor has its own levels).
+// Learned levels: K = 2^BITS ascending levels in [0, 1]. The encoders work in "cell units": every
+// level and every normalised value is scaled by kLevelCells (a power of two, so all comparisons,
+// differences and products below are the unscaled ones times an exact power of two and give the
+// same decisions bit for bit). An encoder first counts the levels below (or at) the value, then
+// fetches what it needs about that landing place with one LDS read from a table built once per
+// workgroup (or per wave, where every tensor has its own levels).
+//   * Counting by cell: the unit interval is cut into kLevelCells cells; a table holds for each cell
+//     how many levels lie below its start and the next level. If no cell holds two levels, the count
+//     for a value is the cell's count plus one comparison with that next level: one LDS read.
+//   * Counting by search (a table with two levels in one cell): branch-free binary search whose
+//     first two pivots are wave-uniform and held in scalar registers.
 // ---------------------------------------------------------------------------------------
+constexpr int kLevelCells = 256;
+constexpr float kLevelCellsF = 256.0f;
+
+struct LevelCell {
+    float next;  // the first level not below (LE: not at or below) the cell's start, +inf if none
+    int count;   // levels below (LE: at or below) the cell's start
+};
+
+// Entries c = c0, c0 + stride, ... <= kLevelCells of the cell table over the first `kc` scaled levels
+// lv (cell c is [c, c+1) in cell units; the last entry serves a value of exactly 1). Returns whether
+// one of these cells holds two levels, in which case the table must not be used.
+template <bool LE>
+__device__ __forceinline__ bool fill_level_cells(const float* lv, LevelCell* cells, int kc, int c0, int stride) {
+    bool crowded = false;
+    for (int c = c0; c <= kLevelCells; c += stride) {
+        const float start = (float)c;
+        int lo = 0, hi = kc;  // lv[k] below start for k < lo, not below for k >= hi
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (LE ? lv[mid] <= start : lv[mid] < start) lo = mid + 1; else hi = mid;
+        }
+        LevelCell e = {lo < kc ? lv[lo] : __builtin_inff(), lo};
+        cells[c] = e;
+        crowded = crowded || (lo + 1 < kc && lv[lo + 1] < start + 1.0f);
+    }
+    return crowded;
+}
+
+// The cell table's count for a value zc (in cell units; the conversion saturates, the index is
+// clamped, so a non-finite value cannot read outside the table).
+template <bool LE>
+__device__ __forceinline__ int count_levels_by_cell(float zc, const LevelCell* cells) {
+    const uint32_t c = (uint32_t)zc;
+    const LevelCell e = cells[c < (uint32_t)kLevelCells ? c : (uint32_t)kLevelCells];
+    return e.count + ((LE ? e.next <= zc : e.next < zc) ? 1 : 0);
+}
+
 struct LevelPivots {
     float mid, lower, upper, last;  // lv[K/2-1], lv[K/4-1], lv[3K/4-1], lv[K-1]
 };
@@ -221,7 +264,7 @@ __device__ __forceinline__ LevelPivots load_level_pivots(const float* lv) {
 
 // How many of the first K-1 levels are < z (LE: <= z): a lower (upper) bound over the power-of-two table.
 template <int BITS, bool LE>
-__device__ __forceinline__ int count_levels_below(float z, const float* lv, const LevelPivots& pv) {
+__device__ __forceinline__ int count_levels_by_search(float z, const float* lv, const LevelPivots& pv) {
     constexpr int K = 1 << BITS;
     auto below = [](float q, float zz) { return LE ? q <= zz : q < zz; };
     int j = below(pv.mid, z) ? K / 2 : 0;
@@ -234,9 +277,10 @@ __device__ __forceinline__ int count_levels_below(float z, const float* lv, cons
 
 // What the nearest-level encoder needs at landing place j (lv[j-1] < z <= lv[j]): the two candidate
 // levels and the code of the lower one, which is the lowest index whose level equals it (ties and
-// equal levels resolve to the lowest index). first_lo is an int kept in a float's bits.
+// equal levels resolve to the lowest index).
 struct LevelNear {
-    float lo, hi, first_lo, unused;
+    float lo, hi;
+    int first_lo, unused;
 };
 
 // Entries k = k0, k0 + stride, ... < K of that table (lv complete and visible to the caller's threads).
@@ -245,20 +289,23 @@ __device__ __forceinline__ void fill_level_near(const float* lv, LevelNear* near
         int f = k > 0 ? k - 1 : 0;
         const float lo = lv[f];
         while (f > 0 && lv[f - 1] == lo) --f;
-        LevelNear e = {lo, lv[k], __int_as_float(f), 0.0f};
+        LevelNear e = {lo, lv[k], f, 0};
         near[k] = e;
     }
 }
 
-// Nearest of the levels to z; ties and equal levels resolve to the lowest index.
+// Nearest of the levels to z (both in cell units); ties and equal levels resolve to the lowest index.
+// by_cell (wave-uniform): the cell table may be used.
 template <int BITS>
-__device__ __forceinline__ int nearest_level(float z, const float* lv, const LevelNear* near, const LevelPivots& pv) {
-    const int j = count_levels_below<BITS, false>(z, lv, pv);  // j in [0, K-1]
+__device__ __forceinline__ uint32_t nearest_level(float z, const float* lv, const LevelCell* cells, const LevelNear* near,
+                                                  const LevelPivots& pv, bool by_cell) {
+    // the number of levels < z among the first K-1: j in [0, K-1]
+    const int j = by_cell ? count_levels_by_cell<false>(z, cells) : count_levels_by_search<BITS, false>(z, lv, pv);
     const LevelNear e = near[j];
-    return fabsf(z - e.hi) < fabsf(z - e.lo) ? j : __float_as_int(e.first_lo);
+    return (uint32_t)(fabsf(z - e.hi) < fabsf(z - e.lo) ? j : e.first_lo);
 }
 
-// The same by the plain definition over a table in LDS (block kernel: one value per thread at a time).
+// The same by the plain definition over an (unscaled) table in LDS (level fit: one value per thread at a time).
 template <int BITS>
 __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     constexpr int K = 1 << BITS;
@@ -274,12 +321,14 @@ __device__ __forceinline__ int nearest_level(float z, const float* lv) {
     return c;
 }
 
-// What the coin-flip encoder needs at level i: the level and the reciprocal of the gap to the next
-// one (0 for the last level: nothing to round up to).
+// What the coin-flip encoder needs at level i: the level (cell units) and the reciprocal of the gap
+// to the next one (per cell unit; 0 for the last level: nothing to round up to).
 struct LevelCoin {
     float q, rgap;
 };
 
+// lv: the scaled levels. The reciprocal of a scaled gap is the unscaled reciprocal divided by
+// kLevelCells, exactly, so (z - q) * rgap in cell units is the unscaled product bit for bit.
 __device__ __forceinline__ void fill_level_coin(const float* lv, LevelCoin* coin, int K, int k0, int stride) {
     for (int k = k0; k < K; k += stride) {
         LevelCoin e = {lv[k], k + 1 < K ? 1.0f / (lv[k + 1] - lv[k]) : 0.0f};
@@ -291,16 +340,22 @@ __device__ __forceinline__ void fill_level_coin(const float* lv, LevelCoin* coin
 // lv[i] <= z and p = (z - lv[i]) * (1 / (lv[i+1] - lv[i])), code = i + [2^16 - (h + 1/2) < p * 2^16]: up
 // for the round(p * 2^16) largest of the 2^16 values of the uniform h (given as a float, exact). z
 // below the first level gives 0 (p < 0 there), at or above the last K-1 (its reciprocal gap is 0).
+// z and the tables are in cell units; p comes out unscaled.
 template <int BITS>
-__device__ __forceinline__ int stochastic_level(float z, float h, const float* lv, const LevelCoin* coin,
-                                                const LevelPivots& pv) {
+__device__ __forceinline__ uint32_t stochastic_level(float z, float h, const float* lv, const LevelCell* cells,
+                                                     const LevelCoin* coin, const LevelPivots& pv, bool by_cell) {
     constexpr int K = 1 << BITS;
-    int cnt = count_levels_below<BITS, true>(z, lv, pv);  // levels <= z among the first K-1 ...
-    cnt += (cnt == K - 1 && pv.last <= z) ? 1 : 0;        // ... and the last one
+    int cnt;  // levels <= z
+    if (by_cell) {
+        cnt = count_levels_by_cell<true>(z, cells);
+    } else {
+        cnt = count_levels_by_search<BITS, true>(z, lv, pv);  // among the first K-1 ...
+        cnt += (cnt == K - 1 && pv.last <= z) ? 1 : 0;         // ... and the last one
+    }
     const int i = cnt > 0 ? cnt - 1 : 0;
     const LevelCoin e = coin[i];
     const float p = (z - e.q) * e.rgap;
-    return i + ((65535.5f - h) < p * 65536.0f ? 1 : 0);
+    return (uint32_t)i + ((65535.5f - h) < p * 65536.0f ? 1u : 0u);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -5,6 +5,10 @@
 
 #include "qsdp_params.hpp"
 
+#ifndef QSDP_LEVELS_MIN_BLOCKS
+#define QSDP_LEVELS_MIN_BLOCKS 4
+#endif
+
 namespace qsdp {
 
 // ---------------------------------------------------------------------------------------
@@ -344,13 +348,46 @@ __device__ __forceinline__ void sum_peer_slices(const Params& p, uint8_t* stage,
     }
 }
 
+// The learned-level encoders over a lane's rows: v -> codes (MODE_LEVELS: nearest level; MODE_LEVELS_COIN:
+// coin flip between the enclosing levels). MASKED: only the lanes with `mine` keep their codes (a pass
+// over the lanes of one tensor of a multi-tensor call).
+template <int MODE, int G, int R, int BITS, bool MASKED>
+__device__ __forceinline__ void encode_levels(const float (&v)[R][4], uint32_t (&code)[R][4], bool mine, float lo,
+                                              float inv_cells, const float* lv, const LevelCell* cells,
+                                              const LevelNear* near, const LevelCoin* coin, const LevelPivots& pivots,
+                                              bool by_cell, uint64_t block_e0, int l, PhiloxKey key) {
+    if constexpr (MODE == MODE_LEVELS_COIN) {
+#pragma unroll
+        for (int cp = 0; cp < R / 2; ++cp) {
+            uint32_t h[4];
+            grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int r = 2 * cp + (i >> 2);
+                const float z = (v[r][i & 3] - lo) * inv_cells;
+                const uint32_t c = stochastic_level<BITS>(z, (float)uniform16(h, i), lv, cells, coin, pivots, by_cell);
+                code[r][i & 3] = (!MASKED || mine) ? c : code[r][i & 3];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float z = (v[r][i] - lo) * inv_cells;
+                const uint32_t c = nearest_level<BITS>(z, lv, cells, near, pivots, by_cell);
+                code[r][i] = (!MASKED || mine) ? c : code[r][i];
+            }
+    }
+}
+
 // Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
 // be short). BITS is the width of the codes that are stored (0: a step without code output, or
 // MODE_SUM). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
 template <int MODE, int G, int R, int BITS, int W>
-__global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment* __restrict__ segs) {
+__global__ void __launch_bounds__(256, mode_is_levels(MODE) ? QSDP_LEVELS_MIN_BLOCKS : 1) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
@@ -376,29 +413,55 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
-    // Learned levels: the level table in LDS, next to it the per-level table its encoder reads at the
-    // end of the search (see LevelNear / LevelCoin), and the search's first pivots in scalar registers.
-    // One table for the whole call is loaded once per workgroup; with one table per tensor every wave
-    // keeps the table of the tensor it works on in a slot of its own and reloads it when its buckets
-    // move on to another tensor.
+    // Learned levels (see the section of that name in qsdp_device.hpp): the level table in LDS, scaled
+    // to cell units, the cell table and the landing table of the mode's encoder, and the binary
+    // search's first pivots in scalar registers. One table for the whole call is set up once per
+    // workgroup; with one table per tensor every wave keeps the tables of the tensor it works on in
+    // slots of its own and sets them up again when its buckets move on to another tensor.
     constexpr int kLevels = 1 << SB;
+    constexpr int kCellSlot = kLevelCells + 1;
     __shared__ float level_tables[mode_is_levels(MODE) ? 4 * kLevels : 1];
+    __shared__ LevelCell level_cells_all[mode_is_levels(MODE) ? 4 * kCellSlot : 1];
     __shared__ LevelNear level_nears[MODE == MODE_LEVELS ? 4 * kLevels : 1];
     __shared__ LevelCoin level_coins[MODE == MODE_LEVELS_COIN ? 4 * kLevels : 1];
+    __shared__ int level_cells_crowded;
     const bool levels_per_tensor = mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr;
     const uint32_t level_slot = levels_per_tensor ? wave_in_block * (uint32_t)kLevels : 0u;
     float* level_table = level_tables + level_slot;
+    LevelCell* level_cells = level_cells_all + (levels_per_tensor ? wave_in_block * (uint32_t)kCellSlot : 0u);
     LevelNear* level_near = level_nears + (MODE == MODE_LEVELS ? level_slot : 0u);
     LevelCoin* level_coin = level_coins + (MODE == MODE_LEVELS_COIN ? level_slot : 0u);
     LevelPivots pivots = {0.0f, 0.0f, 0.0f, 0.0f};
-    uint32_t loaded_tensor = ~0u;  // wave-uniform: whose table the wave's slot holds
+    bool count_by_cell = false;    // wave-uniform: no cell of the current table holds two levels
+    uint32_t loaded_tensor = ~0u;  // wave-uniform: whose tables the wave's slots hold
     if constexpr (mode_is_levels(MODE)) {
         if (!levels_per_tensor) {
-            for (int k = threadIdx.x; k < kLevels; k += blockDim.x) level_tables[k] = p.levels[k];
+            if (threadIdx.x == 0) level_cells_crowded = 0;
+            constexpr int kThreads = W == 1 ? 256 : 64 * W;  // the launch's workgroup size
+            constexpr int kRounds = (kLevels + kThreads - 1) / kThreads;
+            float lv_mine[kRounds];  // this thread's levels
+#pragma unroll
+            for (int i = 0; i < kRounds; ++i) {
+                const int k = threadIdx.x + i * kThreads;
+                lv_mine[i] = k < kLevels ? p.levels[k] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < kRounds; ++i) {
+                const int k = threadIdx.x + i * kThreads;
+                if (k < kLevels) level_tables[k] = lv_mine[i] * kLevelCellsF;
+            }
             __syncthreads();
-            if constexpr (MODE == MODE_LEVELS) fill_level_near(level_tables, level_nears, kLevels, threadIdx.x, blockDim.x);
-            else fill_level_coin(level_tables, level_coins, kLevels, threadIdx.x, blockDim.x);
+            bool crowded;
+            if constexpr (MODE == MODE_LEVELS) {
+                fill_level_near(level_tables, level_nears, kLevels, threadIdx.x, blockDim.x);
+                crowded = fill_level_cells<false>(level_tables, level_cells_all, kLevels - 1, threadIdx.x, blockDim.x);
+            } else {
+                fill_level_coin(level_tables, level_coins, kLevels, threadIdx.x, blockDim.x);
+                crowded = fill_level_cells<true>(level_tables, level_cells_all, kLevels, threadIdx.x, blockDim.x);
+            }
+            if (crowded) level_cells_crowded = 1;
             __syncthreads();
+            count_by_cell = __builtin_amdgcn_readfirstlane(level_cells_crowded) == 0;
             pivots = load_level_pivots<SB>(level_tables);
         }
     }
@@ -441,6 +504,7 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
         const bool writes_meta = active && l == 0 && (W == 1 || wave_in_block == 0);
 
         float w[R][4];  // the values that get weight-quantized (x, or y = x - lr*ghat)
+        uint32_t lcode[mode_is_levels(MODE) ? R : 1][4] = {};  // the learned-level modes' codes
         float base = 0.0f, scale = 0.0f;
 
         if (mode_local_gradient(MODE)) {
@@ -566,58 +630,47 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
             const MinMaxGrid grid = make_minmax_grid(lo, hi, 1.0f, false);  // scale = hi - lo, inv = 1/(hi - lo)
             base = grid.lo;
             scale = grid.scale;
-            // One pass per distinct tensor among the wave's buckets (one pass, unless the buckets
-            // straddle tensors): every lane computes, the lanes of the pass's tensor replace their
-            // values by the codes (a lane belongs to exactly one pass; what it computes in the others,
-            // from values or from codes, is dropped). All lanes stay converged (the uniforms are
-            // exchanged between lanes).
-            uint64_t pending = ~0ull;
-            do {
-                bool mine = true;
-                if (levels_per_tensor) {
+            const float inv_cells = grid.inv * kLevelCellsF;  // normalised value in cell units: (v - lo) * inv_cells
+            if (!levels_per_tensor) {
+                encode_levels<MODE, G, R, SB, false>(w, lcode, true, grid.lo, inv_cells, level_table, level_cells, level_near,
+                                                     level_coin, pivots, count_by_cell, block_e0, l, key);
+            } else {
+                // One pass per distinct tensor among the wave's buckets (one pass, unless the buckets
+                // straddle tensors): every lane computes, the lanes of the pass's tensor keep the codes
+                // (a lane belongs to exactly one pass). All lanes stay converged (the uniforms are
+                // exchanged between lanes).
+                uint64_t pending = ~0ull;
+                do {
                     const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)ref.tensor, __builtin_ctzll(pending));
-                    mine = ref.tensor == cur;
+                    const bool mine = ref.tensor == cur;
                     if (cur != loaded_tensor) {
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slot are done
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slots are done
                         __builtin_amdgcn_wave_barrier();
-                        for (int k = lane; k < kLevels; k += 64) level_table[k] = p.levels[(uint64_t)cur * kLevels + k];
+                        for (int k = lane; k < kLevels; k += 64)
+                            level_table[k] = p.levels[(uint64_t)cur * kLevels + k] * kLevelCellsF;
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        if constexpr (MODE == MODE_LEVELS) fill_level_near(level_table, level_near, kLevels, lane, 64);
-                        else fill_level_coin(level_table, level_coin, kLevels, lane, 64);
+                        bool crowded;
+                        if constexpr (MODE == MODE_LEVELS) {
+                            fill_level_near(level_table, level_near, kLevels, lane, 64);
+                            crowded = fill_level_cells<false>(level_table, level_cells, kLevels - 1, lane, 64);
+                        } else {
+                            fill_level_coin(level_table, level_coin, kLevels, lane, 64);
+                            crowded = fill_level_cells<true>(level_table, level_cells, kLevels, lane, 64);
+                        }
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        count_by_cell = __builtin_amdgcn_ballot_w64(crowded) == 0;
                         pivots = load_level_pivots<SB>(level_table);
                         loaded_tensor = cur;
                     }
-                }
-                if constexpr (MODE == MODE_LEVELS_COIN) {
-#pragma unroll
-                    for (int cp = 0; cp < R / 2; ++cp) {
-                        uint32_t h[4];
-                        grad_uniforms_rows<G>(block_e0, cp, l, key.k0, key.k1, h);
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            const int r = 2 * cp + (i >> 2);
-                            const float z = (w[r][i & 3] - grid.lo) * grid.inv;
-                            const float c = (float)stochastic_level<SB>(z, (float)uniform16(h, i), level_table, level_coin, pivots);
-                            w[r][i & 3] = mine ? c : w[r][i & 3];
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float z = (w[r][i] - grid.lo) * grid.inv;
-                            const float c = (float)nearest_level<SB>(z, level_table, level_near, pivots);
-                            w[r][i] = mine ? c : w[r][i];
-                        }
-                }
-                pending &= ~__builtin_amdgcn_ballot_w64(mine);
-            } while (pending != 0);
+                    encode_levels<MODE, G, R, SB, true>(w, lcode, mine, grid.lo, inv_cells, level_table, level_cells,
+                                                        level_near, level_coin, pivots, count_by_cell, block_e0, l, key);
+                    pending &= ~__builtin_amdgcn_ballot_w64(mine);
+                } while (pending != 0);
+            }
         } else if (lattice) {
             float lo, unused_hi;
             rows_minmax<G, R>(w, l, m, partial, lo, unused_hi);
@@ -657,10 +710,14 @@ __global__ void __launch_bounds__(256) wave_kernel(const Params p, const Segment
 #pragma unroll
                 for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
         }
-        if (partial && BITS != 0) zero_slots_past_end<G, R>(w, l, m);
-
-        if (BITS != 0) {
+        if constexpr (mode_is_levels(MODE)) {
+            if (__builtin_expect(partial, 0)) zero_slots_past_end<G, R>(lcode, l, m);
+            store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, lcode);
+        } else if (BITS != 0) {
+            if (partial) zero_slots_past_end<G, R>(w, l, m);
             store_codes<G, R, SB>(stage, tile_out, lane, active_buckets, w);
+        }
+        if (BITS != 0) {
             if (writes_meta) {
                 p.meta[2 * bucket] = base;
                 p.meta[2 * bucket + 1] = scale;
