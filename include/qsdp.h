@@ -239,6 +239,7 @@ int qsdp_quantize_weight_ex(const float* x, uint64_t n, int bits, int bucket,
                             float delta, uint64_t seed, uint32_t flags,
                             uint32_t* codes, float* meta,
                             uint64_t* n_saturated, void* stream);
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
                        int wbits, int gbits, int bucket, float delta,
                        uint64_t seed, uint64_t index_offset, uint32_t flags,
@@ -258,6 +259,7 @@ int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr,
 int qsdp_quantize_grad_g16(const void* g, qsdp_dtype g_dtype, uint64_t n, int bits, int bucket,
                            uint64_t seed, uint64_t index_offset, uint32_t flags,
                            uint32_t* codes, float* meta, void* stream);
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr,
                         int wbits, int gbits, int bucket, float delta,
                         uint64_t seed, uint64_t index_offset, uint32_t flags,
@@ -275,6 +277,7 @@ int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n,
  * 2 more bytes written per parameter instead of a separate conversion or decoding pass.
  * Everything else as in qsdp_fused_step_ex.
  */
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr,
                        int wbits, int gbits, int bucket, float delta,
                        uint64_t seed, uint64_t index_offset, uint32_t flags,
@@ -283,6 +286,7 @@ int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, 
 
 /* qsdp_fused_adamw_step in the same mixed-precision form (gradient format g_dtype, optional 16-bit
  * copy x16 of the new quantized weights): the training step of the paper's experiments on one worker. */
+/* (thin forward of qsdp_fused_adamw_step_opts) */
 int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float* m, float* v,
                              uint64_t n, float lr, float beta1, float beta2, float eps,
                              float weight_decay, float bias1, float bias2,
@@ -299,6 +303,7 @@ int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float*
  * on between replays. seed_dev: device uint64, 8-byte aligned. Equal to qsdp_fused_step_ex called
  * with that sum.
  */
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr,
                           int wbits, int gbits, int bucket, float delta,
                           uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
@@ -317,6 +322,7 @@ int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr,
  *   m, v  in/out  device float[n], the moment estimates (start at 0)
  * flags as in the *_ex entry points; the other arguments as in qsdp_fused_step.
  */
+/* (thin forward of qsdp_fused_adamw_step_opts) */
 int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr,
                           float beta1, float beta2, float eps, float weight_decay,
                           float bias1, float bias2,
@@ -432,6 +438,60 @@ typedef struct qsdp_segment {
 } qsdp_segment;
 
 uint64_t qsdp_segments_build(const uint64_t* sizes, uint32_t nseg, int bucket, qsdp_segment* table);
+/* The segmented entry points take a DEVICE copy of a table that qsdp_segments_build wrote, unchanged
+ * (offsets multiples of 8, ascending first_bucket, total_buckets its return value). They check only the
+ * pointer and the counts; a table with other contents leads to misaligned or out-of-range accesses. */
+
+/*
+ * ONE options block for every form of the fused step. The step of Section 3.3,
+ * x <- Q^w(x - lr * Q^g(g)) (qsdp_fused_step_opts), or the same with AdamW between the quantizers
+ * (qsdp_fused_adamw_step_opts, arithmetic as documented at qsdp_fused_adamw_step), with every
+ * optional part named in the block: zero-initialise it, set `size`, fill in what is wanted.
+ * opt == NULL means no options (the plain qsdp_fused_step). The entry points
+ * qsdp_fused_step, _ex, _g16, _mp, _dseed, _segmented, _segmented_mp and qsdp_fused_adamw_step,
+ * _mp, _segmented are thin forwards of these two calls that fill the block from their argument
+ * lists; they stay for source compatibility and add nothing.
+ *   size            sizeof(qsdp_step_options); anything else: QSDP_EINVAL
+ *   flags           QSDP_FLAG_* (quantizer variants and KEEP_MASTER)
+ *   g_dtype         what g points to: QSDP_F32 (0, float[n]), QSDP_BF16 or QSDP_F16 (uint16[n],
+ *                   widened exactly on load)
+ *   x16, x16_dtype  optional second copy of the new quantized weights in QSDP_BF16 / QSDP_F16
+ *   segments, nseg, total_buckets   optional multi-tensor table (device memory, see above): the
+ *                   buffers hold the tensors back to back, bucketing restarts per tensor, `n` is ignored
+ *   seed_increment  optional device uint64 (8-byte aligned): the seed in force is seed +
+ *                   *seed_increment, read when the kernel starts (for replayed HIP graphs)
+ *   wcodes, wmeta   optional output (both or neither): packed codes and meta of the new weights
+ *   n_saturated     optional in/out device uint64, incremented by the clamped elements (delta > 0)
+ *   m, v, beta1, beta2, eps, weight_decay, bias1, bias2   AdamW only: moments (in/out, fp32) and
+ *                   scalars; ignored by qsdp_fused_step_opts
+ */
+typedef struct qsdp_step_options {
+    uint32_t size;
+    uint32_t flags;
+    qsdp_dtype g_dtype;
+    qsdp_dtype x16_dtype;
+    void* x16;
+    const qsdp_segment* segments;
+    uint32_t nseg;
+    uint32_t reserved;
+    uint64_t total_buckets;
+    const uint64_t* seed_increment;
+    uint32_t* wcodes;
+    float* wmeta;
+    uint64_t* n_saturated;
+    float* m;
+    float* v;
+    float beta1, beta2, eps, weight_decay, bias1, bias2;
+} qsdp_step_options;
+
+int qsdp_fused_step_opts(float* x, const void* g, uint64_t n, float lr,
+                         int wbits, int gbits, int bucket, float delta,
+                         uint64_t seed, uint64_t index_offset,
+                         const qsdp_step_options* opt, void* stream);
+int qsdp_fused_adamw_step_opts(float* x, const void* g, uint64_t n, float lr,
+                               int wbits, int gbits, int bucket, float delta,
+                               uint64_t seed, uint64_t index_offset,
+                               const qsdp_step_options* opt, void* stream);
 
 int qsdp_quantize_grad_segmented(const float* g, const qsdp_segment* table, uint32_t nseg,
                                  uint64_t total_buckets, int bits, int bucket,
@@ -444,6 +504,7 @@ int qsdp_quantize_weight_segmented(const float* x, const qsdp_segment* table, ui
                                    uint32_t* codes, float* meta,
                                    uint64_t* n_saturated, void* stream);
 
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* table, uint32_t nseg,
                               uint64_t total_buckets, float lr,
                               int wbits, int gbits, int bucket, float delta,
@@ -473,6 +534,7 @@ int qsdp_dequantize_segmented(const uint32_t* codes, const float* meta, const qs
  * (gradient uniforms follow index_offset + the position in the flat buffer, as in
  * qsdp_fused_step_segmented).
  */
+/* (thin forward of qsdp_fused_adamw_step_opts) */
 int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v,
                                     const qsdp_segment* table, uint32_t nseg,
                                     uint64_t total_buckets, float lr, float beta1, float beta2,
@@ -487,6 +549,7 @@ int qsdp_fused_step_codes_segmented(uint32_t* wcodes, float* wmeta, const float*
                                     uint32_t flags, uint64_t* n_saturated, void* stream);
 /* qsdp_fused_step_mp for many tensors in one launch (flags as in qsdp_fused_step_ex; x16, like x and g,
  * is indexed by the position in the flat buffer). */
+/* (thin forward of qsdp_fused_step_opts) */
 int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype,
                                  const qsdp_segment* table, uint32_t nseg, uint64_t total_buckets,
                                  float lr, int wbits, int gbits, int bucket, float delta,

@@ -41,6 +41,8 @@ _SIGNATURES = {
         [_vp, _vp, _i32, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp, _vp, _i32, _vp, _vp]),
     "qsdp_fused_step_dseed": (_i32,
         [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "qsdp_fused_step_opts": (_i32, [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _vp, _vp]),
+    "qsdp_fused_adamw_step_opts": (_i32, [_vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _vp, _vp]),
     "qsdp_fused_step_codes": (_i32, [_vp, _vp, _vp, _u64, _f32, _i32, _i32, _i32, _f32, _u64, _u64, _u32, _vp, _vp]),
     "qsdp_fused_adamw_step": (_i32,
         [_vp, _vp, _vp, _vp, _u64, _f32, _f32, _f32, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _f32, _u64,
@@ -795,6 +797,77 @@ def qsdp_fused_adamw_step_mp(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bi
                                               weight_decay, bias1, bias2, wbits, gbits, bucket, delta, seed,
                                               index_offset, flags, _ptr(wcodes), _ptr(wmeta), _ptr(x16), xdt,
                                               _ptr(n_saturated), _stream(x)), "qsdp_fused_adamw_step_mp")
+
+
+class StepOptions(C.Structure):
+    """qsdp_step_options of include/qsdp.h, field for field."""
+    _fields_ = [("size", C.c_uint32), ("flags", C.c_uint32), ("g_dtype", C.c_int), ("x16_dtype", C.c_int),
+                ("x16", C.c_void_p), ("segments", C.c_void_p), ("nseg", C.c_uint32), ("reserved", C.c_uint32),
+                ("total_buckets", C.c_uint64), ("seed_increment", C.c_void_p), ("wcodes", C.c_void_p),
+                ("wmeta", C.c_void_p), ("n_saturated", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
+                ("bias1", C.c_float), ("bias2", C.c_float)]
+
+
+def _step_opts(entry, x, g, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, segs, x16, seed_increment,
+               wcodes, wmeta, n_saturated, adamw):
+    gdt = {torch.float32: QSDP_F32, torch.bfloat16: QSDP_BF16, torch.float16: QSDP_F16}.get(g.dtype)
+    if gdt is None:
+        raise TypeError("g must be float32, float16 or bfloat16")
+    _is(x, torch.float32); _is(g, g.dtype)
+    n = x.numel() if segs is None else segs.n
+    if x.numel() < n or g.numel() < n or (segs is None and g.numel() != n):
+        raise ValueError("x and g do not cover the elements of the call")
+    o = StepOptions()
+    o.size = C.sizeof(StepOptions)
+    o.flags = flags
+    o.g_dtype = gdt
+    if x16 is not None:
+        if x16.dtype not in _G16:
+            raise TypeError("x16 must be float16 or bfloat16")
+        _is(x16, x16.dtype)
+        _need(x16, n, "x16")
+        o.x16, o.x16_dtype = x16.data_ptr(), _G16[x16.dtype]
+    for t, dt in ((wcodes, torch.int32), (wmeta, torch.float32), (n_saturated, torch.int64),
+                  (seed_increment, torch.int64)):
+        if t is not None:
+            _is(t, dt)
+    if segs is None:
+        _packed_ok(wcodes, wmeta, n, wbits, bucket)
+    else:
+        if bucket != segs.bucket:
+            raise ValueError("bucket differs from the segment table's")
+        segs.check_packed(wcodes, wmeta, wbits)
+        o.segments, o.nseg, o.total_buckets = segs.device.data_ptr(), segs.nseg, segs.total_buckets
+    for name, t in (("wcodes", wcodes), ("wmeta", wmeta), ("n_saturated", n_saturated),
+                    ("seed_increment", seed_increment)):
+        if t is not None:
+            setattr(o, name, t.data_ptr())
+    if adamw is not None:
+        m, v, o.beta1, o.beta2, o.eps, o.weight_decay, o.bias1, o.bias2 = adamw
+        _is(m, torch.float32); _is(v, torch.float32)
+        _need(m, n, "m"); _need(v, n, "v")
+        o.m, o.v = m.data_ptr(), v.data_ptr()
+    with torch.cuda.device(x.device):
+        _check(getattr(lib(), entry)(_ptr(x), _ptr(g), 0 if segs is not None else n, lr, wbits, gbits, bucket, delta,
+                                     seed, index_offset, C.byref(o), _stream(x)), entry)
+
+
+def qsdp_fused_step_opts(x, g, lr, wbits, gbits, bucket, delta, seed, index_offset=0, flags=0, segs=None, x16=None,
+                         seed_increment=None, wcodes=None, wmeta=None, n_saturated=None):
+    """The fused step with its optional parts in one options block (qsdp_step_options): gradient in float32 /
+    float16 / bfloat16 (taken from g's dtype), a segment table, a 16-bit copy of the new weights, a device-resident
+    seed increment, code output, the saturation counter."""
+    _step_opts("qsdp_fused_step_opts", x, g, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, segs, x16,
+               seed_increment, wcodes, wmeta, n_saturated, None)
+
+
+def qsdp_fused_adamw_step_opts(x, g, m, v, lr, beta1, beta2, eps, weight_decay, bias1, bias2, wbits, gbits, bucket,
+                               delta, seed, index_offset=0, flags=0, segs=None, x16=None, seed_increment=None,
+                               wcodes=None, wmeta=None, n_saturated=None):
+    """The same with AdamW (moments m, v in float32, updated in place) between the two quantizers."""
+    _step_opts("qsdp_fused_adamw_step_opts", x, g, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, segs,
+               x16, seed_increment, wcodes, wmeta, n_saturated, (m, v, beta1, beta2, eps, weight_decay, bias1, bias2))
 
 
 def _one_device(fn):

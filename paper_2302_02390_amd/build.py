@@ -1,8 +1,13 @@
 """Build ``libqsdp.so`` (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
 ``python -m paper_2302_02390_amd.build`` compiles every translation unit (in parallel) and
-links ``paper_2302_02390_amd/libqsdp.so``. Flags: strict binary32 (no contraction, no
-fast-math), packed-fp32 instruction selection switched off.
+links ``paper_2302_02390_amd/libqsdp.so``. Flags: strict binary32 arithmetic (no contraction, no
+reassociation, no reciprocal or other approximations: ``-fno-fast-math``), with ONE relaxation,
+``-fno-honor-nans``: inputs are finite by contract, so ``fminf``/``fmaxf`` may compile to single
+``v_min``/``v_max`` instructions instead of NaN-canonicalising sequences (measured on the 1.3B
+vector: quantize_grad 0.97 ms with the flag, 1.05 ms without; the code-resident step 1.43 against
+1.55 ms). The flag changes no result for finite inputs. Packed-fp32 instruction selection is
+switched off.
 """
 import os
 import subprocess

@@ -536,96 +536,127 @@ int qsdp_dequantize_add(const uint32_t* codes, uint64_t codes_stride_bytes, cons
     return QSDP_OK;
 }
 
-int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
-                    float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes, float* wmeta,
-                    uint64_t* n_saturated, void* stream) {
-    return qsdp_fused_step_ex(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, 0u, wcodes, wmeta,
-                              n_saturated, stream);
-}
-
-// The optional parts of a fused step: a multi-tensor table, a device-resident seed increment, the
-// gradient's format (0: fp32, 1: bf16, 2: binary16) and a 16-bit copy of the new weights.
-struct FusedStepOptions {
-    const SegmentTable* segs;
-    const uint64_t* seed_dev;
-    uint32_t g_half;
-    void* x16;
-    uint32_t x16_f16;
-};
-
-static int fused_step_common(const FusedStepOptions& opt, float* x, const void* g, uint64_t n, float lr, int wbits,
-                             int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
-                             uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
-    if (opt.segs) {
-        const int rc = segments_ok(*opt.segs, bucket, &n);
+// Every form of the fused step (SGD or AdamW between the quantizers) from one options block.
+static int step_from_options(bool adamw, float* x, const void* g, uint64_t n, float lr, int wbits, int gbits,
+                             int bucket, float delta, uint64_t seed, uint64_t index_offset,
+                             const qsdp_step_options* opt, void* stream) {
+    qsdp_step_options o = {};
+    if (opt != nullptr) {
+        if (opt->size != sizeof(qsdp_step_options)) return QSDP_EINVAL;
+        o = *opt;
+    }
+    const bool multi = o.segments != nullptr;
+    const SegmentTable segs = {o.segments, o.nseg, o.total_buckets};
+    if (multi) {
+        const int rc = segments_ok(segs, bucket, &n);
         if (rc != QSDP_OK) return rc;
     }
-    if (opt.seed_dev && (reinterpret_cast<uintptr_t>(opt.seed_dev) & 7u)) return QSDP_EALIGN;
-    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) ||
-        (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
+    if (o.g_dtype != QSDP_F32 && half_format(o.g_dtype) == 0u) return QSDP_EINVAL;
+    if (o.x16 != nullptr && half_format(o.x16_dtype) == 0u) return QSDP_EINVAL;
+    const AdamScalars adam = {o.m, o.v, o.beta1, o.beta2, o.eps, o.weight_decay, o.bias1, o.bias2};
+    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) || (adamw && !adam_ok(adam)) ||
+        (o.flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
         return QSDP_EINVAL;
     if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
-    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(wcodes) || !aligned16(wmeta) || !aligned16(opt.x16))
+    if ((o.wcodes == nullptr) != (o.wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
+    if (!aligned16(x) || !aligned16(g) || !aligned16(o.wcodes) || !aligned16(o.wmeta) || !aligned16(o.x16))
         return QSDP_EALIGN;
-    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
+    if (adamw && (!aligned16(adam.m) || !aligned16(adam.v))) return QSDP_EALIGN;
+    if (o.n_saturated && (reinterpret_cast<uintptr_t>(o.n_saturated) & 7u)) return QSDP_EALIGN;
+    if (o.seed_increment && (reinterpret_cast<uintptr_t>(o.seed_increment) & 7u)) return QSDP_EALIGN;
     Params p = {};
-    set_common(p, opt.segs ? 0 : n, bucket, seed, index_offset, delta);
-    if (opt.segs) set_segments(p, *opt.segs);
-    p.flags = flags;
+    set_common(p, multi ? 0 : n, bucket, seed, index_offset, delta);
+    if (multi) set_segments(p, segs);
+    p.flags = o.flags;
     p.x = x;
-    p.x16 = opt.x16;
-    p.x16_f16 = opt.x16_f16;
+    p.x16 = o.x16;
+    p.x16_f16 = o.x16_dtype == QSDP_F16 ? 1u : 0u;
     p.g = static_cast<const float*>(g);
-    p.codes = wcodes;
-    p.meta = wmeta;
-    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
+    p.g_half = half_format(o.g_dtype);
+    p.codes = o.wcodes;
+    p.meta = o.wmeta;
+    p.n_saturated = reinterpret_cast<unsigned long long*>(o.n_saturated);
     p.gbits = gbits;
     p.wbits = wbits;
     p.lr = lr;
-    p.seed_dev = reinterpret_cast<const unsigned long long*>(opt.seed_dev);
-    p.g_half = opt.g_half;
-    return run(MODE_FUSED, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+    p.seed_dev = reinterpret_cast<const unsigned long long*>(o.seed_increment);
+    if (adamw) set_adam(p, adam);
+    return run(adamw ? MODE_ADAMW : MODE_FUSED, p, o.wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+}
+
+int qsdp_fused_step_opts(float* x, const void* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                         float delta, uint64_t seed, uint64_t index_offset, const qsdp_step_options* opt,
+                         void* stream) {
+    return step_from_options(false, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, opt, stream);
+}
+
+int qsdp_fused_adamw_step_opts(float* x, const void* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                               float delta, uint64_t seed, uint64_t index_offset, const qsdp_step_options* opt,
+                               void* stream) {
+    return step_from_options(true, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, opt, stream);
+}
+
+// ---- thin forwards of the two calls above: each fills the options block from its argument list ----
+static qsdp_step_options options_for(uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated) {
+    qsdp_step_options o = {};
+    o.size = sizeof o;
+    o.flags = flags;
+    o.wcodes = wcodes;
+    o.wmeta = wmeta;
+    o.n_saturated = n_saturated;
+    return o;
+}
+
+static void set_adam_options(qsdp_step_options& o, float* m, float* v, float beta1, float beta2, float eps,
+                             float weight_decay, float bias1, float bias2) {
+    o.m = m; o.v = v; o.beta1 = beta1; o.beta2 = beta2; o.eps = eps; o.weight_decay = weight_decay;
+    o.bias1 = bias1; o.bias2 = bias2;
+}
+
+static void set_segment_options(qsdp_step_options& o, const qsdp_segment* table, uint32_t nseg, uint64_t total_buckets) {
+    o.segments = table; o.nseg = nseg; o.total_buckets = total_buckets;
+}
+
+int qsdp_fused_step(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
+                    float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes, float* wmeta,
+                    uint64_t* n_saturated, void* stream) {
+    const qsdp_step_options o = options_for(0u, wcodes, wmeta, n_saturated);
+    return qsdp_fused_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_step_ex(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                        float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, uint64_t* n_saturated, void* stream) {
-    return fused_step_common(FusedStepOptions{}, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
-                             wmeta, n_saturated, stream);
+    const qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    return qsdp_fused_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_step_dseed(float* x, const float* g, uint64_t n, float lr, int wbits, int gbits, int bucket,
                           float delta, uint64_t seed, const uint64_t* seed_dev, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (!seed_dev) return QSDP_EINVAL;
-    FusedStepOptions opt = {};
-    opt.seed_dev = seed_dev;
-    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
-                             wmeta, n_saturated, stream);
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    o.seed_increment = seed_dev;
+    return qsdp_fused_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_step_g16(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr, int wbits, int gbits,
                         int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
                         uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
     if (half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    FusedStepOptions opt = {};
-    opt.g_half = half_format(g_dtype);
-    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
-                             wmeta, n_saturated, stream);
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    o.g_dtype = g_dtype;
+    return qsdp_fused_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_step_mp(float* x, const void* g, qsdp_dtype g_dtype, uint64_t n, float lr, int wbits, int gbits,
                        int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags, uint32_t* wcodes,
                        float* wmeta, void* x16, qsdp_dtype x16_dtype, uint64_t* n_saturated, void* stream) {
-    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
-    FusedStepOptions opt = {};
-    opt.g_half = half_format(g_dtype);
-    opt.x16 = x16;
-    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
-    return fused_step_common(opt, x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta,
-                             n_saturated, stream);
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    o.g_dtype = g_dtype;
+    o.x16 = x16;
+    o.x16_dtype = x16_dtype;
+    return qsdp_fused_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype, const qsdp_segment* table,
@@ -633,62 +664,22 @@ int qsdp_fused_step_segmented_mp(float* x, const void* g, qsdp_dtype g_dtype, co
                                  int bucket, float delta, uint64_t seed, uint64_t index_offset, uint32_t flags,
                                  uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
                                  uint64_t* n_saturated, void* stream) {
-    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
-    const SegmentTable segs = {table, nseg, total_buckets};
-    FusedStepOptions opt = {};
-    opt.segs = &segs;
-    opt.g_half = half_format(g_dtype);
-    opt.x16 = x16;
-    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
-    return fused_step_common(opt, x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes, wmeta,
-                             n_saturated, stream);
-}
-
-static int fused_adamw_common(const FusedStepOptions& opt, float* x, const void* g, const AdamScalars& adam, uint64_t n,
-                              float lr, int wbits, int gbits, int bucket, float delta, uint64_t seed,
-                              uint64_t index_offset, uint32_t flags, uint32_t* wcodes, float* wmeta,
-                              uint64_t* n_saturated, void* stream) {
-    const SegmentTable* segs = opt.segs;
-    if (segs) {
-        const int rc = segments_ok(*segs, bucket, &n);
-        if (rc != QSDP_OK) return rc;
-    }
-    if (!x || !g || !shape_ok(n, wbits, bucket) || !shape_ok(n, gbits, bucket) || !adam_ok(adam) ||
-        (flags & ~(uint32_t)(QSDP_FLAG_ALL | QSDP_FLAG_KEEP_MASTER)))
-        return QSDP_EINVAL;
-    if (!(delta >= 0.0f) || !std::isfinite(delta) || !std::isfinite(lr)) return QSDP_EINVAL;
-    if ((wcodes == nullptr) != (wmeta == nullptr) || (index_offset & 7u)) return QSDP_EINVAL;
-    if (!aligned16(x) || !aligned16(g) || !aligned16(adam.m) || !aligned16(adam.v) || !aligned16(wcodes) ||
-        !aligned16(wmeta) || !aligned16(opt.x16))
-        return QSDP_EALIGN;
-    if (n_saturated && (reinterpret_cast<uintptr_t>(n_saturated) & 7u)) return QSDP_EALIGN;
-    Params p = {};
-    set_common(p, segs ? 0 : n, bucket, seed, index_offset, delta);
-    if (segs) set_segments(p, *segs);
-    p.flags = flags;
-    p.x = x;
-    p.x16 = opt.x16;
-    p.x16_f16 = opt.x16_f16;
-    p.g = static_cast<const float*>(g);
-    p.g_half = opt.g_half;
-    p.codes = wcodes;
-    p.meta = wmeta;
-    p.n_saturated = reinterpret_cast<unsigned long long*>(n_saturated);
-    p.gbits = gbits;
-    p.wbits = wbits;
-    p.lr = lr;
-    set_adam(p, adam);
-    return run(MODE_ADAMW, p, wcodes ? wbits : 0, static_cast<hipStream_t>(stream));
+    if (!table) return QSDP_EINVAL;
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    o.g_dtype = g_dtype;
+    o.x16 = x16;
+    o.x16_dtype = x16_dtype;
+    set_segment_options(o, table, nseg, total_buckets);
+    return qsdp_fused_step_opts(x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_adamw_step(float* x, const float* g, float* m, float* v, uint64_t n, float lr, float beta1,
                           float beta2, float eps, float weight_decay, float bias1, float bias2, int wbits,
                           int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                           uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated, void* stream) {
-    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
-    return fused_adamw_common(FusedStepOptions{}, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags,
-                              wcodes, wmeta, n_saturated, stream);
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    set_adam_options(o, m, v, beta1, beta2, eps, weight_decay, bias1, bias2);
+    return qsdp_fused_adamw_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float* m, float* v, uint64_t n, float lr,
@@ -696,15 +687,12 @@ int qsdp_fused_adamw_step_mp(float* x, const void* g, qsdp_dtype g_dtype, float*
                              int wbits, int gbits, int bucket, float delta, uint64_t seed, uint64_t index_offset,
                              uint32_t flags, uint32_t* wcodes, float* wmeta, void* x16, qsdp_dtype x16_dtype,
                              uint64_t* n_saturated, void* stream) {
-    if (g_dtype != QSDP_F32 && half_format(g_dtype) == 0u) return QSDP_EINVAL;
-    if (x16 != nullptr && half_format(x16_dtype) == 0u) return QSDP_EINVAL;
-    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
-    FusedStepOptions opt = {};
-    opt.g_half = half_format(g_dtype);
-    opt.x16 = x16;
-    opt.x16_f16 = x16_dtype == QSDP_F16 ? 1u : 0u;
-    return fused_adamw_common(opt, x, g, adam, n, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
-                              wmeta, n_saturated, stream);
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    set_adam_options(o, m, v, beta1, beta2, eps, weight_decay, bias1, bias2);
+    o.g_dtype = g_dtype;
+    o.x16 = x16;
+    o.x16_dtype = x16_dtype;
+    return qsdp_fused_adamw_step_opts(x, g, n, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v, const qsdp_segment* table,
@@ -713,12 +701,11 @@ int qsdp_fused_adamw_step_segmented(float* x, const float* g, float* m, float* v
                                     int bucket, float delta, uint64_t seed, uint64_t index_offset,
                                     uint32_t flags, uint32_t* wcodes, float* wmeta, uint64_t* n_saturated,
                                     void* stream) {
-    const AdamScalars adam = {m, v, beta1, beta2, eps, weight_decay, bias1, bias2};
-    const SegmentTable segs = {table, nseg, total_buckets};
-    FusedStepOptions opt = {};
-    opt.segs = &segs;
-    return fused_adamw_common(opt, x, g, adam, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, flags, wcodes,
-                              wmeta, n_saturated, stream);
+    if (!table) return QSDP_EINVAL;
+    qsdp_step_options o = options_for(flags, wcodes, wmeta, n_saturated);
+    set_adam_options(o, m, v, beta1, beta2, eps, weight_decay, bias1, bias2);
+    set_segment_options(o, table, nseg, total_buckets);
+    return qsdp_fused_adamw_step_opts(x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 static int fused_step_codes_common(const AdamScalars* adam, const SegmentTable* segs, uint32_t* wcodes, float* wmeta, const float* g,
@@ -840,11 +827,10 @@ int qsdp_fused_step_segmented(float* x, const float* g, const qsdp_segment* tabl
                               uint64_t total_buckets, float lr, int wbits, int gbits, int bucket,
                               float delta, uint64_t seed, uint64_t index_offset, uint32_t* wcodes,
                               float* wmeta, uint64_t* n_saturated, void* stream) {
-    const SegmentTable segs = {table, nseg, total_buckets};
-    FusedStepOptions opt = {};
-    opt.segs = &segs;
-    return fused_step_common(opt, x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, 0u, wcodes, wmeta,
-                             n_saturated, stream);
+    if (!table) return QSDP_EINVAL;
+    qsdp_step_options o = options_for(0u, wcodes, wmeta, n_saturated);
+    set_segment_options(o, table, nseg, total_buckets);
+    return qsdp_fused_step_opts(x, g, 0, lr, wbits, gbits, bucket, delta, seed, index_offset, &o, stream);
 }
 
 int qsdp_quantize_levels_segmented(const float* v, const qsdp_segment* table, uint32_t nseg,

@@ -65,6 +65,16 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.qsdp_fused_step_g16(ok, ok, 0, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, 0, None, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_fused_step_g16(ok, ok, 1, 10, 1e-3, 8, 4, 1024, 0.0, 0, 4, 0, None, None, None, None) == qb.QSDP_EINVAL
     assert L.qsdp_dequantize_segmented(ok, ok, ok, 1, 1, 8, 1024, 3, ok, None) == qb.QSDP_EINVAL
+    # the options block: its size field is checked, and its pointers like any argument
+    o = qb.StepOptions()
+    assert L.qsdp_fused_step_opts(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ctypes.byref(o), None) == qb.QSDP_EINVAL
+    o.size = ctypes.sizeof(qb.StepOptions)
+    o.wcodes = 4096
+    assert L.qsdp_fused_step_opts(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ctypes.byref(o), None) == qb.QSDP_EINVAL
+    o.wmeta = 4100
+    assert L.qsdp_fused_step_opts(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ctypes.byref(o), None) == qb.QSDP_EALIGN
+    o.wmeta, o.g_dtype = 4096, 7
+    assert L.qsdp_fused_step_opts(ok, ok, 10, 1e-3, 8, 4, 1024, 0.0, 0, 0, ctypes.byref(o), None) == qb.QSDP_EINVAL
     assert qb.status_string(qb.QSDP_EALIGN).startswith("pointer")
 
 
@@ -134,3 +144,19 @@ def test_binding_rejects_tensors_on_different_devices():
         qb.qsdp_dequantize(torch.zeros(256, dtype=torch.int32), torch.zeros(2), 1024, 8, 1024, out=g)
     with pytest.raises(TypeError):                             # same device, but not a GPU tensor
         qb.qsdp_fused_step(x, torch.zeros(1024), 1e-3, 8, 4, 1024, 0.0, 0)
+
+
+def test_options_block_layout_matches_the_header(tmp_path):
+    """binding.StepOptions mirrors qsdp_step_options field for field: same size and offsets as a C compiler gives."""
+    import subprocess
+    fields = [name for name, _ in qb.StepOptions._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "qsdp.h"\nint main(void) {\n'
+                   '    printf("%zu\\n", sizeof(qsdp_step_options));\n' +
+                   "".join(f'    printf("%zu\\n", offsetof(qsdp_step_options, {f}));\n' for f in fields) +
+                   "    return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(qb.StepOptions)
+    assert out[1:] == [getattr(qb.StepOptions, f).offset for f in fields]
