@@ -287,11 +287,15 @@ def attainable(torch, x, g, n, fused_achieved, lr):
     xa, ga = x[:m].clone(), g[:m]
     y = torch.empty_like(xa)
     sink = torch.zeros(4, dtype=torch.float32, device=x.device)
+    codes = torch.empty(m // 4, dtype=torch.int32, device=x.device)
     kernels = (("read_only", lambda i: bs.read(xa, sink), 4.0), ("write_only", lambda i: bs.fill(y, 0.5), 4.0),
                ("copy", lambda i: bs.copy(xa, y), 8.0), ("rrw", lambda i: bs.axpy(xa, ga, lr), 12.0),
+               ("encode_4bit_mix", lambda i: bs.encode(xa, 4, codes), 4.5),
+               ("encode_8bit_mix", lambda i: bs.encode(xa, 8, codes), 5.0),
                ("runtime_device_copy", lambda i: y.copy_(xa), 8.0))
     res = {"kernels": "float4 non-temporal streaming kernels, 4 KiB per wave and operand; rrw = x <- x - lr*g "
-                      "(2 reads : 1 write, the fused step's mix)", "elements": m}
+                      "(2 reads : 1 write, the fused step's mix); encode_Nbit_mix = read 4 B, write N/8 B per "
+                      "element (the encoders' mix)", "elements": m}
     for name, fn, bpe in kernels:
         for i in range(3):
             fn(i)
@@ -489,6 +493,15 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     run(f"dequantize_b{wbits}_f16", lambda i: qb.qsdp_dequantize(wc, wm, n, wbits, bucket, outh),
         2 + wbits / 8.0 + meta_b)
     del outh
+    # learned levels at 4 bits (table fitted on the first 2048 buckets): nearest-level and coin-flip encoders
+    lv = qb.levels_uniform(4, dev)
+    qb.qsdp_fit_levels(x, 4, bucket, 0.01, lv, 2048)
+    lc, lm = qb.alloc_packed(n, 4, bucket, dev)
+    lm = lm.reshape(-1)
+    run("quantize_levels_b4_fitted_table", lambda i: qb.qsdp_quantize_levels(x, 4, bucket, lv, lc, lm), 4.5 + meta_b)
+    run("quantize_levels_stochastic_b4_fitted_table",
+        lambda i: qb.qsdp_quantize_levels_stochastic(g, 4, bucket, lv, i, 0, lc, lm), 4.5 + meta_b)
+    del lc, lm
     # the fused step with x resident as codes (wc, wm hold Q^w(x) from the call above)
     run(f"fused_step_codes_W{wbits}G{gbits}",
         lambda i: qb.qsdp_fused_step_codes(wc, wm, g, 1e-3, wbits, gbits, bucket, 0.0, i),

@@ -25,6 +25,7 @@ def lib():
         L.qsdp_bench_fill.argtypes = [vp, u64, f32, vp]
         L.qsdp_bench_copy.argtypes = [vp, vp, u64, vp]
         L.qsdp_bench_axpy.argtypes = [vp, vp, u64, f32, vp]
+        L.qsdp_bench_encode.argtypes = [vp, u64, C.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -63,3 +64,11 @@ def axpy(x, g, lr):
     if x.numel() != g.numel():
         raise ValueError("size mismatch")
     _check(lib().qsdp_bench_axpy(x.data_ptr(), g.data_ptr(), x.numel(), float(lr), s), "qsdp_bench_axpy")
+
+
+def encode(a, bits, out):
+    """Read a, write bits/8 bytes per element into out (int32, at least a.numel() * bits / 32 words)."""
+    s = _args(a)
+    if not (out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.numel() * 32 >= a.numel() * bits):
+        raise ValueError("out: contiguous int32 GPU tensor of a.numel() * bits / 32 words")
+    _check(lib().qsdp_bench_encode(a.data_ptr(), a.numel(), int(bits), out.data_ptr(), s), "qsdp_bench_encode")

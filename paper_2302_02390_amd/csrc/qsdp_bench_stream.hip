@@ -7,6 +7,8 @@
 //   fill         one operand written                   (4 B per element)
 //   copy         one read, one written                 (8 B per element)
 //   axpy         x <- x - lr*g: two read, one written  (12 B per element, the fused step's mix)
+//   encode       one read, `bits`/8 B written per element with the encoders' store shape (the lanes
+//                that hold a 16-byte piece of the wave's code tile store it): the encoders' mix
 // All take device pointers (16-byte aligned), n a multiple of 1024, a hipStream_t as void*;
 // return 0, or -1 for a bad argument, -3 if the launch was refused. Built into libqsdp_bench.so.
 #include <hip/hip_runtime.h>
@@ -73,6 +75,23 @@ __global__ void __launch_bounds__(256) axpy_kernel(float* x, const float* __rest
     }
 }
 
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// pieces = 16-byte pieces of output per wave tile (32 for 4-bit codes, 64 for 8-bit codes)
+__global__ void __launch_bounds__(256) encode_kernel(const float* __restrict__ a, u4* out, uint64_t ntiles, int pieces) {
+    const uint64_t t = wave_tile();
+    if (t >= ntiles) return;
+    const int lane = threadIdx.x & 63;
+    const f4* p = reinterpret_cast<const f4*>(a + t * kTile) + lane;
+    u4 w;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const f4 v = __builtin_nontemporal_load(p + r * 64);
+        w[r] = __float_as_uint(v[0]) ^ __float_as_uint(v[1]) ^ __float_as_uint(v[2]) ^ __float_as_uint(v[3]);
+    }
+    if (lane < pieces) __builtin_nontemporal_store(w, out + t * (uint64_t)pieces + lane);
+}
+
 bool ok(const void* p, uint64_t n) {
     return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && n >= (uint64_t)kTile && n % kTile == 0 &&
            n / kTile / 4 + 1 < (1ull << 31);
@@ -105,6 +124,13 @@ int qsdp_bench_copy(const float* a, float* b, uint64_t n, void* stream) {
 int qsdp_bench_axpy(float* x, const float* g, uint64_t n, float lr, void* stream) {
     if (!ok(x, n) || !ok(g, n)) return -1;
     hipLaunchKernelGGL(axpy_kernel, dim3(grid_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream), x, g, n / kTile, lr);
+    return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+int qsdp_bench_encode(const float* a, uint64_t n, int bits, uint32_t* out, void* stream) {
+    if (!ok(a, n) || out == nullptr || (reinterpret_cast<uintptr_t>(out) & 15u) != 0 || (bits != 4 && bits != 8)) return -1;
+    hipLaunchKernelGGL(encode_kernel, dim3(grid_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream), a,
+                       reinterpret_cast<u4*>(out), n / kTile, bits * 8);
     return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
