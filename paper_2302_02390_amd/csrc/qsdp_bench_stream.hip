@@ -89,6 +89,12 @@ __global__ void __launch_bounds__(256) encode_kernel(const float* __restrict__ a
         const f4 v = __builtin_nontemporal_load(p + r * 64);
         w[r] = __float_as_uint(v[0]) ^ __float_as_uint(v[1]) ^ __float_as_uint(v[2]) ^ __float_as_uint(v[3]);
     }
+    // every lane's loads feed a stored piece: with fewer pieces than lanes the upper lanes' words are
+    // folded into the lower lanes' (otherwise their loads would be dead code)
+    if (pieces < 64) {
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) w[r] ^= (uint32_t)__shfl_xor((int)w[r], 32, 64);
+    }
     if (lane < pieces) __builtin_nontemporal_store(w, out + t * (uint64_t)pieces + lane);
 }
 
