@@ -15,11 +15,25 @@ static_assert(QSDP_B == 4 * QSDP_G * QSDP_R * QSDP_W, "bucket = 4 * G * R * W");
 namespace qsdp {
 namespace {
 
+// Dynamic LDS that a launch asks for and never touches: it only caps how many workgroups are resident on
+// a compute unit (160 KB of LDS each). The streaming step kernels run faster with fewer waves in flight
+// than their registers would allow (1.3B vector, same box, medians of 30: fused step 2.605-2.610 ms with
+// 7 workgroups per compute unit, 2.546-2.569 with 5, 2.527-2.543 with 3; with code output 5 is best; AdamW
+// step 6.45 ms with 3, 6.22-6.34 with 2); the encoders and the code-resident step, whose arithmetic has to
+// overlap the memory latency, want all the waves they can get. Only for the one-wave-per-bucket shapes.
+constexpr unsigned resident_cap_lds(int mode, int bits) {
+    if (QSDP_W != 1) return 0u;
+    if (mode == MODE_FUSED) return bits == 0 ? 50000u : 27000u;
+    if (mode == MODE_ADAMW) return 60000u;
+    return 0u;
+}
+
 template <int MODE, int BITS>
 hipError_t go(const Params& p, unsigned grid, hipStream_t s) {
     // W == 1: 4 waves per workgroup, each on its own buckets; W > 1: W waves share a bucket
     const unsigned block = QSDP_W == 1 ? 256u : 64u * QSDP_W;
-    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W>), dim3(grid), dim3(block), 0, s, p, p.segs);
+    hipLaunchKernelGGL((wave_kernel<MODE, QSDP_G, QSDP_R, BITS, QSDP_W>), dim3(grid), dim3(block),
+                       resident_cap_lds(MODE, BITS), s, p, p.segs);
     return hipGetLastError();
 }
 

@@ -5,8 +5,19 @@
 
 #include "qsdp_params.hpp"
 
+// Workgroups (of 4 waves) per compute unit the compiler has to leave room for, i.e. waves per SIMD: caps the
+// registers of a kernel. 1 = no constraint.
 #ifndef QSDP_LEVELS_MIN_BLOCKS
 #define QSDP_LEVELS_MIN_BLOCKS 4
+#endif
+#ifndef QSDP_ADAMW_MIN_BLOCKS
+#define QSDP_ADAMW_MIN_BLOCKS 1
+#endif
+#ifndef QSDP_RECV_MIN_BLOCKS
+#define QSDP_RECV_MIN_BLOCKS 5
+#endif
+#ifndef QSDP_FUSED_MIN_BLOCKS
+#define QSDP_FUSED_MIN_BLOCKS 1
 #endif
 
 namespace qsdp {
@@ -16,6 +27,18 @@ namespace qsdp {
 // ---------------------------------------------------------------------------------------
 // Lane l's rows of a tile of 4*G*R elements at `base`. `m` = how many of the tile's elements
 // exist; `partial` (wave-uniform) selects the guarded element-wise path for a short bucket.
+// Whether element i of row r of lane l, i.e. slot (r*G + l)*4 + i of the tile, lies below m. Written as a
+// comparison of the lane's own offset with a per-slot bound so that the short-bucket paths need no
+// per-slot index registers (those would be set up by every wave, short bucket or not).
+template <int G>
+__device__ __forceinline__ bool slot_exists(int l, int m, int r, int i) {
+    int bound = m - (r * G * 4 + i);
+    // keeps the compiler from folding this back into (r*G + l)*4 + i < m and hoisting the 4*R slot
+    // indices out of the bucket loop into every wave's prologue
+    asm volatile("" : "+v"(bound));
+    return l * 4 < bound;
+}
+
 template <int G, int R>
 __device__ __forceinline__ void load_rows(const float* base, int l, int m, bool partial, float (&v)[R][4]) {
     if (__builtin_expect(!partial, 1)) {
@@ -31,7 +54,7 @@ __device__ __forceinline__ void load_rows(const float* base, int l, int m, bool 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int idx = (r * G + l) * 4 + i;
-                v[r][i] = idx < m ? base[idx] : 0.0f;
+                v[r][i] = slot_exists<G>(l, m, r, i) ? base[idx] : 0.0f;
             }
     }
 }
@@ -63,7 +86,7 @@ __device__ __forceinline__ void load_rows_half(const uint16_t* base, int l, int 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int idx = (r * G + l) * 4 + i;
-                v[r][i] = idx < m ? widen16<BF16>(base[idx]) : 0.0f;
+                v[r][i] = slot_exists<G>(l, m, r, i) ? widen16<BF16>(base[idx]) : 0.0f;
             }
     }
 }
@@ -83,7 +106,7 @@ __device__ __forceinline__ void store_rows(float* base, int l, int m, bool parti
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int idx = (r * G + l) * 4 + i;
-                if (idx < m) base[idx] = v[r][i];
+                if (slot_exists<G>(l, m, r, i)) base[idx] = v[r][i];
             }
     }
 }
@@ -106,7 +129,7 @@ __device__ __forceinline__ void store_rows_half(uint16_t* base, int l, int m, bo
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int idx = (r * G + l) * 4 + i;
-                if (idx < m) base[idx] = (uint16_t)half_bits(v[r][i], f16);
+                if (slot_exists<G>(l, m, r, i)) base[idx] = (uint16_t)half_bits(v[r][i], f16);
             }
     }
 }
@@ -132,7 +155,7 @@ __device__ __forceinline__ void rows_minmax(const float (&v)[R][4], int l, int m
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const bool valid = (r * G + l) * 4 + i < m;
+                const bool valid = slot_exists<G>(l, m, r, i);
                 lo = valid ? fminf(lo, v[r][i]) : lo;
                 hi = valid ? fmaxf(hi, v[r][i]) : hi;
             }
@@ -148,7 +171,7 @@ __device__ __forceinline__ void zero_slots_past_end(CodeT (&c)[R][4], int l, int
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if ((r * G + l) * 4 + i >= m) c[r][i] = CodeT(0);
+            if (!slot_exists<G>(l, m, r, i)) c[r][i] = CodeT(0);
 }
 
 // Pack the codes of all rows and stage them in LDS in wire order, then write the wave's code
@@ -386,8 +409,15 @@ __device__ __forceinline__ void encode_levels(const float (&v)[R][4], uint32_t (
 // MODE_SUM). W = waves per bucket (W > 1: the workgroup has exactly W waves and owns one bucket
 // per iteration). delta > 0 selects the explicit grid, p.flags the quantizer variants (both
 // wave-uniform branches).
+constexpr int mode_min_blocks(int mode) {
+    return mode_is_levels(mode) ? QSDP_LEVELS_MIN_BLOCKS
+           : mode == MODE_RECV_ADAMW ? QSDP_ADAMW_MIN_BLOCKS
+           : mode == MODE_RECV ? QSDP_RECV_MIN_BLOCKS
+           : mode == MODE_FUSED ? QSDP_FUSED_MIN_BLOCKS : 1;
+}
+
 template <int MODE, int G, int R, int BITS, int W>
-__global__ void __launch_bounds__(256, mode_is_levels(MODE) ? QSDP_LEVELS_MIN_BLOCKS : 1) wave_kernel(const Params p, const Segment* __restrict__ segs) {
+__global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const Params p, const Segment* __restrict__ segs) {
     static_assert(R % 2 == 0 && G >= 2 && G <= 64, "shape");
     static_assert(W == 1 || (G == 64 && W <= 4), "shared buckets use whole waves");
     constexpr int T = 4 * G * R;  // elements of a bucket one wave holds
@@ -692,7 +722,7 @@ __global__ void __launch_bounds__(256, mode_is_levels(MODE) ? QSDP_LEVELS_MIN_BL
                     for (int i = 0; i < 4; ++i) {
                         uint32_t sat_one = 0;
                         const float c = weight_code_lattice(w[r][i], div, xi, k0, Lw, sat_one);
-                        const bool valid = (r * G + l) * 4 + i < m;
+                        const bool valid = slot_exists<G>(l, m, r, i);
                         w[r][i] = valid ? c : 0.0f;
                         sat_here += valid ? sat_one : 0u;
                     }
