@@ -290,11 +290,14 @@ def attainable(torch, x, g, n, fused_achieved, lr):
     codes = torch.empty(m // 4, dtype=torch.int32, device=x.device)
     kernels = (("read_only", lambda i: bs.read(xa, sink), 4.0), ("write_only", lambda i: bs.fill(y, 0.5), 4.0),
                ("copy", lambda i: bs.copy(xa, y), 8.0), ("rrw", lambda i: bs.axpy(xa, ga, lr), 12.0),
+               ("rrw_5_workgroups_per_cu", lambda i: bs.axpy(xa, ga, lr, 27000), 12.0),
+               ("rrw_3_workgroups_per_cu", lambda i: bs.axpy(xa, ga, lr, 50000), 12.0),
                ("encode_4bit_mix", lambda i: bs.encode(xa, 4, codes), 4.5),
                ("encode_8bit_mix", lambda i: bs.encode(xa, 8, codes), 5.0),
                ("runtime_device_copy", lambda i: y.copy_(xa), 8.0))
     res = {"kernels": "float4 non-temporal streaming kernels, 4 KiB per wave and operand; rrw = x <- x - lr*g "
-                      "(2 reads : 1 write, the fused step's mix); encode_Nbit_mix = read 4 B, write N/8 B per "
+                      "(2 reads : 1 write, the fused step's mix; also launched with the workgroups per compute unit "
+                      "capped the way the fused step is, the best of the three is the ceiling); encode_Nbit_mix = read 4 B, write N/8 B per "
                       "element (the encoders' mix)", "elements": m}
     for name, fn, bpe in kernels:
         for i in range(3):
@@ -302,7 +305,8 @@ def attainable(torch, x, g, n, fused_achieved, lr):
         mean, _ = time_call(fn, 10, torch)
         res[f"{name}_GB/s"] = round(bpe * m / (mean * 1e-3) / 1e9, 1)
         res[f"{name}_ms"] = round(mean, 4)
-    res["fused_step_vs_rrw"] = round(fused_achieved / res["rrw_GB/s"], 3)
+    res["rrw_best_GB/s"] = max(res["rrw_GB/s"], res["rrw_5_workgroups_per_cu_GB/s"], res["rrw_3_workgroups_per_cu_GB/s"])
+    res["fused_step_vs_rrw"] = round(fused_achieved / res["rrw_best_GB/s"], 3)
     res["fused_step_vs_read_only"] = round(fused_achieved / res["read_only_GB/s"], 3)
     res["fused_step_vs_runtime_device_copy"] = round(fused_achieved / res["runtime_device_copy_GB/s"], 3)
     return res

@@ -24,7 +24,7 @@ def lib():
         L.qsdp_bench_read.argtypes = [vp, u64, vp, vp]
         L.qsdp_bench_fill.argtypes = [vp, u64, f32, vp]
         L.qsdp_bench_copy.argtypes = [vp, vp, u64, vp]
-        L.qsdp_bench_axpy.argtypes = [vp, vp, u64, f32, vp]
+        L.qsdp_bench_axpy.argtypes = [vp, vp, u64, f32, C.c_uint, vp]
         L.qsdp_bench_encode.argtypes = [vp, u64, C.c_int, vp, vp]
         _lib = L
     return _lib
@@ -59,11 +59,13 @@ def copy(a, b):
     _check(lib().qsdp_bench_copy(a.data_ptr(), b.data_ptr(), a.numel(), s), "qsdp_bench_copy")
 
 
-def axpy(x, g, lr):
+def axpy(x, g, lr, resident_cap_lds=0):
+    """x <- x - lr*g; resident_cap_lds: unused dynamic LDS per workgroup (caps the workgroups per compute unit)."""
     s = _args(x, g)
     if x.numel() != g.numel():
         raise ValueError("size mismatch")
-    _check(lib().qsdp_bench_axpy(x.data_ptr(), g.data_ptr(), x.numel(), float(lr), s), "qsdp_bench_axpy")
+    _check(lib().qsdp_bench_axpy(x.data_ptr(), g.data_ptr(), x.numel(), float(lr), int(resident_cap_lds), s),
+           "qsdp_bench_axpy")
 
 
 def encode(a, bits, out):

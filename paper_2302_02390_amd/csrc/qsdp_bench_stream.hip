@@ -127,9 +127,12 @@ int qsdp_bench_copy(const float* a, float* b, uint64_t n, void* stream) {
     return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
-int qsdp_bench_axpy(float* x, const float* g, uint64_t n, float lr, void* stream) {
-    if (!ok(x, n) || !ok(g, n)) return -1;
-    hipLaunchKernelGGL(axpy_kernel, dim3(grid_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream), x, g, n / kTile, lr);
+// resident_cap_lds: bytes of dynamic LDS requested and never touched, which caps the workgroups resident per
+// compute unit (the codec's step kernels are launched that way; 0 = no cap)
+int qsdp_bench_axpy(float* x, const float* g, uint64_t n, float lr, unsigned resident_cap_lds, void* stream) {
+    if (!ok(x, n) || !ok(g, n) || resident_cap_lds > 65536u) return -1;
+    hipLaunchKernelGGL(axpy_kernel, dim3(grid_for(n)), dim3(256), resident_cap_lds, static_cast<hipStream_t>(stream), x, g,
+                       n / kTile, lr);
     return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
