@@ -510,7 +510,17 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
-    for (uint64_t q = unit0; q < nunits; q += unit_stride, parity ^= 1u) {
+    // Which units this wave (workgroup) works on: unit0, unit0 + stride, ... for the one-pass modes (a launch
+    // normally has a wave per unit); a contiguous run of units for the learned-level modes, whose resident
+    // waves keep per-tensor tables that should change as rarely as possible.
+    uint64_t q_begin = unit0, q_end = nunits, q_step = unit_stride;
+    if constexpr (mode_is_levels(MODE)) {
+        const uint64_t run = (nunits + unit_stride - 1) / unit_stride;
+        q_begin = unit0 * run;
+        q_end = q_begin + run < nunits ? q_begin + run : nunits;
+        q_step = 1;
+    }
+    for (uint64_t q = q_begin; q < q_end; q += q_step, parity ^= 1u) {
         const uint64_t rel = q * BPW + sub;          // bucket within this launch
         const bool active = rel < p.num_buckets;
         const uint64_t left = p.num_buckets - q * BPW;
