@@ -374,11 +374,12 @@ __device__ __forceinline__ void sum_peer_slices(const Params& p, uint8_t* stage,
 // The learned-level encoders over a lane's rows: v -> codes (MODE_LEVELS: nearest level; MODE_LEVELS_COIN:
 // coin flip between the enclosing levels). MASKED: only the lanes with `mine` keep their codes (a pass
 // over the lanes of one tensor of a multi-tensor call).
-template <int MODE, int G, int R, int BITS, bool MASKED>
-__device__ __forceinline__ void encode_levels(const float (&v)[R][4], uint32_t (&code)[R][4], bool mine, float lo,
-                                              float inv_cells, const float* lv, const LevelCell* cells,
-                                              const LevelNear* near, const LevelCoin* coin, const LevelPivots& pivots,
-                                              bool by_cell, uint64_t block_e0, int l, PhiloxKey key) {
+template <int MODE, int G, int R, int BITS, bool MASKED, bool BY_CELL>
+__device__ __forceinline__ void encode_levels_by(const float (&v)[R][4], uint32_t (&code)[R][4], bool mine, float lo,
+                                                 float inv_cells, const float* lv, const LevelCell* cells,
+                                                 const LevelNear* near, const LevelCoin* coin,
+                                                 const LevelPivots& pivots, uint64_t block_e0, int l, PhiloxKey key) {
+    constexpr bool by_cell = BY_CELL;
     if constexpr (MODE == MODE_LEVELS_COIN) {
 #pragma unroll
         for (int cp = 0; cp < R / 2; ++cp) {
@@ -402,6 +403,21 @@ __device__ __forceinline__ void encode_levels(const float (&v)[R][4], uint32_t (
                 code[r][i] = (!MASKED || mine) ? c : code[r][i];
             }
     }
+}
+
+// by_cell (wave-uniform) picks the counting method once for all of the lane's elements, so that each
+// method is straight-line code over the rows and the LDS reads of different elements overlap.
+template <int MODE, int G, int R, int BITS, bool MASKED>
+__device__ __forceinline__ void encode_levels(const float (&v)[R][4], uint32_t (&code)[R][4], bool mine, float lo,
+                                              float inv_cells, const float* lv, const LevelCell* cells,
+                                              const LevelNear* near, const LevelCoin* coin, const LevelPivots& pivots,
+                                              bool by_cell, uint64_t block_e0, int l, PhiloxKey key) {
+    if (by_cell)
+        encode_levels_by<MODE, G, R, BITS, MASKED, true>(v, code, mine, lo, inv_cells, lv, cells, near, coin, pivots,
+                                                         block_e0, l, key);
+    else
+        encode_levels_by<MODE, G, R, BITS, MASKED, false>(v, code, mine, lo, inv_cells, lv, cells, near, coin, pivots,
+                                                          block_e0, l, key);
 }
 
 // Every mode over the buckets first_bucket .. +num_buckets-1 (the last bucket of a tensor may
@@ -443,6 +459,37 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
+    // Which units this wave (workgroup) works on: unit0, unit0 + stride, ... for the one-pass modes (a launch
+    // normally has a wave per unit); a contiguous run of units for the learned-level modes, whose resident
+    // waves keep per-tensor tables that should change as rarely as possible.
+    uint64_t q_begin = unit0, q_end = nunits, q_step = unit_stride;
+    if constexpr (mode_is_levels(MODE)) {
+        const uint64_t run = (nunits + unit_stride - 1) / unit_stride;
+        q_begin = unit0 * run;
+        q_end = q_begin + run < nunits ? q_begin + run : nunits;
+        q_step = 1;
+    }
+    // The learned-level modes keep the values of the wave's next unit in flight while the current one is
+    // encoded, and those of its first unit while the level tables are set up (the tables' own loads, the
+    // barriers and the searches that fill them would otherwise all come before the first load of data).
+    // ahead: where unit q's tile of the input lies.
+    struct TileAhead { uint64_t e0; int m; bool partial; };
+    auto ahead = [&](uint64_t q) -> TileAhead {
+        const uint64_t rel = q * BPW + sub;
+        const uint64_t bucket0 = p.first_bucket + q * BPW;
+        const uint64_t bucket = rel < p.num_buckets ? p.first_bucket + rel : bucket0;
+        const BucketRef ref = locate_bucket(p, segs, bucket0, bucket, B);
+        const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
+        const int m = ref.m > part0 ? (int)(ref.m - part0 < (uint32_t)T ? ref.m - part0 : (uint32_t)T) : 0;
+        return {ref.e0 + part0, m, __builtin_amdgcn_ballot_w64(m < T) != 0};
+    };
+    float next_w[mode_is_levels(MODE) ? R : 1][4];
+    if constexpr (mode_is_levels(MODE)) {
+        if (q_begin < q_end) {
+            const TileAhead t = ahead(q_begin);
+            load_rows<G, R>(p.xin + t.e0, l, t.m, t.partial, next_w);
+        }
+    }
     // Learned levels (see the section of that name in qsdp_device.hpp): the level table in LDS, scaled
     // to cell units, the cell table and the landing table of the mode's encoder, and the binary
     // search's first pivots in scalar registers. One table for the whole call is set up once per
@@ -510,16 +557,6 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     const float xi = shifts.xi;
     uint32_t saturated = 0;
 
-    // Which units this wave (workgroup) works on: unit0, unit0 + stride, ... for the one-pass modes (a launch
-    // normally has a wave per unit); a contiguous run of units for the learned-level modes, whose resident
-    // waves keep per-tensor tables that should change as rarely as possible.
-    uint64_t q_begin = unit0, q_end = nunits, q_step = unit_stride;
-    if constexpr (mode_is_levels(MODE)) {
-        const uint64_t run = (nunits + unit_stride - 1) / unit_stride;
-        q_begin = unit0 * run;
-        q_end = q_begin + run < nunits ? q_begin + run : nunits;
-        q_step = 1;
-    }
     for (uint64_t q = q_begin; q < q_end; q += q_step, parity ^= 1u) {
         const uint64_t rel = q * BPW + sub;          // bucket within this launch
         const bool active = rel < p.num_buckets;
@@ -656,7 +693,18 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
                 }
             }
         } else {
-            load_rows<G, R>(p.xin + e0, l, m, partial, w);
+            if constexpr (mode_is_levels(MODE)) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[r][i] = next_w[r][i];
+                if (q + q_step < q_end) {
+                    const TileAhead t = ahead(q + q_step);
+                    load_rows<G, R>(p.xin + t.e0, l, t.m, t.partial, next_w);
+                }
+            } else {
+                load_rows<G, R>(p.xin + e0, l, m, partial, w);
+            }
         }
 
         // the full-precision partition keeps the updated value itself (stored before w turns into codes)
