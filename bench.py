@@ -267,6 +267,13 @@ def main():
     if not a.no_extras:
         out["attainable"] = attainable(torch, x, g, n, achieved, lr)
         out["other_entry_points"] = extras(torch, qb, x, g, n, wbits, gbits, bucket, dev)
+        att, oth = out["attainable"], out["other_entry_points"]
+        att["adamw_mix_best_GB/s"] = max(att["adamw_mix_GB/s"], att["adamw_mix_2_workgroups_per_cu_GB/s"])
+        att["fused_adamw_step_vs_adamw_mix"] = round(oth[f"fused_adamw_step_W{wbits}G{gbits}"]["GB/s"] /
+                                                     att["adamw_mix_best_GB/s"], 3)
+        att[f"quantize_grad_b{gbits}_vs_encode_mix"] = round(
+            oth[f"quantize_grad_b{gbits}"]["GB/s"] / att[f"encode_{gbits}bit_mix_GB/s"], 3) \
+            if f"encode_{gbits}bit_mix_GB/s" in att else None
         if a.segmented:
             out["segmented_entry_points"] = segmented_extras(torch, qb, x, n, segs, wbits, bucket, dev)
 
@@ -288,17 +295,21 @@ def attainable(torch, x, g, n, fused_achieved, lr):
     y = torch.empty_like(xa)
     sink = torch.zeros(4, dtype=torch.float32, device=x.device)
     codes = torch.empty(m // 4, dtype=torch.int32, device=x.device)
+    mo, vo = torch.zeros_like(xa), torch.zeros_like(xa)
     kernels = (("read_only", lambda i: bs.read(xa, sink), 4.0), ("write_only", lambda i: bs.fill(y, 0.5), 4.0),
                ("copy", lambda i: bs.copy(xa, y), 8.0), ("rrw", lambda i: bs.axpy(xa, ga, lr), 12.0),
                ("rrw_5_workgroups_per_cu", lambda i: bs.axpy(xa, ga, lr, 27000), 12.0),
                ("rrw_3_workgroups_per_cu", lambda i: bs.axpy(xa, ga, lr, 50000), 12.0),
                ("encode_4bit_mix", lambda i: bs.encode(xa, 4, codes), 4.5),
                ("encode_8bit_mix", lambda i: bs.encode(xa, 8, codes), 5.0),
+               ("adamw_mix", lambda i: bs.moments(xa, ga, mo, vo, lr, 0.5), 28.0),
+               ("adamw_mix_2_workgroups_per_cu", lambda i: bs.moments(xa, ga, mo, vo, lr, 0.5, 60000), 28.0),
                ("runtime_device_copy", lambda i: y.copy_(xa), 8.0))
     res = {"kernels": "float4 non-temporal streaming kernels, 4 KiB per wave and operand; rrw = x <- x - lr*g "
                       "(2 reads : 1 write, the fused step's mix; also launched with the workgroups per compute unit "
                       "capped the way the fused step is, the best of the three is the ceiling); encode_Nbit_mix = read 4 B, write N/8 B per "
-                      "element (the encoders' mix)", "elements": m}
+                      "element (the encoders' mix); adamw_mix = 4 operands read, 3 written (the AdamW step's 28 B per element, also "
+                      "with that step's residency cap)", "elements": m}
     for name, fn, bpe in kernels:
         for i in range(3):
             fn(i)

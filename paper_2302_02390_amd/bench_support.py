@@ -1,4 +1,4 @@
-"""Binding of ``libqsdp_bench.so``: plain streaming kernels (read, fill, copy, axpy) with the fused
+"""Binding of ``libqsdp_bench.so``: plain streaming kernels (read, fill, copy, axpy, moments, encode) with the fused
 step's access pattern, which ``bench.py`` times beside the codec as the memory system's attainable
 ceilings. Benchmark support only: not part of the codec's C ABI and used by no codec entry point.
 """
@@ -26,6 +26,7 @@ def lib():
         L.qsdp_bench_copy.argtypes = [vp, vp, u64, vp]
         L.qsdp_bench_axpy.argtypes = [vp, vp, u64, f32, C.c_uint, vp]
         L.qsdp_bench_encode.argtypes = [vp, u64, C.c_int, vp, vp]
+        L.qsdp_bench_moments.argtypes = [vp, vp, vp, vp, u64, f32, f32, C.c_uint, vp]
         _lib = L
     return _lib
 
@@ -66,6 +67,15 @@ def axpy(x, g, lr, resident_cap_lds=0):
         raise ValueError("size mismatch")
     _check(lib().qsdp_bench_axpy(x.data_ptr(), g.data_ptr(), x.numel(), float(lr), int(resident_cap_lds), s),
            "qsdp_bench_axpy")
+
+
+def moments(x, g, m, v, lr, b, resident_cap_lds=0):
+    """m <- b*m + g, v <- b*v + g*g, x <- x - lr*m (four operands read, three written: the AdamW step's mix)."""
+    s = _args(x, g, m, v)
+    if not (x.numel() == g.numel() == m.numel() == v.numel()):
+        raise ValueError("size mismatch")
+    _check(lib().qsdp_bench_moments(x.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr(), x.numel(), float(lr),
+                                    float(b), int(resident_cap_lds), s), "qsdp_bench_moments")
 
 
 def encode(a, bits, out):

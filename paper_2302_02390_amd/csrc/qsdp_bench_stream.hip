@@ -7,6 +7,8 @@
 //   fill         one operand written                   (4 B per element)
 //   copy         one read, one written                 (8 B per element)
 //   axpy         x <- x - lr*g: two read, one written  (12 B per element, the fused step's mix)
+//   moments      m <- b*m + g, v <- b*v + g*g, x <- x - lr*m: four read, three written (28 B per
+//                element, the AdamW step's mix; three fused multiply-adds per element, no division)
 //   encode       one read, `bits`/8 B written per element with the encoders' store shape (the lanes
 //                that hold a 16-byte piece of the wave's code tile store it): the encoders' mix
 // All take device pointers (16-byte aligned), n a multiple of 1024, a hipStream_t as void*;
@@ -75,6 +77,39 @@ __global__ void __launch_bounds__(256) axpy_kernel(float* x, const float* __rest
     }
 }
 
+__global__ void __launch_bounds__(256) moments_kernel(float* x, const float* __restrict__ g, float* m, float* v,
+                                                      uint64_t ntiles, float lr, float b) {
+    const uint64_t t = wave_tile();
+    if (t >= ntiles) return;
+    const uint64_t at = t * kTile;
+    const int lane = threadIdx.x & 63;
+    f4* px = reinterpret_cast<f4*>(x + at) + lane;
+    f4* pm = reinterpret_cast<f4*>(m + at) + lane;
+    f4* pv = reinterpret_cast<f4*>(v + at) + lane;
+    const f4* pg = reinterpret_cast<const f4*>(g + at) + lane;
+    f4 gv[kRows], xv[kRows], mv[kRows], vv[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) gv[r] = __builtin_nontemporal_load(pg + r * 64);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) xv[r] = __builtin_nontemporal_load(px + r * 64);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) mv[r] = __builtin_nontemporal_load(pm + r * 64);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) vv[r] = __builtin_nontemporal_load(pv + r * 64);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            mv[r][i] = fmaf(b, mv[r][i], gv[r][i]);
+            vv[r][i] = fmaf(b, vv[r][i], gv[r][i] * gv[r][i]);
+            xv[r][i] = fmaf(-lr, mv[r][i], xv[r][i]);
+        }
+        __builtin_nontemporal_store(mv[r], pm + r * 64);
+        __builtin_nontemporal_store(vv[r], pv + r * 64);
+        __builtin_nontemporal_store(xv[r], px + r * 64);
+    }
+}
+
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 // pieces = 16-byte pieces of output per wave tile (32 for 4-bit codes, 64 for 8-bit codes)
@@ -133,6 +168,14 @@ int qsdp_bench_axpy(float* x, const float* g, uint64_t n, float lr, unsigned res
     if (!ok(x, n) || !ok(g, n) || resident_cap_lds > 65536u) return -1;
     hipLaunchKernelGGL(axpy_kernel, dim3(grid_for(n)), dim3(256), resident_cap_lds, static_cast<hipStream_t>(stream), x, g,
                        n / kTile, lr);
+    return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+int qsdp_bench_moments(float* x, const float* g, float* m, float* v, uint64_t n, float lr, float b,
+                       unsigned resident_cap_lds, void* stream) {
+    if (!ok(x, n) || !ok(g, n) || !ok(m, n) || !ok(v, n) || resident_cap_lds > 65536u) return -1;
+    hipLaunchKernelGGL(moments_kernel, dim3(grid_for(n)), dim3(256), resident_cap_lds, static_cast<hipStream_t>(stream),
+                       x, g, m, v, n / kTile, lr, b);
     return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
