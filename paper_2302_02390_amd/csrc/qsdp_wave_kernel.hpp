@@ -459,11 +459,12 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     uint8_t* stage = reinterpret_cast<uint8_t*>(stage_all) + (kStaged ? wave_in_block * kTileBytes : 0);
     __shared__ float red_all[W > 1 ? 2 * 2 * 2 * W : 1];  // [parity][g or w][lo/hi][wave]
     uint32_t parity = 0;
-    // Which units this wave (workgroup) works on: unit0, unit0 + stride, ... for the one-pass modes (a launch
-    // normally has a wave per unit); a contiguous run of units for the learned-level modes, whose resident
-    // waves keep per-tensor tables that should change as rarely as possible.
+    // Which units this wave (workgroup) works on: unit0, unit0 + stride, ... (the one-pass modes normally have
+    // a wave per unit; the learned-level modes a resident grid, whose waves then sweep the buffer side by
+    // side); a contiguous run of units where every tensor has its own level tables, which a wave should
+    // have to set up as rarely as possible.
     uint64_t q_begin = unit0, q_end = nunits, q_step = unit_stride;
-    if constexpr (mode_is_levels(MODE)) {
+    if (mode_is_levels(MODE) && p.levels_per_tensor != 0 && segs != nullptr) {
         const uint64_t run = (nunits + unit_stride - 1) / unit_stride;
         q_begin = unit0 * run;
         q_end = q_begin + run < nunits ? q_begin + run : nunits;
