@@ -473,21 +473,35 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     // The learned-level modes keep the values of the wave's next unit in flight while the current one is
     // encoded, and those of its first unit while the level tables are set up (the tables' own loads, the
     // barriers and the searches that fill them would otherwise all come before the first load of data).
-    // ahead: where unit q's tile of the input lies.
-    struct TileAhead { uint64_t e0; int m; bool partial; };
-    auto ahead = [&](uint64_t q) -> TileAhead {
-        const uint64_t rel = q * BPW + sub;
-        const uint64_t bucket0 = p.first_bucket + q * BPW;
-        const uint64_t bucket = rel < p.num_buckets ? p.first_bucket + rel : bucket0;
-        const BucketRef ref = locate_bucket(p, segs, bucket0, bucket, B);
-        const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
-        const int m = ref.m > part0 ? (int)(ref.m - part0 < (uint32_t)T ? ref.m - part0 : (uint32_t)T) : 0;
-        return {ref.e0 + part0, m, __builtin_amdgcn_ballot_w64(m < T) != 0};
+    // unit_tile: where unit q's tile of the data lies.
+    struct UnitTile {
+        bool active;         // the lane's bucket exists
+        uint64_t bucket;     // the lane's bucket (the unit's first one for a lane without a bucket)
+        uint32_t tensor;     // the tensor the bucket belongs to (multi-tensor calls)
+        uint32_t part0;      // first element of this wave's part of the bucket (W > 1)
+        uint64_t e0;         // first element of the wave's tile
+        int m;               // elements of the tile that exist
+        bool partial;        // wave-uniform: some lane's tile is short
+    };
+    auto unit_tile = [&](uint64_t q) -> UnitTile {
+        UnitTile t;
+        const uint64_t rel = q * BPW + sub;  // bucket within this launch
+        t.active = rel < p.num_buckets;
+        const uint64_t bucket0 = p.first_bucket + q * BPW;  // wave-uniform
+        t.bucket = t.active ? p.first_bucket + rel : bucket0;
+        const BucketRef ref = locate_bucket(p, segs, bucket0, t.bucket, B);
+        t.tensor = ref.tensor;
+        // this wave's tile of the bucket: all of it, or the wave's 1/W
+        t.part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
+        t.e0 = ref.e0 + t.part0;
+        t.m = ref.m > t.part0 ? (int)(ref.m - t.part0 < (uint32_t)T ? ref.m - t.part0 : (uint32_t)T) : 0;
+        t.partial = __builtin_amdgcn_ballot_w64(t.m < T) != 0;
+        return t;
     };
     float next_w[mode_is_levels(MODE) ? R : 1][4];
     if constexpr (mode_is_levels(MODE)) {
         if (q_begin < q_end) {
-            const TileAhead t = ahead(q_begin);
+            const UnitTile t = unit_tile(q_begin);
             load_rows<G, R>(p.xin + t.e0, l, t.m, t.partial, next_w);
         }
     }
@@ -559,18 +573,15 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
     uint32_t saturated = 0;
 
     for (uint64_t q = q_begin; q < q_end; q += q_step, parity ^= 1u) {
-        const uint64_t rel = q * BPW + sub;          // bucket within this launch
-        const bool active = rel < p.num_buckets;
+        const UnitTile tile = unit_tile(q);
+        const bool active = tile.active;
         const uint64_t left = p.num_buckets - q * BPW;
         const int active_buckets = left < (uint64_t)BPW ? (int)left : BPW;
-        const uint64_t bucket0 = p.first_bucket + q * BPW;  // wave-uniform
-        const uint64_t bucket = active ? p.first_bucket + rel : bucket0;
-        const BucketRef ref = locate_bucket(p, segs, bucket0, bucket, B);
-        // this wave's tile of the bucket: all of it, or the wave's 1/W
-        const uint32_t part0 = W > 1 ? wave_in_block * (uint32_t)T : 0u;
-        const uint64_t e0 = ref.e0 + part0;
-        const int m = ref.m > part0 ? (int)(ref.m - part0 < (uint32_t)T ? ref.m - part0 : (uint32_t)T) : 0;
-        const bool partial = __builtin_amdgcn_ballot_w64(m < T) != 0;
+        const uint64_t bucket = tile.bucket;
+        const uint32_t part0 = tile.part0;
+        const uint64_t e0 = tile.e0;
+        const int m = tile.m;
+        const bool partial = tile.partial;
         // Philox block of the tile's first element; the tile's place in the code buffer (the
         // code stream is indexed by bucket number, every bucket padded to B slots)
         const uint64_t block_e0 = p.block0 + (e0 >> 3);
@@ -700,7 +711,7 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
 #pragma unroll
                     for (int i = 0; i < 4; ++i) w[r][i] = next_w[r][i];
                 if (q + q_step < q_end) {
-                    const TileAhead t = ahead(q + q_step);
+                    const UnitTile t = unit_tile(q + q_step);
                     load_rows<G, R>(p.xin + t.e0, l, t.m, t.partial, next_w);
                 }
             } else {
@@ -730,8 +741,8 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
                 // exchanged between lanes).
                 uint64_t pending = ~0ull;
                 do {
-                    const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)ref.tensor, __builtin_ctzll(pending));
-                    const bool mine = ref.tensor == cur;
+                    const uint32_t cur = (uint32_t)__builtin_amdgcn_readlane((int)tile.tensor, __builtin_ctzll(pending));
+                    const bool mine = tile.tensor == cur;
                     if (cur != loaded_tensor) {
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // earlier reads of the slots are done
                         __builtin_amdgcn_wave_barrier();
