@@ -341,7 +341,10 @@ def levels_report(torch, qb, x, g, n, workload, bucket, dev):
             fit_ms, _ = time_call(lambda i: qb.qsdp_fit_levels(v, bits, bucket, 0.01, fitted, fit_buckets), 1, torch)
             row = {"tensor": name, "bits": bits, "fit_ms": round(fit_ms, 3), "fit_batches": fit_buckets}
             for label, table in (("uniform", uniform), ("fitted", fitted)):
-                qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta)          # untimed first calls
+                # untimed first calls: enough of them for the clocks to recover from the fit (one workgroup
+                # running alone for 10 ms leaves the chip nearly idle, and the next kernels run slow for a while)
+                for _ in range(8):
+                    qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta)
                 qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out)
                 _, enc_ms = time_call(lambda i: qb.qsdp_quantize_levels(v, bits, bucket, table, codes, meta), 9, torch)
                 _, dec_ms = time_call(lambda i: qb.qsdp_dequantize_levels(codes, meta, n, bits, bucket, table, out), 9,
@@ -379,7 +382,8 @@ def levels_per_layer(torch, qb, wl, x, g, shape, bucket, dev):
         tables[small] = uniform
         codes, meta = segs.alloc_packed(bits)
         meta = meta.reshape(-1)
-        qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, 0, 0)      # untimed first calls
+        for _ in range(8):                                                                      # untimed first calls
+            qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, 0, 0)
         qb.qsdp_dequantize_levels_segmented(codes, meta, segs, bits, tables, out)
         _, enc_ms = time_call(lambda i: qb.qsdp_quantize_levels_segmented(v, segs, bits, tables, codes, meta, coin, i, 0),
                               9, torch)
@@ -513,6 +517,8 @@ def extras(torch, qb, x, g, n, wbits, gbits, bucket, dev):
     qb.qsdp_fit_levels(x, 4, bucket, 0.01, lv, 2048)
     lc, lm = qb.alloc_packed(n, 4, bucket, dev)
     lm = lm.reshape(-1)
+    for _ in range(8):  # untimed: the fit (one workgroup for some ms) left the chip nearly idle, let the clocks recover
+        qb.qsdp_quantize_levels(x, 4, bucket, lv, lc, lm)
     run("quantize_levels_b4_fitted_table", lambda i: qb.qsdp_quantize_levels(x, 4, bucket, lv, lc, lm), 4.5 + meta_b)
     run("quantize_levels_stochastic_b4_fitted_table",
         lambda i: qb.qsdp_quantize_levels_stochastic(g, 4, bucket, lv, i, 0, lc, lm), 4.5 + meta_b)
