@@ -13,10 +13,6 @@ from gpu_util import DEV, ORACLE_THREADS, first_mismatch, gather_rows, pinned_co
 pytestmark = pytest.mark.gpu
 
 
-def u32(a):
-    return np.ascontiguousarray(a).view(np.uint32)
-
-
 @pytest.fixture(scope="module")
 def gpt1p3b():
     """The 1.3B vector and its gradient on the device, page-locked host copies of both for the
