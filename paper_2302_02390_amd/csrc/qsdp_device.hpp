@@ -184,6 +184,12 @@ __device__ __forceinline__ float weight_code_minmax(float x, const MinMaxGrid& g
     return __builtin_amdgcn_fmed3f(k, 0.0f, Lf);
 }
 
+// The position of x in the grid before rounding: weight_code_minmax is clamp(rint(this), 0, L).
+__device__ __forceinline__ float weight_position_minmax(float x, const MinMaxGrid& grid, float xi) {
+    const float t = (x - grid.lo) * grid.inv;
+    return t - xi;
+}
+
 __device__ __forceinline__ float weight_code_lattice(float x, const Divider& d, float xi, float k0,
                                                      float Lf, uint32_t& saturated) {
     const float k = rintf(div_delta(x, d) - xi);
@@ -369,11 +375,19 @@ __device__ __forceinline__ uint32_t pack4(const uint32_t (&c)[4]) {
     return acc;
 }
 
+// Codes given as floats. At 8 bits one instruction per code converts and places it: the conversion to a
+// byte rounds to nearest even and saturates to [0, 255], so it also accepts the unrounded grid position
+// of weight_position_minmax and then yields clamp(rint(position), 0, 255), the code itself.
 template <int BITS>
 __device__ __forceinline__ uint32_t pack4(const float (&c)[4]) {
     uint32_t acc = 0;
+    if constexpr (BITS == 8) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc |= (uint32_t)c[i] << (i * BITS);
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_cvt_pk_u8_f32(c[i], (uint32_t)i, acc);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc |= (uint32_t)c[i] << (i * BITS);
+    }
     return acc;
 }
 

@@ -805,10 +805,15 @@ __global__ void __launch_bounds__(256, mode_min_blocks(MODE)) wave_kernel(const 
             const MinMaxGrid grid = make_minmax_grid(lo, hi, Lw, symmetric);
             base = fmaf(xi, grid.scale, grid.lo);
             scale = grid.scale;
+            // Modes that only store 8-bit codes leave rounding and clamping to the packing instruction
+            // (see pack4); the others need the code itself to decode the new weights.
+            constexpr bool kPackRounds = BITS == 8 && (MODE == MODE_WEIGHT || mode_codes_resident(MODE));
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) w[r][i] = weight_code_minmax(w[r][i], grid, Lw, xi);
+                for (int i = 0; i < 4; ++i)
+                    w[r][i] = kPackRounds ? weight_position_minmax(w[r][i], grid, xi)
+                                          : weight_code_minmax(w[r][i], grid, Lw, xi);
         }
         if constexpr (mode_is_levels(MODE)) {
             if (__builtin_expect(partial, 0)) zero_slots_past_end<G, R>(lcode, l, m);
