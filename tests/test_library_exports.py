@@ -160,3 +160,32 @@ def test_options_block_layout_matches_the_header(tmp_path):
     out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert out[0] == ctypes.sizeof(qb.StepOptions)
     assert out[1:] == [getattr(qb.StepOptions, f).offset for f in fields]
+
+
+def test_segments_build_writes_the_table_the_segmented_calls_require():
+    """qsdp_segments_build (host only): tensors packed back to back, offsets multiples of 8, bucket numbers
+    ascending with every tensor starting a new bucket; sizes that would break those invariants are refused."""
+    import numpy as np
+    L = qb.lib()
+
+    def build(sizes, bucket):
+        s = np.asarray(sizes, dtype=np.uint64)
+        table = np.zeros((len(sizes), 3), dtype=np.uint64)
+        total = int(L.qsdp_segments_build(s.ctypes.data_as(ctypes.c_void_p), len(sizes), bucket,
+                                          table.ctypes.data_as(ctypes.c_void_p)))
+        return total, table
+
+    sizes = [768, 2304, 8, 1024 * 3 + 8, 4096, 24, 5000 + 3]
+    for bucket in (32, 128, 1024, 4096):
+        total, table = build(sizes, bucket)
+        off = fb = 0
+        for t, s in enumerate(sizes):
+            assert table[t].tolist() == [off, s, fb]
+            assert off % 8 == 0
+            off += s
+            fb += -(-s // bucket)
+        assert total == fb
+    assert build([1024, 0, 8], 1024)[0] == 0          # empty tensor
+    assert build([1020, 8], 1024)[0] == 0             # a size other than the last not a multiple of 8
+    assert build([1024], 100)[0] == 0                 # bucket not a multiple of 32
+    assert build([1024, 1020], 1024)[0] == 2          # only the last size may be ragged
