@@ -164,6 +164,34 @@ def test_config4_gpt1p3b_ten_fused_steps_whole_vector(gpt1p3b):
     assert max(len(np.unique(r)) for r in rows) <= 256
 
 
+def test_config4_eight_shards_reproduce_the_whole_vector(gpt1p3b):
+    """How the path shards: every worker runs the same calls on its eighth of the vector with index_offset =
+    the shard's first global element (the rounding uniforms follow the global index, the weight shift
+    depends on the seed only). Eight such calls, on shards of unequal bucket-aligned sizes, must leave
+    exactly the oracle's whole-vector result: the new weights, their codes and meta, and the gradient's codes."""
+    w = gpt1p3b
+    n, g, B = w["n"], w["g"], 1024
+    nb = n // B
+    # shard boundaries at even bucket numbers: the slices of the shared meta buffer stay 16-byte aligned
+    cuts = [0] + [int(nb * f) // 2 * 2 * B for f in (0.11, 0.25, 0.37, 0.5, 0.68, 0.75, 0.93)] + [n]
+    x = w["x"].clone()
+    wc, wm = qb.alloc_packed(n, 8, B, DEV)
+    gc, gm = qb.alloc_packed(n, 4, B, DEV)
+    wm, gm = wm.reshape(-1), gm.reshape(-1)
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        b0, b1 = lo // B, hi // B
+        qb.qsdp_fused_step(x[lo:hi], g[lo:hi], 1e-3, 8, 4, B, 0.0, 5, lo, wc[b0 * 256:b1 * 256], wm[2 * b0:2 * b1])
+        qb.qsdp_quantize_grad(g[lo:hi], 4, B, 5, lo, gc[b0 * 128:b1 * 128], gm[2 * b0:2 * b1])
+    xo = w["work_np"]
+    np.copyto(xo, w["x_np"])
+    oc = np.zeros(ref.codes_bytes(n, 8, B) // 4, np.uint32)
+    om = np.zeros(ref.meta_bytes(n, B) // 4, np.float32)
+    ref.fused_step_inplace(xo, w["g_np"], 1e-3, 8, 4, B, 0.0, 5, wcodes=oc, wmeta=om)
+    assert first_mismatch(x, w["work_h"]) == -1
+    assert same_packed(wc, wm, oc, om)
+    assert same_packed(gc, gm, *ref.quantize_grad(w["g_np"], 4, B, 5))
+
+
 @pytest.mark.parametrize("B", [128, 512, 1024, 4096])
 def test_config5_bit_and_bucket_sweep_on_a_16m_slice(gpt1p3b, B):
     """Every combination G in {2,3,4,6,8} x W in {4,6,8} at this bucket size on the first 2^24
